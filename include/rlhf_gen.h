@@ -1,0 +1,158 @@
+/*
+ * rlhf_gen - one GPU's share of the RLHF generation stage on MI355X (gfx950).
+ *
+ * The operation is `Response <- Actor.generate(Query)` of the paper's Alg. 1 and
+ * `ShadowActor.generate(Query)` of Alg. 2: a batched autoregressive rollout of a
+ * Llama-style Actor (Sec. V-A, "LLM Backbones") that emits exactly R response tokens
+ * per query (Sec. V-A, "Hyperparameters": minimum = maximum generation length) plus the
+ * log-probability of every emitted token, which PPO consumes (Sec. II, the RLHF pipeline).
+ * The paper names this stage as the bottleneck of a step (Sec. III-B).
+ *
+ * Plain C ABI: no exceptions, no C++ or framework types.  Every call returns an
+ * rlhf_gen_status; a negative value means nothing useful was produced and
+ * rlhf_gen_last_error() describes why.  A context is not thread-safe.
+ *
+ * Memory conventions
+ *   "device" pointers are HIP device allocations on cfg.device, owned by the caller,
+ *   row-major.  "host" pointers are ordinary process memory.  Weight matrices are
+ *   [out_features, in_features] (y = x W^T), stored as cfg.dtype, BORROWED for the
+ *   context's lifetime and never written.  The library owns the paged KV cache, block
+ *   tables, activations and counters; all of it is allocated in rlhf_gen_init and
+ *   nothing is allocated afterwards.
+ *   Work is enqueued on cfg.stream.  prefill and decode_step return after enqueueing
+ *   (prefill synchronises once at entry to validate the token ids); generate
+ *   synchronises the stream before returning.
+ */
+#ifndef RLHF_GEN_H
+#define RLHF_GEN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rlhf_gen_ctx rlhf_gen_ctx; /* opaque */
+
+typedef enum {
+  RLHF_GEN_OK = 0,
+  RLHF_GEN_E_INVALID = -1,     /* bad argument: NULL, shape, token id out of range */
+  RLHF_GEN_E_NOMEM = -2,       /* KV pool or device memory cannot hold the request */
+  RLHF_GEN_E_STATE = -3,       /* call order: decode before prefill, past max_seq */
+  RLHF_GEN_E_DEVICE = -4,      /* a HIP call failed */
+  RLHF_GEN_E_UNSUPPORTED = -5  /* a shape the kernels do not cover */
+} rlhf_gen_status;
+
+enum { RLHF_GEN_DTYPE_FP32 = 0, RLHF_GEN_DTYPE_BF16 = 1 };
+
+/* cfg.flags */
+enum {
+  RLHF_GEN_FLAG_SHUFFLE_BLOCKS = 1u, /* hand out KV blocks in a scrambled order (tests: results must not depend on placement) */
+  RLHF_GEN_FLAG_NO_GRAPH = 2u,       /* generate launches every decode step kernel by kernel instead of replaying a captured graph */
+  RLHF_GEN_FLAG_GENERIC_GEMM = 4u    /* decode uses the large-tile GEMM instead of the weight-streaming one (cross-check) */
+};
+
+/* Model and capacity description.  Architecture: pre-norm decoder, RMSNorm (eps inside the
+ * square root), rotary embedding with half-split pairing (dimension i pairs with i + head_dim/2,
+ * angle pos * rope_theta^(-2i/head_dim)), causal attention scaled by 1/sqrt(head_dim) where
+ * query head j reads KV head j / (n_heads / n_kv_heads), SwiGLU MLP, no biases, untied LM head. */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rms_eps, rope_theta;
+  int32_t dtype;          /* RLHF_GEN_DTYPE_*: storage type of weights and KV cache.  bf16 computes with
+                             bf16 MFMA operands and fp32 accumulation/residual/softmax/logits; fp32 is a
+                             plain-ALU path meant for small models */
+  int32_t max_batch;      /* largest B any call will pass */
+  int32_t max_seq;        /* largest query length + response length of one sequence */
+  int32_t kv_block;       /* tokens per KV page; must be 16 */
+  int32_t kv_pool_blocks; /* pages in the pool (shared by all sequences, one set per layer);
+                             0 = max_batch * ceil(max_seq / kv_block) */
+  int32_t device;         /* HIP device ordinal */
+  void* stream;           /* hipStream_t, borrowed; NULL = the default stream */
+  uint32_t flags;
+} rlhf_gen_cfg;
+
+/* Device pointers.  The per-layer members are HOST arrays of n_layers DEVICE pointers. */
+typedef struct {
+  const void* tok_emb;           /* [vocab, d_model] */
+  const void* lm_head;           /* [vocab, d_model] */
+  const void* final_norm;        /* [d_model] */
+  const void* const* attn_norm;  /* each [d_model] */
+  const void* const* wqkv;       /* each [(n_heads + 2 n_kv_heads) head_dim, d_model]: q rows, k rows, v rows */
+  const void* const* wo;         /* each [d_model, n_heads head_dim] */
+  const void* const* ffn_norm;   /* each [d_model] */
+  const void* const* w_gate_up;  /* each [2 d_ffn, d_model]: gate rows, then up rows */
+  const void* const* w_down;     /* each [d_model, d_ffn] */
+} rlhf_gen_weights;
+
+/* Sampling rule for one rollout.  The paper states none, so it is a parameter.
+ * greedy != 0: argmax, lowest index on exact ties.  Otherwise z = logits / temperature,
+ * p = softmax(z), nucleus = shortest prefix of the tokens ordered by (p descending, index
+ * ascending) whose mass reaches top_p (top_p >= 1 keeps everything), p' = p renormalised on the
+ * nucleus, token = first nucleus member in ascending index order whose running p' sum exceeds u.
+ * u in [0,1) has 24 bits: u = (mix(seed ^ b*0x9E3779B97F4A7C15 ^ t*0xBF58476D1CE4E5B9) >> 40) / 2^24
+ * with mix = the splitmix64 output function applied to its argument + 0x9E3779B97F4A7C15,
+ * b the batch row and t the response index.
+ * logprob_mode 0: log softmax(logits)[token] of the raw model distribution (what a later
+ * Actor.forward over query+response returns, Alg. 1); 1: log p'[token]. */
+typedef struct {
+  float temperature;
+  float top_p;
+  uint64_t seed;
+  int32_t greedy;
+  int32_t logprob_mode;
+} rlhf_gen_sampling;
+
+/* Create a context for one Actor replica.  Validates cfg, allocates every buffer, zeroes the KV
+ * pool.  weights/cfg are host structs; *out receives the context (NULL on failure, in which case
+ * rlhf_gen_last_error(NULL) holds the reason).  Sec. V-A fixes only "Llama" and the lengths; the
+ * architecture details are those listed at rlhf_gen_cfg. */
+int rlhf_gen_init(const rlhf_gen_weights* weights, const rlhf_gen_cfg* cfg, rlhf_gen_ctx** out);
+
+/* Prefill: run the Actor over B right-padded queries, fill the KV cache, and draw response token 0
+ * of every sequence from the logits at its last query position (Alg. 1, the first step of
+ * Actor.generate).  Replaces any previous batch held by the context.
+ *   query_tokens  device int32 [B, Lmax]; row b holds lengths[b] token ids, then padding that is never read
+ *   lengths       HOST int32 [B]; 1 <= lengths[b] <= Lmax, lengths[b] + 1 <= max_seq
+ *   sampling      host struct, copied; stays in force for the following decode steps
+ *   tok_out       device int32 [B]; logprob_out device float [B]
+ * Errors: E_INVALID (NULL, B or lengths out of range, a token id outside [0, vocab)),
+ * E_NOMEM (KV pool too small). */
+int rlhf_gen_prefill(rlhf_gen_ctx* ctx, const int32_t* query_tokens, const int32_t* lengths, int32_t B,
+                     int32_t Lmax, const rlhf_gen_sampling* sampling, int32_t* tok_out, float* logprob_out);
+
+/* One KV-cached decode step for the current batch: feed each sequence one token (the one drawn by
+ * the previous call, or forced_tokens[b] if forced_tokens is not NULL - teacher forcing), append
+ * its key/value to the cache, and draw the next response token and its log-prob.
+ *   forced_tokens device int32 [B] or NULL (ids outside [0, vocab) are clamped)
+ *   tok_out       device int32 [B]; logprob_out device float [B]
+ * Errors: E_STATE (no prefill yet, or a sequence would exceed max_seq), E_NOMEM (pool exhausted). */
+int rlhf_gen_decode_step(rlhf_gen_ctx* ctx, const int32_t* forced_tokens, int32_t* tok_out, float* logprob_out);
+
+/* Whole rollout = prefill + (max_resp_len - 1) decode steps; every sequence gets exactly
+ * max_resp_len tokens (no end-of-sequence stop; Sec. V-A).  Reserves all KV pages up front and
+ * fails with E_NOMEM before computing if they do not fit.  Synchronises the stream before returning.
+ *   resp_tokens   device int32 [B, max_resp_len]; resp_logprobs device float [B, max_resp_len] */
+int rlhf_gen_generate(rlhf_gen_ctx* ctx, const int32_t* query_tokens, const int32_t* lengths, int32_t B,
+                      int32_t Lmax, int32_t max_resp_len, const rlhf_gen_sampling* sampling,
+                      int32_t* resp_tokens, float* resp_logprobs);
+
+/* Copy the fp32 logits [B, vocab] that the last prefill/decode step sampled from into a device
+ * buffer (parity checks).  E_STATE if no step has run. */
+int rlhf_gen_get_logits(rlhf_gen_ctx* ctx, float* out);
+
+/* Timing of the last rlhf_gen_generate on this context, measured with HIP events on cfg.stream:
+ * prefill_ms, decode_ms (all decode steps together) and the number of decode steps. */
+int rlhf_gen_last_timing(const rlhf_gen_ctx* ctx, float* prefill_ms, float* decode_ms, int32_t* decode_steps);
+
+/* Message of the last failed call on ctx (or of the last failed rlhf_gen_init if ctx is NULL).
+ * The pointer stays valid until the next call on the same context. */
+const char* rlhf_gen_last_error(const rlhf_gen_ctx* ctx);
+
+/* Free everything the context owns.  The caller's weights are untouched.  NULL is allowed. */
+void rlhf_gen_destroy(rlhf_gen_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RLHF_GEN_H */

@@ -1,0 +1,220 @@
+"""ctypes binding of librlhf_gen.so: argument marshalling only.
+
+Every function here has the name of the C entry point it forwards to
+(`rlhf_gen_init`, `rlhf_gen_prefill`, ...).  PyTorch supplies device memory and
+the HIP stream; no arithmetic of the method happens in Python.  If the shared
+library is missing the import of the functions fails loudly - there is no CPU
+fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librlhf_gen.so")
+
+OK, E_INVALID, E_NOMEM, E_STATE, E_DEVICE, E_UNSUPPORTED = 0, -1, -2, -3, -4, -5
+DTYPE_FP32, DTYPE_BF16 = 0, 1
+FLAG_SHUFFLE_BLOCKS, FLAG_NO_GRAPH, FLAG_GENERIC_GEMM = 1, 2, 4
+GEMM_TILED, GEMM_STREAMING, GEMM_FP32 = 0, 1, 2
+EPI_STORE_F32, EPI_RESID_F32, EPI_SWIGLU, EPI_STORE_BF16 = 0, 1, 2, 3
+
+EXPORTS = [
+    "rlhf_gen_init", "rlhf_gen_prefill", "rlhf_gen_decode_step", "rlhf_gen_generate", "rlhf_gen_get_logits",
+    "rlhf_gen_last_timing", "rlhf_gen_last_error", "rlhf_gen_destroy",
+    "rlhf_gen_op_gemm", "rlhf_gen_op_rope_append", "rlhf_gen_op_attn_decode", "rlhf_gen_op_attn_prefill",
+    "rlhf_gen_op_sample",
+]
+
+
+class Cfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab")] + [
+        ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32), ("max_batch", C.c_int32),
+        ("max_seq", C.c_int32), ("kv_block", C.c_int32), ("kv_pool_blocks", C.c_int32), ("device", C.c_int32),
+        ("stream", C.c_void_p), ("flags", C.c_uint32)]
+
+
+class Weights(C.Structure):
+    _fields_ = [("tok_emb", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p),
+                ("attn_norm", C.POINTER(C.c_void_p)), ("wqkv", C.POINTER(C.c_void_p)), ("wo", C.POINTER(C.c_void_p)),
+                ("ffn_norm", C.POINTER(C.c_void_p)), ("w_gate_up", C.POINTER(C.c_void_p)),
+                ("w_down", C.POINTER(C.c_void_p))]
+
+
+class Sampling(C.Structure):
+    _fields_ = [("temperature", C.c_float), ("top_p", C.c_float), ("seed", C.c_uint64), ("greedy", C.c_int32),
+                ("logprob_mode", C.c_int32)]
+
+
+class RlhfGenError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"rlhf_gen status {status}: {message}")
+        self.status = status
+        self.message = message
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = C.CDLL(LIB_PATH)
+        L.rlhf_gen_init.argtypes = [C.POINTER(Weights), C.POINTER(Cfg), C.POINTER(C.c_void_p)]
+        L.rlhf_gen_prefill.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.c_int32,
+                                       C.POINTER(Sampling), C.c_void_p, C.c_void_p]
+        L.rlhf_gen_decode_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.rlhf_gen_generate.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_int32,
+                                        C.POINTER(Sampling), C.c_void_p, C.c_void_p]
+        L.rlhf_gen_get_logits.argtypes = [C.c_void_p, C.c_void_p]
+        L.rlhf_gen_last_timing.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_int32)]
+        L.rlhf_gen_last_error.argtypes = [C.c_void_p]
+        L.rlhf_gen_last_error.restype = C.c_char_p
+        L.rlhf_gen_destroy.argtypes = [C.c_void_p]
+        L.rlhf_gen_destroy.restype = None
+        L.rlhf_gen_op_gemm.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                       C.c_int32, C.c_int32, C.c_int32]
+        L.rlhf_gen_op_rope_append.argtypes = [C.c_void_p] * 10 + [C.c_int32] * 6
+        L.rlhf_gen_op_attn_decode.argtypes = [C.c_void_p] * 4 + [C.c_int32, C.c_void_p, C.c_void_p] + [C.c_int32] * 3
+        L.rlhf_gen_op_attn_prefill.argtypes = [C.c_void_p] * 4 + [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p] + [C.c_int32] * 4
+        L.rlhf_gen_op_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.POINTER(Sampling), C.c_void_p,
+                                         C.c_void_p, C.c_void_p, C.c_void_p]
+        for name in EXPORTS:
+            if name not in ("rlhf_gen_last_error", "rlhf_gen_destroy"):
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous CUDA/HIP tensors"
+    return t.data_ptr()
+
+
+def make_sampling(temperature=1.0, top_p=1.0, seed=0, greedy=False, logprob_mode=0) -> Sampling:
+    return Sampling(float(temperature), float(top_p), int(seed), int(bool(greedy)), int(logprob_mode))
+
+
+def _check(ctx: Optional[int], status: int) -> None:
+    if status != OK:
+        msg = lib().rlhf_gen_last_error(ctx)
+        raise RlhfGenError(status, msg.decode() if msg else "")
+
+
+class Context:
+    """Owns one rlhf_gen_ctx.  Methods carry the names of the C entry points."""
+
+    def __init__(self, weights: dict, shape, dtype: str, max_batch: int, max_seq: int, device: int = 0,
+                 kv_pool_blocks: int = 0, flags: int = 0, stream: Optional[torch.cuda.Stream] = None):
+        L = lib()
+        self.shape, self.dtype, self.device = shape, dtype, torch.device("cuda", device)
+        self.stream = stream if stream is not None else torch.cuda.Stream(device=self.device)
+        self._weights = weights  # borrowed by the library: keep alive
+        n = shape.n_layers
+        arr = lambda key: (C.c_void_p * n)(*[_ptr(lw[key]) for lw in weights["layers"]])
+        self._arrs = {k: arr(k) for k in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")}
+        w = Weights(_ptr(weights["tok_emb"]), _ptr(weights["lm_head"]), _ptr(weights["final_norm"]),
+                    *[C.cast(self._arrs[k], C.POINTER(C.c_void_p)) for k in
+                      ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")])
+        cfg = Cfg(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
+                  shape.vocab, shape.rms_eps, shape.rope_theta, DTYPE_BF16 if dtype == "bf16" else DTYPE_FP32,
+                  max_batch, max_seq, 16, kv_pool_blocks, device, self.stream.cuda_stream, flags)
+        self.cfg = cfg
+        h = C.c_void_p()
+        torch.cuda.synchronize(self.device)
+        _check(None, L.rlhf_gen_init(C.byref(w), C.byref(cfg), C.byref(h)))
+        self._h = h
+        self.B = 0
+
+    # -- the C entry points ------------------------------------------------------------------
+    def rlhf_gen_prefill(self, query_tokens: torch.Tensor, lengths: Sequence[int], sampling: Sampling):
+        B, Lmax = query_tokens.shape
+        lens = (C.c_int32 * B)(*[int(x) for x in lengths])
+        tok = torch.empty(B, dtype=torch.int32, device=self.device)
+        lp = torch.empty(B, dtype=torch.float32, device=self.device)
+        self.stream.wait_stream(torch.cuda.current_stream(self.device))
+        _check(self._h, lib().rlhf_gen_prefill(self._h, _ptr(query_tokens), lens, B, Lmax, C.byref(sampling), _ptr(tok), _ptr(lp)))
+        self.B = B
+        return tok, lp
+
+    def rlhf_gen_decode_step(self, forced_tokens: Optional[torch.Tensor] = None):
+        tok = torch.empty(self.B, dtype=torch.int32, device=self.device)
+        lp = torch.empty(self.B, dtype=torch.float32, device=self.device)
+        self.stream.wait_stream(torch.cuda.current_stream(self.device))
+        _check(self._h, lib().rlhf_gen_decode_step(self._h, _ptr(forced_tokens), _ptr(tok), _ptr(lp)))
+        return tok, lp
+
+    def rlhf_gen_generate(self, query_tokens: torch.Tensor, lengths: Sequence[int], max_resp_len: int,
+                          sampling: Sampling, out_tokens: Optional[torch.Tensor] = None,
+                          out_logprobs: Optional[torch.Tensor] = None):
+        B, Lmax = query_tokens.shape
+        lens = (C.c_int32 * B)(*[int(x) for x in lengths])
+        toks = out_tokens if out_tokens is not None else torch.empty(B, max_resp_len, dtype=torch.int32, device=self.device)
+        lps = out_logprobs if out_logprobs is not None else torch.empty(B, max_resp_len, dtype=torch.float32, device=self.device)
+        self.stream.wait_stream(torch.cuda.current_stream(self.device))
+        _check(self._h, lib().rlhf_gen_generate(self._h, _ptr(query_tokens), lens, B, Lmax, max_resp_len,
+                                                C.byref(sampling), _ptr(toks), _ptr(lps)))
+        self.B = B
+        return toks, lps
+
+    def rlhf_gen_get_logits(self) -> torch.Tensor:
+        out = torch.empty(self.B, self.shape.vocab, dtype=torch.float32, device=self.device)
+        _check(self._h, lib().rlhf_gen_get_logits(self._h, _ptr(out)))
+        self.synchronize()
+        return out
+
+    def rlhf_gen_last_timing(self):
+        a, b, n = C.c_float(), C.c_float(), C.c_int32()
+        _check(self._h, lib().rlhf_gen_last_timing(self._h, C.byref(a), C.byref(b), C.byref(n)))
+        return a.value, b.value, n.value
+
+    def synchronize(self) -> None:
+        self.stream.synchronize()
+
+    def rlhf_gen_destroy(self) -> None:
+        if getattr(self, "_h", None):
+            lib().rlhf_gen_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.rlhf_gen_destroy()
+        except Exception:
+            pass
+
+
+# -- single-operation entry points -------------------------------------------------------------------
+def rlhf_gen_op_gemm(kind, A, W, out, M, N, K, epilogue=0, nsplit=1) -> int:
+    return lib().rlhf_gen_op_gemm(None, kind, _ptr(A), _ptr(W), _ptr(out), M, N, K, epilogue, nsplit)
+
+
+def rlhf_gen_op_rope_append(qkv, row_pos, row_seq, cos_t, sin_t, q_out, kv_pool, block_table, max_blocks, M, Hq, Hkv,
+                            head_dim, bf16) -> int:
+    return lib().rlhf_gen_op_rope_append(None, _ptr(qkv), _ptr(row_pos), _ptr(row_seq), _ptr(cos_t), _ptr(sin_t),
+                                         _ptr(q_out), _ptr(kv_pool), _ptr(block_table), max_blocks, M, Hq, Hkv,
+                                         head_dim, int(bf16))
+
+
+def rlhf_gen_op_attn_decode(q, kv_pool, block_table, max_blocks, seq_len, out, B, Hq, Hkv) -> int:
+    return lib().rlhf_gen_op_attn_decode(None, _ptr(q), _ptr(kv_pool), _ptr(block_table), max_blocks, _ptr(seq_len),
+                                         _ptr(out), B, Hq, Hkv)
+
+
+def rlhf_gen_op_attn_prefill(q, kv_pool, block_table, max_blocks, cu_seqlens, seq_ids, out, nseq, max_len, Hq, Hkv) -> int:
+    return lib().rlhf_gen_op_attn_prefill(None, _ptr(q), _ptr(kv_pool), _ptr(block_table), max_blocks,
+                                          _ptr(cu_seqlens), _ptr(seq_ids), _ptr(out), nseq, max_len, Hq, Hkv)
+
+
+def rlhf_gen_op_sample(logits, sampling: Sampling, step, tok_out, lp_out, scratch_tok) -> int:
+    B, V = logits.shape
+    return lib().rlhf_gen_op_sample(None, _ptr(logits), B, V, C.byref(sampling), _ptr(step), _ptr(tok_out),
+                                    _ptr(lp_out), _ptr(scratch_tok))

@@ -1,0 +1,69 @@
+// Shared device helpers for the gfx950 kernels: bf16 bit conversions, MFMA wrappers,
+// wavefront reductions, and the byte layout of one KV-cache page.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef uint16_t bf16_t;  // raw bf16 bits
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+// Round to nearest even; NaN stays NaN.
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// D(16x16) += A(16x32) * B(32x16), bf16 in, fp32 out.  Lane l supplies row (l & 15) of A and
+// column (l & 15) of B, eight consecutive k each, the k group chosen by l >> 4 in the same way for
+// both operands.  Lane l receives D[4 (l >> 4) + i][l & 15], i = 0..3.
+__device__ __forceinline__ f32x4_t mfma_16x16x32(uint4 a, uint4 b, f32x4_t c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+// D(16x16) += A(16x16) * B(16x16): four consecutive k per lane, k group l >> 4.
+__device__ __forceinline__ f32x4_t mfma_16x16x16(uint2 a, uint2 b, f32x4_t c) {
+  return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, a), __builtin_bit_cast(s16x4_t, b), c, 0, 0, 0);
+}
+// D(32x32) += A(32x16) * B(16x32): lane l supplies row/column (l & 31), k group l >> 5 (8 k each).
+// Lane l receives D[8 (i >> 2) + 4 (l >> 5) + (i & 3)][l & 31], i = 0..15.
+__device__ __forceinline__ f32x16_t mfma_32x32x16(uint4 a, uint4 b, f32x16_t c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+
+// ---- KV-cache page -------------------------------------------------------------------------
+// One page holds 16 tokens of one KV head with head_dim 128 in bf16: 4096 B of keys followed by
+// 4096 B of values, both pre-arranged as MFMA operands so that a wavefront reads a page with
+// eight fully coalesced 16 B-per-lane loads and feeds the registers to the matrix cores as is.
+//   keys:   16 B chunk (kk, lane) at kk*1024 + lane*16 holds K[token lane&15][dims 8*(4kk + (lane>>4)) .. +8]
+//   values: 16 B chunk (j, lane) at 4096 + j*1024 + lane*16 holds, for tokens 4*(lane>>4) .. +4,
+//           V[token][dim 32j + (lane&15)] in its first 8 B and V[token][dim 32j + 16 + (lane&15)] in the rest
+constexpr int KV_PAGE_TOKENS = 16;
+constexpr int KV_HEAD_DIM = 128;
+constexpr int KV_PAGE_BYTES = 8192;
+__host__ __device__ __forceinline__ int kpage_offset(int slot, int dim) {
+  int c = dim >> 3, e = dim & 7;
+  return (c >> 2) * 1024 + (((c & 3) << 4) + slot) * 16 + e * 2;
+}
+__host__ __device__ __forceinline__ int vpage_offset(int slot, int dim) {
+  int j = dim >> 5, r = dim & 31;
+  return 4096 + j * 1024 + (((slot >> 2) << 4) + (r & 15)) * 16 + (r >> 4) * 8 + (slot & 3) * 2;
+}

@@ -1,0 +1,282 @@
+// Attention over the paged bf16 KV cache on the matrix cores (head_dim 128, 16-token pages).
+//
+// Both kernels work on tiles of 16 query rows that share one KV head.  For one page they form
+// S^T = K Q^T (keys as the MFMA row operand, so lane l ends up holding the scores of tokens
+// 4 (l >> 4) .. +4 against query row l & 15), run the online softmax on those registers, and feed the
+// probabilities straight back as the column operand of O^T += V^T P^T; the page layout (common.h) is
+// exactly the operand layout, so keys and values go from HBM to the MFMA through eight coalesced 16 B
+// loads per lane with no shuffles and no LDS.
+//   decode : the 16 rows are the query heads of one KV group at the newest position (rows beyond the group
+//            size are zero padding); four wavefronts split the pages of one (sequence, KV head) and merge
+//            their partial (max, sum, O) through LDS.
+//   prefill: the 16 rows are 16 consecutive positions of one query head; a wavefront walks the pages up to
+//            its diagonal page and masks inside it.
+// HBM-bound in decode: every cached byte is read once per step per KV head; the MFMA work is negligible.
+#include <math.h>
+
+#include "common.h"
+#include "kernels.h"
+
+namespace {
+
+struct AttnState {
+  f32x4_t o[8];  // O^T tile: o[db][i] = O[row l&15][dim 16 db + 4 (l>>4) + i]
+  float m;       // running max (log2 domain) of row l & 15
+  float l;       // this lane's share of the running sum
+};
+
+__device__ __forceinline__ void load_page(const char* page, int lane, uint4 kf[4], uint4 vf[4]) {
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) kf[kk] = *(const uint4*)(page + kk * 1024 + lane * 16);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) vf[j] = *(const uint4*)(page + 4096 + j * 1024 + lane * 16);
+}
+
+// tok0: index of the page's first token; limit: number of tokens visible to this lane's query row.
+template <bool MASK>
+__device__ __forceinline__ void attn_page(const uint4 kf[4], const uint4 vf[4], const uint4 qf[4], AttnState& st,
+                                          float scale_log2, int tok0, int limit, int g) {
+  f32x4_t s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) s = mfma_16x16x32(kf[kk], qf[kk], s);
+  float sv[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    sv[i] = s[i] * scale_log2;
+    if (MASK && tok0 + 4 * g + i >= limit) sv[i] = -INFINITY;
+  }
+  float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+  mx = fmaxf(mx, __shfl_xor(mx, 16));
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  float mnew = fmaxf(st.m, mx);
+  float alpha, p[4];
+  if (mnew == -INFINITY) {  // nothing visible yet for this row
+    alpha = 1.f;
+    p[0] = p[1] = p[2] = p[3] = 0.f;
+  } else {
+    alpha = exp2f(st.m - mnew);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) p[i] = exp2f(sv[i] - mnew);
+  }
+  st.l = st.l * alpha + (p[0] + p[1]) + (p[2] + p[3]);
+  st.m = mnew;
+#pragma unroll
+  for (int db = 0; db < 8; ++db) st.o[db] *= alpha;
+  uint2 pb;
+  pb.x = pack_bf16x2(p[0], p[1]);
+  pb.y = pack_bf16x2(p[2], p[3]);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    st.o[2 * j] = mfma_16x16x16(make_uint2(vf[j].x, vf[j].y), pb, st.o[2 * j]);
+    st.o[2 * j + 1] = mfma_16x16x16(make_uint2(vf[j].z, vf[j].w), pb, st.o[2 * j + 1]);
+  }
+}
+
+__device__ __forceinline__ void init_state(AttnState& st) {
+#pragma unroll
+  for (int db = 0; db < 8; ++db) st.o[db] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+  st.m = -INFINITY;
+  st.l = 0.f;
+}
+
+// grid (Hkv, B), 256 threads.  q [B, Hq, 128] bf16, out [B, Hq*128] bf16.  seq_len[b] = tokens cached BEFORE
+// this step; the step's own key/value has already been appended, so seq_len[b] + 1 tokens are visible.
+__global__ __launch_bounds__(256) void attn_decode_kernel(const bf16_t* __restrict__ q, const char* __restrict__ pool,
+                                                          const int* __restrict__ block_table, int max_blocks,
+                                                          const int* __restrict__ seq_len, bf16_t* __restrict__ out,
+                                                          int Hq, int Hkv, float scale_log2) {
+  __shared__ float m_s[4][16];
+  __shared__ float l_s[4][16];
+  __shared__ float o_s[4][16][132];
+  const int kvh = blockIdx.x, b = blockIdx.y;
+  const int group = Hq / Hkv;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, t = lane & 15, g = lane >> 4;
+  const int L = seq_len[b] + 1;
+  const int npages = (L + 15) >> 4;
+  uint4 qf[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    qf[kk] = make_uint4(0, 0, 0, 0);
+    if (t < group) qf[kk] = *(const uint4*)(q + ((size_t)b * Hq + kvh * group + t) * 128 + 8 * (4 * kk + g));
+  }
+  AttnState st;
+  init_state(st);
+  const int* bt = block_table + (size_t)b * max_blocks;
+  uint4 kf[4], vf[4], kn[4], vn[4];
+  int p = w;
+  if (p < npages) load_page(pool + ((size_t)bt[p] * Hkv + kvh) * KV_PAGE_BYTES, lane, kf, vf);
+  while (p < npages) {
+    int pn = p + 4;
+    if (pn < npages) load_page(pool + ((size_t)bt[pn] * Hkv + kvh) * KV_PAGE_BYTES, lane, kn, vn);
+    if (p == npages - 1)
+      attn_page<true>(kf, vf, qf, st, scale_log2, p * 16, L, g);
+    else
+      attn_page<false>(kf, vf, qf, st, scale_log2, p * 16, L, g);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { kf[i] = kn[i]; vf[i] = vn[i]; }
+    p = pn;
+  }
+  float lt = st.l;
+  lt += __shfl_xor(lt, 16);
+  lt += __shfl_xor(lt, 32);
+  if (g == 0) { m_s[w][t] = st.m; l_s[w][t] = lt; }
+  if (t < group) {
+#pragma unroll
+    for (int db = 0; db < 8; ++db)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) o_s[w][t][db * 16 + 4 * g + i] = st.o[db][i];
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < group * 128; idx += 256) {
+    int r = idx >> 7, dim = idx & 127;
+    float M = fmaxf(fmaxf(m_s[0][r], m_s[1][r]), fmaxf(m_s[2][r], m_s[3][r]));
+    float num = 0.f, den = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < 4; ++ww) {
+      float mw = m_s[ww][r];
+      float a = (mw == -INFINITY) ? 0.f : exp2f(mw - M);
+      num += a * o_s[ww][r][dim];
+      den += a * l_s[ww][r];
+    }
+    out[((size_t)b * Hq + kvh * group + r) * 128 + dim] = f32_to_bf16(num / den);
+  }
+}
+
+// grid (ceil(max_len / 64), Hq, nseq), 256 threads: wavefront w owns positions p0 .. p0+15 of sequence
+// seq_ids[blockIdx.z] with p0 = 16 (4 blockIdx.x + w).  q / out are packed over tokens: row cu_seqlens[z] + pos.
+__global__ __launch_bounds__(256) void attn_prefill_kernel(const bf16_t* __restrict__ q, const char* __restrict__ pool,
+                                                           const int* __restrict__ block_table, int max_blocks,
+                                                           const int* __restrict__ cu_seqlens,
+                                                           const int* __restrict__ seq_ids, bf16_t* __restrict__ out,
+                                                           int Hq, int Hkv, float scale_log2) {
+  const int z = blockIdx.z, head = blockIdx.y;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, t = lane & 15, g = lane >> 4;
+  const int row0 = cu_seqlens[z], len = cu_seqlens[z + 1] - row0;
+  const int p0 = 16 * (4 * blockIdx.x + w);
+  if (p0 >= len) return;
+  const int b = seq_ids[z];
+  const int kvh = head / (Hq / Hkv);
+  const bool valid = p0 + t < len;
+  uint4 qf[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    qf[kk] = make_uint4(0, 0, 0, 0);
+    if (valid) qf[kk] = *(const uint4*)(q + ((size_t)(row0 + p0 + t) * Hq + head) * 128 + 8 * (4 * kk + g));
+  }
+  AttnState st;
+  init_state(st);
+  const int* bt = block_table + (size_t)b * max_blocks;
+  const int pd = p0 >> 4;  // diagonal page
+  uint4 kf[4], vf[4], kn[4], vn[4];
+  load_page(pool + ((size_t)bt[0] * Hkv + kvh) * KV_PAGE_BYTES, lane, kf, vf);
+  for (int p = 0; p <= pd; ++p) {
+    if (p < pd) load_page(pool + ((size_t)bt[p + 1] * Hkv + kvh) * KV_PAGE_BYTES, lane, kn, vn);
+    if (p == pd)
+      attn_page<true>(kf, vf, qf, st, scale_log2, p * 16, p0 + t + 1, g);
+    else
+      attn_page<false>(kf, vf, qf, st, scale_log2, p * 16, 0, g);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { kf[i] = kn[i]; vf[i] = vn[i]; }
+  }
+  float lt = st.l;
+  lt += __shfl_xor(lt, 16);
+  lt += __shfl_xor(lt, 32);
+  if (valid) {
+    float inv = 1.f / lt;
+    bf16_t* orow = out + ((size_t)(row0 + p0 + t) * Hq + head) * 128 + 4 * g;
+#pragma unroll
+    for (int db = 0; db < 8; ++db) {
+      uint2 o;
+      o.x = pack_bf16x2(st.o[db][0] * inv, st.o[db][1] * inv);
+      o.y = pack_bf16x2(st.o[db][2] * inv, st.o[db][3] * inv);
+      *(uint2*)(orow + db * 16) = o;
+    }
+  }
+}
+
+// fp32 path: one wavefront per (row, query head); lane j takes tokens j, j+64, ...; page = [2][16][h] floats.
+template <int H>
+__global__ __launch_bounds__(64) void attn_f32_kernel(const float* __restrict__ q, const float* __restrict__ pool,
+                                                      const int* __restrict__ block_table, int max_blocks,
+                                                      const int* __restrict__ row_pos, const int* __restrict__ row_seq,
+                                                      float* __restrict__ out, int Hq, int Hkv) {
+  const int m = blockIdx.y, head = blockIdx.x, lane = threadIdx.x;
+  const int b = row_seq ? row_seq[m] : m;
+  const int L = row_pos[m] + 1;
+  const int kvh = head / (Hq / Hkv);
+  const float* qr = q + ((size_t)m * Hq + head) * H;
+  float qv[H];
+#pragma unroll
+  for (int i = 0; i < H; ++i) qv[i] = qr[i];
+  const float scale = rsqrtf((float)H);
+  float mx = -INFINITY, l = 0.f, o[H];
+#pragma unroll
+  for (int i = 0; i < H; ++i) o[i] = 0.f;
+  const int* bt = block_table + (size_t)b * max_blocks;
+  for (int tok = lane; tok < L; tok += 64) {
+    const float* page = pool + ((size_t)bt[tok >> 4] * Hkv + kvh) * (2 * 16 * H);
+    const float* kr = page + (tok & 15) * H;
+    const float* vr = page + 16 * H + (tok & 15) * H;
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < H; ++i) s += qv[i] * kr[i];
+    s *= scale;
+    float mn = fmaxf(mx, s);
+    float a = expf(mx - mn), pw = expf(s - mn);
+    l = l * a + pw;
+#pragma unroll
+    for (int i = 0; i < H; ++i) o[i] = o[i] * a + pw * vr[i];
+    mx = mn;
+  }
+  float M = wave_max(mx);
+  float a = (mx == -INFINITY) ? 0.f : expf(mx - M);
+  float den = wave_sum(l * a);
+  float* orow = out + ((size_t)m * Hq + head) * H;
+#pragma unroll
+  for (int i = 0; i < H; ++i) {
+    float v = wave_sum(o[i] * a);
+    if (lane == 0) orow[i] = v / den;
+  }
+}
+
+}  // namespace
+
+static const float LOG2E = 1.4426950408889634f;
+
+hipError_t launch_attn_decode_bf16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
+                                   int max_blocks, const int* seq_len, void* out, int B, int Hq, int Hkv) {
+  if (B <= 0) return hipSuccess;
+  if (Hq % Hkv || Hq / Hkv > 16) return hipErrorInvalidValue;
+  float scale_log2 = LOG2E / sqrtf((float)KV_HEAD_DIM);
+  attn_decode_kernel<<<dim3(Hkv, B), 256, 0, s>>>((const bf16_t*)q, (const char*)kv_pool_layer, block_table, max_blocks,
+                                                  seq_len, (bf16_t*)out, Hq, Hkv, scale_log2);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_prefill_bf16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
+                                    int max_blocks, const int* cu_seqlens, const int* seq_ids, void* out, int nseq,
+                                    int max_len, int Hq, int Hkv) {
+  if (nseq <= 0 || max_len <= 0) return hipSuccess;
+  if (Hq % Hkv) return hipErrorInvalidValue;
+  float scale_log2 = LOG2E / sqrtf((float)KV_HEAD_DIM);
+  attn_prefill_kernel<<<dim3((max_len + 63) / 64, Hq, nseq), 256, 0, s>>>(
+      (const bf16_t*)q, (const char*)kv_pool_layer, block_table, max_blocks, cu_seqlens, seq_ids, (bf16_t*)out, Hq, Hkv,
+      scale_log2);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_f32(hipStream_t s, const float* q, const float* kv_pool_layer, const int* block_table,
+                           int max_blocks, const int* row_pos, const int* row_seq, float* out, int M, int Hq, int Hkv,
+                           int h) {
+  if (M <= 0) return hipSuccess;
+  dim3 grid(Hq, M);
+  if (h == 32)
+    attn_f32_kernel<32><<<grid, 64, 0, s>>>(q, kv_pool_layer, block_table, max_blocks, row_pos, row_seq, out, Hq, Hkv);
+  else if (h == 64)
+    attn_f32_kernel<64><<<grid, 64, 0, s>>>(q, kv_pool_layer, block_table, max_blocks, row_pos, row_seq, out, Hq, Hkv);
+  else if (h == 128)
+    attn_f32_kernel<128><<<grid, 64, 0, s>>>(q, kv_pool_layer, block_table, max_blocks, row_pos, row_seq, out, Hq, Hkv);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}

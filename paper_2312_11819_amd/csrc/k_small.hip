@@ -1,0 +1,276 @@
+// Small memory-bound kernels of the rollout: token packing, embedding gather, RMSNorm (optionally fused
+// with the reduction of split-K partial sums and the residual add), rotary embedding + KV-cache append,
+// SwiGLU, and the per-step counter update.  All are plain vector-ALU kernels; none is a contraction.
+#include "common.h"
+#include "kernels.h"
+
+__global__ void pack_tokens_kernel(const int* __restrict__ query_tokens, int Lmax, const int* __restrict__ tok_seq,
+                                   const int* __restrict__ tok_pos, int T, int vocab, int* __restrict__ ids_out,
+                                   int* __restrict__ err_flag) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= T) return;
+  int id = query_tokens[(size_t)tok_seq[i] * Lmax + tok_pos[i]];
+  if (id < 0 || id >= vocab) {
+    *err_flag = 1;
+    id = id < 0 ? 0 : vocab - 1;
+  }
+  ids_out[i] = id;
+}
+
+hipError_t launch_pack_tokens(hipStream_t s, const int* query_tokens, int Lmax, const int* tok_seq, const int* tok_pos,
+                              int T, int vocab, int* ids_out, int* err_flag) {
+  if (T <= 0) return hipSuccess;
+  pack_tokens_kernel<<<(T + 255) / 256, 256, 0, s>>>(query_tokens, Lmax, tok_seq, tok_pos, T, vocab, ids_out, err_flag);
+  return hipGetLastError();
+}
+
+template <bool WBF16>
+__global__ __launch_bounds__(256) void embed_kernel(const int* __restrict__ ids, const void* __restrict__ table,
+                                                    float* __restrict__ x, int d, int vocab, int* __restrict__ err_flag) {
+  int m = blockIdx.x;
+  int id = ids[m];
+  if (id < 0 || id >= vocab) {
+    if (threadIdx.x == 0) *err_flag = 1;
+    id = id < 0 ? 0 : vocab - 1;
+  }
+  float* xr = x + (size_t)m * d;
+  if (WBF16) {
+    const bf16_t* row = (const bf16_t*)table + (size_t)id * d;
+    for (int i = threadIdx.x * 4; i < d; i += 1024) {
+      uint2 v = *(const uint2*)(row + i);
+      float4 o;
+      o.x = __uint_as_float(v.x << 16);
+      o.y = __uint_as_float(v.x & 0xffff0000u);
+      o.z = __uint_as_float(v.y << 16);
+      o.w = __uint_as_float(v.y & 0xffff0000u);
+      *(float4*)(xr + i) = o;
+    }
+  } else {
+    const float* row = (const float*)table + (size_t)id * d;
+    for (int i = threadIdx.x * 4; i < d; i += 1024) *(float4*)(xr + i) = *(const float4*)(row + i);
+  }
+}
+
+hipError_t launch_embed(hipStream_t s, const int* ids, const void* table, int w_bf16, float* x, int M, int d, int vocab,
+                        int* err_flag) {
+  if (M <= 0) return hipSuccess;
+  if (w_bf16)
+    embed_kernel<true><<<M, 256, 0, s>>>(ids, table, x, d, vocab, err_flag);
+  else
+    embed_kernel<false><<<M, 256, 0, s>>>(ids, table, x, d, vocab, err_flag);
+  return hipGetLastError();
+}
+
+__device__ __forceinline__ float block_sum_256(float v, float* red) {
+  v = wave_sum(v);
+  int w = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  float t = red[0] + red[1] + red[2] + red[3];
+  __syncthreads();
+  return t;
+}
+
+// One workgroup per row, d <= 8192, d % 4 == 0.  The sum of squares is taken in a fixed order, so the
+// result does not change from run to run.
+template <bool WBF16, bool ABF16>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ part, int nsplit,
+                                                      size_t part_stride, const void* __restrict__ gain,
+                                                      void* __restrict__ y, int d, float eps,
+                                                      const int* __restrict__ rows) {
+  __shared__ float red[4];
+  int m = blockIdx.x;
+  int src = rows ? rows[m] : m;
+  float* xr = x + (size_t)src * d;
+  float4 v[8];
+  float ss = 0.f;
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    int i = (it * 256 + threadIdx.x) * 4;
+    if (i < d) {
+      float4 a = *(const float4*)(xr + i);
+      if (nsplit > 0) {
+        for (int sidx = 0; sidx < nsplit; ++sidx) {
+          float4 p = *(const float4*)(part + sidx * part_stride + (size_t)m * d + i);
+          a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
+        }
+        *(float4*)(xr + i) = a;
+      }
+      v[it] = a;
+      ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+    }
+  }
+  float tot = block_sum_256(ss, red);
+  float r = rsqrtf(tot / (float)d + eps);
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    int i = (it * 256 + threadIdx.x) * 4;
+    if (i < d) {
+      float g0, g1, g2, g3;
+      if (WBF16) {
+        uint2 g = *(const uint2*)((const bf16_t*)gain + i);
+        g0 = __uint_as_float(g.x << 16); g1 = __uint_as_float(g.x & 0xffff0000u);
+        g2 = __uint_as_float(g.y << 16); g3 = __uint_as_float(g.y & 0xffff0000u);
+      } else {
+        float4 g = *(const float4*)((const float*)gain + i);
+        g0 = g.x; g1 = g.y; g2 = g.z; g3 = g.w;
+      }
+      float4 a = v[it];
+      float o0 = a.x * r * g0, o1 = a.y * r * g1, o2 = a.z * r * g2, o3 = a.w * r * g3;
+      if (ABF16) {
+        uint2 o;
+        o.x = pack_bf16x2(o0, o1);
+        o.y = pack_bf16x2(o2, o3);
+        *(uint2*)((bf16_t*)y + (size_t)m * d + i) = o;
+      } else {
+        *(float4*)((float*)y + (size_t)m * d + i) = make_float4(o0, o1, o2, o3);
+      }
+    }
+  }
+}
+
+hipError_t launch_rmsnorm(hipStream_t s, float* x, const float* part, int nsplit, size_t part_stride, const void* gain,
+                          int w_bf16, void* y, int act_bf16, int M, int d, float eps, const int* rows) {
+  if (M <= 0) return hipSuccess;
+  if (d > 8192 || (d & 3)) return hipErrorInvalidValue;
+  if (!part) nsplit = 0;
+  if (w_bf16 && act_bf16)
+    rmsnorm_kernel<true, true><<<M, 256, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
+  else if (!w_bf16 && !act_bf16)
+    rmsnorm_kernel<false, false><<<M, 256, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+// One workgroup per token row.  The rotation pairs dimension i with i + h/2 and uses the cos/sin tables
+// built on the host in double precision (cos_t[pos * h/2 + i]).  bf16 path: h = 128, keys and values go to
+// the MFMA-ordered page described in common.h.  fp32 path: page = [2][16][h] floats (keys, then values).
+template <bool ABF16>
+__global__ __launch_bounds__(256) void rope_append_kernel(const float* __restrict__ qkv, const float* __restrict__ part,
+                                                          int nsplit, size_t part_stride,
+                                                          const int* __restrict__ row_pos,
+                                                          const int* __restrict__ row_seq,
+                                                          const float* __restrict__ cos_t,
+                                                          const float* __restrict__ sin_t, void* __restrict__ q_out,
+                                                          void* __restrict__ pool, const int* __restrict__ block_table,
+                                                          int max_blocks, int Hq, int Hkv, int h) {
+  int m = blockIdx.x;
+  int pos = row_pos[m];
+  int b = row_seq ? row_seq[m] : m;
+  int half = h >> 1;
+  int width = (Hq + 2 * Hkv) * h;
+  const float* row = qkv + (size_t)m * width;
+  const float* cs = cos_t + (size_t)pos * half;
+  const float* sn = sin_t + (size_t)pos * half;
+  int blk = block_table[(size_t)b * max_blocks + (pos >> 4)];
+  int slot = pos & 15;
+  int npair = (Hq + Hkv) * half;
+  for (int p = threadIdx.x; p < npair; p += 256) {
+    int head = p / half, i = p - head * half;
+    int c0 = head * h + i, c1 = c0 + half;
+    float a = row[c0], bb = row[c1];
+    for (int sidx = 0; sidx < nsplit; ++sidx) {
+      const float* pr = part + sidx * part_stride + (size_t)m * width;
+      a += pr[c0];
+      bb += pr[c1];
+    }
+    float c = cs[i], sv = sn[i];
+    float r0 = a * c - bb * sv, r1 = bb * c + a * sv;
+    if (head < Hq) {
+      if (ABF16) {
+        bf16_t* qo = (bf16_t*)q_out + (size_t)m * Hq * h + head * h;
+        qo[i] = f32_to_bf16(r0);
+        qo[i + half] = f32_to_bf16(r1);
+      } else {
+        float* qo = (float*)q_out + (size_t)m * Hq * h + head * h;
+        qo[i] = r0;
+        qo[i + half] = r1;
+      }
+    } else {
+      int kvh = head - Hq;
+      if (ABF16) {
+        char* page = (char*)pool + ((size_t)blk * Hkv + kvh) * KV_PAGE_BYTES;
+        *(bf16_t*)(page + kpage_offset(slot, i)) = f32_to_bf16(r0);
+        *(bf16_t*)(page + kpage_offset(slot, i + half)) = f32_to_bf16(r1);
+      } else {
+        float* page = (float*)pool + ((size_t)blk * Hkv + kvh) * (2 * 16 * h);
+        page[slot * h + i] = r0;
+        page[slot * h + i + half] = r1;
+      }
+    }
+  }
+  int nv = Hkv * h;
+  const float* vrow = row + (Hq + Hkv) * h;
+  for (int p = threadIdx.x; p < nv; p += 256) {
+    int kvh = p / h, dim = p - kvh * h;
+    float v = vrow[p];
+    for (int sidx = 0; sidx < nsplit; ++sidx) v += part[sidx * part_stride + (size_t)m * width + (Hq + Hkv) * h + p];
+    if (ABF16) {
+      char* page = (char*)pool + ((size_t)blk * Hkv + kvh) * KV_PAGE_BYTES;
+      *(bf16_t*)(page + vpage_offset(slot, dim)) = f32_to_bf16(v);
+    } else {
+      float* page = (float*)pool + ((size_t)blk * Hkv + kvh) * (2 * 16 * h);
+      page[16 * h + slot * h + dim] = v;
+    }
+  }
+}
+
+hipError_t launch_rope_append(hipStream_t s, const float* qkv, const float* part, int nsplit, size_t part_stride,
+                              const int* row_pos, const int* row_seq, const float* cos_t, const float* sin_t,
+                              void* q_out, void* kv_pool_layer, const int* block_table, int max_blocks, int M, int Hq,
+                              int Hkv, int h, int act_bf16) {
+  if (M <= 0) return hipSuccess;
+  if (!part) nsplit = 0;
+  if (act_bf16) {
+    if (h != KV_HEAD_DIM) return hipErrorInvalidValue;
+    rope_append_kernel<true><<<M, 256, 0, s>>>(qkv, part, nsplit, part_stride, row_pos, row_seq, cos_t, sin_t, q_out,
+                                               kv_pool_layer, block_table, max_blocks, Hq, Hkv, h);
+  } else {
+    rope_append_kernel<false><<<M, 256, 0, s>>>(qkv, part, nsplit, part_stride, row_pos, row_seq, cos_t, sin_t, q_out,
+                                                kv_pool_layer, block_table, max_blocks, Hq, Hkv, h);
+  }
+  return hipGetLastError();
+}
+
+template <bool ABF16>
+__global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ gu, int nsplit, size_t part_stride,
+                                                     void* __restrict__ h_out, int F) {
+  int m = blockIdx.y;
+  int f = blockIdx.x * 256 + threadIdx.x;
+  if (f >= F) return;
+  const float* row = gu + (size_t)m * 2 * F;
+  float g = row[f], u = row[F + f];
+  for (int sidx = 1; sidx < nsplit; ++sidx) {
+    g += row[sidx * part_stride + f];
+    u += row[sidx * part_stride + F + f];
+  }
+  float v = g / (1.f + __expf(-g)) * u;
+  if (ABF16)
+    ((bf16_t*)h_out)[(size_t)m * F + f] = f32_to_bf16(v);
+  else
+    ((float*)h_out)[(size_t)m * F + f] = v;
+}
+
+hipError_t launch_swiglu(hipStream_t s, const float* gu, int nsplit, size_t part_stride, void* h_out, int act_bf16,
+                         int M, int F) {
+  if (M <= 0) return hipSuccess;
+  dim3 grid((F + 255) / 256, M);
+  if (nsplit < 1) nsplit = 1;
+  if (act_bf16)
+    swiglu_kernel<true><<<grid, 256, 0, s>>>(gu, nsplit, part_stride, h_out, F);
+  else
+    swiglu_kernel<false><<<grid, 256, 0, s>>>(gu, nsplit, part_stride, h_out, F);
+  return hipGetLastError();
+}
+
+__global__ void advance_kernel(int* seq_len, int* step, int B) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < B) seq_len[i] += 1;
+  if (i == 0) *step += 1;
+}
+
+hipError_t launch_advance(hipStream_t s, int* seq_len, int* step, int B) {
+  advance_kernel<<<(B + 255) / 256, 256, 0, s>>>(seq_len, step, B);
+  return hipGetLastError();
+}

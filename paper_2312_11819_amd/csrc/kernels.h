@@ -1,0 +1,67 @@
+// Host-callable launchers of the gfx950 kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+enum GemmEpilogue {
+  EPI_STORE_F32 = 0,   // out fp32 [M, N] = acc
+  EPI_RESID_F32 = 1,   // out fp32 [M, N] += acc
+  EPI_SWIGLU = 2,      // W is [2F, K] (gate rows then up rows), N = F: out [M, F] = silu(gate) * up
+  EPI_STORE_ACT = 3    // out [M, N] in the activation type (bf16 on the MFMA path)
+};
+
+// ---- bf16 MFMA path ----
+// Large-tile GEMM: out = A[M,K] (bf16) * W[N,K]^T (bf16).  Needs N % 256 == 0 (F % 128 == 0 for SWIGLU),
+// K % 64 == 0; rows of A beyond M are never read.
+hipError_t launch_gemm_bf16(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K, int epi);
+// Weight-streaming GEMM for M <= 256 rows: writes fp32 partial sums part[ks][M][Nw] (Nw = rows of W)
+// for ks < nsplit; the consumer kernel adds them.  Returns the nsplit it used through *nsplit_out.
+hipError_t launch_gemm_skinny_bf16(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K,
+                                   int nsplit);
+int gemm_skinny_pick_split(int M, int Nw, int K);
+// Per-device one-time kernel attribute setup; call before the first launch and outside any stream capture.
+hipError_t gemm_configure();
+
+// ---- elementwise / small kernels (act_bf16: activations are bf16, else fp32) ----
+hipError_t launch_pack_tokens(hipStream_t s, const int* query_tokens, int Lmax, const int* tok_seq, const int* tok_pos,
+                              int T, int vocab, int* ids_out, int* err_flag);
+hipError_t launch_embed(hipStream_t s, const int* ids, const void* table, int w_bf16, float* x, int M, int d, int vocab,
+                        int* err_flag);
+// x[m] += sum_{s<nsplit} part[s][m][:] (if part), then y = rmsnorm(x) * gain.  rows[m] (optional) selects
+// source rows of x (gather); then x is not updated.
+hipError_t launch_rmsnorm(hipStream_t s, float* x, const float* part, int nsplit, size_t part_stride,
+                          const void* gain, int w_bf16, void* y, int act_bf16, int M, int d, float eps, const int* rows);
+// qkv fp32 [M, (Hq+2Hkv)h] (+ optional partial sums) -> rotated q (activation type) and the paged KV cache.
+hipError_t launch_rope_append(hipStream_t s, const float* qkv, const float* part, int nsplit, size_t part_stride,
+                              const int* row_pos, const int* row_seq, const float* cos_t, const float* sin_t,
+                              void* q_out, void* kv_pool_layer, const int* block_table, int max_blocks, int M, int Hq,
+                              int Hkv, int h, int act_bf16);
+// h[m][f] = silu(sum gate) * (sum up) from fp32 [M, 2F] (+ partial sums).
+hipError_t launch_swiglu(hipStream_t s, const float* gu, int nsplit, size_t part_stride, void* h_out, int act_bf16,
+                         int M, int F);
+hipError_t launch_advance(hipStream_t s, int* seq_len, int* step, int B);
+
+// ---- attention over the paged cache ----
+hipError_t launch_attn_decode_bf16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
+                                   int max_blocks, const int* seq_len, void* out, int B, int Hq, int Hkv);
+hipError_t launch_attn_prefill_bf16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
+                                    int max_blocks, const int* cu_seqlens, const int* seq_ids, void* out, int nseq,
+                                    int max_len, int Hq, int Hkv);
+// fp32 path: one wavefront per (row, query head); row_pos[m] = position of the row's token.
+hipError_t launch_attn_f32(hipStream_t s, const float* q, const float* kv_pool_layer, const int* block_table,
+                           int max_blocks, const int* row_pos, const int* row_seq, float* out, int M, int Hq, int Hkv,
+                           int h);
+
+// ---- fp32 GEMM (plain ALU) ----
+hipError_t launch_gemm_f32(hipStream_t s, const float* A, const float* W, float* out, int M, int N, int K, int accumulate);
+
+// ---- sampler ----
+struct SamplerParams {
+  float temperature, top_p;
+  uint64_t seed;
+  int greedy, logprob_mode;
+};
+// One workgroup per row of logits [B, V].  Response index t = *step_ptr + step_add; results go to
+// tok_out[b*out_stride + col], col = use_step_col ? t : 0; cur_tok[b] receives the token too.
+hipError_t launch_sampler(hipStream_t s, const float* logits, int B, int V, SamplerParams p, const int* step_ptr,
+                          int out_stride, int use_step_col, int* tok_out, float* lp_out, int* cur_tok);

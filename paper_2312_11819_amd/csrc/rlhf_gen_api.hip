@@ -1,0 +1,791 @@
+// Host side of the library: context, argument checks, KV page allocator, and the sequencing of the
+// kernels for prefill and decode (Actor.generate of Alg. 1 / ShadowActor.generate of Alg. 2).
+// Everything numerical happens in the kernels; this file only decides what to launch.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <string>
+#include <vector>
+
+#include "../../include/rlhf_gen.h"
+#include "../../include/rlhf_gen_ops.h"
+#include "kernels.h"
+
+namespace {
+
+std::string g_init_error;
+
+struct GraphKey {
+  int B = 0, stride = 0, use_col = 0;
+  const void* tok = nullptr;
+  const void* lp = nullptr;
+  SamplerParams sp{};
+  bool operator==(const GraphKey& o) const {
+    return B == o.B && stride == o.stride && use_col == o.use_col && tok == o.tok && lp == o.lp &&
+           memcmp(&sp, &o.sp, sizeof(sp)) == 0;
+  }
+};
+
+}  // namespace
+
+struct rlhf_gen_ctx {
+  rlhf_gen_cfg cfg{};
+  bool bf16 = false;
+  hipStream_t stream = nullptr;
+  bool own_stream = false;
+  const void *tok_emb = nullptr, *lm_head = nullptr, *final_norm = nullptr;
+  std::vector<const void*> attn_norm, wqkv, wo, ffn_norm, w_gate_up, w_down;
+
+  // device memory owned by the context
+  std::vector<void*> allocs;
+  char* kv_pool = nullptr;
+  size_t layer_pool_bytes = 0;
+  int n_blocks = 0, max_blocks = 0;
+  int *d_table = nullptr, *d_seq_len = nullptr, *d_step = nullptr, *d_err = nullptr, *d_cur_tok = nullptr;
+  float *d_cos = nullptr, *d_sin = nullptr;
+  int *d_tok_seq = nullptr, *d_tok_pos = nullptr, *d_ids = nullptr, *d_cu = nullptr, *d_seq_ids = nullptr,
+      *d_last_rows = nullptr;
+  int act_rows = 0;  // row capacity of the activation buffers
+  float *x = nullptr, *qkv = nullptr, *logits = nullptr, *part = nullptr;
+  void *y = nullptr, *yl = nullptr, *qb = nullptr, *ab = nullptr, *hb = nullptr;
+  int ks_qkv = 1, ks_wo = 1, ks_gu = 1, ks_down = 1;
+
+  // pinned host staging
+  int *h_tok_seq = nullptr, *h_tok_pos = nullptr, *h_cu = nullptr, *h_seq_ids = nullptr, *h_last_rows = nullptr,
+      *h_table = nullptr, *h_lenbuf = nullptr, *h_misc = nullptr;
+
+  // host state
+  std::vector<int> h_len, n_alloc, free_list;
+  int B = 0;
+  bool have_batch = false, have_logits = false;
+  int h_step = 0;
+  int reserve_extra = 0;  // tokens beyond the query that prefill must reserve pages for
+  SamplerParams sp{};
+  std::string err;
+
+  hipGraphExec_t graph_exec = nullptr;
+  GraphKey graph_key;
+  hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+  float prefill_ms = 0.f, decode_ms = 0.f;
+  int decode_steps = 0;
+};
+
+namespace {
+
+int fail(rlhf_gen_ctx* c, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (c) c->err = buf; else g_init_error = buf;
+  return code;
+}
+
+#define HIP_TRY(c, call)                                                                                 \
+  do {                                                                                                   \
+    hipError_t e_ = (call);                                                                              \
+    if (e_ != hipSuccess) return fail(c, RLHF_GEN_E_DEVICE, "%s failed: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+template <typename T>
+int dev_alloc(rlhf_gen_ctx* c, T** p, size_t bytes, bool zero) {
+  void* q = nullptr;
+  if (bytes == 0) bytes = 16;
+  hipError_t e = hipMalloc(&q, bytes);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(c, RLHF_GEN_E_NOMEM, "hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+  }
+  c->allocs.push_back(q);
+  if (zero) HIP_TRY(c, hipMemset(q, 0, bytes));
+  *p = (T*)q;
+  return RLHF_GEN_OK;
+}
+
+template <typename T>
+int host_alloc(rlhf_gen_ctx* c, T** p, size_t bytes) {
+  void* q = nullptr;
+  HIP_TRY(c, hipHostMalloc(&q, bytes ? bytes : 16, hipHostMallocDefault));
+  memset(q, 0, bytes ? bytes : 16);
+  *p = (T*)q;
+  return RLHF_GEN_OK;
+}
+
+size_t act_size(const rlhf_gen_ctx* c) { return c->bf16 ? 2 : 4; }
+
+void reset_free_list(rlhf_gen_ctx* c) {
+  c->free_list.resize(c->n_blocks);
+  // popped from the back: block 0 first unless shuffled
+  for (int i = 0; i < c->n_blocks; ++i) c->free_list[i] = c->n_blocks - 1 - i;
+  if (c->cfg.flags & RLHF_GEN_FLAG_SHUFFLE_BLOCKS) {
+    uint64_t s = 0x2545F4914F6CDD1Dull;
+    for (int i = c->n_blocks - 1; i > 0; --i) {
+      s ^= s << 13; s ^= s >> 7; s ^= s << 17;
+      int j = (int)(s % (uint64_t)(i + 1));
+      std::swap(c->free_list[i], c->free_list[j]);
+    }
+  }
+  std::fill(c->n_alloc.begin(), c->n_alloc.end(), 0);
+}
+
+int blocks_for(int tokens) { return (tokens + 15) / 16; }
+
+// Give sequence b enough pages for `tokens` cached tokens.  Returns true if the table changed.
+bool grow_seq(rlhf_gen_ctx* c, int b, int tokens) {
+  bool changed = false;
+  while (c->n_alloc[b] * 16 < tokens) {
+    int blk = c->free_list.back();
+    c->free_list.pop_back();
+    c->h_table[(size_t)b * c->max_blocks + c->n_alloc[b]] = blk;
+    c->n_alloc[b]++;
+    changed = true;
+  }
+  return changed;
+}
+
+int check_launch(rlhf_gen_ctx* c, hipError_t e, const char* what) {
+  if (e != hipSuccess) return fail(c, RLHF_GEN_E_DEVICE, "launch of %s failed: %s", what, hipGetErrorString(e));
+  return RLHF_GEN_OK;
+}
+#define LAUNCH(c, call, what)                        \
+  do {                                               \
+    int r_ = check_launch(c, (call), what);          \
+    if (r_ != RLHF_GEN_OK) return r_;                \
+  } while (0)
+
+struct RowSet {
+  int M = 0;
+  const int* ids = nullptr;      // device [M] token ids
+  const int* row_pos = nullptr;  // device [M] position of each row's token
+  const int* row_seq = nullptr;  // device [M] batch row, or NULL for identity
+  // prefill only
+  bool prefill = false;
+  const int* cu = nullptr;       // device [nseq + 1] chunk-local row offsets
+  const int* seq_ids = nullptr;  // device [nseq]
+  int nseq = 0, max_len = 0;
+};
+
+int gemm_any(rlhf_gen_ctx* c, const void* A, const void* W, void* out, int M, int N, int K, int epi) {
+  if (c->bf16) {
+    LAUNCH(c, launch_gemm_bf16(c->stream, A, W, out, M, N, K, epi), "gemm_bf16");
+  } else {
+    if (epi == EPI_SWIGLU) return fail(c, RLHF_GEN_E_UNSUPPORTED, "no fused SwiGLU on the fp32 path");
+    LAUNCH(c, launch_gemm_f32(c->stream, (const float*)A, (const float*)W, (float*)out, M, N, K, epi == EPI_RESID_F32),
+           "gemm_f32");
+  }
+  return RLHF_GEN_OK;
+}
+
+// All layers for a set of token rows, activations in x/y/...; leaves the residual stream in c->x.
+int forward_layers_generic(rlhf_gen_ctx* c, const RowSet& r) {
+  const rlhf_gen_cfg& g = c->cfg;
+  const int d = g.d_model, Hq = g.n_heads, Hkv = g.n_kv_heads, h = g.head_dim, F = g.d_ffn;
+  const int qkv_w = (Hq + 2 * Hkv) * h;
+  hipStream_t s = c->stream;
+  LAUNCH(c, launch_embed(s, r.ids, c->tok_emb, c->bf16, c->x, r.M, d, g.vocab, c->d_err), "embed");
+  for (int l = 0; l < g.n_layers; ++l) {
+    char* pool = c->kv_pool + (size_t)l * c->layer_pool_bytes;
+    LAUNCH(c, launch_rmsnorm(s, c->x, nullptr, 0, 0, c->attn_norm[l], c->bf16, c->y, c->bf16, r.M, d, g.rms_eps, nullptr),
+           "rmsnorm");
+    int rc = gemm_any(c, c->y, c->wqkv[l], c->qkv, r.M, qkv_w, d, EPI_STORE_F32);
+    if (rc) return rc;
+    LAUNCH(c, launch_rope_append(s, c->qkv, nullptr, 0, 0, r.row_pos, r.row_seq, c->d_cos, c->d_sin, c->qb, pool,
+                                 c->d_table, c->max_blocks, r.M, Hq, Hkv, h, c->bf16), "rope_append");
+    if (!c->bf16) {
+      LAUNCH(c, launch_attn_f32(s, (const float*)c->qb, (const float*)pool, c->d_table, c->max_blocks, r.row_pos,
+                                r.row_seq, (float*)c->ab, r.M, Hq, Hkv, h), "attn_f32");
+    } else if (r.prefill) {
+      LAUNCH(c, launch_attn_prefill_bf16(s, c->qb, pool, c->d_table, c->max_blocks, r.cu, r.seq_ids, c->ab, r.nseq,
+                                         r.max_len, Hq, Hkv), "attn_prefill");
+    } else {
+      LAUNCH(c, launch_attn_decode_bf16(s, c->qb, pool, c->d_table, c->max_blocks, c->d_seq_len, c->ab, r.M, Hq, Hkv),
+             "attn_decode");
+    }
+    rc = gemm_any(c, c->ab, c->wo[l], c->x, r.M, d, Hq * h, EPI_RESID_F32);
+    if (rc) return rc;
+    LAUNCH(c, launch_rmsnorm(s, c->x, nullptr, 0, 0, c->ffn_norm[l], c->bf16, c->y, c->bf16, r.M, d, g.rms_eps, nullptr),
+           "rmsnorm");
+    if (c->bf16) {
+      rc = gemm_any(c, c->y, c->w_gate_up[l], c->hb, r.M, F, d, EPI_SWIGLU);
+      if (rc) return rc;
+    } else {
+      rc = gemm_any(c, c->y, c->w_gate_up[l], c->qkv, r.M, 2 * F, d, EPI_STORE_F32);
+      if (rc) return rc;
+      LAUNCH(c, launch_swiglu(s, c->qkv, 1, 0, c->hb, 0, r.M, F), "swiglu");
+    }
+    rc = gemm_any(c, c->hb, c->w_down[l], c->x, r.M, d, F, EPI_RESID_F32);
+    if (rc) return rc;
+  }
+  return RLHF_GEN_OK;
+}
+
+// Decode step on the weight-streaming GEMM: every projection writes split-K partial sums, and the next
+// small kernel (RoPE+append, RMSNorm+residual, SwiGLU) adds them up while doing its own work.
+int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
+  const rlhf_gen_cfg& g = c->cfg;
+  const int d = g.d_model, Hq = g.n_heads, Hkv = g.n_kv_heads, h = g.head_dim, F = g.d_ffn;
+  const int qkv_w = (Hq + 2 * Hkv) * h;
+  hipStream_t s = c->stream;
+  LAUNCH(c, launch_embed(s, c->d_cur_tok, c->tok_emb, 1, c->x, B, d, g.vocab, c->d_err), "embed");
+  int pending = 0;  // split count of the down-projection partial sums not yet added to x
+  for (int l = 0; l < g.n_layers; ++l) {
+    char* pool = c->kv_pool + (size_t)l * c->layer_pool_bytes;
+    LAUNCH(c, launch_rmsnorm(s, c->x, pending ? c->part : nullptr, pending, (size_t)B * d, c->attn_norm[l], 1, c->y, 1,
+                             B, d, g.rms_eps, nullptr), "rmsnorm");
+    LAUNCH(c, launch_gemm_skinny_bf16(s, c->y, c->wqkv[l], c->part, B, qkv_w, d, c->ks_qkv), "gemm_skinny qkv");
+    size_t st = (size_t)B * qkv_w;
+    LAUNCH(c, launch_rope_append(s, c->part, c->ks_qkv > 1 ? c->part + st : nullptr, c->ks_qkv - 1, st, c->d_seq_len,
+                                 nullptr, c->d_cos, c->d_sin, c->qb, pool, c->d_table, c->max_blocks, B, Hq, Hkv, h, 1),
+           "rope_append");
+    LAUNCH(c, launch_attn_decode_bf16(s, c->qb, pool, c->d_table, c->max_blocks, c->d_seq_len, c->ab, B, Hq, Hkv),
+           "attn_decode");
+    LAUNCH(c, launch_gemm_skinny_bf16(s, c->ab, c->wo[l], c->part, B, d, Hq * h, c->ks_wo), "gemm_skinny wo");
+    LAUNCH(c, launch_rmsnorm(s, c->x, c->part, c->ks_wo, (size_t)B * d, c->ffn_norm[l], 1, c->y, 1, B, d, g.rms_eps,
+                             nullptr), "rmsnorm");
+    LAUNCH(c, launch_gemm_skinny_bf16(s, c->y, c->w_gate_up[l], c->part, B, 2 * F, d, c->ks_gu), "gemm_skinny gate_up");
+    LAUNCH(c, launch_swiglu(s, c->part, c->ks_gu, (size_t)B * 2 * F, c->hb, 1, B, F), "swiglu");
+    LAUNCH(c, launch_gemm_skinny_bf16(s, c->hb, c->w_down[l], c->part, B, d, F, c->ks_down), "gemm_skinny down");
+    pending = c->ks_down;
+  }
+  LAUNCH(c, launch_rmsnorm(s, c->x, pending ? c->part : nullptr, pending, (size_t)B * d, c->final_norm, 1, c->yl, 1, B,
+                           d, g.rms_eps, nullptr), "final rmsnorm");
+  LAUNCH(c, launch_gemm_skinny_bf16(s, c->yl, c->lm_head, c->logits, B, g.vocab, d, 1), "gemm_skinny lm_head");
+  return RLHF_GEN_OK;
+}
+
+bool use_streaming(const rlhf_gen_ctx* c, int B) {
+  return c->bf16 && !(c->cfg.flags & RLHF_GEN_FLAG_GENERIC_GEMM) && B <= 256;
+}
+
+// Kernels of one decode step, in order, ending with the sampler and the counter update.
+int enqueue_decode_body(rlhf_gen_ctx* c, int* tok_out, float* lp_out, int stride, int use_col) {
+  const rlhf_gen_cfg& g = c->cfg;
+  const int B = c->B;
+  int rc;
+  if (use_streaming(c, B)) {
+    rc = forward_decode_streaming(c, B);
+    if (rc) return rc;
+  } else {
+    RowSet r;
+    r.M = B;
+    r.ids = c->d_cur_tok;
+    r.row_pos = c->d_seq_len;
+    rc = forward_layers_generic(c, r);
+    if (rc) return rc;
+    LAUNCH(c, launch_rmsnorm(c->stream, c->x, nullptr, 0, 0, c->final_norm, c->bf16, c->yl, c->bf16, B, g.d_model,
+                             g.rms_eps, nullptr), "final rmsnorm");
+    rc = gemm_any(c, c->yl, c->lm_head, c->logits, B, g.vocab, g.d_model, EPI_STORE_F32);
+    if (rc) return rc;
+  }
+  LAUNCH(c, launch_sampler(c->stream, c->logits, B, g.vocab, c->sp, c->d_step, stride, use_col, tok_out, lp_out,
+                           c->d_cur_tok), "sampler");
+  LAUNCH(c, launch_advance(c->stream, c->d_seq_len, c->d_step, B), "advance");
+  return RLHF_GEN_OK;
+}
+
+int check_sampling(rlhf_gen_ctx* c, const rlhf_gen_sampling* sp) {
+  if (!sp) return fail(c, RLHF_GEN_E_INVALID, "sampling is NULL");
+  if (!sp->greedy) {
+    if (!(sp->temperature > 0.f) || !isfinite(sp->temperature))
+      return fail(c, RLHF_GEN_E_INVALID, "temperature must be a positive finite number (got %g)", sp->temperature);
+    if (!(sp->top_p > 0.f)) return fail(c, RLHF_GEN_E_INVALID, "top_p must be positive (got %g)", sp->top_p);
+  }
+  if (sp->logprob_mode != 0 && sp->logprob_mode != 1)
+    return fail(c, RLHF_GEN_E_INVALID, "logprob_mode must be 0 or 1 (got %d)", sp->logprob_mode);
+  return RLHF_GEN_OK;
+}
+
+int prefill_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* lengths, int32_t B, int32_t Lmax,
+                 const rlhf_gen_sampling* sampling, int32_t* tok_out, float* lp_out, int out_stride) {
+  const rlhf_gen_cfg& g = c->cfg;
+  if (!query_tokens || !lengths || !tok_out || !lp_out) return fail(c, RLHF_GEN_E_INVALID, "NULL pointer argument");
+  int rc = check_sampling(c, sampling);
+  if (rc) return rc;
+  if (B < 1 || B > g.max_batch) return fail(c, RLHF_GEN_E_INVALID, "B = %d outside [1, max_batch = %d]", B, g.max_batch);
+  if (Lmax < 1) return fail(c, RLHF_GEN_E_INVALID, "Lmax = %d must be positive", Lmax);
+  long need_blocks = 0;
+  for (int b = 0; b < B; ++b) {
+    if (lengths[b] < 1 || lengths[b] > Lmax)
+      return fail(c, RLHF_GEN_E_INVALID, "lengths[%d] = %d outside [1, Lmax = %d]", b, lengths[b], Lmax);
+    if (lengths[b] + 1 + c->reserve_extra > g.max_seq + 1)
+      return fail(c, RLHF_GEN_E_INVALID, "sequence %d: %d query + %d further tokens exceed max_seq = %d", b, lengths[b],
+                  c->reserve_extra, g.max_seq);
+    need_blocks += blocks_for(lengths[b] + c->reserve_extra);
+  }
+  if (need_blocks > c->n_blocks)
+    return fail(c, RLHF_GEN_E_NOMEM, "KV pool has %d pages, the batch needs %ld", c->n_blocks, need_blocks);
+
+  HIP_TRY(c, hipSetDevice(g.device));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));  // staging buffers are free again
+  c->have_batch = false;
+  c->have_logits = false;
+  c->B = B;
+  c->sp.temperature = sampling->temperature;
+  c->sp.top_p = sampling->top_p;
+  c->sp.seed = sampling->seed;
+  c->sp.greedy = sampling->greedy;
+  c->sp.logprob_mode = sampling->logprob_mode;
+  reset_free_list(c);
+  int T = 0;
+  for (int b = 0; b < B; ++b) {
+    c->h_len[b] = lengths[b];
+    grow_seq(c, b, lengths[b] + c->reserve_extra);
+    for (int p = 0; p < lengths[b]; ++p) {
+      c->h_tok_seq[T] = b;
+      c->h_tok_pos[T] = p;
+      ++T;
+    }
+    c->h_lenbuf[b] = lengths[b];
+    c->h_seq_ids[b] = b;
+  }
+  hipStream_t s = c->stream;
+  HIP_TRY(c, hipMemcpyAsync(c->d_table, c->h_table, sizeof(int) * (size_t)g.max_batch * c->max_blocks,
+                            hipMemcpyHostToDevice, s));
+  HIP_TRY(c, hipMemcpyAsync(c->d_tok_seq, c->h_tok_seq, sizeof(int) * T, hipMemcpyHostToDevice, s));
+  HIP_TRY(c, hipMemcpyAsync(c->d_tok_pos, c->h_tok_pos, sizeof(int) * T, hipMemcpyHostToDevice, s));
+  HIP_TRY(c, hipMemcpyAsync(c->d_seq_len, c->h_lenbuf, sizeof(int) * B, hipMemcpyHostToDevice, s));
+  HIP_TRY(c, hipMemcpyAsync(c->d_seq_ids, c->h_seq_ids, sizeof(int) * B, hipMemcpyHostToDevice, s));
+  c->h_misc[0] = 0;
+  c->h_misc[1] = 1;
+  HIP_TRY(c, hipMemcpyAsync(c->d_err, &c->h_misc[0], sizeof(int), hipMemcpyHostToDevice, s));
+  HIP_TRY(c, hipMemcpyAsync(c->d_step, &c->h_misc[0], sizeof(int), hipMemcpyHostToDevice, s));
+  LAUNCH(c, launch_pack_tokens(s, query_tokens, Lmax, c->d_tok_seq, c->d_tok_pos, T, g.vocab, c->d_ids, c->d_err),
+         "pack_tokens");
+  HIP_TRY(c, hipMemcpyAsync(&c->h_misc[2], c->d_err, sizeof(int), hipMemcpyDeviceToHost, s));
+  HIP_TRY(c, hipStreamSynchronize(s));
+  if (c->h_misc[2]) return fail(c, RLHF_GEN_E_INVALID, "a query token id lies outside [0, vocab = %d)", g.vocab);
+
+  // chunks of whole sequences that fit the activation buffers
+  std::vector<int> chunk_begin;
+  {
+    int rows = 0;
+    chunk_begin.push_back(0);
+    for (int b = 0; b < B; ++b) {
+      if (rows + lengths[b] > c->act_rows) {
+        chunk_begin.push_back(b);
+        rows = 0;
+      }
+      rows += lengths[b];
+    }
+    chunk_begin.push_back(B);
+  }
+  // chunk-local row offsets and last-token rows, all chunks at once
+  int cu_fill = 0;
+  std::vector<int> cu_at(chunk_begin.size() - 1);
+  for (size_t ci = 0; ci + 1 < chunk_begin.size(); ++ci) {
+    cu_at[ci] = cu_fill;
+    int rows = 0;
+    c->h_cu[cu_fill++] = 0;
+    for (int b = chunk_begin[ci]; b < chunk_begin[ci + 1]; ++b) {
+      rows += lengths[b];
+      c->h_cu[cu_fill++] = rows;
+      c->h_last_rows[b] = rows - 1;
+    }
+  }
+  HIP_TRY(c, hipMemcpyAsync(c->d_cu, c->h_cu, sizeof(int) * cu_fill, hipMemcpyHostToDevice, s));
+  HIP_TRY(c, hipMemcpyAsync(c->d_last_rows, c->h_last_rows, sizeof(int) * B, hipMemcpyHostToDevice, s));
+
+  int row0 = 0;
+  for (size_t ci = 0; ci + 1 < chunk_begin.size(); ++ci) {
+    int b0 = chunk_begin[ci], b1 = chunk_begin[ci + 1];
+    RowSet r;
+    r.prefill = true;
+    r.nseq = b1 - b0;
+    r.M = 0;
+    r.max_len = 0;
+    for (int b = b0; b < b1; ++b) {
+      r.M += lengths[b];
+      r.max_len = std::max(r.max_len, (int)lengths[b]);
+    }
+    r.ids = c->d_ids + row0;
+    r.row_pos = c->d_tok_pos + row0;
+    r.row_seq = c->d_tok_seq + row0;
+    r.cu = c->d_cu + cu_at[ci];
+    r.seq_ids = c->d_seq_ids + b0;
+    rc = forward_layers_generic(c, r);
+    if (rc) return rc;
+    // final norm of each sequence's last row, gathered into rows b0..b1 of yl
+    LAUNCH(c, launch_rmsnorm(s, c->x, nullptr, 0, 0, c->final_norm, c->bf16,
+                             (char*)c->yl + (size_t)b0 * g.d_model * act_size(c), c->bf16, r.nseq, g.d_model, g.rms_eps,
+                             c->d_last_rows + b0), "final rmsnorm");
+    row0 += r.M;
+  }
+  rc = gemm_any(c, c->yl, c->lm_head, c->logits, B, g.vocab, g.d_model, EPI_STORE_F32);
+  if (rc) return rc;
+  LAUNCH(c, launch_sampler(s, c->logits, B, g.vocab, c->sp, c->d_step, out_stride, 1, tok_out, lp_out, c->d_cur_tok),
+         "sampler");
+  HIP_TRY(c, hipMemcpyAsync(c->d_step, &c->h_misc[1], sizeof(int), hipMemcpyHostToDevice, s));
+  c->h_step = 1;
+  c->have_batch = true;
+  c->have_logits = true;
+  return RLHF_GEN_OK;
+}
+
+int decode_checks(rlhf_gen_ctx* c) {
+  if (!c->have_batch) return fail(c, RLHF_GEN_E_STATE, "decode_step before a successful prefill");
+  long need = 0;
+  for (int b = 0; b < c->B; ++b) {
+    if (c->h_len[b] + 1 > c->cfg.max_seq)
+      return fail(c, RLHF_GEN_E_STATE, "sequence %d already holds %d tokens (max_seq = %d)", b, c->h_len[b], c->cfg.max_seq);
+    if (c->n_alloc[b] * 16 < c->h_len[b] + 1) need++;
+  }
+  if (need > (long)c->free_list.size())
+    return fail(c, RLHF_GEN_E_NOMEM, "KV pool exhausted: %ld more pages needed, %zu free", need, c->free_list.size());
+  if (need) {
+    HIP_TRY(c, hipStreamSynchronize(c->stream));  // the pinned table may still be in flight
+    for (int b = 0; b < c->B; ++b) grow_seq(c, b, c->h_len[b] + 1);
+    HIP_TRY(c, hipMemcpyAsync(c->d_table, c->h_table, sizeof(int) * (size_t)c->cfg.max_batch * c->max_blocks,
+                              hipMemcpyHostToDevice, c->stream));
+  }
+  return RLHF_GEN_OK;
+}
+
+void after_step(rlhf_gen_ctx* c) {
+  for (int b = 0; b < c->B; ++b) c->h_len[b]++;
+  c->h_step++;
+}
+
+void drop_graph(rlhf_gen_ctx* c) {
+  if (c->graph_exec) {
+    (void)hipGraphExecDestroy(c->graph_exec);
+    c->graph_exec = nullptr;
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+int rlhf_gen_init(const rlhf_gen_weights* w, const rlhf_gen_cfg* cfg, rlhf_gen_ctx** out) {
+  if (out) *out = nullptr;
+  if (!w || !cfg || !out) return fail(nullptr, RLHF_GEN_E_INVALID, "NULL argument to rlhf_gen_init");
+  const rlhf_gen_cfg& g = *cfg;
+  if (g.n_layers < 1 || g.d_model < 1 || g.n_heads < 1 || g.n_kv_heads < 1 || g.head_dim < 1 || g.d_ffn < 1 || g.vocab < 1)
+    return fail(nullptr, RLHF_GEN_E_INVALID, "model dimensions must be positive");
+  if (g.n_heads % g.n_kv_heads) return fail(nullptr, RLHF_GEN_E_INVALID, "n_heads must be a multiple of n_kv_heads");
+  if (g.head_dim & 1) return fail(nullptr, RLHF_GEN_E_INVALID, "head_dim must be even");
+  if (g.max_batch < 1 || g.max_seq < 2) return fail(nullptr, RLHF_GEN_E_INVALID, "max_batch >= 1 and max_seq >= 2 required");
+  if (g.kv_block != 16) return fail(nullptr, RLHF_GEN_E_UNSUPPORTED, "kv_block must be 16 (got %d)", g.kv_block);
+  if (g.dtype != RLHF_GEN_DTYPE_FP32 && g.dtype != RLHF_GEN_DTYPE_BF16)
+    return fail(nullptr, RLHF_GEN_E_INVALID, "dtype must be 0 (fp32) or 1 (bf16)");
+  if (!(g.rms_eps > 0.f) || !(g.rope_theta > 0.f)) return fail(nullptr, RLHF_GEN_E_INVALID, "rms_eps and rope_theta must be positive");
+  if (g.kv_pool_blocks < 0) return fail(nullptr, RLHF_GEN_E_INVALID, "kv_pool_blocks must not be negative");
+  if (g.d_model > 8192 || (g.d_model & 3)) return fail(nullptr, RLHF_GEN_E_UNSUPPORTED, "d_model must be a multiple of 4, at most 8192");
+  const int qkv_w = (g.n_heads + 2 * g.n_kv_heads) * g.head_dim;
+  if (g.dtype == RLHF_GEN_DTYPE_BF16) {
+    if (g.head_dim != 128) return fail(nullptr, RLHF_GEN_E_UNSUPPORTED, "bf16 path needs head_dim 128 (got %d)", g.head_dim);
+    if (g.n_heads / g.n_kv_heads > 16) return fail(nullptr, RLHF_GEN_E_UNSUPPORTED, "bf16 path supports at most 16 query heads per KV head");
+    if (g.d_model % 256 || qkv_w % 256 || g.vocab % 256 || g.d_ffn % 128 || (g.n_heads * g.head_dim) % 128)
+      return fail(nullptr, RLHF_GEN_E_UNSUPPORTED,
+                  "bf16 path needs d_model, (n_heads + 2 n_kv_heads) head_dim and vocab to be multiples of 256 and d_ffn of 128");
+  } else {
+    if (g.head_dim != 32 && g.head_dim != 64 && g.head_dim != 128)
+      return fail(nullptr, RLHF_GEN_E_UNSUPPORTED, "fp32 path supports head_dim 32, 64 or 128");
+  }
+  if (!w->tok_emb || !w->lm_head || !w->final_norm || !w->attn_norm || !w->wqkv || !w->wo || !w->ffn_norm ||
+      !w->w_gate_up || !w->w_down)
+    return fail(nullptr, RLHF_GEN_E_INVALID, "NULL weight pointer");
+  for (int l = 0; l < g.n_layers; ++l)
+    if (!w->attn_norm[l] || !w->wqkv[l] || !w->wo[l] || !w->ffn_norm[l] || !w->w_gate_up[l] || !w->w_down[l])
+      return fail(nullptr, RLHF_GEN_E_INVALID, "NULL weight pointer in layer %d", l);
+
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || g.device < 0 || g.device >= ndev) {
+    (void)hipGetLastError();
+    return fail(nullptr, RLHF_GEN_E_DEVICE, "HIP device %d is not available (%d devices)", g.device, ndev);
+  }
+  rlhf_gen_ctx* c = new rlhf_gen_ctx();
+  c->cfg = g;
+  c->bf16 = g.dtype == RLHF_GEN_DTYPE_BF16;
+  c->stream = (hipStream_t)g.stream;
+  c->tok_emb = w->tok_emb;
+  c->lm_head = w->lm_head;
+  c->final_norm = w->final_norm;
+  for (int l = 0; l < g.n_layers; ++l) {
+    c->attn_norm.push_back(w->attn_norm[l]);
+    c->wqkv.push_back(w->wqkv[l]);
+    c->wo.push_back(w->wo[l]);
+    c->ffn_norm.push_back(w->ffn_norm[l]);
+    c->w_gate_up.push_back(w->w_gate_up[l]);
+    c->w_down.push_back(w->w_down[l]);
+  }
+  auto bail = [&](int code) {
+    g_init_error = c->err;
+    rlhf_gen_destroy(c);
+    return code;
+  };
+  if (hipSetDevice(g.device) != hipSuccess) {
+    (void)hipGetLastError();
+    c->err = "hipSetDevice failed";
+    return bail(RLHF_GEN_E_DEVICE);
+  }
+  if (!c->stream) {
+    // the legacy default stream cannot be captured into a graph: use a stream of our own (default priority)
+    if (hipStreamCreate(&c->stream) != hipSuccess) {
+      c->err = "hipStreamCreate failed";
+      c->stream = nullptr;
+      return bail(RLHF_GEN_E_DEVICE);
+    }
+    c->own_stream = true;
+  }
+  if (gemm_configure() != hipSuccess) {
+    (void)hipGetLastError();
+    c->err = "kernel attribute setup failed";
+    return bail(RLHF_GEN_E_DEVICE);
+  }
+  c->max_blocks = blocks_for(g.max_seq);
+  c->n_blocks = g.kv_pool_blocks ? g.kv_pool_blocks : g.max_batch * c->max_blocks;
+  const size_t page_bytes = c->bf16 ? 8192 : (size_t)2 * 16 * g.head_dim * 4;
+  c->layer_pool_bytes = (size_t)c->n_blocks * g.n_kv_heads * page_bytes;
+  c->h_len.assign(g.max_batch, 0);
+  c->n_alloc.assign(g.max_batch, 0);
+  // activation rows: a prefill chunk holds whole sequences, so at least max_seq rows; 16384 keeps the
+  // large GEMMs in their efficient regime while bounding the scratch
+  c->act_rows = std::max(std::max(g.max_seq, g.max_batch), 16384);
+  c->act_rows = std::min(c->act_rows, std::max(g.max_batch * g.max_seq, g.max_batch));
+  c->act_rows = (c->act_rows + 255) / 256 * 256;
+  const size_t rows = c->act_rows, as = act_size(c);
+  const size_t total_tok = (size_t)g.max_batch * g.max_seq;
+  const int half = g.head_dim / 2;
+  int rc = RLHF_GEN_OK;
+#define A_(expr) do { rc = (expr); if (rc) return bail(rc); } while (0)
+  A_(dev_alloc(c, &c->kv_pool, c->layer_pool_bytes * g.n_layers, true));
+  A_(dev_alloc(c, &c->d_table, sizeof(int) * (size_t)g.max_batch * c->max_blocks, true));
+  A_(dev_alloc(c, &c->d_seq_len, sizeof(int) * g.max_batch, true));
+  A_(dev_alloc(c, &c->d_step, sizeof(int), true));
+  A_(dev_alloc(c, &c->d_err, sizeof(int), true));
+  A_(dev_alloc(c, &c->d_cur_tok, sizeof(int) * g.max_batch, true));
+  A_(dev_alloc(c, &c->d_cos, sizeof(float) * (size_t)(g.max_seq + 1) * half, false));
+  A_(dev_alloc(c, &c->d_sin, sizeof(float) * (size_t)(g.max_seq + 1) * half, false));
+  A_(dev_alloc(c, &c->d_tok_seq, sizeof(int) * total_tok, true));
+  A_(dev_alloc(c, &c->d_tok_pos, sizeof(int) * total_tok, true));
+  A_(dev_alloc(c, &c->d_ids, sizeof(int) * total_tok, true));
+  A_(dev_alloc(c, &c->d_cu, sizeof(int) * (2 * (size_t)g.max_batch + 2), true));
+  A_(dev_alloc(c, &c->d_seq_ids, sizeof(int) * g.max_batch, true));
+  A_(dev_alloc(c, &c->d_last_rows, sizeof(int) * g.max_batch, true));
+  A_(dev_alloc(c, &c->x, 4 * rows * g.d_model, true));
+  A_(dev_alloc(c, &c->qkv, 4 * rows * std::max(qkv_w, c->bf16 ? 0 : 2 * g.d_ffn), true));
+  A_(dev_alloc(c, &c->y, as * rows * g.d_model, true));
+  A_(dev_alloc(c, &c->yl, as * ((size_t)g.max_batch + 256) * g.d_model, true));
+  A_(dev_alloc(c, &c->qb, as * rows * g.n_heads * g.head_dim, true));
+  A_(dev_alloc(c, &c->ab, as * rows * g.n_heads * g.head_dim, true));
+  A_(dev_alloc(c, &c->hb, as * rows * g.d_ffn, true));
+  A_(dev_alloc(c, &c->logits, 4 * (size_t)g.max_batch * g.vocab, true));
+  if (c->bf16) {
+    const int Bm = std::min(g.max_batch, 256);
+    c->ks_qkv = gemm_skinny_pick_split(Bm, qkv_w, g.d_model);
+    c->ks_wo = gemm_skinny_pick_split(Bm, g.d_model, g.n_heads * g.head_dim);
+    c->ks_gu = gemm_skinny_pick_split(Bm, 2 * g.d_ffn, g.d_model);
+    c->ks_down = gemm_skinny_pick_split(Bm, g.d_model, g.d_ffn);
+    size_t pe = std::max(std::max((size_t)c->ks_qkv * qkv_w, (size_t)c->ks_wo * g.d_model),
+                         std::max((size_t)c->ks_gu * 2 * g.d_ffn, (size_t)c->ks_down * g.d_model));
+    A_(dev_alloc(c, &c->part, 4 * pe * Bm, true));
+  }
+  A_(host_alloc(c, &c->h_tok_seq, sizeof(int) * total_tok));
+  A_(host_alloc(c, &c->h_tok_pos, sizeof(int) * total_tok));
+  A_(host_alloc(c, &c->h_cu, sizeof(int) * (2 * (size_t)g.max_batch + 2)));
+  A_(host_alloc(c, &c->h_seq_ids, sizeof(int) * g.max_batch));
+  A_(host_alloc(c, &c->h_last_rows, sizeof(int) * g.max_batch));
+  A_(host_alloc(c, &c->h_table, sizeof(int) * (size_t)g.max_batch * c->max_blocks));
+  A_(host_alloc(c, &c->h_lenbuf, sizeof(int) * g.max_batch));
+  A_(host_alloc(c, &c->h_misc, sizeof(int) * 8));
+#undef A_
+  {
+    // rotation tables in double, rounded once to fp32: angle = pos * theta^(-2i/h)
+    std::vector<float> cs((size_t)(g.max_seq + 1) * half), sn((size_t)(g.max_seq + 1) * half);
+    for (int p = 0; p <= g.max_seq; ++p)
+      for (int i = 0; i < half; ++i) {
+        double ang = (double)p * pow((double)g.rope_theta, -2.0 * i / g.head_dim);
+        cs[(size_t)p * half + i] = (float)cos(ang);
+        sn[(size_t)p * half + i] = (float)sin(ang);
+      }
+    if (hipMemcpy(c->d_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(c->d_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice) != hipSuccess) {
+      c->err = "upload of the rotation tables failed";
+      return bail(RLHF_GEN_E_DEVICE);
+    }
+  }
+  for (int i = 0; i < 3; ++i)
+    if (hipEventCreate(&c->ev[i]) != hipSuccess) {
+      c->err = "hipEventCreate failed";
+      return bail(RLHF_GEN_E_DEVICE);
+    }
+  reset_free_list(c);
+  if (hipDeviceSynchronize() != hipSuccess) {
+    c->err = "device synchronisation after init failed";
+    return bail(RLHF_GEN_E_DEVICE);
+  }
+  *out = c;
+  return RLHF_GEN_OK;
+}
+
+int rlhf_gen_prefill(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* lengths, int32_t B, int32_t Lmax,
+                     const rlhf_gen_sampling* sampling, int32_t* tok_out, float* logprob_out) {
+  if (!c) return RLHF_GEN_E_INVALID;
+  c->reserve_extra = 0;
+  return prefill_impl(c, query_tokens, lengths, B, Lmax, sampling, tok_out, logprob_out, 1);
+}
+
+int rlhf_gen_decode_step(rlhf_gen_ctx* c, const int32_t* forced_tokens, int32_t* tok_out, float* logprob_out) {
+  if (!c) return RLHF_GEN_E_INVALID;
+  if (!tok_out || !logprob_out) return fail(c, RLHF_GEN_E_INVALID, "NULL output pointer");
+  HIP_TRY(c, hipSetDevice(c->cfg.device));
+  int rc = decode_checks(c);
+  if (rc) return rc;
+  if (forced_tokens)
+    HIP_TRY(c, hipMemcpyAsync(c->d_cur_tok, forced_tokens, sizeof(int) * c->B, hipMemcpyDeviceToDevice, c->stream));
+  rc = enqueue_decode_body(c, tok_out, logprob_out, 1, 0);
+  if (rc) return rc;
+  after_step(c);
+  return RLHF_GEN_OK;
+}
+
+int rlhf_gen_generate(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* lengths, int32_t B, int32_t Lmax,
+                      int32_t R, const rlhf_gen_sampling* sampling, int32_t* resp_tokens, float* resp_logprobs) {
+  if (!c) return RLHF_GEN_E_INVALID;
+  if (R < 1) return fail(c, RLHF_GEN_E_INVALID, "max_resp_len = %d must be positive", R);
+  HIP_TRY(c, hipSetDevice(c->cfg.device));
+  c->reserve_extra = R - 1;
+  hipStream_t s = c->stream;
+  HIP_TRY(c, hipStreamSynchronize(s));
+  HIP_TRY(c, hipEventRecord(c->ev[0], s));
+  int rc = prefill_impl(c, query_tokens, lengths, B, Lmax, sampling, resp_tokens, resp_logprobs, R);
+  c->reserve_extra = 0;
+  if (rc) return rc;
+  HIP_TRY(c, hipEventRecord(c->ev[1], s));
+  const bool use_graph = !(c->cfg.flags & RLHF_GEN_FLAG_NO_GRAPH) && R > 2;
+  if (use_graph) {
+    GraphKey key;
+    key.B = B; key.stride = R; key.use_col = 1; key.tok = resp_tokens; key.lp = resp_logprobs; key.sp = c->sp;
+    if (!c->graph_exec || !(key == c->graph_key)) {
+      drop_graph(c);
+      hipGraph_t graph = nullptr;
+      HIP_TRY(c, hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+      rc = enqueue_decode_body(c, resp_tokens, resp_logprobs, R, 1);
+      hipError_t e = hipStreamEndCapture(s, &graph);
+      if (rc) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return rc;
+      }
+      if (e != hipSuccess) return fail(c, RLHF_GEN_E_DEVICE, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+      e = hipGraphInstantiate(&c->graph_exec, graph, nullptr, nullptr, 0);
+      (void)hipGraphDestroy(graph);
+      if (e != hipSuccess) {
+        c->graph_exec = nullptr;
+        return fail(c, RLHF_GEN_E_DEVICE, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
+      }
+      c->graph_key = key;
+    }
+  }
+  for (int t = 1; t < R; ++t) {
+    rc = decode_checks(c);  // pages were reserved by prefill: never allocates here
+    if (rc) return rc;
+    if (use_graph) {
+      HIP_TRY(c, hipGraphLaunch(c->graph_exec, s));
+    } else {
+      rc = enqueue_decode_body(c, resp_tokens, resp_logprobs, R, 1);
+      if (rc) return rc;
+    }
+    after_step(c);
+  }
+  HIP_TRY(c, hipEventRecord(c->ev[2], s));
+  HIP_TRY(c, hipMemcpyAsync(&c->h_misc[2], c->d_err, sizeof(int), hipMemcpyDeviceToHost, s));
+  HIP_TRY(c, hipStreamSynchronize(s));
+  HIP_TRY(c, hipEventElapsedTime(&c->prefill_ms, c->ev[0], c->ev[1]));
+  HIP_TRY(c, hipEventElapsedTime(&c->decode_ms, c->ev[1], c->ev[2]));
+  c->decode_steps = R - 1;
+  if (c->h_misc[2]) return fail(c, RLHF_GEN_E_INVALID, "a token id outside [0, vocab) reached the embedding");
+  return RLHF_GEN_OK;
+}
+
+int rlhf_gen_get_logits(rlhf_gen_ctx* c, float* out) {
+  if (!c) return RLHF_GEN_E_INVALID;
+  if (!out) return fail(c, RLHF_GEN_E_INVALID, "NULL output pointer");
+  if (!c->have_logits) return fail(c, RLHF_GEN_E_STATE, "no step has produced logits yet");
+  HIP_TRY(c, hipMemcpyAsync(out, c->logits, sizeof(float) * (size_t)c->B * c->cfg.vocab, hipMemcpyDeviceToDevice, c->stream));
+  return RLHF_GEN_OK;
+}
+
+int rlhf_gen_last_timing(const rlhf_gen_ctx* c, float* prefill_ms, float* decode_ms, int32_t* decode_steps) {
+  if (!c) return RLHF_GEN_E_INVALID;
+  if (prefill_ms) *prefill_ms = c->prefill_ms;
+  if (decode_ms) *decode_ms = c->decode_ms;
+  if (decode_steps) *decode_steps = c->decode_steps;
+  return RLHF_GEN_OK;
+}
+
+const char* rlhf_gen_last_error(const rlhf_gen_ctx* c) { return c ? c->err.c_str() : g_init_error.c_str(); }
+
+void rlhf_gen_destroy(rlhf_gen_ctx* c) {
+  if (!c) return;
+  (void)hipSetDevice(c->cfg.device);
+  if (c->stream || !c->allocs.empty()) (void)hipStreamSynchronize(c->stream);
+  drop_graph(c);
+  for (void* p : c->allocs) (void)hipFree(p);
+  int* pinned[] = {c->h_tok_seq, c->h_tok_pos, c->h_cu, c->h_seq_ids, c->h_last_rows, c->h_table, c->h_lenbuf, c->h_misc};
+  for (int* p : pinned)
+    if (p) (void)hipHostFree(p);
+  for (int i = 0; i < 3; ++i)
+    if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
+  if (c->own_stream && c->stream) (void)hipStreamDestroy(c->stream);
+  delete c;
+}
+
+// ---- single-operation entry points (kernel parity tests) ----------------------------------------
+int rlhf_gen_op_gemm(void* stream, int kind, const void* A, const void* W, void* out, int32_t M, int32_t N, int32_t K,
+                     int32_t epilogue, int32_t nsplit) {
+  hipStream_t s = (hipStream_t)stream;
+  hipError_t e;
+  if (!A || !W || !out || M < 1 || N < 1 || K < 1) return RLHF_GEN_E_INVALID;
+  if (kind == RLHF_GEN_GEMM_TILED) e = launch_gemm_bf16(s, A, W, out, M, N, K, epilogue);
+  else if (kind == RLHF_GEN_GEMM_STREAMING) e = launch_gemm_skinny_bf16(s, A, W, (float*)out, M, N, K, nsplit);
+  else if (kind == RLHF_GEN_GEMM_FP32) e = launch_gemm_f32(s, (const float*)A, (const float*)W, (float*)out, M, N, K, epilogue == EPI_RESID_F32);
+  else return RLHF_GEN_E_INVALID;
+  if (e == hipErrorInvalidValue) return RLHF_GEN_E_UNSUPPORTED;
+  return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;
+}
+
+int rlhf_gen_op_rope_append(void* stream, const float* qkv, const int32_t* row_pos, const int32_t* row_seq,
+                            const float* cos_t, const float* sin_t, void* q_out, void* kv_pool,
+                            const int32_t* block_table, int32_t max_blocks, int32_t M, int32_t Hq, int32_t Hkv,
+                            int32_t head_dim, int32_t bf16) {
+  if (!qkv || !row_pos || !cos_t || !sin_t || !q_out || !kv_pool || !block_table) return RLHF_GEN_E_INVALID;
+  hipError_t e = launch_rope_append((hipStream_t)stream, qkv, nullptr, 0, 0, row_pos, row_seq, cos_t, sin_t, q_out, kv_pool,
+                                    block_table, max_blocks, M, Hq, Hkv, head_dim, bf16);
+  if (e == hipErrorInvalidValue) return RLHF_GEN_E_UNSUPPORTED;
+  return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;
+}
+
+int rlhf_gen_op_attn_decode(void* stream, const void* q, const void* kv_pool, const int32_t* block_table,
+                            int32_t max_blocks, const int32_t* seq_len, void* out, int32_t B, int32_t Hq, int32_t Hkv) {
+  if (!q || !kv_pool || !block_table || !seq_len || !out) return RLHF_GEN_E_INVALID;
+  hipError_t e = launch_attn_decode_bf16((hipStream_t)stream, q, kv_pool, block_table, max_blocks, seq_len, out, B, Hq, Hkv);
+  if (e == hipErrorInvalidValue) return RLHF_GEN_E_UNSUPPORTED;
+  return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;
+}
+
+int rlhf_gen_op_attn_prefill(void* stream, const void* q, const void* kv_pool, const int32_t* block_table,
+                             int32_t max_blocks, const int32_t* cu_seqlens, const int32_t* seq_ids, void* out,
+                             int32_t nseq, int32_t max_len, int32_t Hq, int32_t Hkv) {
+  if (!q || !kv_pool || !block_table || !cu_seqlens || !seq_ids || !out) return RLHF_GEN_E_INVALID;
+  hipError_t e = launch_attn_prefill_bf16((hipStream_t)stream, q, kv_pool, block_table, max_blocks, cu_seqlens, seq_ids, out,
+                                          nseq, max_len, Hq, Hkv);
+  if (e == hipErrorInvalidValue) return RLHF_GEN_E_UNSUPPORTED;
+  return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;
+}
+
+int rlhf_gen_op_sample(void* stream, const float* logits, int32_t B, int32_t V, const rlhf_gen_sampling* sp,
+                       const int32_t* step, int32_t* tok_out, float* logprob_out, int32_t* scratch_tok) {
+  if (!logits || !sp || !step || !tok_out || !logprob_out || !scratch_tok || B < 1 || V < 1) return RLHF_GEN_E_INVALID;
+  SamplerParams p;
+  p.temperature = sp->temperature; p.top_p = sp->top_p; p.seed = sp->seed; p.greedy = sp->greedy; p.logprob_mode = sp->logprob_mode;
+  hipError_t e = launch_sampler((hipStream_t)stream, logits, B, V, p, step, 1, 0, tok_out, logprob_out, scratch_tok);
+  return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;
+}
+
+}  // extern "C"

@@ -1,0 +1,167 @@
+"""Kernel-by-kernel parity of the HIP library against CPU definitions (oracle pieces, float64)."""
+import math
+
+import pytest
+import torch
+
+from oracle import sampling as OS
+from oracle import transformer as OT
+from tests.gpu_util import bf16_round, need_gpu, oracle_attention_rows, rope_tables
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    need_gpu()
+    from paper_2312_11819_amd import binding
+    binding.lib()
+    return binding
+
+
+def _rand(shape, seed, scale=1.0, dtype=torch.bfloat16):
+    g = torch.Generator().manual_seed(seed)
+    return (torch.randn(*shape, generator=g) * scale).to(dtype)
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 512, 256), (1024, 256, 448), (7, 256, 64), (513, 768, 1024)])
+def test_gemm_tiled_store_and_accumulate(B, M, N, K):
+    a, w = _rand((M, K), 1), _rand((N, K), 2, 0.05)
+    ref = a.double() @ w.double().T
+    A, W = a.cuda(), w.cuda()
+    out = torch.full((M, N), 7.0, dtype=torch.float32, device="cuda")
+    assert B.rlhf_gen_op_gemm(B.GEMM_TILED, A, W, out, M, N, K, B.EPI_STORE_F32) == 0
+    torch.cuda.synchronize()
+    tol = 1e-5 * math.sqrt(K) + 1e-6
+    assert (out.cpu().double() - ref).abs().max() < tol
+    assert B.rlhf_gen_op_gemm(B.GEMM_TILED, A, W, out, M, N, K, B.EPI_RESID_F32) == 0
+    torch.cuda.synchronize()
+    assert (out.cpu().double() - 2 * ref).abs().max() < 2 * tol
+    outb = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+    assert B.rlhf_gen_op_gemm(B.GEMM_TILED, A, W, outb, M, N, K, B.EPI_STORE_BF16) == 0
+    torch.cuda.synchronize()
+    assert (outb.cpu().double() - ref).abs().max() <= ref.abs().max() * 2 ** -8 + tol
+
+
+@pytest.mark.parametrize("M,F,K", [(300, 384, 256), (64, 128, 128), (1000, 1152, 512)])
+def test_gemm_tiled_swiglu(B, M, F, K):
+    a, w = _rand((M, K), 3), _rand((2 * F, K), 4, 0.1)
+    gu = a.double() @ w.double().T
+    ref = OT.silu(gu[:, :F]) * gu[:, F:]
+    out = torch.zeros((M, F), dtype=torch.bfloat16, device="cuda")
+    assert B.rlhf_gen_op_gemm(B.GEMM_TILED, a.cuda(), w.cuda(), out, M, F, K, B.EPI_SWIGLU) == 0
+    torch.cuda.synchronize()
+    err = (out.cpu().double() - ref).abs()
+    assert (err <= ref.abs() * 2 ** -8 + 1e-4).all()
+
+
+@pytest.mark.parametrize("M,N,K,ns", [(4, 128, 256, 1), (16, 512, 1024, 3), (64, 640, 1024, 2), (50, 256, 1408, 4),
+                                      (200, 256, 512, 2), (256, 192, 1024, 8), (33, 64, 128, 1)])
+def test_gemm_streaming(B, M, N, K, ns):
+    a, w = _rand((M, K), 5), _rand((N, K), 6, 0.05)
+    ref = a.double() @ w.double().T
+    part = torch.full((ns, M, N), float("nan"), dtype=torch.float32, device="cuda")
+    assert B.rlhf_gen_op_gemm(B.GEMM_STREAMING, a.cuda(), w.cuda(), part, M, N, K, 0, ns) == 0
+    torch.cuda.synchronize()
+    got = part.cpu().double().sum(0)
+    assert (got - ref).abs().max() < 1e-5 * math.sqrt(K) + 1e-6
+
+
+def test_gemm_fp32(B):
+    M, N, K = 37, 344, 128
+    a, w = _rand((M, K), 7, 1.0, torch.float32), _rand((N, K), 8, 0.05, torch.float32)
+    ref = a.double() @ w.double().T
+    out = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    assert B.rlhf_gen_op_gemm(B.GEMM_FP32, a.cuda(), w.cuda(), out, M, N, K, B.EPI_STORE_F32) == 0
+    assert B.rlhf_gen_op_gemm(B.GEMM_FP32, a.cuda(), w.cuda(), out, M, N, K, B.EPI_RESID_F32) == 0
+    torch.cuda.synchronize()
+    assert (out.cpu().double() - 2 * ref).abs().max() < 1e-5
+
+
+def test_gemm_rejects_bad_shapes(B):
+    t = torch.zeros(256, 256, dtype=torch.bfloat16, device="cuda")
+    o = torch.zeros(256, 256, dtype=torch.float32, device="cuda")
+    assert B.rlhf_gen_op_gemm(B.GEMM_TILED, t, t, o, 256, 200, 256, 0) == B.E_UNSUPPORTED
+    assert B.rlhf_gen_op_gemm(B.GEMM_TILED, t, t, o, 256, 256, 100, 0) == B.E_UNSUPPORTED
+    assert B.rlhf_gen_op_gemm(B.GEMM_STREAMING, t, t, o, 300, 256, 256, 0, 1) == B.E_UNSUPPORTED
+    assert B.rlhf_gen_op_gemm(9, t, t, o, 256, 256, 256, 0, 1) == B.E_INVALID
+
+
+@pytest.mark.parametrize("Hq,Hkv,lens", [(2, 2, [1, 17, 64, 5]), (8, 1, [33, 100]), (4, 2, [16, 48, 31])])
+def test_attention_prefill_then_decode(B, Hq, Hkv, lens):
+    h, nseq = 128, len(lens)
+    width = (Hq + 2 * Hkv) * h
+    T = sum(lens)
+    maxpos = max(lens) + 1
+    max_blocks = (maxpos + 15) // 16
+    n_blocks = nseq * max_blocks + 3
+    g = torch.Generator().manual_seed(11)
+    table = torch.randperm(n_blocks, generator=g)[: nseq * max_blocks].reshape(nseq, max_blocks).to(torch.int32)
+    qkv = torch.randn(T + nseq, width, generator=g)                      # prefill rows, then one decode row per sequence
+    cos_t, sin_t = rope_tables(maxpos, h)
+    row_seq = torch.tensor([b for b, L in enumerate(lens) for _ in range(L)], dtype=torch.int32)
+    row_pos = torch.tensor([p for L in lens for p in range(L)], dtype=torch.int32)
+    cu = torch.tensor([0] + list(torch.tensor(lens).cumsum(0)), dtype=torch.int32)
+    pool = torch.zeros(n_blocks, Hkv, 8192, dtype=torch.uint8, device="cuda")
+    dev = lambda t: t.cuda().contiguous()
+    qkv_d, cos_d, sin_d, table_d = dev(qkv), dev(cos_t), dev(sin_t), dev(table)
+    q_out = torch.zeros(T, Hq, h, dtype=torch.bfloat16, device="cuda")
+    assert B.rlhf_gen_op_rope_append(qkv_d[:T].contiguous(), dev(row_pos), dev(row_seq), cos_d, sin_d, q_out, pool,
+                                     table_d, max_blocks, T, Hq, Hkv, h, True) == 0
+    out = torch.zeros(T, Hq * h, dtype=torch.bfloat16, device="cuda")
+    seq_ids = torch.arange(nseq, dtype=torch.int32, device="cuda")
+    assert B.rlhf_gen_op_attn_prefill(q_out, pool, table_d, max_blocks, dev(cu), seq_ids, out, nseq, max(lens), Hq, Hkv) == 0
+    # decode row for each sequence at position len
+    qd = torch.zeros(nseq, Hq, h, dtype=torch.bfloat16, device="cuda")
+    seq_len = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    assert B.rlhf_gen_op_rope_append(qkv_d[T:].contiguous(), seq_len, None, cos_d, sin_d, qd, pool, table_d, max_blocks,
+                                     nseq, Hq, Hkv, h, True) == 0
+    outd = torch.zeros(nseq, Hq * h, dtype=torch.bfloat16, device="cuda")
+    assert B.rlhf_gen_op_attn_decode(qd, pool, table_d, max_blocks, seq_len, outd, nseq, Hq, Hkv) == 0
+    torch.cuda.synchronize()
+    # CPU definition on the unrounded fp32 inputs
+    scale = 1.0 / math.sqrt(h)
+    worst = 0.0
+    for b, L in enumerate(lens):
+        rows = torch.cat([qkv[cu[b]: cu[b] + L], qkv[T + b: T + b + 1]]).double()
+        pos = torch.arange(L + 1)
+        q = OT.rope(rows[:, : Hq * h].reshape(L + 1, Hq, h), pos, 10000.0)
+        k = OT.rope(rows[:, Hq * h: (Hq + Hkv) * h].reshape(L + 1, Hkv, h), pos, 10000.0)
+        v = rows[:, (Hq + Hkv) * h:].reshape(L + 1, Hkv, h)
+        for i in range(L + 1):
+            for j in range(Hq):
+                kv = j // (Hq // Hkv)
+                want = oracle_attention_rows(q[i, j], k[: i + 1, kv], v[: i + 1, kv], scale)
+                got = (out[cu[b] + i, j * h:(j + 1) * h] if i < L else outd[b, j * h:(j + 1) * h]).cpu().double()
+                worst = max(worst, float((got - want).abs().max()))
+    assert worst < 3e-2, worst
+
+
+@pytest.mark.parametrize("mode", ["greedy", "plain", "nucleus", "nucleus_lp1", "tight"])
+def test_sampler(B, mode):
+    V, rows = 32000, 6
+    g = torch.Generator().manual_seed(21)
+    logits = torch.randn(rows, V, generator=g) * 2.0
+    logits[2, 777] = logits[2].max() + 3.0                                  # one peaked row
+    cfgs = {"greedy": dict(greedy=True), "plain": dict(temperature=1.0, top_p=1.0, seed=5),
+            "nucleus": dict(temperature=0.8, top_p=0.9, seed=6), "nucleus_lp1": dict(temperature=1.3, top_p=0.5, seed=7, logprob_mode=1),
+            "tight": dict(temperature=1.0, top_p=1e-6, seed=8)}[mode]
+    sp = B.make_sampling(**cfgs)
+    osp = OS.Sampling(**cfgs)
+    ld = logits.cuda()
+    for t in (0, 3, 500):
+        step = torch.tensor([t], dtype=torch.int32, device="cuda")
+        tok = torch.zeros(rows, dtype=torch.int32, device="cuda")
+        lp = torch.zeros(rows, dtype=torch.float32, device="cuda")
+        scr = torch.zeros(rows, dtype=torch.int32, device="cuda")
+        assert B.rlhf_gen_op_sample(ld, sp, step, tok, lp, scr) == 0
+        torch.cuda.synchronize()
+        assert torch.equal(tok, scr)
+        for b in range(rows):
+            want_tok, want_lp, info = OS.sample(logits[b], osp, b, t)
+            got = int(tok[b])
+            if got != want_tok:
+                # allowed only when u sits within 1e-3 of an edge of the oracle's CDF interval
+                assert not osp.greedy and OS.cdf_margin(info, want_tok) < 1e-3, (b, t, got, want_tok)
+                continue
+            assert abs(float(lp[b]) - want_lp) < 1e-4, (b, t, float(lp[b]), want_lp)
