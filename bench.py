@@ -1,0 +1,168 @@
+"""Benchmark of the Actor rollout on one MI355X: `python bench.py --gpus 1 --steps K --warmup W`.
+
+One "step" is one whole rollout (rlhf_gen_generate: prefill of the queries + R - 1 KV-cached decode steps)
+of the 7B-shaped bf16 workload: 64 queries of 512 tokens, 512 response tokens each, temperature 1, top-p 1,
+seeded sampling, random-init weights, uniform random token ids.  Inputs are resident in HBM before the
+timed region.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12          # B/s, MI355X datasheet
+MFMA_BF16_PEAK = 2.5e15    # flop/s dense, MI355X datasheet
+
+
+def weight_bytes(shape, elt=2):
+    from paper_2312_11819_amd import synth
+    return (synth.param_count(shape) - shape.vocab * shape.d_model) * elt   # the embedding table is gathered, not streamed
+
+
+def cpu_baseline(wl, w_dev, toks, lens, decode_steps=2):
+    """The oracle as it stands, fp32 mode, on one sequence of the batch: full prefill + a few decode steps."""
+    import torch
+    from oracle.generate import generate as oracle_generate
+    from oracle.sampling import Sampling as OSampling
+    from paper_2312_11819_amd import synth
+    w_cpu = synth.weights_to(w_dev, "cpu")
+    qs = [toks[b, : lens[b]].tolist() for b in range(toks.shape[0])]
+    osp = OSampling(temperature=wl.temperature, top_p=wl.top_p, seed=wl.sample_seed, greedy=wl.greedy)
+    n_tok = decode_steps + 1
+    t0 = time.perf_counter()
+    oracle_generate(w_cpu, wl.shape, qs, n_tok, osp, rows=[0], dtype=torch.float32, keep_logits=False)
+    dt = time.perf_counter() - t0
+    return {"value": n_tok / dt, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+            "sample": f"row 0 of the batch: {int(lens[0])}-token prefill + {decode_steps} decode steps "
+                      f"({n_tok} tokens) in {dt:.1f} s, oracle in float32 mode, torch CPU threads as listed"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="7b_b64")
+    ap.add_argument("--layers", type=int, default=0, help="override the depth (debugging only; invalidates the metric)")
+    ap.add_argument("--resp-len", type=int, default=0, help="override R (debugging only; invalidates the metric)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-every", type=int, default=64)
+    ap.add_argument("--flags", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the rollout shards by query across replicas with no "
+              "communication); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2312_11819_amd import binding, synth
+
+    binding.lib()  # fail loudly if the HIP library is missing
+    wl = synth.WORKLOADS[args.workload]
+    shape = wl.shape if not args.layers else synth.with_layers(wl.shape, args.layers)
+    R = args.resp_len or wl.resp_len
+    dev = torch.device("cuda:0")
+    w = synth.make_weights(shape, wl.weight_seed, wl.dtype, dev)
+    toks, lens = synth.workload_queries(wl)
+    toks_d = toks.to(dev)
+    B = wl.batch
+    ctx = binding.Context(w, shape, wl.dtype, B, int(lens.max()) + R, flags=args.flags)
+    sp = binding.make_sampling(wl.temperature, wl.top_p, wl.sample_seed, wl.greedy, 0)
+    out_t = torch.empty(B, R, dtype=torch.int32, device=dev)
+    out_lp = torch.empty(B, R, dtype=torch.float32, device=dev)
+
+    for _ in range(args.warmup):
+        ctx.rlhf_gen_generate(toks_d, lens.tolist(), R, sp, out_t, out_lp)
+    ctx.rlhf_gen_set_profile(args.profile_every)
+    torch.cuda.synchronize()
+    pre_ms = dec_ms = 0.0
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ctx.rlhf_gen_generate(toks_d, lens.tolist(), R, sp, out_t, out_lp)
+        a, b, nsteps = ctx.rlhf_gen_last_timing()
+        pre_ms += a
+        dec_ms += b
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    prof = ctx.rlhf_gen_get_profile()
+    assert bool(torch.isfinite(out_lp).all()) and int(out_t.min()) >= 0 and int(out_t.max()) < shape.vocab
+
+    K = args.steps
+    ms_per_step = wall / K * 1e3
+    tokens_per_s = B * R / (wall / K)
+    pre_ms /= K
+    dec_ms /= K
+    # algorithmic bytes of the decode steps: weights once per step + every cached K/V byte once per step + the appended K/V
+    kv_tok = 2 * shape.n_kv_heads * shape.head_dim * 2 * shape.n_layers
+    lsum = int(lens.sum())
+    wb = weight_bytes(shape)
+    dec_bytes = 0
+    for t in range(1, R):
+        ctx_tokens = lsum + B * t          # cached tokens the step reads, its own included
+        dec_bytes += wb + ctx_tokens * kv_tok + B * kv_tok
+    dec_frac = dec_bytes / (dec_ms * 1e-3) / HBM_PEAK if dec_ms > 0 else None
+    # prefill flops: projections over all query tokens + causal attention + LM head on B rows
+    layer_mm = (shape.qkv_rows * shape.d_model + shape.d_model * shape.n_heads * shape.head_dim
+                + 3 * shape.d_ffn * shape.d_model)
+    pre_flop = 2 * layer_mm * shape.n_layers * lsum + 2 * B * shape.vocab * shape.d_model
+    pre_flop_attn = sum(2 * int(l) * int(l) * shape.n_heads * shape.head_dim * shape.n_layers for l in lens)
+    pre_frac = (pre_flop + pre_flop_attn) / (pre_ms * 1e-3) / MFMA_BF16_PEAK if pre_ms > 0 else None
+
+    roofline = None
+    kernels = {}
+    if prof["steps"] > 0:
+        for k in binding.PROF_CLASSES:
+            if prof["launches"][k]:
+                kernels[k] = {"ms_per_sampled_step": prof["ms"][k] / prof["steps"], "launches": prof["launches"][k]}
+        n_attn = prof["launches"]["attn_decode"]
+        attn_bytes = prof["attn_tokens"] * 2 * shape.n_kv_heads * shape.head_dim * 2 * shape.n_layers  # all sampled launches
+        attn_s = prof["ms"]["attn_decode"] * 1e-3
+        gemm_ms = sum(prof["ms"][k] for k in ("gemm_qkv", "gemm_wo", "gemm_gate_up", "gemm_down", "lm_head"))
+        gemm_bytes = prof["steps"] * (wb - (2 * shape.n_layers + 1) * shape.d_model * 2)
+        if attn_s >= gemm_ms * 1e-3:
+            roofline = {"kernel": "attn_decode_kernel", "bound": "hbm", "achieved": attn_bytes / attn_s / 1e9,
+                        "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": attn_bytes / attn_s / HBM_PEAK, "traffic": None,
+                        "avg_launch_us": attn_s / n_attn * 1e6, "launches_timed": n_attn,
+                        "bytes_per_launch": attn_bytes / n_attn}
+        else:
+            n_g = sum(prof["launches"][k] for k in ("gemm_qkv", "gemm_wo", "gemm_gate_up", "gemm_down", "lm_head"))
+            roofline = {"kernel": "gemm_skinny_kernel", "bound": "hbm", "achieved": gemm_bytes / (gemm_ms * 1e-3) / 1e9,
+                        "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": gemm_bytes / (gemm_ms * 1e-3) / HBM_PEAK,
+                        "traffic": None, "avg_launch_us": gemm_ms / n_g * 1e3, "launches_timed": n_g,
+                        "bytes_per_launch": gemm_bytes / n_g}
+        roofline["attn_decode_GBps"] = attn_bytes / attn_s / 1e9 if attn_s > 0 else None
+        roofline["gemm_skinny_GBps"] = gemm_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else None
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(wl if not args.layers else synth.dataclasses.replace(wl, shape=shape), w, toks, lens)
+
+    line = {
+        "metric": "generated tokens/sec + % HBM roofline per decode step, 7B-shape bf16 B=64",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "layers": shape.n_layers, "d_model": shape.d_model, "batch": B,
+                   "query_len": [wl.len_lo, wl.len_hi], "resp_len": R, "temperature": wl.temperature, "top_p": wl.top_p,
+                   "kv_block": 16, "valid": not args.layers and not args.resp_len},
+        "decode": {"ms_per_decode_step": dec_ms / max(R - 1, 1), "tokens_per_s_decode_only": B * (R - 1) / (dec_ms * 1e-3) if dec_ms else None,
+                   "hbm_roofline_frac_per_decode_step": dec_frac, "algorithmic_GB_per_step_mean": dec_bytes / max(R - 1, 1) / 1e9},
+        "prefill": {"ms": pre_ms, "mfma_bf16_frac": pre_frac, "flop": pre_flop + pre_flop_attn},
+        "roofline": roofline,
+        "kernels_sampled": kernels,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+    ctx.rlhf_gen_destroy()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -113,7 +113,7 @@ int rlhf_gen_init(const rlhf_gen_weights* weights, const rlhf_gen_cfg* cfg, rlhf
  * of every sequence from the logits at its last query position (Alg. 1, the first step of
  * Actor.generate).  Replaces any previous batch held by the context.
  *   query_tokens  device int32 [B, Lmax]; row b holds lengths[b] token ids, then padding that is never read
- *   lengths       HOST int32 [B]; 1 <= lengths[b] <= Lmax, lengths[b] + 1 <= max_seq
+ *   lengths       HOST int32 [B]; 1 <= lengths[b] <= min(Lmax, max_seq)
  *   sampling      host struct, copied; stays in force for the following decode steps
  *   tok_out       device int32 [B]; logprob_out device float [B]
  * Errors: E_INVALID (NULL, B or lengths out of range, a token id outside [0, vocab)),
@@ -144,6 +144,22 @@ int rlhf_gen_get_logits(rlhf_gen_ctx* ctx, float* out);
 /* Timing of the last rlhf_gen_generate on this context, measured with HIP events on cfg.stream:
  * prefill_ms, decode_ms (all decode steps together) and the number of decode steps. */
 int rlhf_gen_last_timing(const rlhf_gen_ctx* ctx, float* prefill_ms, float* decode_ms, int32_t* decode_steps);
+
+/* Per-kernel timing of the decode loop, for roofline reports.  With every > 0, rlhf_gen_generate runs decode
+ * step t kernel by kernel (instead of replaying its graph) whenever t % every == 0 and brackets each kernel with
+ * HIP events on cfg.stream; at most 16 steps per call are sampled.  every = 0 switches it off.  Counters
+ * accumulate over calls until the next rlhf_gen_set_profile.  Only the bf16 weight-streaming decode path is
+ * instrumented. */
+enum {
+  RLHF_GEN_PROF_EMBED = 0, RLHF_GEN_PROF_NORM, RLHF_GEN_PROF_GEMM_QKV, RLHF_GEN_PROF_ROPE, RLHF_GEN_PROF_ATTN,
+  RLHF_GEN_PROF_GEMM_WO, RLHF_GEN_PROF_GEMM_GATE_UP, RLHF_GEN_PROF_SWIGLU, RLHF_GEN_PROF_GEMM_DOWN,
+  RLHF_GEN_PROF_LM_HEAD, RLHF_GEN_PROF_SAMPLER, RLHF_GEN_PROF_CLASSES
+};
+int rlhf_gen_set_profile(rlhf_gen_ctx* ctx, int32_t every);
+/* ms[RLHF_GEN_PROF_CLASSES]: summed kernel time per class over the sampled steps; launches[...]: kernels timed;
+ * *attn_tokens: sum over sampled steps and sequences of the cached tokens one attention launch read per KV head;
+ * *steps: sampled steps.  Host pointers, any may be NULL. */
+int rlhf_gen_get_profile(const rlhf_gen_ctx* ctx, double* ms, int64_t* launches, int64_t* attn_tokens, int32_t* steps);
 
 /* Message of the last failed call on ctx (or of the last failed rlhf_gen_init if ctx is NULL).
  * The pointer stays valid until the next call on the same context. */

@@ -23,9 +23,12 @@ FLAG_SHUFFLE_BLOCKS, FLAG_NO_GRAPH, FLAG_GENERIC_GEMM = 1, 2, 4
 GEMM_TILED, GEMM_STREAMING, GEMM_FP32 = 0, 1, 2
 EPI_STORE_F32, EPI_RESID_F32, EPI_SWIGLU, EPI_STORE_BF16 = 0, 1, 2, 3
 
+PROF_CLASSES = ["embed", "norm", "gemm_qkv", "rope_append", "attn_decode", "gemm_wo", "gemm_gate_up", "swiglu",
+                "gemm_down", "lm_head", "sampler"]
+
 EXPORTS = [
     "rlhf_gen_init", "rlhf_gen_prefill", "rlhf_gen_decode_step", "rlhf_gen_generate", "rlhf_gen_get_logits",
-    "rlhf_gen_last_timing", "rlhf_gen_last_error", "rlhf_gen_destroy",
+    "rlhf_gen_last_timing", "rlhf_gen_set_profile", "rlhf_gen_get_profile", "rlhf_gen_last_error", "rlhf_gen_destroy",
     "rlhf_gen_op_gemm", "rlhf_gen_op_rope_append", "rlhf_gen_op_attn_decode", "rlhf_gen_op_attn_prefill",
     "rlhf_gen_op_sample",
 ]
@@ -75,13 +78,16 @@ def lib() -> C.CDLL:
                                         C.POINTER(Sampling), C.c_void_p, C.c_void_p]
         L.rlhf_gen_get_logits.argtypes = [C.c_void_p, C.c_void_p]
         L.rlhf_gen_last_timing.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_int32)]
+        L.rlhf_gen_set_profile.argtypes = [C.c_void_p, C.c_int32]
+        L.rlhf_gen_get_profile.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_int64),
+                                           C.POINTER(C.c_int32)]
         L.rlhf_gen_last_error.argtypes = [C.c_void_p]
         L.rlhf_gen_last_error.restype = C.c_char_p
         L.rlhf_gen_destroy.argtypes = [C.c_void_p]
         L.rlhf_gen_destroy.restype = None
         L.rlhf_gen_op_gemm.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                        C.c_int32, C.c_int32, C.c_int32]
-        L.rlhf_gen_op_rope_append.argtypes = [C.c_void_p] * 10 + [C.c_int32] * 6
+        L.rlhf_gen_op_rope_append.argtypes = [C.c_void_p] * 9 + [C.c_int32] * 6
         L.rlhf_gen_op_attn_decode.argtypes = [C.c_void_p] * 4 + [C.c_int32, C.c_void_p, C.c_void_p] + [C.c_int32] * 3
         L.rlhf_gen_op_attn_prefill.argtypes = [C.c_void_p] * 4 + [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p] + [C.c_int32] * 4
         L.rlhf_gen_op_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.POINTER(Sampling), C.c_void_p,
@@ -147,8 +153,8 @@ class Context:
         return tok, lp
 
     def rlhf_gen_decode_step(self, forced_tokens: Optional[torch.Tensor] = None):
-        tok = torch.empty(self.B, dtype=torch.int32, device=self.device)
-        lp = torch.empty(self.B, dtype=torch.float32, device=self.device)
+        tok = torch.empty(max(self.B, 1), dtype=torch.int32, device=self.device)
+        lp = torch.empty(max(self.B, 1), dtype=torch.float32, device=self.device)
         self.stream.wait_stream(torch.cuda.current_stream(self.device))
         _check(self._h, lib().rlhf_gen_decode_step(self._h, _ptr(forced_tokens), _ptr(tok), _ptr(lp)))
         return tok, lp
@@ -176,6 +182,17 @@ class Context:
         a, b, n = C.c_float(), C.c_float(), C.c_int32()
         _check(self._h, lib().rlhf_gen_last_timing(self._h, C.byref(a), C.byref(b), C.byref(n)))
         return a.value, b.value, n.value
+
+    def rlhf_gen_set_profile(self, every: int) -> None:
+        _check(self._h, lib().rlhf_gen_set_profile(self._h, every))
+
+    def rlhf_gen_get_profile(self):
+        ms = (C.c_double * len(PROF_CLASSES))()
+        n = (C.c_int64 * len(PROF_CLASSES))()
+        tok, steps = C.c_int64(), C.c_int32()
+        _check(self._h, lib().rlhf_gen_get_profile(self._h, ms, n, C.byref(tok), C.byref(steps)))
+        return {"ms": dict(zip(PROF_CLASSES, list(ms))), "launches": dict(zip(PROF_CLASSES, list(n))),
+                "attn_tokens": tok.value, "steps": steps.value}
 
     def synchronize(self) -> None:
         self.stream.synchronize()

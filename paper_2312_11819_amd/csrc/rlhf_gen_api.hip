@@ -67,6 +67,17 @@ struct rlhf_gen_ctx {
   SamplerParams sp{};
   std::string err;
 
+  // optional per-kernel timing of sampled decode steps (rlhf_gen_set_profile)
+  int prof_every = 0;
+  bool prof_on = false;            // the step being enqueued is a sampled one
+  std::vector<hipEvent_t> prof_ev;  // event pool
+  std::vector<int> prof_cls;        // prof_cls[i] = class of the kernel that ends at event i (-1: start marker)
+  int prof_used = 0;
+  long long prof_attn_tokens = 0;   // cached tokens read by the sampled attention launches (per layer, per KV head)
+  int prof_steps = 0;
+  double prof_ms[RLHF_GEN_PROF_CLASSES] = {0};
+  long long prof_n[RLHF_GEN_PROF_CLASSES] = {0};
+
   hipGraphExec_t graph_exec = nullptr;
   GraphKey graph_key;
   hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
@@ -158,6 +169,13 @@ int check_launch(rlhf_gen_ctx* c, hipError_t e, const char* what) {
     if (r_ != RLHF_GEN_OK) return r_;                \
   } while (0)
 
+// Record the end of a kernel of class `cls` (or a start marker, cls = -1) when the step is being profiled.
+void prof_mark(rlhf_gen_ctx* c, int cls) {
+  if (!c->prof_on || c->prof_used >= (int)c->prof_ev.size()) return;
+  if (hipEventRecord(c->prof_ev[c->prof_used], c->stream) != hipSuccess) return;
+  c->prof_cls[c->prof_used++] = cls;
+}
+
 struct RowSet {
   int M = 0;
   const int* ids = nullptr;      // device [M] token ids
@@ -231,30 +249,43 @@ int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
   const int d = g.d_model, Hq = g.n_heads, Hkv = g.n_kv_heads, h = g.head_dim, F = g.d_ffn;
   const int qkv_w = (Hq + 2 * Hkv) * h;
   hipStream_t s = c->stream;
+  prof_mark(c, -1);
   LAUNCH(c, launch_embed(s, c->d_cur_tok, c->tok_emb, 1, c->x, B, d, g.vocab, c->d_err), "embed");
+  prof_mark(c, RLHF_GEN_PROF_EMBED);
   int pending = 0;  // split count of the down-projection partial sums not yet added to x
   for (int l = 0; l < g.n_layers; ++l) {
     char* pool = c->kv_pool + (size_t)l * c->layer_pool_bytes;
     LAUNCH(c, launch_rmsnorm(s, c->x, pending ? c->part : nullptr, pending, (size_t)B * d, c->attn_norm[l], 1, c->y, 1,
                              B, d, g.rms_eps, nullptr), "rmsnorm");
+    prof_mark(c, RLHF_GEN_PROF_NORM);
     LAUNCH(c, launch_gemm_skinny_bf16(s, c->y, c->wqkv[l], c->part, B, qkv_w, d, c->ks_qkv), "gemm_skinny qkv");
+    prof_mark(c, RLHF_GEN_PROF_GEMM_QKV);
     size_t st = (size_t)B * qkv_w;
     LAUNCH(c, launch_rope_append(s, c->part, c->ks_qkv > 1 ? c->part + st : nullptr, c->ks_qkv - 1, st, c->d_seq_len,
                                  nullptr, c->d_cos, c->d_sin, c->qb, pool, c->d_table, c->max_blocks, B, Hq, Hkv, h, 1),
            "rope_append");
+    prof_mark(c, RLHF_GEN_PROF_ROPE);
     LAUNCH(c, launch_attn_decode_bf16(s, c->qb, pool, c->d_table, c->max_blocks, c->d_seq_len, c->ab, B, Hq, Hkv),
            "attn_decode");
+    prof_mark(c, RLHF_GEN_PROF_ATTN);
     LAUNCH(c, launch_gemm_skinny_bf16(s, c->ab, c->wo[l], c->part, B, d, Hq * h, c->ks_wo), "gemm_skinny wo");
+    prof_mark(c, RLHF_GEN_PROF_GEMM_WO);
     LAUNCH(c, launch_rmsnorm(s, c->x, c->part, c->ks_wo, (size_t)B * d, c->ffn_norm[l], 1, c->y, 1, B, d, g.rms_eps,
                              nullptr), "rmsnorm");
+    prof_mark(c, RLHF_GEN_PROF_NORM);
     LAUNCH(c, launch_gemm_skinny_bf16(s, c->y, c->w_gate_up[l], c->part, B, 2 * F, d, c->ks_gu), "gemm_skinny gate_up");
+    prof_mark(c, RLHF_GEN_PROF_GEMM_GATE_UP);
     LAUNCH(c, launch_swiglu(s, c->part, c->ks_gu, (size_t)B * 2 * F, c->hb, 1, B, F), "swiglu");
+    prof_mark(c, RLHF_GEN_PROF_SWIGLU);
     LAUNCH(c, launch_gemm_skinny_bf16(s, c->hb, c->w_down[l], c->part, B, d, F, c->ks_down), "gemm_skinny down");
+    prof_mark(c, RLHF_GEN_PROF_GEMM_DOWN);
     pending = c->ks_down;
   }
   LAUNCH(c, launch_rmsnorm(s, c->x, pending ? c->part : nullptr, pending, (size_t)B * d, c->final_norm, 1, c->yl, 1, B,
                            d, g.rms_eps, nullptr), "final rmsnorm");
+  prof_mark(c, RLHF_GEN_PROF_NORM);
   LAUNCH(c, launch_gemm_skinny_bf16(s, c->yl, c->lm_head, c->logits, B, g.vocab, d, 1), "gemm_skinny lm_head");
+  prof_mark(c, RLHF_GEN_PROF_LM_HEAD);
   return RLHF_GEN_OK;
 }
 
@@ -285,6 +316,7 @@ int enqueue_decode_body(rlhf_gen_ctx* c, int* tok_out, float* lp_out, int stride
   LAUNCH(c, launch_sampler(c->stream, c->logits, B, g.vocab, c->sp, c->d_step, stride, use_col, tok_out, lp_out,
                            c->d_cur_tok), "sampler");
   LAUNCH(c, launch_advance(c->stream, c->d_seq_len, c->d_step, B), "advance");
+  prof_mark(c, RLHF_GEN_PROF_SAMPLER);
   return RLHF_GEN_OK;
 }
 
@@ -685,11 +717,19 @@ int rlhf_gen_generate(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_
   for (int t = 1; t < R; ++t) {
     rc = decode_checks(c);  // pages were reserved by prefill: never allocates here
     if (rc) return rc;
-    if (use_graph) {
+    const bool sampled = c->prof_every > 0 && t % c->prof_every == 0 && use_streaming(c, B) &&
+                         c->prof_used + 16 * c->cfg.n_layers + 16 <= (int)c->prof_ev.size();
+    if (use_graph && !sampled) {
       HIP_TRY(c, hipGraphLaunch(c->graph_exec, s));
     } else {
+      c->prof_on = sampled;
       rc = enqueue_decode_body(c, resp_tokens, resp_logprobs, R, 1);
+      c->prof_on = false;
       if (rc) return rc;
+      if (sampled) {
+        for (int b = 0; b < B; ++b) c->prof_attn_tokens += c->h_len[b] + 1;
+        c->prof_steps++;
+      }
     }
     after_step(c);
   }
@@ -699,6 +739,15 @@ int rlhf_gen_generate(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_
   HIP_TRY(c, hipEventElapsedTime(&c->prefill_ms, c->ev[0], c->ev[1]));
   HIP_TRY(c, hipEventElapsedTime(&c->decode_ms, c->ev[1], c->ev[2]));
   c->decode_steps = R - 1;
+  for (int i = 1; i < c->prof_used; ++i) {
+    if (c->prof_cls[i] < 0) continue;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, c->prof_ev[i - 1], c->prof_ev[i]) == hipSuccess) {
+      c->prof_ms[c->prof_cls[i]] += ms;
+      c->prof_n[c->prof_cls[i]]++;
+    }
+  }
+  c->prof_used = 0;
   if (c->h_misc[2]) return fail(c, RLHF_GEN_E_INVALID, "a token id outside [0, vocab) reached the embedding");
   return RLHF_GEN_OK;
 }
@@ -719,6 +768,39 @@ int rlhf_gen_last_timing(const rlhf_gen_ctx* c, float* prefill_ms, float* decode
   return RLHF_GEN_OK;
 }
 
+int rlhf_gen_set_profile(rlhf_gen_ctx* c, int32_t every) {
+  if (!c) return RLHF_GEN_E_INVALID;
+  if (every < 0) return fail(c, RLHF_GEN_E_INVALID, "every must not be negative");
+  HIP_TRY(c, hipSetDevice(c->cfg.device));
+  c->prof_every = every;
+  c->prof_used = 0;
+  c->prof_attn_tokens = 0;
+  c->prof_steps = 0;
+  for (int i = 0; i < RLHF_GEN_PROF_CLASSES; ++i) { c->prof_ms[i] = 0; c->prof_n[i] = 0; }
+  if (every > 0 && c->prof_ev.empty()) {
+    const int want = 16 * (16 * c->cfg.n_layers + 16);  // up to 16 sampled steps per generate
+    c->prof_ev.reserve(want);
+    for (int i = 0; i < want; ++i) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) break;
+      c->prof_ev.push_back(e);
+    }
+    c->prof_cls.assign(c->prof_ev.size(), -1);
+  }
+  return RLHF_GEN_OK;
+}
+
+int rlhf_gen_get_profile(const rlhf_gen_ctx* c, double* ms, int64_t* launches, int64_t* attn_tokens, int32_t* steps) {
+  if (!c) return RLHF_GEN_E_INVALID;
+  for (int i = 0; i < RLHF_GEN_PROF_CLASSES; ++i) {
+    if (ms) ms[i] = c->prof_ms[i];
+    if (launches) launches[i] = c->prof_n[i];
+  }
+  if (attn_tokens) *attn_tokens = c->prof_attn_tokens;
+  if (steps) *steps = c->prof_steps;
+  return RLHF_GEN_OK;
+}
+
 const char* rlhf_gen_last_error(const rlhf_gen_ctx* c) { return c ? c->err.c_str() : g_init_error.c_str(); }
 
 void rlhf_gen_destroy(rlhf_gen_ctx* c) {
@@ -732,6 +814,7 @@ void rlhf_gen_destroy(rlhf_gen_ctx* c) {
     if (p) (void)hipHostFree(p);
   for (int i = 0; i < 3; ++i)
     if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
+  for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
   if (c->own_stream && c->stream) (void)hipStreamDestroy(c->stream);
   delete c;
 }
