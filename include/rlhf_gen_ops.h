@@ -26,7 +26,8 @@ enum { RLHF_GEN_EPI_STORE_F32 = 0, RLHF_GEN_EPI_RESID_F32 = 1, RLHF_GEN_EPI_SWIG
  *             SWIGLU where W is [2N, K] (gate rows then up rows) and out is bf16 [M,N] = silu(gate) * up.
  *             N % 256 == 0 (N % 128 for SWIGLU), K % 64 == 0.
  *   STREAMING bf16 A and W, M <= 256, N % 64 == 0, K % 128 == 0; out is fp32 [nsplit, M, N] partial sums whose
- *             sum over the first axis is the product.  nsplit in [1, K/128].
+ *             sum over the first axis is the product.  nsplit in [1, K/128].  With epilogue SWIGLU instead: W is
+ *             [2N, K] (gate rows then up rows), N % 32 == 0, no split, out is bf16 [M, N] = silu(gate) * up.
  *   FP32      fp32 A, W, out; epilogue STORE_F32 or RESID_F32. */
 int rlhf_gen_op_gemm(void* stream, int kind, const void* A, const void* W, void* out, int32_t M, int32_t N, int32_t K,
                      int32_t epilogue, int32_t nsplit);

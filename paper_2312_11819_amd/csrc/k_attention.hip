@@ -102,19 +102,25 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const bf16_t* __restri
   AttnState st;
   init_state(st);
   const int* bt = block_table + (size_t)b * max_blocks;
-  uint4 kf[4], vf[4], kn[4], vn[4];
-  int p = w;
-  if (p < npages) load_page(pool + ((size_t)bt[p] * Hkv + kvh) * KV_PAGE_BYTES, lane, kf, vf);
-  while (p < npages) {
-    int pn = p + 4;
-    if (pn < npages) load_page(pool + ((size_t)bt[pn] * Hkv + kvh) * KV_PAGE_BYTES, lane, kn, vn);
-    if (p == npages - 1)
-      attn_page<true>(kf, vf, qf, st, scale_log2, p * 16, L, g);
-    else
-      attn_page<false>(kf, vf, qf, st, scale_log2, p * 16, L, g);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { kf[i] = kn[i]; vf[i] = vn[i]; }
-    p = pn;
+  // This wavefront takes pages w, w + 4, w + 8, ...  Their block-table entries are fetched up front, 64 at a time
+  // (lane i holds the entry of page w + 4 i), and broadcast from registers inside the loop.  Page loads are issued
+  // with no branch around them (an index past the end re-reads the last page), so that the loads of the next page
+  // stay in flight while the current one is consumed.
+  const int last = npages - 1;
+  for (int base = w; base < npages; base += 256) {
+    const int mine = min(base + 4 * lane, last);
+    const int my_blk = bt[mine];
+    const int cnt = min(64, (npages - base + 3) >> 2);  // pages of this wavefront in this batch
+    uint4 ka[4], va[4], kb[4], vb[4];
+    load_page(pool + ((size_t)__shfl(my_blk, 0) * Hkv + kvh) * KV_PAGE_BYTES, lane, ka, va);
+    int i = 0;
+    for (; i + 2 <= cnt; i += 2) {
+      load_page(pool + ((size_t)__shfl(my_blk, i + 1) * Hkv + kvh) * KV_PAGE_BYTES, lane, kb, vb);
+      attn_page<true>(ka, va, qf, st, scale_log2, (base + 4 * i) * 16, L, g);
+      load_page(pool + ((size_t)__shfl(my_blk, min(i + 2, cnt - 1)) * Hkv + kvh) * KV_PAGE_BYTES, lane, ka, va);
+      attn_page<true>(kb, vb, qf, st, scale_log2, (base + 4 * (i + 1)) * 16, L, g);
+    }
+    if (i < cnt) attn_page<true>(ka, va, qf, st, scale_log2, (base + 4 * i) * 16, L, g);
   }
   float lt = st.l;
   lt += __shfl_xor(lt, 16);

@@ -5,6 +5,8 @@
 //                         straight from HBM into registers exactly once, the activation slice is staged in LDS,
 //                         split-K partial sums go to a workspace that the consumer kernel adds up in a fixed order.
 //   gemm_f32_kernel     : plain-ALU fp32 GEMM for the small fp32 configuration.
+#include <stdlib.h>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -167,14 +169,20 @@ constexpr int SK = 128;                 // k extent of one staged activation sli
 constexpr int SK_ROW = SK * 2 + 16;     // bytes per LDS row (padded)
 
 // grid (Nw / 64, nsplit), 256 threads; wavefront w owns W rows n0 + 16 w .. +16 and all M (<= 16 MB) columns.
-template <int MB>
+// Loads run D - 1 k-steps ahead of the MFMAs through a register ring (weights and the activation slice alike:
+// the memory counter retires in order, so both must share one prefetch distance); the activation slice then
+// passes through a double-buffered LDS tile that the four wavefronts share.
+template <int MB, int D, bool GLU = false>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W,
                                                           float* __restrict__ part, int M, int Nw, int K,
                                                           int steps_per_split) {
+  static_assert(D == 2 || D == 4, "ring depth 2 or 4");
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int XBYTES = 16 * MB * SK_ROW;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, t = lane & 15, g = lane >> 4;
-  const int n0 = blockIdx.x * 64;
+  // GLU: W = [gate rows | up rows] of F = Nw / 2 features each; the workgroup owns 32 features, each wavefront
+  // 8 of them with the gate rows in MFMA rows 0..7 and the matching up rows in 8..15.
+  const int n0 = GLU ? blockIdx.x * 32 : blockIdx.x * 64;
   const int nsteps_total = K / SK;
   const int s0 = blockIdx.y * steps_per_split;
   const int s1 = min(nsteps_total, s0 + steps_per_split);
@@ -183,48 +191,115 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
 #pragma unroll
   for (int i = 0; i < MB; ++i) acc[i] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
-  const bf16_t* wp = W + (size_t)(n0 + 16 * w + t) * K + 8 * g;
-  // activation slice: 16 MB rows x 16 chunks of 16 B; thread handles MB chunks
+  const int wrow = GLU ? ((t < 8) ? n0 + 8 * w + t : (Nw >> 1) + n0 + 8 * w + (t - 8)) : n0 + 16 * w + t;
+  const bf16_t* wp = W + (size_t)wrow * K + 8 * g;
+  // Activation slice: 16 MB rows x 16 chunks of 16 B per k-step, MB chunks per thread.  Rows beyond M are read
+  // from row M - 1 instead: they only feed output columns that are never stored.
   const bf16_t* xp[MB];
   int xo[MB];
-  bool xv[MB];
 #pragma unroll
   for (int it = 0; it < MB; ++it) {
     int c = it * 256 + tid, r = c >> 4, kc = c & 15;
-    xv[it] = r < M;
-    xp[it] = X + (size_t)(xv[it] ? r : 0) * K + kc * 8;
+    xp[it] = X + (size_t)min(r, M - 1) * K + kc * 8;
     xo[it] = r * SK_ROW + kc * 16;
   }
-  uint4 wa[4], wb[4], xr[MB];
-  if (s0 < s1) {
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) wa[kk] = *(const uint4*)(wp + (size_t)s0 * SK + kk * 32);
-#pragma unroll
-    for (int it = 0; it < MB; ++it)
-      xr[it] = xv[it] ? *(const uint4*)(xp[it] + (size_t)s0 * SK) : make_uint4(0, 0, 0, 0);
+  // Workgroups walk their k range from different starting points (wrapping around), so that they do not all
+  // touch the same columns of W at the same time.
+  const int nst = s1 - s0;
+  const int rot = nst > 0 ? (int)((blockIdx.x * 5u + blockIdx.y * 3u) % (unsigned)nst) : 0;
+  // Loads are issued without any branch around them (a step index past the end re-reads the last step, which
+  // hits in cache): with straight-line code the compiler can keep D - 1 steps of loads in flight and wait only
+  // for the oldest.
+  auto step_off = [&](int i) -> size_t {
+    int r = min(i, nst - 1) + rot;
+    if (r >= nst) r -= nst;
+    return (size_t)(s0 + r) * SK;
+  };
+  // Ring of D named slots (separate variables, so that they live in registers).
+  struct Slot { uint4 w[4]; uint4 x[MB]; };
+  Slot r0, r1, r2, r3;
+#define SKINNY_LOAD(S, I)                                                                                \
+  {                                                                                                      \
+    const size_t ko = step_off(I);                                                                       \
+    _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) S.w[kk] = *(const uint4*)(wp + ko + kk * 32);       \
+    _Pragma("unroll") for (int it = 0; it < MB; ++it) S.x[it] = *(const uint4*)(xp[it] + ko);            \
   }
-  for (int st = s0; st < s1; ++st) {
-    char* buf = smem + ((st - s0) & 1) * XBYTES;
-#pragma unroll
-    for (int it = 0; it < MB; ++it) *(uint4*)(buf + xo[it]) = xr[it];
-    __syncthreads();
-    if (st + 1 < s1) {
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) wb[kk] = *(const uint4*)(wp + (size_t)(st + 1) * SK + kk * 32);
-#pragma unroll
-      for (int it = 0; it < MB; ++it)
-        xr[it] = xv[it] ? *(const uint4*)(xp[it] + (size_t)(st + 1) * SK) : make_uint4(0, 0, 0, 0);
+  // one k-step on slot S (LDS buffer PAR)
+#define SKINNY_STEP(S, PAR)                                                                              \
+  {                                                                                                      \
+    char* buf = smem + (PAR) * XBYTES;                                                                   \
+    _Pragma("unroll") for (int it = 0; it < MB; ++it) *(uint4*)(buf + xo[it]) = S.x[it];                 \
+    __syncthreads();                                                                                     \
+    uint4 xf[2][MB];                                                                                     \
+    _Pragma("unroll") for (int mb = 0; mb < MB; ++mb)                                                    \
+        xf[0][mb] = *(const uint4*)(buf + (mb * 16 + t) * SK_ROW + g * 16);                              \
+    _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                                   \
+      if (kk < 3) {                                                                                      \
+        _Pragma("unroll") for (int mb = 0; mb < MB; ++mb)                                                \
+            xf[(kk + 1) & 1][mb] = *(const uint4*)(buf + (mb * 16 + t) * SK_ROW + (kk + 1) * 64 + g * 16); \
+      }                                                                                                  \
+      _Pragma("unroll") for (int mb = 0; mb < MB; ++mb)                                                  \
+          acc[mb] = mfma_16x16x32(S.w[kk], xf[kk & 1][mb], acc[mb]);                                     \
+    }                                                                                                    \
+  }
+  if (nst > 0) {
+    int i = 0;
+    if constexpr (D == 4) {
+      SKINNY_LOAD(r0, 0)
+      SKINNY_LOAD(r1, 1)
+      SKINNY_LOAD(r2, 2)
+      for (; i + 4 <= nst; i += 4) {
+        SKINNY_LOAD(r3, i + 3)
+        SKINNY_STEP(r0, 0)
+        SKINNY_LOAD(r0, i + 4)
+        SKINNY_STEP(r1, 1)
+        SKINNY_LOAD(r1, i + 5)
+        SKINNY_STEP(r2, 0)
+        SKINNY_LOAD(r2, i + 6)
+        SKINNY_STEP(r3, 1)
+      }
+      if (i < nst) {
+        SKINNY_STEP(r0, 0)
+        if (i + 1 < nst) {
+          SKINNY_STEP(r1, 1)
+          if (i + 2 < nst) SKINNY_STEP(r2, 0)
+        }
+      }
+    } else {
+      SKINNY_LOAD(r0, 0)
+      for (; i + 2 <= nst; i += 2) {
+        SKINNY_LOAD(r1, i + 1)
+        SKINNY_STEP(r0, 0)
+        SKINNY_LOAD(r0, i + 2)
+        SKINNY_STEP(r1, 1)
+      }
+      if (i < nst) SKINNY_STEP(r0, 0)
+      (void)r2; (void)r3;
     }
+  }
+#undef SKINNY_STEP
+#undef SKINNY_LOAD
+  if (GLU) {
+    // lane (t, g < 2) holds gate features 4g..4g+3 of column t, lane (t, g + 2) the matching up values
+    bf16_t* hout = (bf16_t*)part;
+    const int F = Nw >> 1;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
+    for (int mb = 0; mb < MB; ++mb) {
+      float up[4];
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-        uint4 xf = *(const uint4*)(buf + (mb * 16 + t) * SK_ROW + kk * 64 + g * 16);
-        acc[mb] = mfma_16x16x32(wa[kk], xf, acc[mb]);
+      for (int i = 0; i < 4; ++i) up[i] = __shfl_xor(acc[mb][i], 32);
+      int m = mb * 16 + t;
+      if (g < 2 && m < M) {
+        float hv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) hv[i] = acc[mb][i] / (1.f + __expf(-acc[mb][i])) * up[i];
+        uint2 o;
+        o.x = pack_bf16x2(hv[0], hv[1]);
+        o.y = pack_bf16x2(hv[2], hv[3]);
+        *(uint2*)(hout + (size_t)m * F + n0 + 8 * w + 4 * g) = o;
       }
     }
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) wa[kk] = wb[kk];
+    return;
   }
   float* dst = part + (size_t)blockIdx.y * M * Nw;
 #pragma unroll
@@ -238,8 +313,17 @@ template <int MB>
 hipError_t launch_skinny(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K, int nsplit,
                          bool configure_only = false) {
   constexpr int SMEM = 2 * 16 * MB * SK_ROW;
-  auto kern = gemm_skinny_kernel<MB>;
-  if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+  constexpr int D = MB <= 4 ? 4 : 2;
+  auto kern = gemm_skinny_kernel<MB, D>;
+  if (configure_only) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute((const void*)gemm_skinny_kernel<MB, D, true>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+  }
+  if (nsplit == 0) {  // fused SwiGLU: W = [2F, K], output bf16 [M, F], no split
+    gemm_skinny_kernel<MB, D, true><<<dim3(Nw / 64, 1), 256, SMEM, s>>>((const bf16_t*)A, (const bf16_t*)W, part, M, Nw, K, K / SK);
+    return hipGetLastError();
+  }
   int steps = K / SK;
   int per = (steps + nsplit - 1) / nsplit;
   kern<<<dim3(Nw / 64, nsplit), 256, SMEM, s>>>((const bf16_t*)A, (const bf16_t*)W, part, M, Nw, K, per);
@@ -312,7 +396,7 @@ int gemm_skinny_pick_split(int M, int Nw, int K) {
 hipError_t launch_gemm_skinny_bf16(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K,
                                    int nsplit) {
   if (M <= 0) return hipSuccess;
-  if (K % SK || Nw % 64 || M > 256 || nsplit < 1) return hipErrorInvalidValue;
+  if (K % SK || Nw % 64 || M > 256 || nsplit < 0) return hipErrorInvalidValue;
   if (M <= 16) return launch_skinny<1>(s, A, W, part, M, Nw, K, nsplit);
   if (M <= 32) return launch_skinny<2>(s, A, W, part, M, Nw, K, nsplit);
   if (M <= 64) return launch_skinny<4>(s, A, W, part, M, Nw, K, nsplit);

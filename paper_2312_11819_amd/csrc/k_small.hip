@@ -61,37 +61,40 @@ hipError_t launch_embed(hipStream_t s, const int* ids, const void* table, int w_
   return hipGetLastError();
 }
 
-__device__ __forceinline__ float block_sum_256(float v, float* red) {
-  v = wave_sum(v);
-  int w = threadIdx.x >> 6;
-  if ((threadIdx.x & 63) == 0) red[w] = v;
-  __syncthreads();
-  float t = red[0] + red[1] + red[2] + red[3];
-  __syncthreads();
-  return t;
-}
-
-// One workgroup per row, d <= 8192, d % 4 == 0.  The sum of squares is taken in a fixed order, so the
-// result does not change from run to run.
-template <bool WBF16, bool ABF16>
-__global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ part, int nsplit,
-                                                      size_t part_stride, const void* __restrict__ gain,
-                                                      void* __restrict__ y, int d, float eps,
-                                                      const int* __restrict__ rows) {
-  __shared__ float red[4];
+// One workgroup of NT threads per row, d <= 8 * 4 * NT, d % 4 == 0.  The sum of squares is taken in a fixed
+// order, so the result does not change from run to run.  Partial sums are added in split order 0, 1, ...
+template <bool WBF16, bool ABF16, int NT>
+__global__ __launch_bounds__(NT) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ part, int nsplit,
+                                                     size_t part_stride, const void* __restrict__ gain,
+                                                     void* __restrict__ y, int d, float eps,
+                                                     const int* __restrict__ rows) {
+  constexpr int IT = 8192 / (4 * NT);
+  __shared__ float red[NT / 64];
   int m = blockIdx.x;
   int src = rows ? rows[m] : m;
   float* xr = x + (size_t)src * d;
-  float4 v[8];
+  float4 v[IT];
   float ss = 0.f;
 #pragma unroll
-  for (int it = 0; it < 8; ++it) {
-    int i = (it * 256 + threadIdx.x) * 4;
+  for (int it = 0; it < IT; ++it) {
+    int i = (it * NT + threadIdx.x) * 4;
     if (i < d) {
       float4 a = *(const float4*)(xr + i);
       if (nsplit > 0) {
-        for (int sidx = 0; sidx < nsplit; ++sidx) {
-          float4 p = *(const float4*)(part + sidx * part_stride + (size_t)m * d + i);
+        const float* pp = part + (size_t)m * d + i;
+        int sidx = 0;
+        for (; sidx + 4 <= nsplit; sidx += 4) {  // four independent loads in flight, added in order
+          float4 p0 = *(const float4*)(pp + (size_t)(sidx + 0) * part_stride);
+          float4 p1 = *(const float4*)(pp + (size_t)(sidx + 1) * part_stride);
+          float4 p2 = *(const float4*)(pp + (size_t)(sidx + 2) * part_stride);
+          float4 p3 = *(const float4*)(pp + (size_t)(sidx + 3) * part_stride);
+          a.x += p0.x; a.y += p0.y; a.z += p0.z; a.w += p0.w;
+          a.x += p1.x; a.y += p1.y; a.z += p1.z; a.w += p1.w;
+          a.x += p2.x; a.y += p2.y; a.z += p2.z; a.w += p2.w;
+          a.x += p3.x; a.y += p3.y; a.z += p3.z; a.w += p3.w;
+        }
+        for (; sidx < nsplit; ++sidx) {
+          float4 p = *(const float4*)(pp + (size_t)sidx * part_stride);
           a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
         }
         *(float4*)(xr + i) = a;
@@ -100,11 +103,16 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, con
       ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
     }
   }
-  float tot = block_sum_256(ss, red);
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  float tot = 0.f;
+#pragma unroll
+  for (int i = 0; i < NT / 64; ++i) tot += red[i];
   float r = rsqrtf(tot / (float)d + eps);
 #pragma unroll
-  for (int it = 0; it < 8; ++it) {
-    int i = (it * 256 + threadIdx.x) * 4;
+  for (int it = 0; it < IT; ++it) {
+    int i = (it * NT + threadIdx.x) * 4;
     if (i < d) {
       float g0, g1, g2, g3;
       if (WBF16) {
@@ -134,84 +142,84 @@ hipError_t launch_rmsnorm(hipStream_t s, float* x, const float* part, int nsplit
   if (M <= 0) return hipSuccess;
   if (d > 8192 || (d & 3)) return hipErrorInvalidValue;
   if (!part) nsplit = 0;
-  if (w_bf16 && act_bf16)
-    rmsnorm_kernel<true, true><<<M, 256, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
-  else if (!w_bf16 && !act_bf16)
-    rmsnorm_kernel<false, false><<<M, 256, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
-  else
+  const bool wide = M <= 1024 && d >= 2048;  // few rows: spread each row over 1024 threads
+  if (w_bf16 && act_bf16) {
+    if (wide) rmsnorm_kernel<true, true, 1024><<<M, 1024, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
+    else rmsnorm_kernel<true, true, 256><<<M, 256, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
+  } else if (!w_bf16 && !act_bf16) {
+    rmsnorm_kernel<false, false, 256><<<M, 256, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
+  } else {
     return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 
-// One workgroup per token row.  The rotation pairs dimension i with i + h/2 and uses the cos/sin tables
-// built on the host in double precision (cos_t[pos * h/2 + i]).  bf16 path: h = 128, keys and values go to
-// the MFMA-ordered page described in common.h.  fp32 path: page = [2][16][h] floats (keys, then values).
+// One 64-thread workgroup per (token row, head of the fused q|k|v projection), so that every load of a launch is
+// independent and in flight at once.  The rotation pairs dimension i with i + h/2 and uses the cos/sin tables built
+// on the host in double precision (cos_t[pos * h/2 + i]).  bf16 path: h = 128, keys and values go to the
+// MFMA-ordered page described in common.h.  fp32 path: page = [2][16][h] floats (keys, then values).
 template <bool ABF16>
-__global__ __launch_bounds__(256) void rope_append_kernel(const float* __restrict__ qkv, const float* __restrict__ part,
-                                                          int nsplit, size_t part_stride,
-                                                          const int* __restrict__ row_pos,
-                                                          const int* __restrict__ row_seq,
-                                                          const float* __restrict__ cos_t,
-                                                          const float* __restrict__ sin_t, void* __restrict__ q_out,
-                                                          void* __restrict__ pool, const int* __restrict__ block_table,
-                                                          int max_blocks, int Hq, int Hkv, int h) {
-  int m = blockIdx.x;
-  int pos = row_pos[m];
-  int b = row_seq ? row_seq[m] : m;
-  int half = h >> 1;
-  int width = (Hq + 2 * Hkv) * h;
-  const float* row = qkv + (size_t)m * width;
-  const float* cs = cos_t + (size_t)pos * half;
-  const float* sn = sin_t + (size_t)pos * half;
-  int blk = block_table[(size_t)b * max_blocks + (pos >> 4)];
-  int slot = pos & 15;
-  int npair = (Hq + Hkv) * half;
-  for (int p = threadIdx.x; p < npair; p += 256) {
-    int head = p / half, i = p - head * half;
-    int c0 = head * h + i, c1 = c0 + half;
-    float a = row[c0], bb = row[c1];
-    for (int sidx = 0; sidx < nsplit; ++sidx) {
-      const float* pr = part + sidx * part_stride + (size_t)m * width;
-      a += pr[c0];
-      bb += pr[c1];
-    }
-    float c = cs[i], sv = sn[i];
-    float r0 = a * c - bb * sv, r1 = bb * c + a * sv;
-    if (head < Hq) {
-      if (ABF16) {
-        bf16_t* qo = (bf16_t*)q_out + (size_t)m * Hq * h + head * h;
-        qo[i] = f32_to_bf16(r0);
-        qo[i + half] = f32_to_bf16(r1);
-      } else {
-        float* qo = (float*)q_out + (size_t)m * Hq * h + head * h;
-        qo[i] = r0;
-        qo[i + half] = r1;
+__global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict__ qkv, const float* __restrict__ part,
+                                                         int nsplit, size_t part_stride,
+                                                         const int* __restrict__ row_pos,
+                                                         const int* __restrict__ row_seq,
+                                                         const float* __restrict__ cos_t,
+                                                         const float* __restrict__ sin_t, void* __restrict__ q_out,
+                                                         void* __restrict__ pool, const int* __restrict__ block_table,
+                                                         int max_blocks, int Hq, int Hkv, int h) {
+  const int m = blockIdx.y, head = blockIdx.x;
+  const int pos = row_pos[m];
+  const int b = row_seq ? row_seq[m] : m;
+  const int half = h >> 1;
+  const int width = (Hq + 2 * Hkv) * h;
+  const float* row = qkv + (size_t)m * width + head * h;
+  const float* prow = part + (size_t)m * width + head * h;
+  const int blk = block_table[(size_t)b * max_blocks + (pos >> 4)];
+  const int slot = pos & 15;
+  if (head < Hq + Hkv) {
+    for (int i = threadIdx.x; i < half; i += 64) {
+      float a = row[i], bb = row[i + half];
+      for (int sidx = 0; sidx < nsplit; ++sidx) {
+        a += prow[sidx * part_stride + i];
+        bb += prow[sidx * part_stride + i + half];
       }
-    } else {
-      int kvh = head - Hq;
+      float c = cos_t[(size_t)pos * half + i], sv = sin_t[(size_t)pos * half + i];
+      float r0 = a * c - bb * sv, r1 = bb * c + a * sv;
+      if (head < Hq) {
+        if (ABF16) {
+          bf16_t* qo = (bf16_t*)q_out + ((size_t)m * Hq + head) * h;
+          qo[i] = f32_to_bf16(r0);
+          qo[i + half] = f32_to_bf16(r1);
+        } else {
+          float* qo = (float*)q_out + ((size_t)m * Hq + head) * h;
+          qo[i] = r0;
+          qo[i + half] = r1;
+        }
+      } else {
+        const int kvh = head - Hq;
+        if (ABF16) {
+          char* page = (char*)pool + ((size_t)blk * Hkv + kvh) * KV_PAGE_BYTES;
+          *(bf16_t*)(page + kpage_offset(slot, i)) = f32_to_bf16(r0);
+          *(bf16_t*)(page + kpage_offset(slot, i + half)) = f32_to_bf16(r1);
+        } else {
+          float* page = (float*)pool + ((size_t)blk * Hkv + kvh) * (2 * 16 * h);
+          page[slot * h + i] = r0;
+          page[slot * h + i + half] = r1;
+        }
+      }
+    }
+  } else {
+    const int kvh = head - Hq - Hkv;
+    for (int dim = threadIdx.x; dim < h; dim += 64) {
+      float v = row[dim];
+      for (int sidx = 0; sidx < nsplit; ++sidx) v += prow[sidx * part_stride + dim];
       if (ABF16) {
         char* page = (char*)pool + ((size_t)blk * Hkv + kvh) * KV_PAGE_BYTES;
-        *(bf16_t*)(page + kpage_offset(slot, i)) = f32_to_bf16(r0);
-        *(bf16_t*)(page + kpage_offset(slot, i + half)) = f32_to_bf16(r1);
+        *(bf16_t*)(page + vpage_offset(slot, dim)) = f32_to_bf16(v);
       } else {
         float* page = (float*)pool + ((size_t)blk * Hkv + kvh) * (2 * 16 * h);
-        page[slot * h + i] = r0;
-        page[slot * h + i + half] = r1;
+        page[16 * h + slot * h + dim] = v;
       }
-    }
-  }
-  int nv = Hkv * h;
-  const float* vrow = row + (Hq + Hkv) * h;
-  for (int p = threadIdx.x; p < nv; p += 256) {
-    int kvh = p / h, dim = p - kvh * h;
-    float v = vrow[p];
-    for (int sidx = 0; sidx < nsplit; ++sidx) v += part[sidx * part_stride + (size_t)m * width + (Hq + Hkv) * h + p];
-    if (ABF16) {
-      char* page = (char*)pool + ((size_t)blk * Hkv + kvh) * KV_PAGE_BYTES;
-      *(bf16_t*)(page + vpage_offset(slot, dim)) = f32_to_bf16(v);
-    } else {
-      float* page = (float*)pool + ((size_t)blk * Hkv + kvh) * (2 * 16 * h);
-      page[16 * h + slot * h + dim] = v;
     }
   }
 }
@@ -221,14 +229,15 @@ hipError_t launch_rope_append(hipStream_t s, const float* qkv, const float* part
                               void* q_out, void* kv_pool_layer, const int* block_table, int max_blocks, int M, int Hq,
                               int Hkv, int h, int act_bf16) {
   if (M <= 0) return hipSuccess;
-  if (!part) nsplit = 0;
+  if (!part) { nsplit = 0; part = qkv; }
+  dim3 grid(Hq + 2 * Hkv, M);
   if (act_bf16) {
     if (h != KV_HEAD_DIM) return hipErrorInvalidValue;
-    rope_append_kernel<true><<<M, 256, 0, s>>>(qkv, part, nsplit, part_stride, row_pos, row_seq, cos_t, sin_t, q_out,
-                                               kv_pool_layer, block_table, max_blocks, Hq, Hkv, h);
+    rope_append_kernel<true><<<grid, 64, 0, s>>>(qkv, part, nsplit, part_stride, row_pos, row_seq, cos_t, sin_t, q_out,
+                                                 kv_pool_layer, block_table, max_blocks, Hq, Hkv, h);
   } else {
-    rope_append_kernel<false><<<M, 256, 0, s>>>(qkv, part, nsplit, part_stride, row_pos, row_seq, cos_t, sin_t, q_out,
-                                                kv_pool_layer, block_table, max_blocks, Hq, Hkv, h);
+    rope_append_kernel<false><<<grid, 64, 0, s>>>(qkv, part, nsplit, part_stride, row_pos, row_seq, cos_t, sin_t, q_out,
+                                                  kv_pool_layer, block_table, max_blocks, Hq, Hkv, h);
   }
   return hipGetLastError();
 }

@@ -15,7 +15,8 @@ enum GemmEpilogue {
 // K % 64 == 0; rows of A beyond M are never read.
 hipError_t launch_gemm_bf16(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K, int epi);
 // Weight-streaming GEMM for M <= 256 rows: writes fp32 partial sums part[ks][M][Nw] (Nw = rows of W)
-// for ks < nsplit; the consumer kernel adds them.  Returns the nsplit it used through *nsplit_out.
+// for ks < nsplit; the consumer kernel adds them.  nsplit = 0 selects the fused SwiGLU form: W = [2F, K]
+// (gate rows, then up rows; Nw = 2F), no split, and `part` receives bf16 [M, F] = silu(gate) * up.
 hipError_t launch_gemm_skinny_bf16(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K,
                                    int nsplit);
 int gemm_skinny_pick_split(int M, int Nw, int K);

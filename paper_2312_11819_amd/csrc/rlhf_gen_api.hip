@@ -273,10 +273,8 @@ int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
     LAUNCH(c, launch_rmsnorm(s, c->x, c->part, c->ks_wo, (size_t)B * d, c->ffn_norm[l], 1, c->y, 1, B, d, g.rms_eps,
                              nullptr), "rmsnorm");
     prof_mark(c, RLHF_GEN_PROF_NORM);
-    LAUNCH(c, launch_gemm_skinny_bf16(s, c->y, c->w_gate_up[l], c->part, B, 2 * F, d, c->ks_gu), "gemm_skinny gate_up");
+    LAUNCH(c, launch_gemm_skinny_bf16(s, c->y, c->w_gate_up[l], (float*)c->hb, B, 2 * F, d, 0), "gemm_skinny gate_up");
     prof_mark(c, RLHF_GEN_PROF_GEMM_GATE_UP);
-    LAUNCH(c, launch_swiglu(s, c->part, c->ks_gu, (size_t)B * 2 * F, c->hb, 1, B, F), "swiglu");
-    prof_mark(c, RLHF_GEN_PROF_SWIGLU);
     LAUNCH(c, launch_gemm_skinny_bf16(s, c->hb, c->w_down[l], c->part, B, d, F, c->ks_down), "gemm_skinny down");
     prof_mark(c, RLHF_GEN_PROF_GEMM_DOWN);
     pending = c->ks_down;
@@ -826,7 +824,8 @@ int rlhf_gen_op_gemm(void* stream, int kind, const void* A, const void* W, void*
   hipError_t e;
   if (!A || !W || !out || M < 1 || N < 1 || K < 1) return RLHF_GEN_E_INVALID;
   if (kind == RLHF_GEN_GEMM_TILED) e = launch_gemm_bf16(s, A, W, out, M, N, K, epilogue);
-  else if (kind == RLHF_GEN_GEMM_STREAMING) e = launch_gemm_skinny_bf16(s, A, W, (float*)out, M, N, K, nsplit);
+  else if (kind == RLHF_GEN_GEMM_STREAMING)
+    e = launch_gemm_skinny_bf16(s, A, W, (float*)out, M, epilogue == EPI_SWIGLU ? 2 * N : N, K, epilogue == EPI_SWIGLU ? 0 : nsplit);
   else if (kind == RLHF_GEN_GEMM_FP32) e = launch_gemm_f32(s, (const float*)A, (const float*)W, (float*)out, M, N, K, epilogue == EPI_RESID_F32);
   else return RLHF_GEN_E_INVALID;
   if (e == hipErrorInvalidValue) return RLHF_GEN_E_UNSUPPORTED;

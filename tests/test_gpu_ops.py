@@ -67,6 +67,18 @@ def test_gemm_streaming(B, M, N, K, ns):
     assert (got - ref).abs().max() < 1e-5 * math.sqrt(K) + 1e-6
 
 
+@pytest.mark.parametrize("M,F,K", [(64, 352, 256), (5, 32, 128), (200, 96, 512)])
+def test_gemm_streaming_swiglu(B, M, F, K):
+    a, w = _rand((M, K), 13), _rand((2 * F, K), 14, 0.1)
+    gu = a.double() @ w.double().T
+    ref = OT.silu(gu[:, :F]) * gu[:, F:]
+    out = torch.zeros((M, F), dtype=torch.bfloat16, device="cuda")
+    assert B.rlhf_gen_op_gemm(B.GEMM_STREAMING, a.cuda(), w.cuda(), out, M, F, K, B.EPI_SWIGLU, 1) == 0
+    torch.cuda.synchronize()
+    err = (out.cpu().double() - ref).abs()
+    assert (err <= ref.abs() * 2 ** -8 + 1e-4).all()
+
+
 def test_gemm_fp32(B):
     M, N, K = 37, 344, 128
     a, w = _rand((M, K), 7, 1.0, torch.float32), _rand((N, K), 8, 0.05, torch.float32)
