@@ -52,22 +52,20 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(c
     return tn * BN + r;
   };
 
-  const bf16_t* a_ptr[A_IT];
-  const bf16_t* b_ptr[B_IT];
-  int a_off[A_IT], b_off[B_IT];
+  // 32-bit byte offsets from the (scalar) operand bases keep the address registers few
+  uint32_t a_go[A_IT], b_go[B_IT];
+  const int ld_r = tid >> 3, ld_kc = tid & 7;       // chunk c = it * NT + tid -> row it * (NT / 8) + ld_r, k chunk ld_kc
 #pragma unroll
   for (int it = 0; it < A_IT; ++it) {
-    int c = it * NT + tid, r = c >> 3, kc = c & 7;
-    int gr = min(m0 + r, M - 1);
-    a_ptr[it] = A + (size_t)gr * K + kc * 8;
-    a_off[it] = r * LDS_ROW + kc * 16;
+    int r = it * (NT / 8) + ld_r;
+    a_go[it] = (uint32_t)min(m0 + r, M - 1) * (uint32_t)K * 2u + ld_kc * 16;
   }
 #pragma unroll
   for (int it = 0; it < B_IT; ++it) {
-    int c = it * NT + tid, r = c >> 3, kc = c & 7;
-    b_ptr[it] = W + (size_t)wrow(r) * K + kc * 8;
-    b_off[it] = BM * LDS_ROW + r * LDS_ROW + kc * 16;
+    int r = it * (NT / 8) + ld_r;
+    b_go[it] = (uint32_t)wrow(r) * (uint32_t)K * 2u + ld_kc * 16;
   }
+  const int st_off = ld_r * LDS_ROW + ld_kc * 16;   // LDS byte offset of this thread's chunk in row block 0
 
   f32x16_t acc[MI][NI];
 #pragma unroll
@@ -77,50 +75,63 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(c
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  uint4 ra[A_IT], rb[B_IT];
+  // Global loads run two k-tiles ahead of the MFMAs: a ring of two register slots feeds the double-buffered LDS
+  // tile.  No branch surrounds a load (a tile index past the end re-reads the last tile), so the compiler can
+  // keep both slots in flight and wait only for the older one.
+  struct Slot { uint4 a[A_IT]; uint4 b[B_IT]; };
+  Slot r0, r1;
   const int nk = K / BK;
-#pragma unroll
-  for (int it = 0; it < A_IT; ++it) ra[it] = *(const uint4*)(a_ptr[it]);
-#pragma unroll
-  for (int it = 0; it < B_IT; ++it) rb[it] = *(const uint4*)(b_ptr[it]);
-#pragma unroll
-  for (int it = 0; it < A_IT; ++it) *(uint4*)(smem + a_off[it]) = ra[it];
-#pragma unroll
-  for (int it = 0; it < B_IT; ++it) *(uint4*)(smem + b_off[it]) = rb[it];
-  __syncthreads();
-
+#define G_LOAD(S, KT)                                                                                   \
+  {                                                                                                     \
+    const char* ab = (const char*)A + (size_t)min((KT), nk - 1) * (BK * 2);                             \
+    const char* wb = (const char*)W + (size_t)min((KT), nk - 1) * (BK * 2);                             \
+    _Pragma("unroll") for (int it = 0; it < A_IT; ++it) S.a[it] = *(const uint4*)(ab + a_go[it]);       \
+    _Pragma("unroll") for (int it = 0; it < B_IT; ++it) S.b[it] = *(const uint4*)(wb + b_go[it]);       \
+  }
+#define G_STORE(S, STAGE)                                                                               \
+  {                                                                                                     \
+    char* dstb = smem + (STAGE) * TILE_BYTES + st_off;                                                  \
+    _Pragma("unroll") for (int it = 0; it < A_IT; ++it)                                                 \
+        *(uint4*)(dstb + it * (NT / 8) * LDS_ROW) = S.a[it];                                            \
+    _Pragma("unroll") for (int it = 0; it < B_IT; ++it)                                                 \
+        *(uint4*)(dstb + (BM + it * (NT / 8)) * LDS_ROW) = S.b[it];                                     \
+  }
+#define G_COMPUTE(STAGE)                                                                                \
+  {                                                                                                     \
+    const char* cur = smem + (STAGE) * TILE_BYTES;                                                      \
+    _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                            \
+      uint4 af[MI], bfr[NI];                                                                            \
+      _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                    \
+          af[i] = *(const uint4*)(cur + a_frag + i * 32 * LDS_ROW + ks * 32);                           \
+      _Pragma("unroll") for (int j = 0; j < NI; ++j)                                                    \
+          bfr[j] = *(const uint4*)(cur + b_frag + j * 32 * LDS_ROW + ks * 32);                          \
+      _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                    \
+          _Pragma("unroll") for (int j = 0; j < NI; ++j)                                                \
+              acc[i][j] = mfma_32x32x16(af[i], bfr[j], acc[i][j]);                                      \
+    }                                                                                                   \
+  }
   const int a_frag = (wm * WM + (lane & 31)) * LDS_ROW + (lane >> 5) * 16;
   const int b_frag = BM * LDS_ROW + (wn * WN + (lane & 31)) * LDS_ROW + (lane >> 5) * 16;
-
-  for (int kt = 0; kt < nk; ++kt) {
-    const char* cur = smem + (kt & 1) * TILE_BYTES;
-    char* nxt = smem + ((kt + 1) & 1) * TILE_BYTES;
-    if (kt + 1 < nk) {
-#pragma unroll
-      for (int it = 0; it < A_IT; ++it) ra[it] = *(const uint4*)(a_ptr[it] + (size_t)(kt + 1) * BK);
-#pragma unroll
-      for (int it = 0; it < B_IT; ++it) rb[it] = *(const uint4*)(b_ptr[it] + (size_t)(kt + 1) * BK);
-    }
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      uint4 af[MI], bfr[NI];
-#pragma unroll
-      for (int i = 0; i < MI; ++i) af[i] = *(const uint4*)(cur + a_frag + i * 32 * LDS_ROW + ks * 32);
-#pragma unroll
-      for (int j = 0; j < NI; ++j) bfr[j] = *(const uint4*)(cur + b_frag + j * 32 * LDS_ROW + ks * 32);
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j) acc[i][j] = mfma_32x32x16(af[i], bfr[j], acc[i][j]);
-    }
-    if (kt + 1 < nk) {
-#pragma unroll
-      for (int it = 0; it < A_IT; ++it) *(uint4*)(nxt + a_off[it]) = ra[it];
-#pragma unroll
-      for (int it = 0; it < B_IT; ++it) *(uint4*)(nxt + b_off[it]) = rb[it];
-    }
+  G_LOAD(r0, 0)
+  G_LOAD(r1, 1)
+  G_STORE(r0, 0)
+  G_LOAD(r0, 2)
+  __syncthreads();
+  int kt = 0;
+  for (; kt + 2 <= nk; kt += 2) {
+    G_COMPUTE(0)
+    G_STORE(r1, 1)
+    G_LOAD(r1, kt + 3)
+    __syncthreads();
+    G_COMPUTE(1)
+    G_STORE(r0, 0)
+    G_LOAD(r0, kt + 4)
     __syncthreads();
   }
+  if (kt < nk) G_COMPUTE(0)
+#undef G_LOAD
+#undef G_STORE
+#undef G_COMPUTE
 
   // epilogue: lane holds column (lane & 31) and rows 8 (e >> 2) + 4 (lane >> 5) + (e & 3) of each 32x32 tile
 #pragma unroll
@@ -161,6 +172,169 @@ hipError_t launch_large(hipStream_t s, const void* A, const void* W, void* out, 
   int tilesM = (M + BM - 1) / BM;
   int tilesN = (EPI == EPI_SWIGLU) ? N / (BN / 2) : N / BN;
   kern<<<tilesM * tilesN, NT, SMEM, s>>>((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, tilesM, tilesN);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Large-tile GEMM, second form: the operand tiles go from global memory straight into LDS (LDS-DMA loads, no
+// staging registers), 256x256x64 block tile, two LDS stages of 64 KB, 8 wavefronts of 128x64.
+//   * A wavefront-wide DMA load writes lane i's 16 bytes to LDS base + 16 i, so one instruction fills eight
+//     128-byte tile rows.  To keep the later 16-byte MFMA operand reads free of bank conflicts the 16-byte chunk
+//     c of row r is stored at slot c ^ (r & 7); the permutation is applied on the global side (lane i fetches
+//     chunk (i & 7) ^ (i >> 3) of its row), so global reads stay whole 128-byte rows.
+//   * The compiler would wait for every outstanding DMA load before any LDS read it knows about, which would
+//     serialise the pipeline, so the operand reads are issued as inline ds_read_b128 and their completion is
+//     awaited explicitly (s_waitcnt lgkmcnt), two k-steps of fragments in flight.
+constexpr int DMA_STAGE = 65536;
+
+typedef unsigned __attribute__((ext_vector_type(4))) u32x4_t;  // native vector: can live in an asm "v" operand
+template <int OFF>
+__device__ __forceinline__ u32x4_t lds_read128(uint32_t addr) {
+  u32x4_t v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
+}
+__device__ __forceinline__ f32x16_t mfma_32x32x16_v(u32x4_t a, u32x4_t b, f32x16_t c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+#define LDS_WAIT6(N, f0, f1, f2, f3, f4, f5) \
+  asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(f0), "+v"(f1), "+v"(f2), "+v"(f3), "+v"(f4), "+v"(f5))
+
+template <int EPI>
+__global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
+                                                            void* __restrict__ out, int M, int N, int K, int tilesM,
+                                                            int tilesN) {
+  constexpr int BM = 256, BN = 256, WN = 64;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  int pid = blockIdx.x;
+  const int total = tilesM * tilesN;
+  if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
+  const int band = 8 * tilesN;
+  const int first_m = (pid / band) * 8;
+  const int gsz = min(tilesM - first_m, 8);
+  const int tm = first_m + (pid % band) % gsz;
+  const int tn = (pid % band) / gsz;
+  const int m0 = tm * BM;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 2, wn = wave & 3;
+
+  auto wrow = [&](int r) -> int {
+    if (EPI == EPI_SWIGLU) {
+      int wv = r / WN, qd = r % WN;
+      int half = qd / (WN / 2), j = qd % (WN / 2);
+      return half * N + tn * (BN / 2) + wv * (WN / 2) + j;
+    }
+    return tn * BN + r;
+  };
+
+  // DMA sources: wavefronts 0-3 bring the A tile (32 row groups of 8), 4-7 the W tile
+  const bool loads_a = wave < 4;
+  const char* gbase = loads_a ? (const char*)A : (const char*)W;
+  uint32_t go[8];
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    int row = 8 * ((wave & 3) * 8 + it) + (lane >> 3);
+    int grow = loads_a ? min(m0 + row, M - 1) : wrow(row);
+    go[it] = (uint32_t)grow * (uint32_t)K * 2u + (uint32_t)(((lane & 7) ^ (lane >> 3)) * 16);
+  }
+  typedef __attribute__((address_space(3))) void lds_void;
+  typedef const __attribute__((address_space(1))) void g_void;
+  char* dma_dst = smem + wave * 8192;  // + stage * DMA_STAGE + it * 1024
+#define DMA_ISSUE(KT, STAGE)                                                                              \
+  {                                                                                                       \
+    const char* src = gbase + (size_t)(KT) * 128;                                                         \
+    _Pragma("unroll") for (int it = 0; it < 8; ++it)                                                      \
+        __builtin_amdgcn_global_load_lds((g_void*)(src + go[it]),                                         \
+                                         (lds_void*)(dma_dst + (STAGE) * DMA_STAGE + it * 1024), 16, 0, 0); \
+  }
+
+  f32x16_t acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // operand read addresses: row (lane & 31) of a 32-row block, chunk 2 ks + (lane >> 5), stored at slot chunk ^ (row & 7)
+  const uint32_t lds0 = (uint32_t)(size_t)smem;
+  const uint32_t y = (uint32_t)((lane >> 5) ^ (lane & 7));
+  uint32_t a_rd[4], b_rd[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    uint32_t slot = (uint32_t)(2 * ks) ^ y;
+    a_rd[ks] = lds0 + (uint32_t)((wm * 128 + (lane & 31)) * 128) + slot * 16;
+    b_rd[ks] = lds0 + (uint32_t)((BM + wn * 64 + (lane & 31)) * 128) + slot * 16;
+  }
+
+  const int nk = K / 64;
+  DMA_ISSUE(0, 0)
+  for (int kt = 0; kt < nk; ++kt) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (kt + 1 < nk) DMA_ISSUE(kt + 1, (kt + 1) & 1)
+    const uint32_t so = (uint32_t)(kt & 1) * DMA_STAGE;
+    u32x4_t p0, p1, p2, p3, p4, p5, q0, q1, q2, q3, q4, q5;
+#define RD(S0, S1, S2, S3, S4, S5, KS)                                                      \
+    S0 = lds_read128<0>(a_rd[KS] + so); S1 = lds_read128<4096>(a_rd[KS] + so);              \
+    S2 = lds_read128<8192>(a_rd[KS] + so); S3 = lds_read128<12288>(a_rd[KS] + so);          \
+    S4 = lds_read128<0>(b_rd[KS] + so); S5 = lds_read128<4096>(b_rd[KS] + so);
+#define MM(S0, S1, S2, S3, S4, S5)                                                          \
+    acc[0][0] = mfma_32x32x16_v(S0, S4, acc[0][0]); acc[0][1] = mfma_32x32x16_v(S0, S5, acc[0][1]); \
+    acc[1][0] = mfma_32x32x16_v(S1, S4, acc[1][0]); acc[1][1] = mfma_32x32x16_v(S1, S5, acc[1][1]); \
+    acc[2][0] = mfma_32x32x16_v(S2, S4, acc[2][0]); acc[2][1] = mfma_32x32x16_v(S2, S5, acc[2][1]); \
+    acc[3][0] = mfma_32x32x16_v(S3, S4, acc[3][0]); acc[3][1] = mfma_32x32x16_v(S3, S5, acc[3][1]);
+    RD(p0, p1, p2, p3, p4, p5, 0)
+    RD(q0, q1, q2, q3, q4, q5, 1)
+    LDS_WAIT6(6, p0, p1, p2, p3, p4, p5);
+    MM(p0, p1, p2, p3, p4, p5)
+    RD(p0, p1, p2, p3, p4, p5, 2)
+    LDS_WAIT6(6, q0, q1, q2, q3, q4, q5);
+    MM(q0, q1, q2, q3, q4, q5)
+    RD(q0, q1, q2, q3, q4, q5, 3)
+    LDS_WAIT6(6, p0, p1, p2, p3, p4, p5);
+    MM(p0, p1, p2, p3, p4, p5)
+    LDS_WAIT6(0, q0, q1, q2, q3, q4, q5);
+    MM(q0, q1, q2, q3, q4, q5)
+#undef RD
+#undef MM
+  }
+#undef DMA_ISSUE
+
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      int m = m0 + wm * 128 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+      if (m >= M) continue;
+      if (EPI == EPI_SWIGLU) {
+        int f = tn * (BN / 2) + wn * (WN / 2) + (lane & 31);
+        float gte = acc[i][0][e], up = acc[i][1][e];
+        float v = gte / (1.f + __expf(-gte)) * up;
+        ((bf16_t*)out)[(size_t)m * N + f] = f32_to_bf16(v);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          int n = tn * BN + wn * WN + j * 32 + (lane & 31);
+          float v = acc[i][j][e];
+          if (EPI == EPI_STORE_F32) ((float*)out)[(size_t)m * N + n] = v;
+          if (EPI == EPI_RESID_F32) ((float*)out)[(size_t)m * N + n] += v;
+          if (EPI == EPI_STORE_ACT) ((bf16_t*)out)[(size_t)m * N + n] = f32_to_bf16(v);
+        }
+      }
+    }
+  }
+}
+
+template <int EPI>
+hipError_t launch_large_dma(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K,
+                            bool configure_only = false) {
+  constexpr int SMEM = 2 * DMA_STAGE;
+  auto kern = gemm_bf16_dma_kernel<EPI>;
+  if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+  int tilesM = (M + 255) / 256;
+  int tilesN = (EPI == EPI_SWIGLU) ? N / 128 : N / 256;
+  kern<<<tilesM * tilesN, 512, SMEM, s>>>((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, tilesM, tilesN);
   return hipGetLastError();
 }
 
@@ -358,6 +532,15 @@ hipError_t launch_gemm_bf16(hipStream_t s, const void* A, const void* W, void* o
   if (M <= 0) return hipSuccess;
   if (K % BK) return hipErrorInvalidValue;
   if (epi == EPI_SWIGLU ? (N % 128) : (N % 256)) return hipErrorInvalidValue;
+  static const bool use_dma = !(getenv("RLHF_GEMM_NO_DMA") && atoi(getenv("RLHF_GEMM_NO_DMA")));
+  if (use_dma) {
+    switch (epi) {
+      case EPI_STORE_F32: return launch_large_dma<EPI_STORE_F32>(s, A, W, out, M, N, K);
+      case EPI_RESID_F32: return launch_large_dma<EPI_RESID_F32>(s, A, W, out, M, N, K);
+      case EPI_SWIGLU: return launch_large_dma<EPI_SWIGLU>(s, A, W, out, M, N, K);
+      case EPI_STORE_ACT: return launch_large_dma<EPI_STORE_ACT>(s, A, W, out, M, N, K);
+    }
+  }
   switch (epi) {
     case EPI_STORE_F32: return launch_large<EPI_STORE_F32>(s, A, W, out, M, N, K);
     case EPI_RESID_F32: return launch_large<EPI_RESID_F32>(s, A, W, out, M, N, K);
@@ -374,6 +557,10 @@ hipError_t gemm_configure() {
   if ((e = launch_large<EPI_RESID_F32>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, true)) != hipSuccess) return e;
   if ((e = launch_large<EPI_SWIGLU>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, true)) != hipSuccess) return e;
   if ((e = launch_large<EPI_STORE_ACT>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, true)) != hipSuccess) return e;
+  if ((e = launch_large_dma<EPI_STORE_F32>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, true)) != hipSuccess) return e;
+  if ((e = launch_large_dma<EPI_RESID_F32>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, true)) != hipSuccess) return e;
+  if ((e = launch_large_dma<EPI_SWIGLU>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, true)) != hipSuccess) return e;
+  if ((e = launch_large_dma<EPI_STORE_ACT>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, true)) != hipSuccess) return e;
   if ((e = launch_skinny<1>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, true)) != hipSuccess) return e;
   if ((e = launch_skinny<2>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, true)) != hipSuccess) return e;
   if ((e = launch_skinny<4>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, true)) != hipSuccess) return e;
