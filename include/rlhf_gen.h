@@ -16,7 +16,7 @@
  *   "device" pointers are HIP device allocations on cfg.device, owned by the caller,
  *   row-major.  "host" pointers are ordinary process memory.  Weight matrices are
  *   [out_features, in_features] (y = x W^T), stored as cfg.dtype, BORROWED for the
- *   context's lifetime and never written.  The library owns the paged KV cache, block
+ *   context's lifetime and never written (unless RLHF_GEN_FLAG_CONVERT_IN_PLACE is set).  The library owns the paged KV cache, block
  *   tables, activations and counters; all of it is allocated in rlhf_gen_init and
  *   nothing is allocated afterwards.
  *   Work is enqueued on cfg.stream.  prefill and decode_step return after enqueueing
@@ -49,7 +49,10 @@ enum { RLHF_GEN_DTYPE_FP32 = 0, RLHF_GEN_DTYPE_BF16 = 1 };
 enum {
   RLHF_GEN_FLAG_SHUFFLE_BLOCKS = 1u, /* hand out KV blocks in a scrambled order (tests: results must not depend on placement) */
   RLHF_GEN_FLAG_NO_GRAPH = 2u,       /* generate launches every decode step kernel by kernel instead of replaying a captured graph */
-  RLHF_GEN_FLAG_GENERIC_GEMM = 4u    /* decode uses the large-tile GEMM instead of the weight-streaming one (cross-check) */
+  RLHF_GEN_FLAG_GENERIC_GEMM = 4u,   /* decode uses the large-tile GEMM instead of the weight-streaming one (cross-check) */
+  RLHF_GEN_FLAG_CONVERT_IN_PLACE = 8u /* bf16 mode: rewrite the caller's projection matrices and LM head to fp16 in place
+                                         instead of allocating working copies (for models that fill the card; the
+                                         buffers then no longer hold bf16 and must not be reused as such) */
 };
 
 /* Model and capacity description.  Architecture: pre-norm decoder, RMSNorm (eps inside the
@@ -59,8 +62,11 @@ enum {
 typedef struct {
   int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
   float rms_eps, rope_theta;
-  int32_t dtype;          /* RLHF_GEN_DTYPE_*: storage type of weights and KV cache.  bf16 computes with
-                             bf16 MFMA operands and fp32 accumulation/residual/softmax/logits; fp32 is a
+  int32_t dtype;          /* RLHF_GEN_DTYPE_*: storage type of the caller's weights.  bf16: the projection matrices are
+                             converted once to fp16 working copies (exact unless |w| < 2^-17), every MFMA operand,
+                             activation and the KV cache is fp16 (bf16's 8 significant bits cannot meet the parity
+                             tolerance over 32 layers), accumulation / residual / softmax / logits are fp32.  Like any
+                             fp16 inference it assumes activations within +-65504 (they saturate there).  fp32 is a
                              plain-ALU path meant for small models */
   int32_t max_batch;      /* largest B any call will pass */
   int32_t max_seq;        /* largest query length + response length of one sequence */

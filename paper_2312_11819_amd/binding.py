@@ -19,9 +19,9 @@ LIB_PATH = os.path.join(_HERE, "librlhf_gen.so")
 
 OK, E_INVALID, E_NOMEM, E_STATE, E_DEVICE, E_UNSUPPORTED = 0, -1, -2, -3, -4, -5
 DTYPE_FP32, DTYPE_BF16 = 0, 1
-FLAG_SHUFFLE_BLOCKS, FLAG_NO_GRAPH, FLAG_GENERIC_GEMM = 1, 2, 4
+FLAG_SHUFFLE_BLOCKS, FLAG_NO_GRAPH, FLAG_GENERIC_GEMM, FLAG_CONVERT_IN_PLACE = 1, 2, 4, 8
 GEMM_TILED, GEMM_STREAMING, GEMM_FP32 = 0, 1, 2
-EPI_STORE_F32, EPI_RESID_F32, EPI_SWIGLU, EPI_STORE_BF16 = 0, 1, 2, 3
+EPI_STORE_F32, EPI_RESID_F32, EPI_SWIGLU, EPI_STORE_H16 = 0, 1, 2, 3
 
 PROF_CLASSES = ["embed", "norm", "gemm_qkv", "rope_append", "attn_decode", "gemm_wo", "gemm_gate_up", "swiglu",
                 "gemm_down", "lm_head", "sampler"]
@@ -215,10 +215,10 @@ def rlhf_gen_op_gemm(kind, A, W, out, M, N, K, epilogue=0, nsplit=1) -> int:
 
 
 def rlhf_gen_op_rope_append(qkv, row_pos, row_seq, cos_t, sin_t, q_out, kv_pool, block_table, max_blocks, M, Hq, Hkv,
-                            head_dim, bf16) -> int:
+                            head_dim, half16) -> int:
     return lib().rlhf_gen_op_rope_append(None, _ptr(qkv), _ptr(row_pos), _ptr(row_seq), _ptr(cos_t), _ptr(sin_t),
                                          _ptr(q_out), _ptr(kv_pool), _ptr(block_table), max_blocks, M, Hq, Hkv,
-                                         head_dim, int(bf16))
+                                         head_dim, int(half16))
 
 
 def rlhf_gen_op_attn_decode(q, kv_pool, block_table, max_blocks, seq_len, out, B, Hq, Hkv) -> int:

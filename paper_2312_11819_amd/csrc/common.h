@@ -1,41 +1,42 @@
-// Shared device helpers for the gfx950 kernels: bf16 bit conversions, MFMA wrappers,
+// Shared device helpers for the gfx950 kernels: 16-bit conversions, MFMA wrappers,
 // wavefront reductions, and the byte layout of one KV-cache page.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-typedef uint16_t bf16_t;  // raw bf16 bits
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef uint16_t bf16_t;  // raw bf16 bits (weights as the caller stores them)
+typedef uint16_t h16_t;   // raw IEEE fp16 bits (activations, KV cache, working copies of the weights)
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
-// Round to nearest even; NaN stays NaN.
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+// fp32 -> fp16, round to nearest even, saturating at the largest finite fp16 instead of overflowing to infinity.
+__device__ __forceinline__ h16_t f32_to_h16(float f) {
+  _Float16 h = (_Float16)fminf(fmaxf(f, -65504.f), 65504.f);
+  return __builtin_bit_cast(uint16_t, h);
 }
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+__device__ __forceinline__ uint32_t pack_h16x2(float lo, float hi) {
+  return (uint32_t)f32_to_h16(lo) | ((uint32_t)f32_to_h16(hi) << 16);
 }
 
-// D(16x16) += A(16x32) * B(32x16), bf16 in, fp32 out.  Lane l supplies row (l & 15) of A and
-// column (l & 15) of B, eight consecutive k each, the k group chosen by l >> 4 in the same way for
-// both operands.  Lane l receives D[4 (l >> 4) + i][l & 15], i = 0..3.
+// All 16-bit MFMA operands are fp16 (11 significant bits): with bf16 activations the rounding error of a
+// 32-layer rollout exceeds the parity tolerance several times over; the bf16 weights convert to fp16 exactly.
+// D(16x16) += A(16x32) * B(32x16), fp16 in, fp32 out.  Lane l supplies row (l & 15) of A and column (l & 15) of
+// B, eight consecutive k each, the k group chosen by l >> 4 in the same way for both operands.  Lane l receives
+// D[4 (l >> 4) + i][l & 15], i = 0..3.
 __device__ __forceinline__ f32x4_t mfma_16x16x32(uint4 a, uint4 b, f32x4_t c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
 }
 // D(16x16) += A(16x16) * B(16x16): four consecutive k per lane, k group l >> 4.
 __device__ __forceinline__ f32x4_t mfma_16x16x16(uint2 a, uint2 b, f32x4_t c) {
-  return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, a), __builtin_bit_cast(s16x4_t, b), c, 0, 0, 0);
+  return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4_t, a), __builtin_bit_cast(f16x4_t, b), c, 0, 0, 0);
 }
 // D(32x32) += A(32x16) * B(16x32): lane l supplies row/column (l & 31), k group l >> 5 (8 k each).
 // Lane l receives D[8 (i >> 2) + 4 (l >> 5) + (i & 3)][l & 31], i = 0..15.
 __device__ __forceinline__ f32x16_t mfma_32x32x16(uint4 a, uint4 b, f32x16_t c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
 }
 
 __device__ __forceinline__ float wave_sum(float v) {
@@ -50,7 +51,7 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // ---- KV-cache page -------------------------------------------------------------------------
-// One page holds 16 tokens of one KV head with head_dim 128 in bf16: 4096 B of keys followed by
+// One page holds 16 tokens of one KV head with head_dim 128 in fp16: 4096 B of keys followed by
 // 4096 B of values, both pre-arranged as MFMA operands so that a wavefront reads a page with
 // eight fully coalesced 16 B-per-lane loads and feeds the registers to the matrix cores as is.
 //   keys:   16 B chunk (kk, lane) at kk*1024 + lane*16 holds K[token lane&15][dims 8*(4kk + (lane>>4)) .. +8]

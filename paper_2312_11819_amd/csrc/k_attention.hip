@@ -1,4 +1,4 @@
-// Attention over the paged bf16 KV cache on the matrix cores (head_dim 128, 16-token pages).
+// Attention over the paged fp16 KV cache on the matrix cores (head_dim 128, 16-token pages).
 //
 // Both kernels work on tiles of 16 query rows that share one KV head.  For one page they form
 // S^T = K Q^T (keys as the MFMA row operand, so lane l ends up holding the scores of tokens
@@ -63,8 +63,8 @@ __device__ __forceinline__ void attn_page(const uint4 kf[4], const uint4 vf[4], 
 #pragma unroll
   for (int db = 0; db < 8; ++db) st.o[db] *= alpha;
   uint2 pb;
-  pb.x = pack_bf16x2(p[0], p[1]);
-  pb.y = pack_bf16x2(p[2], p[3]);
+  pb.x = pack_h16x2(p[0], p[1]);
+  pb.y = pack_h16x2(p[2], p[3]);
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     st.o[2 * j] = mfma_16x16x16(make_uint2(vf[j].x, vf[j].y), pb, st.o[2 * j]);
@@ -79,11 +79,11 @@ __device__ __forceinline__ void init_state(AttnState& st) {
   st.l = 0.f;
 }
 
-// grid (Hkv, B), 256 threads.  q [B, Hq, 128] bf16, out [B, Hq*128] bf16.  seq_len[b] = tokens cached BEFORE
+// grid (Hkv, B), 256 threads.  q [B, Hq, 128] fp16, out [B, Hq*128] fp16.  seq_len[b] = tokens cached BEFORE
 // this step; the step's own key/value has already been appended, so seq_len[b] + 1 tokens are visible.
-__global__ __launch_bounds__(256) void attn_decode_kernel(const bf16_t* __restrict__ q, const char* __restrict__ pool,
+__global__ __launch_bounds__(256) void attn_decode_kernel(const h16_t* __restrict__ q, const char* __restrict__ pool,
                                                           const int* __restrict__ block_table, int max_blocks,
-                                                          const int* __restrict__ seq_len, bf16_t* __restrict__ out,
+                                                          const int* __restrict__ seq_len, h16_t* __restrict__ out,
                                                           int Hq, int Hkv, float scale_log2) {
   __shared__ float m_s[4][16];
   __shared__ float l_s[4][16];
@@ -144,16 +144,16 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const bf16_t* __restri
       num += a * o_s[ww][r][dim];
       den += a * l_s[ww][r];
     }
-    out[((size_t)b * Hq + kvh * group + r) * 128 + dim] = f32_to_bf16(num / den);
+    out[((size_t)b * Hq + kvh * group + r) * 128 + dim] = f32_to_h16(num / den);
   }
 }
 
 // grid (ceil(max_len / 64), Hq, nseq), 256 threads: wavefront w owns positions p0 .. p0+15 of sequence
 // seq_ids[blockIdx.z] with p0 = 16 (4 blockIdx.x + w).  q / out are packed over tokens: row cu_seqlens[z] + pos.
-__global__ __launch_bounds__(256) void attn_prefill_kernel(const bf16_t* __restrict__ q, const char* __restrict__ pool,
+__global__ __launch_bounds__(256) void attn_prefill_kernel(const h16_t* __restrict__ q, const char* __restrict__ pool,
                                                            const int* __restrict__ block_table, int max_blocks,
                                                            const int* __restrict__ cu_seqlens,
-                                                           const int* __restrict__ seq_ids, bf16_t* __restrict__ out,
+                                                           const int* __restrict__ seq_ids, h16_t* __restrict__ out,
                                                            int Hq, int Hkv, float scale_log2) {
   const int z = blockIdx.z, head = blockIdx.y;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, t = lane & 15, g = lane >> 4;
@@ -189,12 +189,12 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const bf16_t* __restr
   lt += __shfl_xor(lt, 32);
   if (valid) {
     float inv = 1.f / lt;
-    bf16_t* orow = out + ((size_t)(row0 + p0 + t) * Hq + head) * 128 + 4 * g;
+    h16_t* orow = out + ((size_t)(row0 + p0 + t) * Hq + head) * 128 + 4 * g;
 #pragma unroll
     for (int db = 0; db < 8; ++db) {
       uint2 o;
-      o.x = pack_bf16x2(st.o[db][0] * inv, st.o[db][1] * inv);
-      o.y = pack_bf16x2(st.o[db][2] * inv, st.o[db][3] * inv);
+      o.x = pack_h16x2(st.o[db][0] * inv, st.o[db][1] * inv);
+      o.y = pack_h16x2(st.o[db][2] * inv, st.o[db][3] * inv);
       *(uint2*)(orow + db * 16) = o;
     }
   }
@@ -249,24 +249,24 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float* __restrict__ 
 
 static const float LOG2E = 1.4426950408889634f;
 
-hipError_t launch_attn_decode_bf16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
+hipError_t launch_attn_decode_h16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
                                    int max_blocks, const int* seq_len, void* out, int B, int Hq, int Hkv) {
   if (B <= 0) return hipSuccess;
   if (Hq % Hkv || Hq / Hkv > 16) return hipErrorInvalidValue;
   float scale_log2 = LOG2E / sqrtf((float)KV_HEAD_DIM);
-  attn_decode_kernel<<<dim3(Hkv, B), 256, 0, s>>>((const bf16_t*)q, (const char*)kv_pool_layer, block_table, max_blocks,
-                                                  seq_len, (bf16_t*)out, Hq, Hkv, scale_log2);
+  attn_decode_kernel<<<dim3(Hkv, B), 256, 0, s>>>((const h16_t*)q, (const char*)kv_pool_layer, block_table, max_blocks,
+                                                  seq_len, (h16_t*)out, Hq, Hkv, scale_log2);
   return hipGetLastError();
 }
 
-hipError_t launch_attn_prefill_bf16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
+hipError_t launch_attn_prefill_h16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
                                     int max_blocks, const int* cu_seqlens, const int* seq_ids, void* out, int nseq,
                                     int max_len, int Hq, int Hkv) {
   if (nseq <= 0 || max_len <= 0) return hipSuccess;
   if (Hq % Hkv) return hipErrorInvalidValue;
   float scale_log2 = LOG2E / sqrtf((float)KV_HEAD_DIM);
   attn_prefill_kernel<<<dim3((max_len + 63) / 64, Hq, nseq), 256, 0, s>>>(
-      (const bf16_t*)q, (const char*)kv_pool_layer, block_table, max_blocks, cu_seqlens, seq_ids, (bf16_t*)out, Hq, Hkv,
+      (const h16_t*)q, (const char*)kv_pool_layer, block_table, max_blocks, cu_seqlens, seq_ids, (h16_t*)out, Hq, Hkv,
       scale_log2);
   return hipGetLastError();
 }

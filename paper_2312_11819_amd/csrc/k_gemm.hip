@@ -1,5 +1,5 @@
 // GEMMs of the rollout, out = A[M,K] * W[N,K]^T with both operands K-contiguous.
-//   gemm_bf16_kernel    : large-tile bf16 MFMA GEMM for prefill (M = thousands of tokens): 256x256x64 block tile,
+//   gemm_h16_kernel     : large-tile fp16 MFMA GEMM for prefill (M = thousands of tokens): 256x256x64 block tile,
 //                         8 wavefronts of 128x64, LDS double buffer fed through registers, 32x32x16 MFMA.
 //   gemm_skinny_kernel  : weight-streaming GEMM for decode (M = batch <= 256): W is the MFMA row operand read
 //                         straight from HBM into registers exactly once, the activation slice is staged in LDS,
@@ -16,8 +16,8 @@ constexpr int BK = 64;            // k extent of one LDS tile
 constexpr int LDS_ROW = BK * 2 + 16;  // bytes per tile row; the 16 B pad spreads 16 B reads over all banks
 
 template <int BM, int BN, int WM, int WN, int EPI>
-__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(const bf16_t* __restrict__ A,
-                                                                               const bf16_t* __restrict__ W,
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_h16_kernel(const h16_t* __restrict__ A,
+                                                                               const h16_t* __restrict__ W,
                                                                                void* __restrict__ out, int M, int N,
                                                                                int K, int tilesM, int tilesN) {
   constexpr int NT = (BM / WM) * (BN / WN) * 64;
@@ -146,7 +146,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(c
           int f = tn * (BN / 2) + wn * (WN / 2) + j * 32 + (lane & 31);
           float gte = acc[i][j][e], up = acc[i][j + NI / 2][e];
           float v = gte / (1.f + __expf(-gte)) * up;
-          ((bf16_t*)out)[(size_t)m * N + f] = f32_to_bf16(v);
+          ((h16_t*)out)[(size_t)m * N + f] = f32_to_h16(v);
         }
       } else {
 #pragma unroll
@@ -155,7 +155,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(c
           float v = acc[i][j][e];
           if (EPI == EPI_STORE_F32) ((float*)out)[(size_t)m * N + n] = v;
           if (EPI == EPI_RESID_F32) ((float*)out)[(size_t)m * N + n] += v;
-          if (EPI == EPI_STORE_ACT) ((bf16_t*)out)[(size_t)m * N + n] = f32_to_bf16(v);
+          if (EPI == EPI_STORE_ACT) ((h16_t*)out)[(size_t)m * N + n] = f32_to_h16(v);
         }
       }
     }
@@ -167,11 +167,11 @@ hipError_t launch_large(hipStream_t s, const void* A, const void* W, void* out, 
   constexpr int BM = 256, BN = 256, WM = 128, WN = 64;
   constexpr int NT = (BM / WM) * (BN / WN) * 64;
   constexpr int SMEM = 2 * (BM + BN) * LDS_ROW;
-  auto kern = gemm_bf16_kernel<BM, BN, WM, WN, EPI>;
+  auto kern = gemm_h16_kernel<BM, BN, WM, WN, EPI>;
   if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
   int tilesM = (M + BM - 1) / BM;
   int tilesN = (EPI == EPI_SWIGLU) ? N / (BN / 2) : N / BN;
-  kern<<<tilesM * tilesN, NT, SMEM, s>>>((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, tilesM, tilesN);
+  kern<<<tilesM * tilesN, NT, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, out, M, N, K, tilesM, tilesN);
   return hipGetLastError();
 }
 
@@ -195,13 +195,13 @@ __device__ __forceinline__ u32x4_t lds_read128(uint32_t addr) {
   return v;
 }
 __device__ __forceinline__ f32x16_t mfma_32x32x16_v(u32x4_t a, u32x4_t b, f32x16_t c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
 }
 #define LDS_WAIT6(N, f0, f1, f2, f3, f4, f5) \
   asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(f0), "+v"(f1), "+v"(f2), "+v"(f3), "+v"(f4), "+v"(f5))
 
 template <int EPI>
-__global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
+__global__ __launch_bounds__(512) void gemm_h16_dma_kernel(const h16_t* __restrict__ A, const h16_t* __restrict__ W,
                                                             void* __restrict__ out, int M, int N, int K, int tilesM,
                                                             int tilesN) {
   constexpr int BM = 256, BN = 256, WN = 64;
@@ -311,7 +311,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const bf16_t* __rest
         int f = tn * (BN / 2) + wn * (WN / 2) + (lane & 31);
         float gte = acc[i][0][e], up = acc[i][1][e];
         float v = gte / (1.f + __expf(-gte)) * up;
-        ((bf16_t*)out)[(size_t)m * N + f] = f32_to_bf16(v);
+        ((h16_t*)out)[(size_t)m * N + f] = f32_to_h16(v);
       } else {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
@@ -319,7 +319,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const bf16_t* __rest
           float v = acc[i][j][e];
           if (EPI == EPI_STORE_F32) ((float*)out)[(size_t)m * N + n] = v;
           if (EPI == EPI_RESID_F32) ((float*)out)[(size_t)m * N + n] += v;
-          if (EPI == EPI_STORE_ACT) ((bf16_t*)out)[(size_t)m * N + n] = f32_to_bf16(v);
+          if (EPI == EPI_STORE_ACT) ((h16_t*)out)[(size_t)m * N + n] = f32_to_h16(v);
         }
       }
     }
@@ -330,11 +330,11 @@ template <int EPI>
 hipError_t launch_large_dma(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K,
                             bool configure_only = false) {
   constexpr int SMEM = 2 * DMA_STAGE;
-  auto kern = gemm_bf16_dma_kernel<EPI>;
+  auto kern = gemm_h16_dma_kernel<EPI>;
   if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
   int tilesM = (M + 255) / 256;
   int tilesN = (EPI == EPI_SWIGLU) ? N / 128 : N / 256;
-  kern<<<tilesM * tilesN, 512, SMEM, s>>>((const bf16_t*)A, (const bf16_t*)W, out, M, N, K, tilesM, tilesN);
+  kern<<<tilesM * tilesN, 512, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, out, M, N, K, tilesM, tilesN);
   return hipGetLastError();
 }
 
@@ -347,7 +347,7 @@ constexpr int SK_ROW = SK * 2 + 16;     // bytes per LDS row (padded)
 // the memory counter retires in order, so both must share one prefetch distance); the activation slice then
 // passes through a double-buffered LDS tile that the four wavefronts share.
 template <int MB, int D, bool GLU = false>
-__global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W,
+__global__ __launch_bounds__(256) void gemm_skinny_kernel(const h16_t* __restrict__ X, const h16_t* __restrict__ W,
                                                           float* __restrict__ part, int M, int Nw, int K,
                                                           int steps_per_split) {
   static_assert(D == 2 || D == 4, "ring depth 2 or 4");
@@ -366,10 +366,10 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
   for (int i = 0; i < MB; ++i) acc[i] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
   const int wrow = GLU ? ((t < 8) ? n0 + 8 * w + t : (Nw >> 1) + n0 + 8 * w + (t - 8)) : n0 + 16 * w + t;
-  const bf16_t* wp = W + (size_t)wrow * K + 8 * g;
+  const h16_t* wp = W + (size_t)wrow * K + 8 * g;
   // Activation slice: 16 MB rows x 16 chunks of 16 B per k-step, MB chunks per thread.  Rows beyond M are read
   // from row M - 1 instead: they only feed output columns that are never stored.
-  const bf16_t* xp[MB];
+  const h16_t* xp[MB];
   int xo[MB];
 #pragma unroll
   for (int it = 0; it < MB; ++it) {
@@ -455,7 +455,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
 #undef SKINNY_LOAD
   if (GLU) {
     // lane (t, g < 2) holds gate features 4g..4g+3 of column t, lane (t, g + 2) the matching up values
-    bf16_t* hout = (bf16_t*)part;
+    h16_t* hout = (h16_t*)part;
     const int F = Nw >> 1;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
@@ -468,8 +468,8 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
 #pragma unroll
         for (int i = 0; i < 4; ++i) hv[i] = acc[mb][i] / (1.f + __expf(-acc[mb][i])) * up[i];
         uint2 o;
-        o.x = pack_bf16x2(hv[0], hv[1]);
-        o.y = pack_bf16x2(hv[2], hv[3]);
+        o.x = pack_h16x2(hv[0], hv[1]);
+        o.y = pack_h16x2(hv[2], hv[3]);
         *(uint2*)(hout + (size_t)m * F + n0 + 8 * w + 4 * g) = o;
       }
     }
@@ -494,13 +494,13 @@ hipError_t launch_skinny(hipStream_t s, const void* A, const void* W, float* par
     if (e != hipSuccess) return e;
     return hipFuncSetAttribute((const void*)gemm_skinny_kernel<MB, D, true>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
   }
-  if (nsplit == 0) {  // fused SwiGLU: W = [2F, K], output bf16 [M, F], no split
-    gemm_skinny_kernel<MB, D, true><<<dim3(Nw / 64, 1), 256, SMEM, s>>>((const bf16_t*)A, (const bf16_t*)W, part, M, Nw, K, K / SK);
+  if (nsplit == 0) {  // fused SwiGLU: W = [2F, K], output fp16 [M, F], no split
+    gemm_skinny_kernel<MB, D, true><<<dim3(Nw / 64, 1), 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, K / SK);
     return hipGetLastError();
   }
   int steps = K / SK;
   int per = (steps + nsplit - 1) / nsplit;
-  kern<<<dim3(Nw / 64, nsplit), 256, SMEM, s>>>((const bf16_t*)A, (const bf16_t*)W, part, M, Nw, K, per);
+  kern<<<dim3(Nw / 64, nsplit), 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, per);
   return hipGetLastError();
 }
 
@@ -528,7 +528,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 
 }  // namespace
 
-hipError_t launch_gemm_bf16(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K, int epi) {
+hipError_t launch_gemm_h16(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K, int epi) {
   if (M <= 0) return hipSuccess;
   if (K % BK) return hipErrorInvalidValue;
   if (epi == EPI_SWIGLU ? (N % 128) : (N % 256)) return hipErrorInvalidValue;
@@ -580,7 +580,7 @@ int gemm_skinny_pick_split(int M, int Nw, int K) {
   return (steps + per - 1) / per;  // no empty split
 }
 
-hipError_t launch_gemm_skinny_bf16(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K,
+hipError_t launch_gemm_skinny_h16(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K,
                                    int nsplit) {
   if (M <= 0) return hipSuccess;
   if (K % SK || Nw % 64 || M > 256 || nsplit < 0) return hipErrorInvalidValue;

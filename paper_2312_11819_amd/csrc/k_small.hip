@@ -63,7 +63,7 @@ hipError_t launch_embed(hipStream_t s, const int* ids, const void* table, int w_
 
 // One workgroup of NT threads per row, d <= 8 * 4 * NT, d % 4 == 0.  The sum of squares is taken in a fixed
 // order, so the result does not change from run to run.  Partial sums are added in split order 0, 1, ...
-template <bool WBF16, bool ABF16, int NT>
+template <bool WBF16, bool A16, int NT>
 __global__ __launch_bounds__(NT) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ part, int nsplit,
                                                      size_t part_stride, const void* __restrict__ gain,
                                                      void* __restrict__ y, int d, float eps,
@@ -125,11 +125,11 @@ __global__ __launch_bounds__(NT) void rmsnorm_kernel(float* __restrict__ x, cons
       }
       float4 a = v[it];
       float o0 = a.x * r * g0, o1 = a.y * r * g1, o2 = a.z * r * g2, o3 = a.w * r * g3;
-      if (ABF16) {
+      if (A16) {
         uint2 o;
-        o.x = pack_bf16x2(o0, o1);
-        o.y = pack_bf16x2(o2, o3);
-        *(uint2*)((bf16_t*)y + (size_t)m * d + i) = o;
+        o.x = pack_h16x2(o0, o1);
+        o.y = pack_h16x2(o2, o3);
+        *(uint2*)((h16_t*)y + (size_t)m * d + i) = o;
       } else {
         *(float4*)((float*)y + (size_t)m * d + i) = make_float4(o0, o1, o2, o3);
       }
@@ -156,9 +156,9 @@ hipError_t launch_rmsnorm(hipStream_t s, float* x, const float* part, int nsplit
 
 // One 64-thread workgroup per (token row, head of the fused q|k|v projection), so that every load of a launch is
 // independent and in flight at once.  The rotation pairs dimension i with i + h/2 and uses the cos/sin tables built
-// on the host in double precision (cos_t[pos * h/2 + i]).  bf16 path: h = 128, keys and values go to the
+// on the host in double precision (cos_t[pos * h/2 + i]).  16-bit path: h = 128, keys and values go to the
 // MFMA-ordered page described in common.h.  fp32 path: page = [2][16][h] floats (keys, then values).
-template <bool ABF16>
+template <bool A16>
 __global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict__ qkv, const float* __restrict__ part,
                                                          int nsplit, size_t part_stride,
                                                          const int* __restrict__ row_pos,
@@ -186,10 +186,10 @@ __global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict
       float c = cos_t[(size_t)pos * half + i], sv = sin_t[(size_t)pos * half + i];
       float r0 = a * c - bb * sv, r1 = bb * c + a * sv;
       if (head < Hq) {
-        if (ABF16) {
-          bf16_t* qo = (bf16_t*)q_out + ((size_t)m * Hq + head) * h;
-          qo[i] = f32_to_bf16(r0);
-          qo[i + half] = f32_to_bf16(r1);
+        if (A16) {
+          h16_t* qo = (h16_t*)q_out + ((size_t)m * Hq + head) * h;
+          qo[i] = f32_to_h16(r0);
+          qo[i + half] = f32_to_h16(r1);
         } else {
           float* qo = (float*)q_out + ((size_t)m * Hq + head) * h;
           qo[i] = r0;
@@ -197,10 +197,10 @@ __global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict
         }
       } else {
         const int kvh = head - Hq;
-        if (ABF16) {
+        if (A16) {
           char* page = (char*)pool + ((size_t)blk * Hkv + kvh) * KV_PAGE_BYTES;
-          *(bf16_t*)(page + kpage_offset(slot, i)) = f32_to_bf16(r0);
-          *(bf16_t*)(page + kpage_offset(slot, i + half)) = f32_to_bf16(r1);
+          *(h16_t*)(page + kpage_offset(slot, i)) = f32_to_h16(r0);
+          *(h16_t*)(page + kpage_offset(slot, i + half)) = f32_to_h16(r1);
         } else {
           float* page = (float*)pool + ((size_t)blk * Hkv + kvh) * (2 * 16 * h);
           page[slot * h + i] = r0;
@@ -213,9 +213,9 @@ __global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict
     for (int dim = threadIdx.x; dim < h; dim += 64) {
       float v = row[dim];
       for (int sidx = 0; sidx < nsplit; ++sidx) v += prow[sidx * part_stride + dim];
-      if (ABF16) {
+      if (A16) {
         char* page = (char*)pool + ((size_t)blk * Hkv + kvh) * KV_PAGE_BYTES;
-        *(bf16_t*)(page + vpage_offset(slot, dim)) = f32_to_bf16(v);
+        *(h16_t*)(page + vpage_offset(slot, dim)) = f32_to_h16(v);
       } else {
         float* page = (float*)pool + ((size_t)blk * Hkv + kvh) * (2 * 16 * h);
         page[16 * h + slot * h + dim] = v;
@@ -242,7 +242,7 @@ hipError_t launch_rope_append(hipStream_t s, const float* qkv, const float* part
   return hipGetLastError();
 }
 
-template <bool ABF16>
+template <bool A16>
 __global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ gu, int nsplit, size_t part_stride,
                                                      void* __restrict__ h_out, int F) {
   int m = blockIdx.y;
@@ -255,8 +255,8 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ g
     u += row[sidx * part_stride + F + f];
   }
   float v = g / (1.f + __expf(-g)) * u;
-  if (ABF16)
-    ((bf16_t*)h_out)[(size_t)m * F + f] = f32_to_bf16(v);
+  if (A16)
+    ((h16_t*)h_out)[(size_t)m * F + f] = f32_to_h16(v);
   else
     ((float*)h_out)[(size_t)m * F + f] = v;
 }
@@ -281,5 +281,29 @@ __global__ void advance_kernel(int* seq_len, int* step, int B) {
 
 hipError_t launch_advance(hipStream_t s, int* seq_len, int* step, int B) {
   advance_kernel<<<(B + 255) / 256, 256, 0, s>>>(seq_len, step, B);
+  return hipGetLastError();
+}
+
+// One-time conversion of a bf16 weight matrix to the fp16 working format (exact unless |w| < 2^-17, where fp16
+// subnormals keep an absolute accuracy of 2^-25; saturates beyond 65504).
+__global__ void bf16_to_h16_kernel(const bf16_t* __restrict__ src, h16_t* __restrict__ dst, size_t n) {
+  size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 8;
+  if (i + 8 <= n) {
+    uint4 v = *(const uint4*)(src + i);
+    uint4 o;
+    o.x = pack_h16x2(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u));
+    o.y = pack_h16x2(__uint_as_float(v.y << 16), __uint_as_float(v.y & 0xffff0000u));
+    o.z = pack_h16x2(__uint_as_float(v.z << 16), __uint_as_float(v.z & 0xffff0000u));
+    o.w = pack_h16x2(__uint_as_float(v.w << 16), __uint_as_float(v.w & 0xffff0000u));
+    *(uint4*)(dst + i) = o;
+  } else {
+    for (; i < n; ++i) dst[i] = f32_to_h16(bf16_to_f32(src[i]));
+  }
+}
+
+hipError_t launch_bf16_to_h16(hipStream_t s, const void* src, void* dst, size_t n) {
+  if (n == 0) return hipSuccess;
+  size_t threads = (n + 7) / 8;
+  bf16_to_h16_kernel<<<(unsigned)((threads + 255) / 256), 256, 0, s>>>((const bf16_t*)src, (h16_t*)dst, n);
   return hipGetLastError();
 }

@@ -7,23 +7,23 @@ enum GemmEpilogue {
   EPI_STORE_F32 = 0,   // out fp32 [M, N] = acc
   EPI_RESID_F32 = 1,   // out fp32 [M, N] += acc
   EPI_SWIGLU = 2,      // W is [2F, K] (gate rows then up rows), N = F: out [M, F] = silu(gate) * up
-  EPI_STORE_ACT = 3    // out [M, N] in the activation type (bf16 on the MFMA path)
+  EPI_STORE_ACT = 3    // out [M, N] in the activation type (fp16 on the MFMA path)
 };
 
-// ---- bf16 MFMA path ----
-// Large-tile GEMM: out = A[M,K] (bf16) * W[N,K]^T (bf16).  Needs N % 256 == 0 (F % 128 == 0 for SWIGLU),
+// ---- 16-bit MFMA path (fp16 operands, fp32 accumulation) ----
+// Large-tile GEMM: out = A[M,K] (fp16) * W[N,K]^T (fp16).  Needs N % 256 == 0 (F % 128 == 0 for SWIGLU),
 // K % 64 == 0; rows of A beyond M are never read.
-hipError_t launch_gemm_bf16(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K, int epi);
+hipError_t launch_gemm_h16(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K, int epi);
 // Weight-streaming GEMM for M <= 256 rows: writes fp32 partial sums part[ks][M][Nw] (Nw = rows of W)
 // for ks < nsplit; the consumer kernel adds them.  nsplit = 0 selects the fused SwiGLU form: W = [2F, K]
-// (gate rows, then up rows; Nw = 2F), no split, and `part` receives bf16 [M, F] = silu(gate) * up.
-hipError_t launch_gemm_skinny_bf16(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K,
+// (gate rows, then up rows; Nw = 2F), no split, and `part` receives fp16 [M, F] = silu(gate) * up.
+hipError_t launch_gemm_skinny_h16(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K,
                                    int nsplit);
 int gemm_skinny_pick_split(int M, int Nw, int K);
 // Per-device one-time kernel attribute setup; call before the first launch and outside any stream capture.
 hipError_t gemm_configure();
 
-// ---- elementwise / small kernels (act_bf16: activations are bf16, else fp32) ----
+// ---- elementwise / small kernels (act_bf16 != 0: 16-bit (fp16) activations, else fp32) ----
 hipError_t launch_pack_tokens(hipStream_t s, const int* query_tokens, int Lmax, const int* tok_seq, const int* tok_pos,
                               int T, int vocab, int* ids_out, int* err_flag);
 hipError_t launch_embed(hipStream_t s, const int* ids, const void* table, int w_bf16, float* x, int M, int d, int vocab,
@@ -41,11 +41,13 @@ hipError_t launch_rope_append(hipStream_t s, const float* qkv, const float* part
 hipError_t launch_swiglu(hipStream_t s, const float* gu, int nsplit, size_t part_stride, void* h_out, int act_bf16,
                          int M, int F);
 hipError_t launch_advance(hipStream_t s, int* seq_len, int* step, int B);
+// bf16 -> fp16 copy of n elements (working copies of the weight matrices).
+hipError_t launch_bf16_to_h16(hipStream_t s, const void* src, void* dst, size_t n);
 
 // ---- attention over the paged cache ----
-hipError_t launch_attn_decode_bf16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
+hipError_t launch_attn_decode_h16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
                                    int max_blocks, const int* seq_len, void* out, int B, int Hq, int Hkv);
-hipError_t launch_attn_prefill_bf16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
+hipError_t launch_attn_prefill_h16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
                                     int max_blocks, const int* cu_seqlens, const int* seq_ids, void* out, int nseq,
                                     int max_len, int Hq, int Hkv);
 // fp32 path: one wavefront per (row, query head); row_pos[m] = position of the row's token.

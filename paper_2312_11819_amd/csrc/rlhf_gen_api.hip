@@ -39,6 +39,9 @@ struct rlhf_gen_ctx {
   bool own_stream = false;
   const void *tok_emb = nullptr, *lm_head = nullptr, *final_norm = nullptr;
   std::vector<const void*> attn_norm, wqkv, wo, ffn_norm, w_gate_up, w_down;
+  // caller's bf16 matrices; in bf16 mode the members above point at fp16 working copies instead
+  std::vector<const void*> src_wqkv, src_wo, src_w_gate_up, src_w_down;
+  const void* src_lm_head = nullptr;
 
   // device memory owned by the context
   std::vector<void*> allocs;
@@ -190,7 +193,7 @@ struct RowSet {
 
 int gemm_any(rlhf_gen_ctx* c, const void* A, const void* W, void* out, int M, int N, int K, int epi) {
   if (c->bf16) {
-    LAUNCH(c, launch_gemm_bf16(c->stream, A, W, out, M, N, K, epi), "gemm_bf16");
+    LAUNCH(c, launch_gemm_h16(c->stream, A, W, out, M, N, K, epi), "gemm_bf16");
   } else {
     if (epi == EPI_SWIGLU) return fail(c, RLHF_GEN_E_UNSUPPORTED, "no fused SwiGLU on the fp32 path");
     LAUNCH(c, launch_gemm_f32(c->stream, (const float*)A, (const float*)W, (float*)out, M, N, K, epi == EPI_RESID_F32),
@@ -218,10 +221,10 @@ int forward_layers_generic(rlhf_gen_ctx* c, const RowSet& r) {
       LAUNCH(c, launch_attn_f32(s, (const float*)c->qb, (const float*)pool, c->d_table, c->max_blocks, r.row_pos,
                                 r.row_seq, (float*)c->ab, r.M, Hq, Hkv, h), "attn_f32");
     } else if (r.prefill) {
-      LAUNCH(c, launch_attn_prefill_bf16(s, c->qb, pool, c->d_table, c->max_blocks, r.cu, r.seq_ids, c->ab, r.nseq,
+      LAUNCH(c, launch_attn_prefill_h16(s, c->qb, pool, c->d_table, c->max_blocks, r.cu, r.seq_ids, c->ab, r.nseq,
                                          r.max_len, Hq, Hkv), "attn_prefill");
     } else {
-      LAUNCH(c, launch_attn_decode_bf16(s, c->qb, pool, c->d_table, c->max_blocks, c->d_seq_len, c->ab, r.M, Hq, Hkv),
+      LAUNCH(c, launch_attn_decode_h16(s, c->qb, pool, c->d_table, c->max_blocks, c->d_seq_len, c->ab, r.M, Hq, Hkv),
              "attn_decode");
     }
     rc = gemm_any(c, c->ab, c->wo[l], c->x, r.M, d, Hq * h, EPI_RESID_F32);
@@ -258,31 +261,31 @@ int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
     LAUNCH(c, launch_rmsnorm(s, c->x, pending ? c->part : nullptr, pending, (size_t)B * d, c->attn_norm[l], 1, c->y, 1,
                              B, d, g.rms_eps, nullptr), "rmsnorm");
     prof_mark(c, RLHF_GEN_PROF_NORM);
-    LAUNCH(c, launch_gemm_skinny_bf16(s, c->y, c->wqkv[l], c->part, B, qkv_w, d, c->ks_qkv), "gemm_skinny qkv");
+    LAUNCH(c, launch_gemm_skinny_h16(s, c->y, c->wqkv[l], c->part, B, qkv_w, d, c->ks_qkv), "gemm_skinny qkv");
     prof_mark(c, RLHF_GEN_PROF_GEMM_QKV);
     size_t st = (size_t)B * qkv_w;
     LAUNCH(c, launch_rope_append(s, c->part, c->ks_qkv > 1 ? c->part + st : nullptr, c->ks_qkv - 1, st, c->d_seq_len,
                                  nullptr, c->d_cos, c->d_sin, c->qb, pool, c->d_table, c->max_blocks, B, Hq, Hkv, h, 1),
            "rope_append");
     prof_mark(c, RLHF_GEN_PROF_ROPE);
-    LAUNCH(c, launch_attn_decode_bf16(s, c->qb, pool, c->d_table, c->max_blocks, c->d_seq_len, c->ab, B, Hq, Hkv),
+    LAUNCH(c, launch_attn_decode_h16(s, c->qb, pool, c->d_table, c->max_blocks, c->d_seq_len, c->ab, B, Hq, Hkv),
            "attn_decode");
     prof_mark(c, RLHF_GEN_PROF_ATTN);
-    LAUNCH(c, launch_gemm_skinny_bf16(s, c->ab, c->wo[l], c->part, B, d, Hq * h, c->ks_wo), "gemm_skinny wo");
+    LAUNCH(c, launch_gemm_skinny_h16(s, c->ab, c->wo[l], c->part, B, d, Hq * h, c->ks_wo), "gemm_skinny wo");
     prof_mark(c, RLHF_GEN_PROF_GEMM_WO);
     LAUNCH(c, launch_rmsnorm(s, c->x, c->part, c->ks_wo, (size_t)B * d, c->ffn_norm[l], 1, c->y, 1, B, d, g.rms_eps,
                              nullptr), "rmsnorm");
     prof_mark(c, RLHF_GEN_PROF_NORM);
-    LAUNCH(c, launch_gemm_skinny_bf16(s, c->y, c->w_gate_up[l], (float*)c->hb, B, 2 * F, d, 0), "gemm_skinny gate_up");
+    LAUNCH(c, launch_gemm_skinny_h16(s, c->y, c->w_gate_up[l], (float*)c->hb, B, 2 * F, d, 0), "gemm_skinny gate_up");
     prof_mark(c, RLHF_GEN_PROF_GEMM_GATE_UP);
-    LAUNCH(c, launch_gemm_skinny_bf16(s, c->hb, c->w_down[l], c->part, B, d, F, c->ks_down), "gemm_skinny down");
+    LAUNCH(c, launch_gemm_skinny_h16(s, c->hb, c->w_down[l], c->part, B, d, F, c->ks_down), "gemm_skinny down");
     prof_mark(c, RLHF_GEN_PROF_GEMM_DOWN);
     pending = c->ks_down;
   }
   LAUNCH(c, launch_rmsnorm(s, c->x, pending ? c->part : nullptr, pending, (size_t)B * d, c->final_norm, 1, c->yl, 1, B,
                            d, g.rms_eps, nullptr), "final rmsnorm");
   prof_mark(c, RLHF_GEN_PROF_NORM);
-  LAUNCH(c, launch_gemm_skinny_bf16(s, c->yl, c->lm_head, c->logits, B, g.vocab, d, 1), "gemm_skinny lm_head");
+  LAUNCH(c, launch_gemm_skinny_h16(s, c->yl, c->lm_head, c->logits, B, g.vocab, d, 1), "gemm_skinny lm_head");
   prof_mark(c, RLHF_GEN_PROF_LM_HEAD);
   return RLHF_GEN_OK;
 }
@@ -544,6 +547,8 @@ int rlhf_gen_init(const rlhf_gen_weights* w, const rlhf_gen_cfg* cfg, rlhf_gen_c
     c->w_gate_up.push_back(w->w_gate_up[l]);
     c->w_down.push_back(w->w_down[l]);
   }
+  c->src_wqkv = c->wqkv; c->src_wo = c->wo; c->src_w_gate_up = c->w_gate_up; c->src_w_down = c->w_down;
+  c->src_lm_head = c->lm_head;
   auto bail = [&](int code) {
     g_init_error = c->err;
     rlhf_gen_destroy(c);
@@ -584,6 +589,34 @@ int rlhf_gen_init(const rlhf_gen_weights* w, const rlhf_gen_cfg* cfg, rlhf_gen_c
   const int half = g.head_dim / 2;
   int rc = RLHF_GEN_OK;
 #define A_(expr) do { rc = (expr); if (rc) return bail(rc); } while (0)
+  if (c->bf16) {
+    // fp16 working copies of the projection matrices (or an in-place rewrite if the caller allows it)
+    const bool in_place = (g.flags & RLHF_GEN_FLAG_CONVERT_IN_PLACE) != 0;
+    auto convert = [&](const void* src, const void** dst, size_t n) -> int {
+      void* d = const_cast<void*>(src);
+      if (!in_place) {
+        char* fresh = nullptr;
+        int r = dev_alloc(c, &fresh, n * 2, false);
+        if (r) return r;
+        d = fresh;
+      }
+      if (launch_bf16_to_h16(c->stream, src, d, n) != hipSuccess) {
+        c->err = "weight conversion kernel failed to launch";
+        return RLHF_GEN_E_DEVICE;
+      }
+      *dst = d;
+      return RLHF_GEN_OK;
+    };
+    const size_t dq = (size_t)qkv_w * g.d_model, dw = (size_t)g.d_model * g.n_heads * g.head_dim,
+                 dg = (size_t)2 * g.d_ffn * g.d_model, dd = (size_t)g.d_model * g.d_ffn;
+    for (int l = 0; l < g.n_layers; ++l) {
+      A_(convert(c->src_wqkv[l], &c->wqkv[l], dq));
+      A_(convert(c->src_wo[l], &c->wo[l], dw));
+      A_(convert(c->src_w_gate_up[l], &c->w_gate_up[l], dg));
+      A_(convert(c->src_w_down[l], &c->w_down[l], dd));
+    }
+    A_(convert(c->src_lm_head, &c->lm_head, (size_t)g.vocab * g.d_model));
+  }
   A_(dev_alloc(c, &c->kv_pool, c->layer_pool_bytes * g.n_layers, true));
   A_(dev_alloc(c, &c->d_table, sizeof(int) * (size_t)g.max_batch * c->max_blocks, true));
   A_(dev_alloc(c, &c->d_seq_len, sizeof(int) * g.max_batch, true));
@@ -823,9 +856,9 @@ int rlhf_gen_op_gemm(void* stream, int kind, const void* A, const void* W, void*
   hipStream_t s = (hipStream_t)stream;
   hipError_t e;
   if (!A || !W || !out || M < 1 || N < 1 || K < 1) return RLHF_GEN_E_INVALID;
-  if (kind == RLHF_GEN_GEMM_TILED) e = launch_gemm_bf16(s, A, W, out, M, N, K, epilogue);
+  if (kind == RLHF_GEN_GEMM_TILED) e = launch_gemm_h16(s, A, W, out, M, N, K, epilogue);
   else if (kind == RLHF_GEN_GEMM_STREAMING)
-    e = launch_gemm_skinny_bf16(s, A, W, (float*)out, M, epilogue == EPI_SWIGLU ? 2 * N : N, K, epilogue == EPI_SWIGLU ? 0 : nsplit);
+    e = launch_gemm_skinny_h16(s, A, W, (float*)out, M, epilogue == EPI_SWIGLU ? 2 * N : N, K, epilogue == EPI_SWIGLU ? 0 : nsplit);
   else if (kind == RLHF_GEN_GEMM_FP32) e = launch_gemm_f32(s, (const float*)A, (const float*)W, (float*)out, M, N, K, epilogue == EPI_RESID_F32);
   else return RLHF_GEN_E_INVALID;
   if (e == hipErrorInvalidValue) return RLHF_GEN_E_UNSUPPORTED;
@@ -835,10 +868,10 @@ int rlhf_gen_op_gemm(void* stream, int kind, const void* A, const void* W, void*
 int rlhf_gen_op_rope_append(void* stream, const float* qkv, const int32_t* row_pos, const int32_t* row_seq,
                             const float* cos_t, const float* sin_t, void* q_out, void* kv_pool,
                             const int32_t* block_table, int32_t max_blocks, int32_t M, int32_t Hq, int32_t Hkv,
-                            int32_t head_dim, int32_t bf16) {
+                            int32_t head_dim, int32_t half16) {
   if (!qkv || !row_pos || !cos_t || !sin_t || !q_out || !kv_pool || !block_table) return RLHF_GEN_E_INVALID;
   hipError_t e = launch_rope_append((hipStream_t)stream, qkv, nullptr, 0, 0, row_pos, row_seq, cos_t, sin_t, q_out, kv_pool,
-                                    block_table, max_blocks, M, Hq, Hkv, head_dim, bf16);
+                                    block_table, max_blocks, M, Hq, Hkv, head_dim, half16);
   if (e == hipErrorInvalidValue) return RLHF_GEN_E_UNSUPPORTED;
   return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;
 }
@@ -846,7 +879,7 @@ int rlhf_gen_op_rope_append(void* stream, const float* qkv, const int32_t* row_p
 int rlhf_gen_op_attn_decode(void* stream, const void* q, const void* kv_pool, const int32_t* block_table,
                             int32_t max_blocks, const int32_t* seq_len, void* out, int32_t B, int32_t Hq, int32_t Hkv) {
   if (!q || !kv_pool || !block_table || !seq_len || !out) return RLHF_GEN_E_INVALID;
-  hipError_t e = launch_attn_decode_bf16((hipStream_t)stream, q, kv_pool, block_table, max_blocks, seq_len, out, B, Hq, Hkv);
+  hipError_t e = launch_attn_decode_h16((hipStream_t)stream, q, kv_pool, block_table, max_blocks, seq_len, out, B, Hq, Hkv);
   if (e == hipErrorInvalidValue) return RLHF_GEN_E_UNSUPPORTED;
   return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;
 }
@@ -855,7 +888,7 @@ int rlhf_gen_op_attn_prefill(void* stream, const void* q, const void* kv_pool, c
                              int32_t max_blocks, const int32_t* cu_seqlens, const int32_t* seq_ids, void* out,
                              int32_t nseq, int32_t max_len, int32_t Hq, int32_t Hkv) {
   if (!q || !kv_pool || !block_table || !cu_seqlens || !seq_ids || !out) return RLHF_GEN_E_INVALID;
-  hipError_t e = launch_attn_prefill_bf16((hipStream_t)stream, q, kv_pool, block_table, max_blocks, cu_seqlens, seq_ids, out,
+  hipError_t e = launch_attn_prefill_h16((hipStream_t)stream, q, kv_pool, block_table, max_blocks, cu_seqlens, seq_ids, out,
                                           nseq, max_len, Hq, Hkv);
   if (e == hipErrorInvalidValue) return RLHF_GEN_E_UNSUPPORTED;
   return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;

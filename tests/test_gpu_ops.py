@@ -19,7 +19,7 @@ def B():
     return binding
 
 
-def _rand(shape, seed, scale=1.0, dtype=torch.bfloat16):
+def _rand(shape, seed, scale=1.0, dtype=torch.float16):
     g = torch.Generator().manual_seed(seed)
     return (torch.randn(*shape, generator=g) * scale).to(dtype)
 
@@ -37,10 +37,10 @@ def test_gemm_tiled_store_and_accumulate(B, M, N, K):
     assert B.rlhf_gen_op_gemm(B.GEMM_TILED, A, W, out, M, N, K, B.EPI_RESID_F32) == 0
     torch.cuda.synchronize()
     assert (out.cpu().double() - 2 * ref).abs().max() < 2 * tol
-    outb = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
-    assert B.rlhf_gen_op_gemm(B.GEMM_TILED, A, W, outb, M, N, K, B.EPI_STORE_BF16) == 0
+    outb = torch.zeros((M, N), dtype=torch.float16, device="cuda")
+    assert B.rlhf_gen_op_gemm(B.GEMM_TILED, A, W, outb, M, N, K, B.EPI_STORE_H16) == 0
     torch.cuda.synchronize()
-    assert (outb.cpu().double() - ref).abs().max() <= ref.abs().max() * 2 ** -8 + tol
+    assert (outb.cpu().double() - ref).abs().max() <= ref.abs().max() * 2 ** -11 + tol
 
 
 @pytest.mark.parametrize("M,F,K", [(300, 384, 256), (64, 128, 128), (1000, 1152, 512)])
@@ -48,11 +48,11 @@ def test_gemm_tiled_swiglu(B, M, F, K):
     a, w = _rand((M, K), 3), _rand((2 * F, K), 4, 0.1)
     gu = a.double() @ w.double().T
     ref = OT.silu(gu[:, :F]) * gu[:, F:]
-    out = torch.zeros((M, F), dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros((M, F), dtype=torch.float16, device="cuda")
     assert B.rlhf_gen_op_gemm(B.GEMM_TILED, a.cuda(), w.cuda(), out, M, F, K, B.EPI_SWIGLU) == 0
     torch.cuda.synchronize()
     err = (out.cpu().double() - ref).abs()
-    assert (err <= ref.abs() * 2 ** -8 + 1e-4).all()
+    assert (err <= ref.abs() * 2 ** -11 + 1e-4).all()
 
 
 @pytest.mark.parametrize("M,N,K,ns", [(4, 128, 256, 1), (16, 512, 1024, 3), (64, 640, 1024, 2), (50, 256, 1408, 4),
@@ -72,11 +72,11 @@ def test_gemm_streaming_swiglu(B, M, F, K):
     a, w = _rand((M, K), 13), _rand((2 * F, K), 14, 0.1)
     gu = a.double() @ w.double().T
     ref = OT.silu(gu[:, :F]) * gu[:, F:]
-    out = torch.zeros((M, F), dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros((M, F), dtype=torch.float16, device="cuda")
     assert B.rlhf_gen_op_gemm(B.GEMM_STREAMING, a.cuda(), w.cuda(), out, M, F, K, B.EPI_SWIGLU, 1) == 0
     torch.cuda.synchronize()
     err = (out.cpu().double() - ref).abs()
-    assert (err <= ref.abs() * 2 ** -8 + 1e-4).all()
+    assert (err <= ref.abs() * 2 ** -11 + 1e-4).all()
 
 
 def test_gemm_fp32(B):
@@ -91,7 +91,7 @@ def test_gemm_fp32(B):
 
 
 def test_gemm_rejects_bad_shapes(B):
-    t = torch.zeros(256, 256, dtype=torch.bfloat16, device="cuda")
+    t = torch.zeros(256, 256, dtype=torch.float16, device="cuda")
     o = torch.zeros(256, 256, dtype=torch.float32, device="cuda")
     assert B.rlhf_gen_op_gemm(B.GEMM_TILED, t, t, o, 256, 200, 256, 0) == B.E_UNSUPPORTED
     assert B.rlhf_gen_op_gemm(B.GEMM_TILED, t, t, o, 256, 256, 100, 0) == B.E_UNSUPPORTED
@@ -117,18 +117,18 @@ def test_attention_prefill_then_decode(B, Hq, Hkv, lens):
     pool = torch.zeros(n_blocks, Hkv, 8192, dtype=torch.uint8, device="cuda")
     dev = lambda t: t.cuda().contiguous()
     qkv_d, cos_d, sin_d, table_d = dev(qkv), dev(cos_t), dev(sin_t), dev(table)
-    q_out = torch.zeros(T, Hq, h, dtype=torch.bfloat16, device="cuda")
+    q_out = torch.zeros(T, Hq, h, dtype=torch.float16, device="cuda")
     assert B.rlhf_gen_op_rope_append(qkv_d[:T].contiguous(), dev(row_pos), dev(row_seq), cos_d, sin_d, q_out, pool,
                                      table_d, max_blocks, T, Hq, Hkv, h, True) == 0
-    out = torch.zeros(T, Hq * h, dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros(T, Hq * h, dtype=torch.float16, device="cuda")
     seq_ids = torch.arange(nseq, dtype=torch.int32, device="cuda")
     assert B.rlhf_gen_op_attn_prefill(q_out, pool, table_d, max_blocks, dev(cu), seq_ids, out, nseq, max(lens), Hq, Hkv) == 0
     # decode row for each sequence at position len
-    qd = torch.zeros(nseq, Hq, h, dtype=torch.bfloat16, device="cuda")
+    qd = torch.zeros(nseq, Hq, h, dtype=torch.float16, device="cuda")
     seq_len = torch.tensor(lens, dtype=torch.int32, device="cuda")
     assert B.rlhf_gen_op_rope_append(qkv_d[T:].contiguous(), seq_len, None, cos_d, sin_d, qd, pool, table_d, max_blocks,
                                      nseq, Hq, Hkv, h, True) == 0
-    outd = torch.zeros(nseq, Hq * h, dtype=torch.bfloat16, device="cuda")
+    outd = torch.zeros(nseq, Hq * h, dtype=torch.float16, device="cuda")
     assert B.rlhf_gen_op_attn_decode(qd, pool, table_d, max_blocks, seq_len, outd, nseq, Hq, Hkv) == 0
     torch.cuda.synchronize()
     # CPU definition on the unrounded fp32 inputs
@@ -146,7 +146,7 @@ def test_attention_prefill_then_decode(B, Hq, Hkv, lens):
                 want = oracle_attention_rows(q[i, j], k[: i + 1, kv], v[: i + 1, kv], scale)
                 got = (out[cu[b] + i, j * h:(j + 1) * h] if i < L else outd[b, j * h:(j + 1) * h]).cpu().double()
                 worst = max(worst, float((got - want).abs().max()))
-    assert worst < 3e-2, worst
+    assert worst < 4e-3, worst   # fp16 rounding of q, k, v, p and the output on values of order 1
 
 
 @pytest.mark.parametrize("mode", ["greedy", "plain", "nucleus", "nucleus_lp1", "tight"])
