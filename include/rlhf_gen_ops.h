@@ -29,27 +29,31 @@ enum { RLHF_GEN_EPI_STORE_F32 = 0, RLHF_GEN_EPI_RESID_F32 = 1, RLHF_GEN_EPI_SWIG
  *   STREAMING fp16 A and W, M <= 256, N % 64 == 0, K % 128 == 0; out is fp32 [nsplit, M, N] partial sums whose
  *             sum over the first axis is the product.  nsplit in [1, K/128].  With epilogue SWIGLU instead: W is
  *             [2N, K] (gate rows then up rows), N % 32 == 0, no split, out is fp16 [M, N] = silu(gate) * up.
- *   FP32      fp32 A, W, out; epilogue STORE_F32 or RESID_F32. */
+ *   FP32      fp32 A, W, out; epilogue STORE_F32 or RESID_F32.
+ * a_pairs != 0 (TILED, and STREAMING up to 128 rows without SWIGLU): A is [M, 2K], each row the fp16 pair
+ * [hi (K) | lo (K)] of a higher-precision activation, and out = (hi + lo) W^T. */
 int rlhf_gen_op_gemm(void* stream, int kind, const void* A, const void* W, void* out, int32_t M, int32_t N, int32_t K,
-                     int32_t epilogue, int32_t nsplit);
+                     int32_t epilogue, int32_t nsplit, int32_t a_pairs);
 
 /* Rotate q and k of fp32 qkv rows [M, (Hq + 2 Hkv) head_dim] by their positions and append k, v to the paged
  * cache.  row_pos [M] position of each row; row_seq [M] batch row (NULL = identity); cos_t / sin_t
  * [positions, head_dim/2] fp32 tables; block_table int32 [batch, max_blocks]; kv_pool = one layer's pool
  * ([n_blocks, Hkv, 8192] bytes of fp16 in 16-bit mode, [n_blocks, Hkv, 2, 16, head_dim] floats in fp32 mode);
- * q_out [M, Hq, head_dim] in fp16 (half16 != 0) or fp32. */
+ * q_out: half16 != 0: fp16 [M, Hq, 2, head_dim], the pair [hi | lo] of each rotated query head; else fp32
+ * [M, Hq, head_dim]. */
 int rlhf_gen_op_rope_append(void* stream, const float* qkv, const int32_t* row_pos, const int32_t* row_seq,
                             const float* cos_t, const float* sin_t, void* q_out, void* kv_pool,
                             const int32_t* block_table, int32_t max_blocks, int32_t M, int32_t Hq, int32_t Hkv,
                             int32_t head_dim, int32_t half16);
 
 /* One query row per (sequence, query head) against the seq_len[b] + 1 newest-inclusive cached tokens (fp16 cache,
- * head_dim 128).  q [B, Hq, 128] fp16, out [B, Hq * 128] fp16. */
+ * head_dim 128).  q fp16 [B, Hq, 2, 128] (hi | lo pairs), out fp16 [B, 2, Hq * 128] (hi block, then lo block). */
 int rlhf_gen_op_attn_decode(void* stream, const void* q, const void* kv_pool, const int32_t* block_table,
                             int32_t max_blocks, const int32_t* seq_len, void* out, int32_t B, int32_t Hq, int32_t Hkv);
 
 /* Causal attention of packed query rows over the cache their own keys were appended to.  cu_seqlens [nseq + 1]
- * row offsets, seq_ids [nseq] batch rows (block-table rows), q / out [rows, Hq, 128] fp16, max_len = longest sequence. */
+ * row offsets, seq_ids [nseq] batch rows (block-table rows), q [rows, Hq, 2, 128] and out [rows, 2, Hq * 128] fp16 pairs
+ * as in the decode call, max_len = longest sequence. */
 int rlhf_gen_op_attn_prefill(void* stream, const void* q, const void* kv_pool, const int32_t* block_table,
                              int32_t max_blocks, const int32_t* cu_seqlens, const int32_t* seq_ids, void* out,
                              int32_t nseq, int32_t max_len, int32_t Hq, int32_t Hkv);

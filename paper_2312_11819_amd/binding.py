@@ -86,7 +86,7 @@ def lib() -> C.CDLL:
         L.rlhf_gen_destroy.argtypes = [C.c_void_p]
         L.rlhf_gen_destroy.restype = None
         L.rlhf_gen_op_gemm.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
-                                       C.c_int32, C.c_int32, C.c_int32]
+                                       C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         L.rlhf_gen_op_rope_append.argtypes = [C.c_void_p] * 9 + [C.c_int32] * 6
         L.rlhf_gen_op_attn_decode.argtypes = [C.c_void_p] * 4 + [C.c_int32, C.c_void_p, C.c_void_p] + [C.c_int32] * 3
         L.rlhf_gen_op_attn_prefill.argtypes = [C.c_void_p] * 4 + [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p] + [C.c_int32] * 4
@@ -210,8 +210,8 @@ class Context:
 
 
 # -- single-operation entry points -------------------------------------------------------------------
-def rlhf_gen_op_gemm(kind, A, W, out, M, N, K, epilogue=0, nsplit=1) -> int:
-    return lib().rlhf_gen_op_gemm(None, kind, _ptr(A), _ptr(W), _ptr(out), M, N, K, epilogue, nsplit)
+def rlhf_gen_op_gemm(kind, A, W, out, M, N, K, epilogue=0, nsplit=1, a_pairs=0) -> int:
+    return lib().rlhf_gen_op_gemm(None, kind, _ptr(A), _ptr(W), _ptr(out), M, N, K, epilogue, nsplit, a_pairs)
 
 
 def rlhf_gen_op_rope_append(qkv, row_pos, row_seq, cos_t, sin_t, q_out, kv_pool, block_table, max_blocks, M, Hq, Hkv,

@@ -20,6 +20,14 @@ __device__ __forceinline__ h16_t f32_to_h16(float f) {
 __device__ __forceinline__ uint32_t pack_h16x2(float lo, float hi) {
   return (uint32_t)f32_to_h16(lo) | ((uint32_t)f32_to_h16(hi) << 16);
 }
+__device__ __forceinline__ float h16_to_f32(h16_t v) { return (float)__builtin_bit_cast(_Float16, v); }
+// Two-term fp16 representation v ~ hi + lo (22 significant bits).  The tensors whose rounding dominates the
+// rollout's logit error (the input of the QKV and output projections, the rotated queries and the attention
+// probabilities) are carried as such pairs and contracted with two MFMAs into the same accumulator.
+__device__ __forceinline__ void split_h16(float v, h16_t& hi, h16_t& lo) {
+  hi = f32_to_h16(v);
+  lo = f32_to_h16(v - h16_to_f32(hi));
+}
 
 // All 16-bit MFMA operands are fp16 (11 significant bits): with bf16 activations the rounding error of a
 // 32-layer rollout exceeds the parity tolerance several times over; the bf16 weights convert to fp16 exactly.

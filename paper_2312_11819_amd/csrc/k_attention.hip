@@ -33,10 +33,13 @@ __device__ __forceinline__ void load_page(const char* page, int lane, uint4 kf[4
 }
 
 // tok0: index of the page's first token; limit: number of tokens visible to this lane's query row.
+// qf[0..3]: high parts of the query fragments, qf[4..7]: low parts (queries are fp16 pairs).
 template <bool MASK>
-__device__ __forceinline__ void attn_page(const uint4 kf[4], const uint4 vf[4], const uint4 qf[4], AttnState& st,
+__device__ __forceinline__ void attn_page(const uint4 kf[4], const uint4 vf[4], const uint4 qf[8], AttnState& st,
                                           float scale_log2, int tok0, int limit, int g) {
   f32x4_t s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) s = mfma_16x16x32(kf[kk], qf[4 + kk], s);
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) s = mfma_16x16x32(kf[kk], qf[kk], s);
   float sv[4];
@@ -62,11 +65,16 @@ __device__ __forceinline__ void attn_page(const uint4 kf[4], const uint4 vf[4], 
   st.m = mnew;
 #pragma unroll
   for (int db = 0; db < 8; ++db) st.o[db] *= alpha;
-  uint2 pb;
-  pb.x = pack_h16x2(p[0], p[1]);
-  pb.y = pack_h16x2(p[2], p[3]);
+  // probabilities as fp16 pairs: two MFMAs per value tile
+  h16_t ph[4], pl[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) split_h16(p[i], ph[i], pl[i]);
+  const uint2 pb = make_uint2((uint32_t)ph[0] | ((uint32_t)ph[1] << 16), (uint32_t)ph[2] | ((uint32_t)ph[3] << 16));
+  const uint2 pc = make_uint2((uint32_t)pl[0] | ((uint32_t)pl[1] << 16), (uint32_t)pl[2] | ((uint32_t)pl[3] << 16));
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
+    st.o[2 * j] = mfma_16x16x16(make_uint2(vf[j].x, vf[j].y), pc, st.o[2 * j]);
+    st.o[2 * j + 1] = mfma_16x16x16(make_uint2(vf[j].z, vf[j].w), pc, st.o[2 * j + 1]);
     st.o[2 * j] = mfma_16x16x16(make_uint2(vf[j].x, vf[j].y), pb, st.o[2 * j]);
     st.o[2 * j + 1] = mfma_16x16x16(make_uint2(vf[j].z, vf[j].w), pb, st.o[2 * j + 1]);
   }
@@ -79,7 +87,7 @@ __device__ __forceinline__ void init_state(AttnState& st) {
   st.l = 0.f;
 }
 
-// grid (Hkv, B), 256 threads.  q [B, Hq, 128] fp16, out [B, Hq*128] fp16.  seq_len[b] = tokens cached BEFORE
+// grid (Hkv, B), 256 threads.  q [B, Hq, 2, 128] fp16 (hi | lo per head), out [B, 2, Hq*128] fp16 (hi | lo).  seq_len[b] = tokens cached BEFORE
 // this step; the step's own key/value has already been appended, so seq_len[b] + 1 tokens are visible.
 __global__ __launch_bounds__(256) void attn_decode_kernel(const h16_t* __restrict__ q, const char* __restrict__ pool,
                                                           const int* __restrict__ block_table, int max_blocks,
@@ -93,11 +101,12 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const h16_t* __restric
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, t = lane & 15, g = lane >> 4;
   const int L = seq_len[b] + 1;
   const int npages = (L + 15) >> 4;
-  uint4 qf[4];
+  uint4 qf[8];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
+  for (int kk = 0; kk < 8; ++kk) {
     qf[kk] = make_uint4(0, 0, 0, 0);
-    if (t < group) qf[kk] = *(const uint4*)(q + ((size_t)b * Hq + kvh * group + t) * 128 + 8 * (4 * kk + g));
+    if (t < group)
+      qf[kk] = *(const uint4*)(q + ((size_t)b * Hq + kvh * group + t) * 256 + (kk >> 2) * 128 + 8 * (4 * (kk & 3) + g));
   }
   AttnState st;
   init_state(st);
@@ -144,12 +153,14 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const h16_t* __restric
       num += a * o_s[ww][r][dim];
       den += a * l_s[ww][r];
     }
-    out[((size_t)b * Hq + kvh * group + r) * 128 + dim] = f32_to_h16(num / den);
+    h16_t* orow = out + (size_t)b * 2 * Hq * 128 + (kvh * group + r) * 128 + dim;
+    split_h16(num / den, orow[0], orow[Hq * 128]);
   }
 }
 
 // grid (ceil(max_len / 64), Hq, nseq), 256 threads: wavefront w owns positions p0 .. p0+15 of sequence
-// seq_ids[blockIdx.z] with p0 = 16 (4 blockIdx.x + w).  q / out are packed over tokens: row cu_seqlens[z] + pos.
+// seq_ids[blockIdx.z] with p0 = 16 (4 blockIdx.x + w).  q / out are packed over tokens (row cu_seqlens[z] + pos)
+// in the same hi | lo layouts as the decode kernel.
 __global__ __launch_bounds__(256) void attn_prefill_kernel(const h16_t* __restrict__ q, const char* __restrict__ pool,
                                                            const int* __restrict__ block_table, int max_blocks,
                                                            const int* __restrict__ cu_seqlens,
@@ -163,11 +174,12 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const h16_t* __restri
   const int b = seq_ids[z];
   const int kvh = head / (Hq / Hkv);
   const bool valid = p0 + t < len;
-  uint4 qf[4];
+  uint4 qf[8];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
+  for (int kk = 0; kk < 8; ++kk) {
     qf[kk] = make_uint4(0, 0, 0, 0);
-    if (valid) qf[kk] = *(const uint4*)(q + ((size_t)(row0 + p0 + t) * Hq + head) * 128 + 8 * (4 * kk + g));
+    if (valid)
+      qf[kk] = *(const uint4*)(q + ((size_t)(row0 + p0 + t) * Hq + head) * 256 + (kk >> 2) * 128 + 8 * (4 * (kk & 3) + g));
   }
   AttnState st;
   init_state(st);
@@ -189,13 +201,14 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const h16_t* __restri
   lt += __shfl_xor(lt, 32);
   if (valid) {
     float inv = 1.f / lt;
-    h16_t* orow = out + ((size_t)(row0 + p0 + t) * Hq + head) * 128 + 4 * g;
+    h16_t* orow = out + (size_t)(row0 + p0 + t) * 2 * Hq * 128 + head * 128 + 4 * g;  // row = [hi (Hq*128) | lo]
 #pragma unroll
     for (int db = 0; db < 8; ++db) {
-      uint2 o;
-      o.x = pack_h16x2(st.o[db][0] * inv, st.o[db][1] * inv);
-      o.y = pack_h16x2(st.o[db][2] * inv, st.o[db][3] * inv);
-      *(uint2*)(orow + db * 16) = o;
+      h16_t hi[4], lo[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) split_h16(st.o[db][i] * inv, hi[i], lo[i]);
+      *(uint2*)(orow + db * 16) = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+      *(uint2*)(orow + Hq * 128 + db * 16) = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
     }
   }
 }

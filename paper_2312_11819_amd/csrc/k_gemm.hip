@@ -1,6 +1,6 @@
 // GEMMs of the rollout, out = A[M,K] * W[N,K]^T with both operands K-contiguous.
-//   gemm_h16_kernel     : large-tile fp16 MFMA GEMM for prefill (M = thousands of tokens): 256x256x64 block tile,
-//                         8 wavefronts of 128x64, LDS double buffer fed through registers, 32x32x16 MFMA.
+//   gemm_h16_dma_kernel : large-tile fp16 MFMA GEMM for prefill (M = thousands of tokens): 256x256x64 block tile,
+//                         8 wavefronts of 128x64, LDS double buffer filled by LDS-DMA loads, 32x32x16 MFMA.
 //   gemm_skinny_kernel  : weight-streaming GEMM for decode (M = batch <= 256): W is the MFMA row operand read
 //                         straight from HBM into registers exactly once, the activation slice is staged in LDS,
 //                         split-K partial sums go to a workspace that the consumer kernel adds up in a fixed order.
@@ -12,172 +12,9 @@
 
 namespace {
 
-constexpr int BK = 64;            // k extent of one LDS tile
-constexpr int LDS_ROW = BK * 2 + 16;  // bytes per tile row; the 16 B pad spreads 16 B reads over all banks
-
-template <int BM, int BN, int WM, int WN, int EPI>
-__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_h16_kernel(const h16_t* __restrict__ A,
-                                                                               const h16_t* __restrict__ W,
-                                                                               void* __restrict__ out, int M, int N,
-                                                                               int K, int tilesM, int tilesN) {
-  constexpr int NT = (BM / WM) * (BN / WN) * 64;
-  constexpr int WAVES_N = BN / WN;
-  constexpr int MI = WM / 32, NI = WN / 32;
-  constexpr int A_IT = BM * 8 / NT, B_IT = BN * 8 / NT;
-  constexpr int TILE_BYTES = (BM + BN) * LDS_ROW;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-
-  // workgroup -> tile: consecutive ids on one XCD (ids are dealt round-robin to 8 XCDs) walk a band of 8 row
-  // tiles column by column, so the W tile and the 8 A tiles in flight stay in that XCD's L2.
-  int pid = blockIdx.x;
-  const int total = tilesM * tilesN;
-  if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
-  const int band = 8 * tilesN;
-  const int first_m = (pid / band) * 8;
-  const int gsz = min(tilesM - first_m, 8);
-  const int tm = first_m + (pid % band) % gsz;
-  const int tn = (pid % band) / gsz;
-  const int m0 = tm * BM;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-
-  // global row of W for LDS B-tile row r
-  auto wrow = [&](int r) -> int {
-    if (EPI == EPI_SWIGLU) {
-      int wv = r / WN, qd = r % WN;
-      int half = qd / (WN / 2), j = qd % (WN / 2);
-      return half * N + tn * (BN / 2) + wv * (WN / 2) + j;  // N = F here
-    }
-    return tn * BN + r;
-  };
-
-  // 32-bit byte offsets from the (scalar) operand bases keep the address registers few
-  uint32_t a_go[A_IT], b_go[B_IT];
-  const int ld_r = tid >> 3, ld_kc = tid & 7;       // chunk c = it * NT + tid -> row it * (NT / 8) + ld_r, k chunk ld_kc
-#pragma unroll
-  for (int it = 0; it < A_IT; ++it) {
-    int r = it * (NT / 8) + ld_r;
-    a_go[it] = (uint32_t)min(m0 + r, M - 1) * (uint32_t)K * 2u + ld_kc * 16;
-  }
-#pragma unroll
-  for (int it = 0; it < B_IT; ++it) {
-    int r = it * (NT / 8) + ld_r;
-    b_go[it] = (uint32_t)wrow(r) * (uint32_t)K * 2u + ld_kc * 16;
-  }
-  const int st_off = ld_r * LDS_ROW + ld_kc * 16;   // LDS byte offset of this thread's chunk in row block 0
-
-  f32x16_t acc[MI][NI];
-#pragma unroll
-  for (int i = 0; i < MI; ++i)
-#pragma unroll
-    for (int j = 0; j < NI; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-  // Global loads run two k-tiles ahead of the MFMAs: a ring of two register slots feeds the double-buffered LDS
-  // tile.  No branch surrounds a load (a tile index past the end re-reads the last tile), so the compiler can
-  // keep both slots in flight and wait only for the older one.
-  struct Slot { uint4 a[A_IT]; uint4 b[B_IT]; };
-  Slot r0, r1;
-  const int nk = K / BK;
-#define G_LOAD(S, KT)                                                                                   \
-  {                                                                                                     \
-    const char* ab = (const char*)A + (size_t)min((KT), nk - 1) * (BK * 2);                             \
-    const char* wb = (const char*)W + (size_t)min((KT), nk - 1) * (BK * 2);                             \
-    _Pragma("unroll") for (int it = 0; it < A_IT; ++it) S.a[it] = *(const uint4*)(ab + a_go[it]);       \
-    _Pragma("unroll") for (int it = 0; it < B_IT; ++it) S.b[it] = *(const uint4*)(wb + b_go[it]);       \
-  }
-#define G_STORE(S, STAGE)                                                                               \
-  {                                                                                                     \
-    char* dstb = smem + (STAGE) * TILE_BYTES + st_off;                                                  \
-    _Pragma("unroll") for (int it = 0; it < A_IT; ++it)                                                 \
-        *(uint4*)(dstb + it * (NT / 8) * LDS_ROW) = S.a[it];                                            \
-    _Pragma("unroll") for (int it = 0; it < B_IT; ++it)                                                 \
-        *(uint4*)(dstb + (BM + it * (NT / 8)) * LDS_ROW) = S.b[it];                                     \
-  }
-#define G_COMPUTE(STAGE)                                                                                \
-  {                                                                                                     \
-    const char* cur = smem + (STAGE) * TILE_BYTES;                                                      \
-    _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                            \
-      uint4 af[MI], bfr[NI];                                                                            \
-      _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                    \
-          af[i] = *(const uint4*)(cur + a_frag + i * 32 * LDS_ROW + ks * 32);                           \
-      _Pragma("unroll") for (int j = 0; j < NI; ++j)                                                    \
-          bfr[j] = *(const uint4*)(cur + b_frag + j * 32 * LDS_ROW + ks * 32);                          \
-      _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                    \
-          _Pragma("unroll") for (int j = 0; j < NI; ++j)                                                \
-              acc[i][j] = mfma_32x32x16(af[i], bfr[j], acc[i][j]);                                      \
-    }                                                                                                   \
-  }
-  const int a_frag = (wm * WM + (lane & 31)) * LDS_ROW + (lane >> 5) * 16;
-  const int b_frag = BM * LDS_ROW + (wn * WN + (lane & 31)) * LDS_ROW + (lane >> 5) * 16;
-  G_LOAD(r0, 0)
-  G_LOAD(r1, 1)
-  G_STORE(r0, 0)
-  G_LOAD(r0, 2)
-  __syncthreads();
-  int kt = 0;
-  for (; kt + 2 <= nk; kt += 2) {
-    G_COMPUTE(0)
-    G_STORE(r1, 1)
-    G_LOAD(r1, kt + 3)
-    __syncthreads();
-    G_COMPUTE(1)
-    G_STORE(r0, 0)
-    G_LOAD(r0, kt + 4)
-    __syncthreads();
-  }
-  if (kt < nk) G_COMPUTE(0)
-#undef G_LOAD
-#undef G_STORE
-#undef G_COMPUTE
-
-  // epilogue: lane holds column (lane & 31) and rows 8 (e >> 2) + 4 (lane >> 5) + (e & 3) of each 32x32 tile
-#pragma unroll
-  for (int i = 0; i < MI; ++i) {
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      int m = m0 + wm * WM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-      if (m >= M) continue;
-      if (EPI == EPI_SWIGLU) {
-#pragma unroll
-        for (int j = 0; j < NI / 2; ++j) {
-          int f = tn * (BN / 2) + wn * (WN / 2) + j * 32 + (lane & 31);
-          float gte = acc[i][j][e], up = acc[i][j + NI / 2][e];
-          float v = gte / (1.f + __expf(-gte)) * up;
-          ((h16_t*)out)[(size_t)m * N + f] = f32_to_h16(v);
-        }
-      } else {
-#pragma unroll
-        for (int j = 0; j < NI; ++j) {
-          int n = tn * BN + wn * WN + j * 32 + (lane & 31);
-          float v = acc[i][j][e];
-          if (EPI == EPI_STORE_F32) ((float*)out)[(size_t)m * N + n] = v;
-          if (EPI == EPI_RESID_F32) ((float*)out)[(size_t)m * N + n] += v;
-          if (EPI == EPI_STORE_ACT) ((h16_t*)out)[(size_t)m * N + n] = f32_to_h16(v);
-        }
-      }
-    }
-  }
-}
-
-template <int EPI>
-hipError_t launch_large(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K, bool configure_only = false) {
-  constexpr int BM = 256, BN = 256, WM = 128, WN = 64;
-  constexpr int NT = (BM / WM) * (BN / WN) * 64;
-  constexpr int SMEM = 2 * (BM + BN) * LDS_ROW;
-  auto kern = gemm_h16_kernel<BM, BN, WM, WN, EPI>;
-  if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
-  int tilesM = (M + BM - 1) / BM;
-  int tilesN = (EPI == EPI_SWIGLU) ? N / (BN / 2) : N / BN;
-  kern<<<tilesM * tilesN, NT, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, out, M, N, K, tilesM, tilesN);
-  return hipGetLastError();
-}
-
 // ---------------------------------------------------------------------------------------------------
-// Large-tile GEMM, second form: the operand tiles go from global memory straight into LDS (LDS-DMA loads, no
-// staging registers), 256x256x64 block tile, two LDS stages of 64 KB, 8 wavefronts of 128x64.
+// Large-tile GEMM: the operand tiles go from global memory straight into LDS (LDS-DMA loads, no staging
+// registers), 256x256x64 block tile, two LDS stages of 64 KB, 8 wavefronts of 128x64, 32x32x16 MFMA.
 //   * A wavefront-wide DMA load writes lane i's 16 bytes to LDS base + 16 i, so one instruction fills eight
 //     128-byte tile rows.  To keep the later 16-byte MFMA operand reads free of bank conflicts the 16-byte chunk
 //     c of row r is stored at slot c ^ (r & 7); the permutation is applied on the global side (lane i fetches
@@ -203,7 +40,8 @@ __device__ __forceinline__ f32x16_t mfma_32x32x16_v(u32x4_t a, u32x4_t b, f32x16
 template <int EPI>
 __global__ __launch_bounds__(512) void gemm_h16_dma_kernel(const h16_t* __restrict__ A, const h16_t* __restrict__ W,
                                                             void* __restrict__ out, int M, int N, int K, int tilesM,
-                                                            int tilesN) {
+                                                            int tilesN, int a_dual) {
+  // a_dual: A rows are [hi (K) | lo (K)]; the k loop then runs over 2K columns of A against W's K columns twice.
   constexpr int BM = 256, BN = 256, WN = 64;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   int pid = blockIdx.x;
@@ -235,14 +73,16 @@ __global__ __launch_bounds__(512) void gemm_h16_dma_kernel(const h16_t* __restri
   for (int it = 0; it < 8; ++it) {
     int row = 8 * ((wave & 3) * 8 + it) + (lane >> 3);
     int grow = loads_a ? min(m0 + row, M - 1) : wrow(row);
-    go[it] = (uint32_t)grow * (uint32_t)K * 2u + (uint32_t)(((lane & 7) ^ (lane >> 3)) * 16);
+    go[it] = (uint32_t)grow * (uint32_t)(loads_a && a_dual ? 2 * K : K) * 2u + (uint32_t)(((lane & 7) ^ (lane >> 3)) * 16);
   }
+  const int nkw = K / 64;                       // k-tiles of W
+  const int nk = a_dual ? 2 * nkw : nkw;        // k-tiles of the product
   typedef __attribute__((address_space(3))) void lds_void;
   typedef const __attribute__((address_space(1))) void g_void;
   char* dma_dst = smem + wave * 8192;  // + stage * DMA_STAGE + it * 1024
 #define DMA_ISSUE(KT, STAGE)                                                                              \
   {                                                                                                       \
-    const char* src = gbase + (size_t)(KT) * 128;                                                         \
+    const char* src = gbase + (size_t)(loads_a ? (KT) : ((KT) >= nkw ? (KT) - nkw : (KT))) * 128;        \
     _Pragma("unroll") for (int it = 0; it < 8; ++it)                                                      \
         __builtin_amdgcn_global_load_lds((g_void*)(src + go[it]),                                         \
                                          (lds_void*)(dma_dst + (STAGE) * DMA_STAGE + it * 1024), 16, 0, 0); \
@@ -267,7 +107,6 @@ __global__ __launch_bounds__(512) void gemm_h16_dma_kernel(const h16_t* __restri
     b_rd[ks] = lds0 + (uint32_t)((BM + wn * 64 + (lane & 31)) * 128) + slot * 16;
   }
 
-  const int nk = K / 64;
   DMA_ISSUE(0, 0)
   for (int kt = 0; kt < nk; ++kt) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -327,14 +166,14 @@ __global__ __launch_bounds__(512) void gemm_h16_dma_kernel(const h16_t* __restri
 }
 
 template <int EPI>
-hipError_t launch_large_dma(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K,
+hipError_t launch_large_dma(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K, int a_dual,
                             bool configure_only = false) {
   constexpr int SMEM = 2 * DMA_STAGE;
   auto kern = gemm_h16_dma_kernel<EPI>;
   if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
   int tilesM = (M + 255) / 256;
   int tilesN = (EPI == EPI_SWIGLU) ? N / 128 : N / 256;
-  kern<<<tilesM * tilesN, 512, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, out, M, N, K, tilesM, tilesN);
+  kern<<<tilesM * tilesN, 512, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, out, M, N, K, tilesM, tilesN, a_dual);
   return hipGetLastError();
 }
 
@@ -346,13 +185,17 @@ constexpr int SK_ROW = SK * 2 + 16;     // bytes per LDS row (padded)
 // Loads run D - 1 k-steps ahead of the MFMAs through a register ring (weights and the activation slice alike:
 // the memory counter retires in order, so both must share one prefetch distance); the activation slice then
 // passes through a double-buffered LDS tile that the four wavefronts share.
-template <int MB, int D, bool GLU = false>
+template <int MB, int D, bool GLU, bool DUAL>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(const h16_t* __restrict__ X, const h16_t* __restrict__ W,
                                                           float* __restrict__ part, int M, int Nw, int K,
                                                           int steps_per_split) {
   static_assert(D == 2 || D == 4, "ring depth 2 or 4");
+  // DUAL: X rows are [hi (K) | lo (K)] fp16 pairs; the LDS tile holds the hi rows followed by the lo rows and every
+  // weight fragment is multiplied with both.
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  constexpr int XBYTES = 16 * MB * SK_ROW;
+  constexpr int XR = DUAL ? 2 * MB : MB;   // 16-row blocks of the staged slice
+  constexpr int XBYTES = 16 * XR * SK_ROW;
+  const int ldx = DUAL ? 2 * K : K;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, t = lane & 15, g = lane >> 4;
   // GLU: W = [gate rows | up rows] of F = Nw / 2 features each; the workgroup owns 32 features, each wavefront
   // 8 of them with the gate rows in MFMA rows 0..7 and the matching up rows in 8..15.
@@ -369,12 +212,13 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const h16_t* __restric
   const h16_t* wp = W + (size_t)wrow * K + 8 * g;
   // Activation slice: 16 MB rows x 16 chunks of 16 B per k-step, MB chunks per thread.  Rows beyond M are read
   // from row M - 1 instead: they only feed output columns that are never stored.
-  const h16_t* xp[MB];
-  int xo[MB];
+  const h16_t* xp[XR];
+  int xo[XR];
 #pragma unroll
-  for (int it = 0; it < MB; ++it) {
-    int c = it * 256 + tid, r = c >> 4, kc = c & 15;
-    xp[it] = X + (size_t)min(r, M - 1) * K + kc * 8;
+  for (int it = 0; it < XR; ++it) {
+    int c = it * 256 + tid, r = c >> 4, kc = c & 15;   // r in [0, 16 XR): rows >= 16 MB are the lo parts
+    int rr = DUAL ? r % (16 * MB) : r;
+    xp[it] = X + (size_t)min(rr, M - 1) * ldx + ((DUAL && r >= 16 * MB) ? K : 0) + kc * 8;
     xo[it] = r * SK_ROW + kc * 16;
   }
   // Workgroups walk their k range from different starting points (wrapping around), so that they do not all
@@ -390,30 +234,30 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const h16_t* __restric
     return (size_t)(s0 + r) * SK;
   };
   // Ring of D named slots (separate variables, so that they live in registers).
-  struct Slot { uint4 w[4]; uint4 x[MB]; };
+  struct Slot { uint4 w[4]; uint4 x[XR]; };
   Slot r0, r1, r2, r3;
 #define SKINNY_LOAD(S, I)                                                                                \
   {                                                                                                      \
     const size_t ko = step_off(I);                                                                       \
     _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) S.w[kk] = *(const uint4*)(wp + ko + kk * 32);       \
-    _Pragma("unroll") for (int it = 0; it < MB; ++it) S.x[it] = *(const uint4*)(xp[it] + ko);            \
+    _Pragma("unroll") for (int it = 0; it < XR; ++it) S.x[it] = *(const uint4*)(xp[it] + ko);            \
   }
   // one k-step on slot S (LDS buffer PAR)
 #define SKINNY_STEP(S, PAR)                                                                              \
   {                                                                                                      \
     char* buf = smem + (PAR) * XBYTES;                                                                   \
-    _Pragma("unroll") for (int it = 0; it < MB; ++it) *(uint4*)(buf + xo[it]) = S.x[it];                 \
+    _Pragma("unroll") for (int it = 0; it < XR; ++it) *(uint4*)(buf + xo[it]) = S.x[it];                 \
     __syncthreads();                                                                                     \
-    uint4 xf[2][MB];                                                                                     \
-    _Pragma("unroll") for (int mb = 0; mb < MB; ++mb)                                                    \
+    uint4 xf[2][XR];                                                                                     \
+    _Pragma("unroll") for (int mb = 0; mb < XR; ++mb)                                                    \
         xf[0][mb] = *(const uint4*)(buf + (mb * 16 + t) * SK_ROW + g * 16);                              \
     _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                                   \
       if (kk < 3) {                                                                                      \
-        _Pragma("unroll") for (int mb = 0; mb < MB; ++mb)                                                \
+        _Pragma("unroll") for (int mb = 0; mb < XR; ++mb)                                                \
             xf[(kk + 1) & 1][mb] = *(const uint4*)(buf + (mb * 16 + t) * SK_ROW + (kk + 1) * 64 + g * 16); \
       }                                                                                                  \
-      _Pragma("unroll") for (int mb = 0; mb < MB; ++mb)                                                  \
-          acc[mb] = mfma_16x16x32(S.w[kk], xf[kk & 1][mb], acc[mb]);                                     \
+      _Pragma("unroll") for (int mb = 0; mb < XR; ++mb)                                                  \
+          acc[mb % MB] = mfma_16x16x32(S.w[kk], xf[kk & 1][mb], acc[mb % MB]);                           \
     }                                                                                                    \
   }
   if (nst > 0) {
@@ -485,22 +329,33 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const h16_t* __restric
 
 template <int MB>
 hipError_t launch_skinny(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K, int nsplit,
-                         bool configure_only = false) {
+                         int a_dual, bool configure_only = false) {
   constexpr int SMEM = 2 * 16 * MB * SK_ROW;
   constexpr int D = MB <= 4 ? 4 : 2;
-  auto kern = gemm_skinny_kernel<MB, D>;
+  constexpr bool HAS_DUAL = MB <= 8;   // the doubled slice of the largest variant would not fit in LDS
   if (configure_only) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute((const void*)gemm_skinny_kernel<MB, D, true>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+    hipError_t e;
+    if ((e = hipFuncSetAttribute((const void*)gemm_skinny_kernel<MB, D, false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute((const void*)gemm_skinny_kernel<MB, D, true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM)) != hipSuccess) return e;
+    if constexpr (HAS_DUAL)
+      if ((e = hipFuncSetAttribute((const void*)gemm_skinny_kernel<MB, 2, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * SMEM)) != hipSuccess) return e;
+    return hipSuccess;
   }
   if (nsplit == 0) {  // fused SwiGLU: W = [2F, K], output fp16 [M, F], no split
-    gemm_skinny_kernel<MB, D, true><<<dim3(Nw / 64, 1), 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, K / SK);
+    if (a_dual) return hipErrorInvalidValue;
+    gemm_skinny_kernel<MB, D, true, false><<<dim3(Nw / 64, 1), 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, K / SK);
     return hipGetLastError();
   }
   int steps = K / SK;
   int per = (steps + nsplit - 1) / nsplit;
-  kern<<<dim3(Nw / 64, nsplit), 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, per);
+  if (a_dual) {
+    if constexpr (HAS_DUAL)
+      gemm_skinny_kernel<MB, 2, false, true><<<dim3(Nw / 64, nsplit), 256, 2 * SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, per);
+    else
+      return hipErrorInvalidValue;
+  } else {
+    gemm_skinny_kernel<MB, D, false, false><<<dim3(Nw / 64, nsplit), 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, per);
+  }
   return hipGetLastError();
 }
 
@@ -528,24 +383,16 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 
 }  // namespace
 
-hipError_t launch_gemm_h16(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K, int epi) {
+hipError_t launch_gemm_h16(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K, int epi,
+                           int a_dual) {
   if (M <= 0) return hipSuccess;
-  if (K % BK) return hipErrorInvalidValue;
+  if (K % 64) return hipErrorInvalidValue;
   if (epi == EPI_SWIGLU ? (N % 128) : (N % 256)) return hipErrorInvalidValue;
-  static const bool use_dma = !(getenv("RLHF_GEMM_NO_DMA") && atoi(getenv("RLHF_GEMM_NO_DMA")));
-  if (use_dma) {
-    switch (epi) {
-      case EPI_STORE_F32: return launch_large_dma<EPI_STORE_F32>(s, A, W, out, M, N, K);
-      case EPI_RESID_F32: return launch_large_dma<EPI_RESID_F32>(s, A, W, out, M, N, K);
-      case EPI_SWIGLU: return launch_large_dma<EPI_SWIGLU>(s, A, W, out, M, N, K);
-      case EPI_STORE_ACT: return launch_large_dma<EPI_STORE_ACT>(s, A, W, out, M, N, K);
-    }
-  }
   switch (epi) {
-    case EPI_STORE_F32: return launch_large<EPI_STORE_F32>(s, A, W, out, M, N, K);
-    case EPI_RESID_F32: return launch_large<EPI_RESID_F32>(s, A, W, out, M, N, K);
-    case EPI_SWIGLU: return launch_large<EPI_SWIGLU>(s, A, W, out, M, N, K);
-    case EPI_STORE_ACT: return launch_large<EPI_STORE_ACT>(s, A, W, out, M, N, K);
+    case EPI_STORE_F32: return launch_large_dma<EPI_STORE_F32>(s, A, W, out, M, N, K, a_dual);
+    case EPI_RESID_F32: return launch_large_dma<EPI_RESID_F32>(s, A, W, out, M, N, K, a_dual);
+    case EPI_SWIGLU: return launch_large_dma<EPI_SWIGLU>(s, A, W, out, M, N, K, a_dual);
+    case EPI_STORE_ACT: return launch_large_dma<EPI_STORE_ACT>(s, A, W, out, M, N, K, a_dual);
   }
   return hipErrorInvalidValue;
 }
@@ -553,19 +400,15 @@ hipError_t launch_gemm_h16(hipStream_t s, const void* A, const void* W, void* ou
 // Raise the dynamic-LDS limit of every instantiation once per device (must not happen inside a stream capture).
 hipError_t gemm_configure() {
   hipError_t e;
-  if ((e = launch_large<EPI_STORE_F32>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, true)) != hipSuccess) return e;
-  if ((e = launch_large<EPI_RESID_F32>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, true)) != hipSuccess) return e;
-  if ((e = launch_large<EPI_SWIGLU>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, true)) != hipSuccess) return e;
-  if ((e = launch_large<EPI_STORE_ACT>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, true)) != hipSuccess) return e;
-  if ((e = launch_large_dma<EPI_STORE_F32>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, true)) != hipSuccess) return e;
-  if ((e = launch_large_dma<EPI_RESID_F32>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, true)) != hipSuccess) return e;
-  if ((e = launch_large_dma<EPI_SWIGLU>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, true)) != hipSuccess) return e;
-  if ((e = launch_large_dma<EPI_STORE_ACT>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, true)) != hipSuccess) return e;
-  if ((e = launch_skinny<1>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, true)) != hipSuccess) return e;
-  if ((e = launch_skinny<2>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, true)) != hipSuccess) return e;
-  if ((e = launch_skinny<4>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, true)) != hipSuccess) return e;
-  if ((e = launch_skinny<8>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, true)) != hipSuccess) return e;
-  if ((e = launch_skinny<16>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, true)) != hipSuccess) return e;
+  if ((e = launch_large_dma<EPI_STORE_F32>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, true)) != hipSuccess) return e;
+  if ((e = launch_large_dma<EPI_RESID_F32>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, true)) != hipSuccess) return e;
+  if ((e = launch_large_dma<EPI_SWIGLU>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, true)) != hipSuccess) return e;
+  if ((e = launch_large_dma<EPI_STORE_ACT>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, true)) != hipSuccess) return e;
+  if ((e = launch_skinny<1>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, true)) != hipSuccess) return e;
+  if ((e = launch_skinny<2>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, true)) != hipSuccess) return e;
+  if ((e = launch_skinny<4>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, true)) != hipSuccess) return e;
+  if ((e = launch_skinny<8>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, true)) != hipSuccess) return e;
+  if ((e = launch_skinny<16>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, true)) != hipSuccess) return e;
   return hipSuccess;
 }
 
@@ -581,14 +424,14 @@ int gemm_skinny_pick_split(int M, int Nw, int K) {
 }
 
 hipError_t launch_gemm_skinny_h16(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K,
-                                   int nsplit) {
+                                  int nsplit, int a_dual) {
   if (M <= 0) return hipSuccess;
   if (K % SK || Nw % 64 || M > 256 || nsplit < 0) return hipErrorInvalidValue;
-  if (M <= 16) return launch_skinny<1>(s, A, W, part, M, Nw, K, nsplit);
-  if (M <= 32) return launch_skinny<2>(s, A, W, part, M, Nw, K, nsplit);
-  if (M <= 64) return launch_skinny<4>(s, A, W, part, M, Nw, K, nsplit);
-  if (M <= 128) return launch_skinny<8>(s, A, W, part, M, Nw, K, nsplit);
-  return launch_skinny<16>(s, A, W, part, M, Nw, K, nsplit);
+  if (M <= 16) return launch_skinny<1>(s, A, W, part, M, Nw, K, nsplit, a_dual);
+  if (M <= 32) return launch_skinny<2>(s, A, W, part, M, Nw, K, nsplit, a_dual);
+  if (M <= 64) return launch_skinny<4>(s, A, W, part, M, Nw, K, nsplit, a_dual);
+  if (M <= 128) return launch_skinny<8>(s, A, W, part, M, Nw, K, nsplit, a_dual);
+  return launch_skinny<16>(s, A, W, part, M, Nw, K, nsplit, a_dual);
 }
 
 hipError_t launch_gemm_f32(hipStream_t s, const float* A, const float* W, float* out, int M, int N, int K,

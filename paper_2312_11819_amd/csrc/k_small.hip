@@ -63,7 +63,7 @@ hipError_t launch_embed(hipStream_t s, const int* ids, const void* table, int w_
 
 // One workgroup of NT threads per row, d <= 8 * 4 * NT, d % 4 == 0.  The sum of squares is taken in a fixed
 // order, so the result does not change from run to run.  Partial sums are added in split order 0, 1, ...
-template <bool WBF16, bool A16, int NT>
+template <bool WBF16, bool A16, int NT, bool DUAL>
 __global__ __launch_bounds__(NT) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ part, int nsplit,
                                                      size_t part_stride, const void* __restrict__ gain,
                                                      void* __restrict__ y, int d, float eps,
@@ -125,7 +125,14 @@ __global__ __launch_bounds__(NT) void rmsnorm_kernel(float* __restrict__ x, cons
       }
       float4 a = v[it];
       float o0 = a.x * r * g0, o1 = a.y * r * g1, o2 = a.z * r * g2, o3 = a.w * r * g3;
-      if (A16) {
+      if (A16 && DUAL) {  // row = [hi (d) | lo (d)]
+        h16_t hi[4], lo[4];
+        split_h16(o0, hi[0], lo[0]); split_h16(o1, hi[1], lo[1]);
+        split_h16(o2, hi[2], lo[2]); split_h16(o3, hi[3], lo[3]);
+        h16_t* yr = (h16_t*)y + (size_t)m * 2 * d + i;
+        *(uint2*)yr = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+        *(uint2*)(yr + d) = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
+      } else if (A16) {
         uint2 o;
         o.x = pack_h16x2(o0, o1);
         o.y = pack_h16x2(o2, o3);
@@ -138,16 +145,18 @@ __global__ __launch_bounds__(NT) void rmsnorm_kernel(float* __restrict__ x, cons
 }
 
 hipError_t launch_rmsnorm(hipStream_t s, float* x, const float* part, int nsplit, size_t part_stride, const void* gain,
-                          int w_bf16, void* y, int act_bf16, int M, int d, float eps, const int* rows) {
+                          int w_bf16, void* y, int act_bf16, int M, int d, float eps, const int* rows, int dual) {
   if (M <= 0) return hipSuccess;
   if (d > 8192 || (d & 3)) return hipErrorInvalidValue;
   if (!part) nsplit = 0;
   const bool wide = M <= 1024 && d >= 2048;  // few rows: spread each row over 1024 threads
   if (w_bf16 && act_bf16) {
-    if (wide) rmsnorm_kernel<true, true, 1024><<<M, 1024, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
-    else rmsnorm_kernel<true, true, 256><<<M, 256, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
+    if (wide && dual) rmsnorm_kernel<true, true, 1024, true><<<M, 1024, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
+    else if (wide) rmsnorm_kernel<true, true, 1024, false><<<M, 1024, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
+    else if (dual) rmsnorm_kernel<true, true, 256, true><<<M, 256, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
+    else rmsnorm_kernel<true, true, 256, false><<<M, 256, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
   } else if (!w_bf16 && !act_bf16) {
-    rmsnorm_kernel<false, false, 256><<<M, 256, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
+    rmsnorm_kernel<false, false, 256, false><<<M, 256, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
   } else {
     return hipErrorInvalidValue;
   }
@@ -186,10 +195,10 @@ __global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict
       float c = cos_t[(size_t)pos * half + i], sv = sin_t[(size_t)pos * half + i];
       float r0 = a * c - bb * sv, r1 = bb * c + a * sv;
       if (head < Hq) {
-        if (A16) {
-          h16_t* qo = (h16_t*)q_out + ((size_t)m * Hq + head) * h;
-          qo[i] = f32_to_h16(r0);
-          qo[i + half] = f32_to_h16(r1);
+        if (A16) {  // [hi (h) | lo (h)] per head
+          h16_t* qo = (h16_t*)q_out + ((size_t)m * Hq + head) * 2 * h;
+          split_h16(r0, qo[i], qo[h + i]);
+          split_h16(r1, qo[i + half], qo[h + i + half]);
         } else {
           float* qo = (float*)q_out + ((size_t)m * Hq + head) * h;
           qo[i] = r0;

@@ -12,13 +12,15 @@ enum GemmEpilogue {
 
 // ---- 16-bit MFMA path (fp16 operands, fp32 accumulation) ----
 // Large-tile GEMM: out = A[M,K] (fp16) * W[N,K]^T (fp16).  Needs N % 256 == 0 (F % 128 == 0 for SWIGLU),
-// K % 64 == 0; rows of A beyond M are never read.
-hipError_t launch_gemm_h16(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K, int epi);
+// K % 64 == 0; rows of A beyond M are never read.  a_dual: A is [M, 2K], each row = [hi (K) | lo (K)], and
+// out = (hi + lo) W^T.
+hipError_t launch_gemm_h16(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K, int epi,
+                           int a_dual);
 // Weight-streaming GEMM for M <= 256 rows: writes fp32 partial sums part[ks][M][Nw] (Nw = rows of W)
 // for ks < nsplit; the consumer kernel adds them.  nsplit = 0 selects the fused SwiGLU form: W = [2F, K]
 // (gate rows, then up rows; Nw = 2F), no split, and `part` receives fp16 [M, F] = silu(gate) * up.
 hipError_t launch_gemm_skinny_h16(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K,
-                                   int nsplit);
+                                  int nsplit, int a_dual);
 int gemm_skinny_pick_split(int M, int Nw, int K);
 // Per-device one-time kernel attribute setup; call before the first launch and outside any stream capture.
 hipError_t gemm_configure();
@@ -29,10 +31,12 @@ hipError_t launch_pack_tokens(hipStream_t s, const int* query_tokens, int Lmax, 
 hipError_t launch_embed(hipStream_t s, const int* ids, const void* table, int w_bf16, float* x, int M, int d, int vocab,
                         int* err_flag);
 // x[m] += sum_{s<nsplit} part[s][m][:] (if part), then y = rmsnorm(x) * gain.  rows[m] (optional) selects
-// source rows of x (gather); then x is not updated.
+// source rows of x (gather); then x is not updated.  dual (16-bit activations only): y rows are [hi (d) | lo (d)].
 hipError_t launch_rmsnorm(hipStream_t s, float* x, const float* part, int nsplit, size_t part_stride,
-                          const void* gain, int w_bf16, void* y, int act_bf16, int M, int d, float eps, const int* rows);
-// qkv fp32 [M, (Hq+2Hkv)h] (+ optional partial sums) -> rotated q (activation type) and the paged KV cache.
+                          const void* gain, int w_bf16, void* y, int act_bf16, int M, int d, float eps, const int* rows,
+                          int dual);
+// qkv fp32 [M, (Hq+2Hkv)h] (+ optional partial sums) -> rotated q and the paged KV cache.  16-bit mode: q_out is
+// [M, Hq, 2, h] fp16 (hi | lo pair per head); fp32 mode: [M, Hq, h] floats.
 hipError_t launch_rope_append(hipStream_t s, const float* qkv, const float* part, int nsplit, size_t part_stride,
                               const int* row_pos, const int* row_seq, const float* cos_t, const float* sin_t,
                               void* q_out, void* kv_pool_layer, const int* block_table, int max_blocks, int M, int Hq,
@@ -44,7 +48,7 @@ hipError_t launch_advance(hipStream_t s, int* seq_len, int* step, int B);
 // bf16 -> fp16 copy of n elements (working copies of the weight matrices).
 hipError_t launch_bf16_to_h16(hipStream_t s, const void* src, void* dst, size_t n);
 
-// ---- attention over the paged cache ----
+// ---- attention over the paged cache (16-bit mode: q [rows, Hq, 2, 128] hi|lo pairs, out [rows, 2, Hq*128] hi|lo) ----
 hipError_t launch_attn_decode_h16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
                                    int max_blocks, const int* seq_len, void* out, int B, int Hq, int Hkv);
 hipError_t launch_attn_prefill_h16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,

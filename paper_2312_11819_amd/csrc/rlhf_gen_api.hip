@@ -191,9 +191,9 @@ struct RowSet {
   int nseq = 0, max_len = 0;
 };
 
-int gemm_any(rlhf_gen_ctx* c, const void* A, const void* W, void* out, int M, int N, int K, int epi) {
+int gemm_any(rlhf_gen_ctx* c, const void* A, const void* W, void* out, int M, int N, int K, int epi, int a_dual = 0) {
   if (c->bf16) {
-    LAUNCH(c, launch_gemm_h16(c->stream, A, W, out, M, N, K, epi), "gemm_bf16");
+    LAUNCH(c, launch_gemm_h16(c->stream, A, W, out, M, N, K, epi, a_dual), "gemm_h16");
   } else {
     if (epi == EPI_SWIGLU) return fail(c, RLHF_GEN_E_UNSUPPORTED, "no fused SwiGLU on the fp32 path");
     LAUNCH(c, launch_gemm_f32(c->stream, (const float*)A, (const float*)W, (float*)out, M, N, K, epi == EPI_RESID_F32),
@@ -211,9 +211,10 @@ int forward_layers_generic(rlhf_gen_ctx* c, const RowSet& r) {
   LAUNCH(c, launch_embed(s, r.ids, c->tok_emb, c->bf16, c->x, r.M, d, g.vocab, c->d_err), "embed");
   for (int l = 0; l < g.n_layers; ++l) {
     char* pool = c->kv_pool + (size_t)l * c->layer_pool_bytes;
-    LAUNCH(c, launch_rmsnorm(s, c->x, nullptr, 0, 0, c->attn_norm[l], c->bf16, c->y, c->bf16, r.M, d, g.rms_eps, nullptr),
-           "rmsnorm");
-    int rc = gemm_any(c, c->y, c->wqkv[l], c->qkv, r.M, qkv_w, d, EPI_STORE_F32);
+    // 16-bit mode: the inputs of the QKV and output projections travel as fp16 hi|lo pairs
+    LAUNCH(c, launch_rmsnorm(s, c->x, nullptr, 0, 0, c->attn_norm[l], c->bf16, c->y, c->bf16, r.M, d, g.rms_eps, nullptr,
+                             c->bf16), "rmsnorm");
+    int rc = gemm_any(c, c->y, c->wqkv[l], c->qkv, r.M, qkv_w, d, EPI_STORE_F32, c->bf16);
     if (rc) return rc;
     LAUNCH(c, launch_rope_append(s, c->qkv, nullptr, 0, 0, r.row_pos, r.row_seq, c->d_cos, c->d_sin, c->qb, pool,
                                  c->d_table, c->max_blocks, r.M, Hq, Hkv, h, c->bf16), "rope_append");
@@ -227,9 +228,9 @@ int forward_layers_generic(rlhf_gen_ctx* c, const RowSet& r) {
       LAUNCH(c, launch_attn_decode_h16(s, c->qb, pool, c->d_table, c->max_blocks, c->d_seq_len, c->ab, r.M, Hq, Hkv),
              "attn_decode");
     }
-    rc = gemm_any(c, c->ab, c->wo[l], c->x, r.M, d, Hq * h, EPI_RESID_F32);
+    rc = gemm_any(c, c->ab, c->wo[l], c->x, r.M, d, Hq * h, EPI_RESID_F32, c->bf16);
     if (rc) return rc;
-    LAUNCH(c, launch_rmsnorm(s, c->x, nullptr, 0, 0, c->ffn_norm[l], c->bf16, c->y, c->bf16, r.M, d, g.rms_eps, nullptr),
+    LAUNCH(c, launch_rmsnorm(s, c->x, nullptr, 0, 0, c->ffn_norm[l], c->bf16, c->y, c->bf16, r.M, d, g.rms_eps, nullptr, 0),
            "rmsnorm");
     if (c->bf16) {
       rc = gemm_any(c, c->y, c->w_gate_up[l], c->hb, r.M, F, d, EPI_SWIGLU);
@@ -259,9 +260,9 @@ int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
   for (int l = 0; l < g.n_layers; ++l) {
     char* pool = c->kv_pool + (size_t)l * c->layer_pool_bytes;
     LAUNCH(c, launch_rmsnorm(s, c->x, pending ? c->part : nullptr, pending, (size_t)B * d, c->attn_norm[l], 1, c->y, 1,
-                             B, d, g.rms_eps, nullptr), "rmsnorm");
+                             B, d, g.rms_eps, nullptr, 1), "rmsnorm");
     prof_mark(c, RLHF_GEN_PROF_NORM);
-    LAUNCH(c, launch_gemm_skinny_h16(s, c->y, c->wqkv[l], c->part, B, qkv_w, d, c->ks_qkv), "gemm_skinny qkv");
+    LAUNCH(c, launch_gemm_skinny_h16(s, c->y, c->wqkv[l], c->part, B, qkv_w, d, c->ks_qkv, 1), "gemm_skinny qkv");
     prof_mark(c, RLHF_GEN_PROF_GEMM_QKV);
     size_t st = (size_t)B * qkv_w;
     LAUNCH(c, launch_rope_append(s, c->part, c->ks_qkv > 1 ? c->part + st : nullptr, c->ks_qkv - 1, st, c->d_seq_len,
@@ -271,27 +272,28 @@ int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
     LAUNCH(c, launch_attn_decode_h16(s, c->qb, pool, c->d_table, c->max_blocks, c->d_seq_len, c->ab, B, Hq, Hkv),
            "attn_decode");
     prof_mark(c, RLHF_GEN_PROF_ATTN);
-    LAUNCH(c, launch_gemm_skinny_h16(s, c->ab, c->wo[l], c->part, B, d, Hq * h, c->ks_wo), "gemm_skinny wo");
+    LAUNCH(c, launch_gemm_skinny_h16(s, c->ab, c->wo[l], c->part, B, d, Hq * h, c->ks_wo, 1), "gemm_skinny wo");
     prof_mark(c, RLHF_GEN_PROF_GEMM_WO);
     LAUNCH(c, launch_rmsnorm(s, c->x, c->part, c->ks_wo, (size_t)B * d, c->ffn_norm[l], 1, c->y, 1, B, d, g.rms_eps,
-                             nullptr), "rmsnorm");
+                             nullptr, 0), "rmsnorm");
     prof_mark(c, RLHF_GEN_PROF_NORM);
-    LAUNCH(c, launch_gemm_skinny_h16(s, c->y, c->w_gate_up[l], (float*)c->hb, B, 2 * F, d, 0), "gemm_skinny gate_up");
+    LAUNCH(c, launch_gemm_skinny_h16(s, c->y, c->w_gate_up[l], (float*)c->hb, B, 2 * F, d, 0, 0), "gemm_skinny gate_up");
     prof_mark(c, RLHF_GEN_PROF_GEMM_GATE_UP);
-    LAUNCH(c, launch_gemm_skinny_h16(s, c->hb, c->w_down[l], c->part, B, d, F, c->ks_down), "gemm_skinny down");
+    LAUNCH(c, launch_gemm_skinny_h16(s, c->hb, c->w_down[l], c->part, B, d, F, c->ks_down, 0), "gemm_skinny down");
     prof_mark(c, RLHF_GEN_PROF_GEMM_DOWN);
     pending = c->ks_down;
   }
   LAUNCH(c, launch_rmsnorm(s, c->x, pending ? c->part : nullptr, pending, (size_t)B * d, c->final_norm, 1, c->yl, 1, B,
-                           d, g.rms_eps, nullptr), "final rmsnorm");
+                           d, g.rms_eps, nullptr, 0), "final rmsnorm");
   prof_mark(c, RLHF_GEN_PROF_NORM);
-  LAUNCH(c, launch_gemm_skinny_h16(s, c->yl, c->lm_head, c->logits, B, g.vocab, d, 1), "gemm_skinny lm_head");
+  LAUNCH(c, launch_gemm_skinny_h16(s, c->yl, c->lm_head, c->logits, B, g.vocab, d, 1, 0), "gemm_skinny lm_head");
   prof_mark(c, RLHF_GEN_PROF_LM_HEAD);
   return RLHF_GEN_OK;
 }
 
 bool use_streaming(const rlhf_gen_ctx* c, int B) {
-  return c->bf16 && !(c->cfg.flags & RLHF_GEN_FLAG_GENERIC_GEMM) && B <= 256;
+  // the weight-streaming GEMM takes hi|lo activation pairs up to 128 rows; larger batches use the tiled GEMM
+  return c->bf16 && !(c->cfg.flags & RLHF_GEN_FLAG_GENERIC_GEMM) && B <= 128;
 }
 
 // Kernels of one decode step, in order, ending with the sampler and the counter update.
@@ -310,7 +312,7 @@ int enqueue_decode_body(rlhf_gen_ctx* c, int* tok_out, float* lp_out, int stride
     rc = forward_layers_generic(c, r);
     if (rc) return rc;
     LAUNCH(c, launch_rmsnorm(c->stream, c->x, nullptr, 0, 0, c->final_norm, c->bf16, c->yl, c->bf16, B, g.d_model,
-                             g.rms_eps, nullptr), "final rmsnorm");
+                             g.rms_eps, nullptr, 0), "final rmsnorm");
     rc = gemm_any(c, c->yl, c->lm_head, c->logits, B, g.vocab, g.d_model, EPI_STORE_F32);
     if (rc) return rc;
   }
@@ -445,7 +447,7 @@ int prefill_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* le
     // final norm of each sequence's last row, gathered into rows b0..b1 of yl
     LAUNCH(c, launch_rmsnorm(s, c->x, nullptr, 0, 0, c->final_norm, c->bf16,
                              (char*)c->yl + (size_t)b0 * g.d_model * act_size(c), c->bf16, r.nseq, g.d_model, g.rms_eps,
-                             c->d_last_rows + b0), "final rmsnorm");
+                             c->d_last_rows + b0, 0), "final rmsnorm");
     row0 += r.M;
   }
   rc = gemm_any(c, c->yl, c->lm_head, c->logits, B, g.vocab, g.d_model, EPI_STORE_F32);
@@ -633,14 +635,14 @@ int rlhf_gen_init(const rlhf_gen_weights* w, const rlhf_gen_cfg* cfg, rlhf_gen_c
   A_(dev_alloc(c, &c->d_last_rows, sizeof(int) * g.max_batch, true));
   A_(dev_alloc(c, &c->x, 4 * rows * g.d_model, true));
   A_(dev_alloc(c, &c->qkv, 4 * rows * std::max(qkv_w, c->bf16 ? 0 : 2 * g.d_ffn), true));
-  A_(dev_alloc(c, &c->y, as * rows * g.d_model, true));
+  A_(dev_alloc(c, &c->y, 2 * as * rows * g.d_model, true));              // room for hi|lo pairs
   A_(dev_alloc(c, &c->yl, as * ((size_t)g.max_batch + 256) * g.d_model, true));
-  A_(dev_alloc(c, &c->qb, as * rows * g.n_heads * g.head_dim, true));
-  A_(dev_alloc(c, &c->ab, as * rows * g.n_heads * g.head_dim, true));
+  A_(dev_alloc(c, &c->qb, 2 * as * rows * g.n_heads * g.head_dim, true));
+  A_(dev_alloc(c, &c->ab, 2 * as * rows * g.n_heads * g.head_dim, true));
   A_(dev_alloc(c, &c->hb, as * rows * g.d_ffn, true));
   A_(dev_alloc(c, &c->logits, 4 * (size_t)g.max_batch * g.vocab, true));
   if (c->bf16) {
-    const int Bm = std::min(g.max_batch, 256);
+    const int Bm = std::min(g.max_batch, 128);
     c->ks_qkv = gemm_skinny_pick_split(Bm, qkv_w, g.d_model);
     c->ks_wo = gemm_skinny_pick_split(Bm, g.d_model, g.n_heads * g.head_dim);
     c->ks_gu = gemm_skinny_pick_split(Bm, 2 * g.d_ffn, g.d_model);
@@ -852,13 +854,19 @@ void rlhf_gen_destroy(rlhf_gen_ctx* c) {
 
 // ---- single-operation entry points (kernel parity tests) ----------------------------------------
 int rlhf_gen_op_gemm(void* stream, int kind, const void* A, const void* W, void* out, int32_t M, int32_t N, int32_t K,
-                     int32_t epilogue, int32_t nsplit) {
+                     int32_t epilogue, int32_t nsplit, int32_t a_pairs) {
   hipStream_t s = (hipStream_t)stream;
   hipError_t e;
   if (!A || !W || !out || M < 1 || N < 1 || K < 1) return RLHF_GEN_E_INVALID;
-  if (kind == RLHF_GEN_GEMM_TILED) e = launch_gemm_h16(s, A, W, out, M, N, K, epilogue);
+  static bool configured = false;
+  if (!configured) {
+    if (gemm_configure() != hipSuccess) return RLHF_GEN_E_DEVICE;
+    configured = true;
+  }
+  if (kind == RLHF_GEN_GEMM_TILED) e = launch_gemm_h16(s, A, W, out, M, N, K, epilogue, a_pairs);
   else if (kind == RLHF_GEN_GEMM_STREAMING)
-    e = launch_gemm_skinny_h16(s, A, W, (float*)out, M, epilogue == EPI_SWIGLU ? 2 * N : N, K, epilogue == EPI_SWIGLU ? 0 : nsplit);
+    e = launch_gemm_skinny_h16(s, A, W, (float*)out, M, epilogue == EPI_SWIGLU ? 2 * N : N, K,
+                               epilogue == EPI_SWIGLU ? 0 : nsplit, a_pairs);
   else if (kind == RLHF_GEN_GEMM_FP32) e = launch_gemm_f32(s, (const float*)A, (const float*)W, (float*)out, M, N, K, epilogue == EPI_RESID_F32);
   else return RLHF_GEN_E_INVALID;
   if (e == hipErrorInvalidValue) return RLHF_GEN_E_UNSUPPORTED;
