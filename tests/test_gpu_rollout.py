@@ -78,6 +78,9 @@ def test_tiny_fp32_generate_matches_oracle(B):
     assert float((top2[..., 0] - top2[..., 1]).min()) > 2e-4      # this seed has no near-tie
     assert torch.equal(gt.cpu().long(), ref["tokens"])
     assert (glp.cpu().double() - ref["logprobs"]).abs().max() < 1e-4
+    import json, os
+    doc = json.load(open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "tiny_greedy.json")))
+    assert gt.cpu().tolist() == doc["tokens"]                      # the stored oracle rollout
     # same result without graph replay
     ctx2 = B.Context(synth.weights_to(w, "cuda"), wl.shape, "fp32", wl.batch, 32, flags=B.FLAG_NO_GRAPH)
     gt2, glp2 = ctx2.rlhf_gen_generate(toks.cuda(), lens.tolist(), wl.resp_len, B.make_sampling(greedy=True))
