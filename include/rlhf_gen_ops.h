@@ -38,24 +38,25 @@ int rlhf_gen_op_gemm(void* stream, int kind, const void* A, const void* W, void*
 /* Rotate q and k of fp32 qkv rows [M, (Hq + 2 Hkv) head_dim] by their positions and append k, v to the paged
  * cache.  row_pos [M] position of each row; row_seq [M] batch row (NULL = identity); cos_t / sin_t
  * [positions, head_dim/2] fp32 tables; block_table int32 [batch, max_blocks]; kv_pool = one layer's pool
- * ([n_blocks, Hkv, 8192] bytes of fp16 in 16-bit mode, [n_blocks, Hkv, 2, 16, head_dim] floats in fp32 mode);
+ * ([Hkv, n_blocks, 8192] bytes of fp16 in 16-bit mode, [Hkv, n_blocks, 2, 16, head_dim] floats in fp32 mode);
  * q_out: half16 != 0: fp16 [M, Hq, 2, head_dim], the pair [hi | lo] of each rotated query head; else fp32
  * [M, Hq, head_dim]. */
 int rlhf_gen_op_rope_append(void* stream, const float* qkv, const int32_t* row_pos, const int32_t* row_seq,
                             const float* cos_t, const float* sin_t, void* q_out, void* kv_pool,
-                            const int32_t* block_table, int32_t max_blocks, int32_t M, int32_t Hq, int32_t Hkv,
-                            int32_t head_dim, int32_t half16);
+                            const int32_t* block_table, int32_t max_blocks, int32_t n_blocks, int32_t M, int32_t Hq,
+                            int32_t Hkv, int32_t head_dim, int32_t half16);
 
 /* One query row per (sequence, query head) against the seq_len[b] + 1 newest-inclusive cached tokens (fp16 cache,
  * head_dim 128).  q fp16 [B, Hq, 2, 128] (hi | lo pairs), out fp16 [B, 2, Hq * 128] (hi block, then lo block). */
 int rlhf_gen_op_attn_decode(void* stream, const void* q, const void* kv_pool, const int32_t* block_table,
-                            int32_t max_blocks, const int32_t* seq_len, void* out, int32_t B, int32_t Hq, int32_t Hkv);
+                            int32_t max_blocks, int32_t n_blocks, const int32_t* seq_len, void* out, int32_t B, int32_t Hq,
+                            int32_t Hkv);
 
 /* Causal attention of packed query rows over the cache their own keys were appended to.  cu_seqlens [nseq + 1]
  * row offsets, seq_ids [nseq] batch rows (block-table rows), q [rows, Hq, 2, 128] and out [rows, 2, Hq * 128] fp16 pairs
  * as in the decode call, max_len = longest sequence. */
 int rlhf_gen_op_attn_prefill(void* stream, const void* q, const void* kv_pool, const int32_t* block_table,
-                             int32_t max_blocks, const int32_t* cu_seqlens, const int32_t* seq_ids, void* out,
+                             int32_t max_blocks, int32_t n_blocks, const int32_t* cu_seqlens, const int32_t* seq_ids, void* out,
                              int32_t nseq, int32_t max_len, int32_t Hq, int32_t Hkv);
 
 /* Sampler on fp32 logits [B, V]: token and log-prob per row for response index *step (device int32).

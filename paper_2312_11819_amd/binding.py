@@ -87,9 +87,9 @@ def lib() -> C.CDLL:
         L.rlhf_gen_destroy.restype = None
         L.rlhf_gen_op_gemm.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                        C.c_int32, C.c_int32, C.c_int32, C.c_int32]
-        L.rlhf_gen_op_rope_append.argtypes = [C.c_void_p] * 9 + [C.c_int32] * 6
-        L.rlhf_gen_op_attn_decode.argtypes = [C.c_void_p] * 4 + [C.c_int32, C.c_void_p, C.c_void_p] + [C.c_int32] * 3
-        L.rlhf_gen_op_attn_prefill.argtypes = [C.c_void_p] * 4 + [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p] + [C.c_int32] * 4
+        L.rlhf_gen_op_rope_append.argtypes = [C.c_void_p] * 9 + [C.c_int32] * 7
+        L.rlhf_gen_op_attn_decode.argtypes = [C.c_void_p] * 4 + [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p] + [C.c_int32] * 3
+        L.rlhf_gen_op_attn_prefill.argtypes = [C.c_void_p] * 4 + [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p] + [C.c_int32] * 4
         L.rlhf_gen_op_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.POINTER(Sampling), C.c_void_p,
                                          C.c_void_p, C.c_void_p, C.c_void_p]
         for name in EXPORTS:
@@ -214,20 +214,21 @@ def rlhf_gen_op_gemm(kind, A, W, out, M, N, K, epilogue=0, nsplit=1, a_pairs=0) 
     return lib().rlhf_gen_op_gemm(None, kind, _ptr(A), _ptr(W), _ptr(out), M, N, K, epilogue, nsplit, a_pairs)
 
 
-def rlhf_gen_op_rope_append(qkv, row_pos, row_seq, cos_t, sin_t, q_out, kv_pool, block_table, max_blocks, M, Hq, Hkv,
-                            head_dim, half16) -> int:
+def rlhf_gen_op_rope_append(qkv, row_pos, row_seq, cos_t, sin_t, q_out, kv_pool, block_table, max_blocks, n_blocks, M,
+                            Hq, Hkv, head_dim, half16) -> int:
     return lib().rlhf_gen_op_rope_append(None, _ptr(qkv), _ptr(row_pos), _ptr(row_seq), _ptr(cos_t), _ptr(sin_t),
-                                         _ptr(q_out), _ptr(kv_pool), _ptr(block_table), max_blocks, M, Hq, Hkv,
-                                         head_dim, int(half16))
+                                         _ptr(q_out), _ptr(kv_pool), _ptr(block_table), max_blocks, n_blocks, M, Hq,
+                                         Hkv, head_dim, int(half16))
 
 
-def rlhf_gen_op_attn_decode(q, kv_pool, block_table, max_blocks, seq_len, out, B, Hq, Hkv) -> int:
-    return lib().rlhf_gen_op_attn_decode(None, _ptr(q), _ptr(kv_pool), _ptr(block_table), max_blocks, _ptr(seq_len),
-                                         _ptr(out), B, Hq, Hkv)
+def rlhf_gen_op_attn_decode(q, kv_pool, block_table, max_blocks, n_blocks, seq_len, out, B, Hq, Hkv) -> int:
+    return lib().rlhf_gen_op_attn_decode(None, _ptr(q), _ptr(kv_pool), _ptr(block_table), max_blocks, n_blocks,
+                                         _ptr(seq_len), _ptr(out), B, Hq, Hkv)
 
 
-def rlhf_gen_op_attn_prefill(q, kv_pool, block_table, max_blocks, cu_seqlens, seq_ids, out, nseq, max_len, Hq, Hkv) -> int:
-    return lib().rlhf_gen_op_attn_prefill(None, _ptr(q), _ptr(kv_pool), _ptr(block_table), max_blocks,
+def rlhf_gen_op_attn_prefill(q, kv_pool, block_table, max_blocks, n_blocks, cu_seqlens, seq_ids, out, nseq, max_len, Hq,
+                             Hkv) -> int:
+    return lib().rlhf_gen_op_attn_prefill(None, _ptr(q), _ptr(kv_pool), _ptr(block_table), max_blocks, n_blocks,
                                           _ptr(cu_seqlens), _ptr(seq_ids), _ptr(out), nseq, max_len, Hq, Hkv)
 
 

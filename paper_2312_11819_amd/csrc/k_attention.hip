@@ -90,7 +90,7 @@ __device__ __forceinline__ void init_state(AttnState& st) {
 // grid (Hkv, B), 256 threads.  q [B, Hq, 2, 128] fp16 (hi | lo per head), out [B, 2, Hq*128] fp16 (hi | lo).  seq_len[b] = tokens cached BEFORE
 // this step; the step's own key/value has already been appended, so seq_len[b] + 1 tokens are visible.
 __global__ __launch_bounds__(256) void attn_decode_kernel(const h16_t* __restrict__ q, const char* __restrict__ pool,
-                                                          const int* __restrict__ block_table, int max_blocks,
+                                                          const int* __restrict__ block_table, int max_blocks, int n_blocks,
                                                           const int* __restrict__ seq_len, h16_t* __restrict__ out,
                                                           int Hq, int Hkv, float scale_log2) {
   __shared__ float m_s[4][16];
@@ -121,12 +121,12 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const h16_t* __restric
     const int my_blk = bt[mine];
     const int cnt = min(64, (npages - base + 3) >> 2);  // pages of this wavefront in this batch
     uint4 ka[4], va[4], kb[4], vb[4];
-    load_page(pool + ((size_t)__shfl(my_blk, 0) * Hkv + kvh) * KV_PAGE_BYTES, lane, ka, va);
+    load_page(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, 0)) * KV_PAGE_BYTES, lane, ka, va);
     int i = 0;
     for (; i + 2 <= cnt; i += 2) {
-      load_page(pool + ((size_t)__shfl(my_blk, i + 1) * Hkv + kvh) * KV_PAGE_BYTES, lane, kb, vb);
+      load_page(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, i + 1)) * KV_PAGE_BYTES, lane, kb, vb);
       attn_page<true>(ka, va, qf, st, scale_log2, (base + 4 * i) * 16, L, g);
-      load_page(pool + ((size_t)__shfl(my_blk, min(i + 2, cnt - 1)) * Hkv + kvh) * KV_PAGE_BYTES, lane, ka, va);
+      load_page(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, min(i + 2, cnt - 1))) * KV_PAGE_BYTES, lane, ka, va);
       attn_page<true>(kb, vb, qf, st, scale_log2, (base + 4 * (i + 1)) * 16, L, g);
     }
     if (i < cnt) attn_page<true>(ka, va, qf, st, scale_log2, (base + 4 * i) * 16, L, g);
@@ -162,7 +162,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const h16_t* __restric
 // seq_ids[blockIdx.z] with p0 = 16 (4 blockIdx.x + w).  q / out are packed over tokens (row cu_seqlens[z] + pos)
 // in the same hi | lo layouts as the decode kernel.
 __global__ __launch_bounds__(256) void attn_prefill_kernel(const h16_t* __restrict__ q, const char* __restrict__ pool,
-                                                           const int* __restrict__ block_table, int max_blocks,
+                                                           const int* __restrict__ block_table, int max_blocks, int n_blocks,
                                                            const int* __restrict__ cu_seqlens,
                                                            const int* __restrict__ seq_ids, h16_t* __restrict__ out,
                                                            int Hq, int Hkv, float scale_log2) {
@@ -186,9 +186,9 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const h16_t* __restri
   const int* bt = block_table + (size_t)b * max_blocks;
   const int pd = p0 >> 4;  // diagonal page
   uint4 kf[4], vf[4], kn[4], vn[4];
-  load_page(pool + ((size_t)bt[0] * Hkv + kvh) * KV_PAGE_BYTES, lane, kf, vf);
+  load_page(pool + ((size_t)kvh * n_blocks + bt[0]) * KV_PAGE_BYTES, lane, kf, vf);
   for (int p = 0; p <= pd; ++p) {
-    if (p < pd) load_page(pool + ((size_t)bt[p + 1] * Hkv + kvh) * KV_PAGE_BYTES, lane, kn, vn);
+    if (p < pd) load_page(pool + ((size_t)kvh * n_blocks + bt[p + 1]) * KV_PAGE_BYTES, lane, kn, vn);
     if (p == pd)
       attn_page<true>(kf, vf, qf, st, scale_log2, p * 16, p0 + t + 1, g);
     else
@@ -216,7 +216,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const h16_t* __restri
 // fp32 path: one wavefront per (row, query head); lane j takes tokens j, j+64, ...; page = [2][16][h] floats.
 template <int H>
 __global__ __launch_bounds__(64) void attn_f32_kernel(const float* __restrict__ q, const float* __restrict__ pool,
-                                                      const int* __restrict__ block_table, int max_blocks,
+                                                      const int* __restrict__ block_table, int max_blocks, int n_blocks,
                                                       const int* __restrict__ row_pos, const int* __restrict__ row_seq,
                                                       float* __restrict__ out, int Hq, int Hkv) {
   const int m = blockIdx.y, head = blockIdx.x, lane = threadIdx.x;
@@ -233,7 +233,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float* __restrict__ 
   for (int i = 0; i < H; ++i) o[i] = 0.f;
   const int* bt = block_table + (size_t)b * max_blocks;
   for (int tok = lane; tok < L; tok += 64) {
-    const float* page = pool + ((size_t)bt[tok >> 4] * Hkv + kvh) * (2 * 16 * H);
+    const float* page = pool + ((size_t)kvh * n_blocks + bt[tok >> 4]) * (2 * 16 * H);
     const float* kr = page + (tok & 15) * H;
     const float* vr = page + 16 * H + (tok & 15) * H;
     float s = 0.f;
@@ -263,38 +263,38 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float* __restrict__ 
 static const float LOG2E = 1.4426950408889634f;
 
 hipError_t launch_attn_decode_h16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
-                                   int max_blocks, const int* seq_len, void* out, int B, int Hq, int Hkv) {
+                                   int max_blocks, int n_blocks, const int* seq_len, void* out, int B, int Hq, int Hkv) {
   if (B <= 0) return hipSuccess;
   if (Hq % Hkv || Hq / Hkv > 16) return hipErrorInvalidValue;
   float scale_log2 = LOG2E / sqrtf((float)KV_HEAD_DIM);
   attn_decode_kernel<<<dim3(Hkv, B), 256, 0, s>>>((const h16_t*)q, (const char*)kv_pool_layer, block_table, max_blocks,
-                                                  seq_len, (h16_t*)out, Hq, Hkv, scale_log2);
+                                                  n_blocks, seq_len, (h16_t*)out, Hq, Hkv, scale_log2);
   return hipGetLastError();
 }
 
 hipError_t launch_attn_prefill_h16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
-                                    int max_blocks, const int* cu_seqlens, const int* seq_ids, void* out, int nseq,
+                                    int max_blocks, int n_blocks, const int* cu_seqlens, const int* seq_ids, void* out, int nseq,
                                     int max_len, int Hq, int Hkv) {
   if (nseq <= 0 || max_len <= 0) return hipSuccess;
   if (Hq % Hkv) return hipErrorInvalidValue;
   float scale_log2 = LOG2E / sqrtf((float)KV_HEAD_DIM);
   attn_prefill_kernel<<<dim3((max_len + 63) / 64, Hq, nseq), 256, 0, s>>>(
-      (const h16_t*)q, (const char*)kv_pool_layer, block_table, max_blocks, cu_seqlens, seq_ids, (h16_t*)out, Hq, Hkv,
+      (const h16_t*)q, (const char*)kv_pool_layer, block_table, max_blocks, n_blocks, cu_seqlens, seq_ids, (h16_t*)out, Hq, Hkv,
       scale_log2);
   return hipGetLastError();
 }
 
 hipError_t launch_attn_f32(hipStream_t s, const float* q, const float* kv_pool_layer, const int* block_table,
-                           int max_blocks, const int* row_pos, const int* row_seq, float* out, int M, int Hq, int Hkv,
+                           int max_blocks, int n_blocks, const int* row_pos, const int* row_seq, float* out, int M, int Hq, int Hkv,
                            int h) {
   if (M <= 0) return hipSuccess;
   dim3 grid(Hq, M);
   if (h == 32)
-    attn_f32_kernel<32><<<grid, 64, 0, s>>>(q, kv_pool_layer, block_table, max_blocks, row_pos, row_seq, out, Hq, Hkv);
+    attn_f32_kernel<32><<<grid, 64, 0, s>>>(q, kv_pool_layer, block_table, max_blocks, n_blocks, row_pos, row_seq, out, Hq, Hkv);
   else if (h == 64)
-    attn_f32_kernel<64><<<grid, 64, 0, s>>>(q, kv_pool_layer, block_table, max_blocks, row_pos, row_seq, out, Hq, Hkv);
+    attn_f32_kernel<64><<<grid, 64, 0, s>>>(q, kv_pool_layer, block_table, max_blocks, n_blocks, row_pos, row_seq, out, Hq, Hkv);
   else if (h == 128)
-    attn_f32_kernel<128><<<grid, 64, 0, s>>>(q, kv_pool_layer, block_table, max_blocks, row_pos, row_seq, out, Hq, Hkv);
+    attn_f32_kernel<128><<<grid, 64, 0, s>>>(q, kv_pool_layer, block_table, max_blocks, n_blocks, row_pos, row_seq, out, Hq, Hkv);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();

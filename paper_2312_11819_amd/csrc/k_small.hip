@@ -175,7 +175,7 @@ __global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict
                                                          const float* __restrict__ cos_t,
                                                          const float* __restrict__ sin_t, void* __restrict__ q_out,
                                                          void* __restrict__ pool, const int* __restrict__ block_table,
-                                                         int max_blocks, int Hq, int Hkv, int h) {
+                                                         int max_blocks, int n_blocks, int Hq, int Hkv, int h) {
   const int m = blockIdx.y, head = blockIdx.x;
   const int pos = row_pos[m];
   const int b = row_seq ? row_seq[m] : m;
@@ -207,11 +207,11 @@ __global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict
       } else {
         const int kvh = head - Hq;
         if (A16) {
-          char* page = (char*)pool + ((size_t)blk * Hkv + kvh) * KV_PAGE_BYTES;
+          char* page = (char*)pool + ((size_t)kvh * n_blocks + blk) * KV_PAGE_BYTES;
           *(h16_t*)(page + kpage_offset(slot, i)) = f32_to_h16(r0);
           *(h16_t*)(page + kpage_offset(slot, i + half)) = f32_to_h16(r1);
         } else {
-          float* page = (float*)pool + ((size_t)blk * Hkv + kvh) * (2 * 16 * h);
+          float* page = (float*)pool + ((size_t)kvh * n_blocks + blk) * (2 * 16 * h);
           page[slot * h + i] = r0;
           page[slot * h + i + half] = r1;
         }
@@ -223,10 +223,10 @@ __global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict
       float v = row[dim];
       for (int sidx = 0; sidx < nsplit; ++sidx) v += prow[sidx * part_stride + dim];
       if (A16) {
-        char* page = (char*)pool + ((size_t)blk * Hkv + kvh) * KV_PAGE_BYTES;
+        char* page = (char*)pool + ((size_t)kvh * n_blocks + blk) * KV_PAGE_BYTES;
         *(h16_t*)(page + vpage_offset(slot, dim)) = f32_to_h16(v);
       } else {
-        float* page = (float*)pool + ((size_t)blk * Hkv + kvh) * (2 * 16 * h);
+        float* page = (float*)pool + ((size_t)kvh * n_blocks + blk) * (2 * 16 * h);
         page[16 * h + slot * h + dim] = v;
       }
     }
@@ -235,18 +235,18 @@ __global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict
 
 hipError_t launch_rope_append(hipStream_t s, const float* qkv, const float* part, int nsplit, size_t part_stride,
                               const int* row_pos, const int* row_seq, const float* cos_t, const float* sin_t,
-                              void* q_out, void* kv_pool_layer, const int* block_table, int max_blocks, int M, int Hq,
-                              int Hkv, int h, int act_bf16) {
+                              void* q_out, void* kv_pool_layer, const int* block_table, int max_blocks, int n_blocks,
+                              int M, int Hq, int Hkv, int h, int act_bf16) {
   if (M <= 0) return hipSuccess;
   if (!part) { nsplit = 0; part = qkv; }
   dim3 grid(Hq + 2 * Hkv, M);
   if (act_bf16) {
     if (h != KV_HEAD_DIM) return hipErrorInvalidValue;
     rope_append_kernel<true><<<grid, 64, 0, s>>>(qkv, part, nsplit, part_stride, row_pos, row_seq, cos_t, sin_t, q_out,
-                                                 kv_pool_layer, block_table, max_blocks, Hq, Hkv, h);
+                                                 kv_pool_layer, block_table, max_blocks, n_blocks, Hq, Hkv, h);
   } else {
     rope_append_kernel<false><<<grid, 64, 0, s>>>(qkv, part, nsplit, part_stride, row_pos, row_seq, cos_t, sin_t, q_out,
-                                                  kv_pool_layer, block_table, max_blocks, Hq, Hkv, h);
+                                                  kv_pool_layer, block_table, max_blocks, n_blocks, Hq, Hkv, h);
   }
   return hipGetLastError();
 }

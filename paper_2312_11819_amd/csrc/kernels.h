@@ -39,8 +39,8 @@ hipError_t launch_rmsnorm(hipStream_t s, float* x, const float* part, int nsplit
 // [M, Hq, 2, h] fp16 (hi | lo pair per head); fp32 mode: [M, Hq, h] floats.
 hipError_t launch_rope_append(hipStream_t s, const float* qkv, const float* part, int nsplit, size_t part_stride,
                               const int* row_pos, const int* row_seq, const float* cos_t, const float* sin_t,
-                              void* q_out, void* kv_pool_layer, const int* block_table, int max_blocks, int M, int Hq,
-                              int Hkv, int h, int act_bf16);
+                              void* q_out, void* kv_pool_layer, const int* block_table, int max_blocks, int n_blocks,
+                              int M, int Hq, int Hkv, int h, int act_bf16);
 // h[m][f] = silu(sum gate) * (sum up) from fp32 [M, 2F] (+ partial sums).
 hipError_t launch_swiglu(hipStream_t s, const float* gu, int nsplit, size_t part_stride, void* h_out, int act_bf16,
                          int M, int F);
@@ -48,15 +48,17 @@ hipError_t launch_advance(hipStream_t s, int* seq_len, int* step, int B);
 // bf16 -> fp16 copy of n elements (working copies of the weight matrices).
 hipError_t launch_bf16_to_h16(hipStream_t s, const void* src, void* dst, size_t n);
 
+// One layer's pool is [Hkv][n_blocks] pages: the pages a sequence gets from consecutive block ids are contiguous per
+// KV head, so a workgroup streams one contiguous region and different workgroups spread over the memory channels.
 // ---- attention over the paged cache (16-bit mode: q [rows, Hq, 2, 128] hi|lo pairs, out [rows, 2, Hq*128] hi|lo) ----
 hipError_t launch_attn_decode_h16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
-                                   int max_blocks, const int* seq_len, void* out, int B, int Hq, int Hkv);
+                                   int max_blocks, int n_blocks, const int* seq_len, void* out, int B, int Hq, int Hkv);
 hipError_t launch_attn_prefill_h16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
-                                    int max_blocks, const int* cu_seqlens, const int* seq_ids, void* out, int nseq,
+                                    int max_blocks, int n_blocks, const int* cu_seqlens, const int* seq_ids, void* out, int nseq,
                                     int max_len, int Hq, int Hkv);
 // fp32 path: one wavefront per (row, query head); row_pos[m] = position of the row's token.
 hipError_t launch_attn_f32(hipStream_t s, const float* q, const float* kv_pool_layer, const int* block_table,
-                           int max_blocks, const int* row_pos, const int* row_seq, float* out, int M, int Hq, int Hkv,
+                           int max_blocks, int n_blocks, const int* row_pos, const int* row_seq, float* out, int M, int Hq, int Hkv,
                            int h);
 
 // ---- fp32 GEMM (plain ALU) ----

@@ -217,15 +217,15 @@ int forward_layers_generic(rlhf_gen_ctx* c, const RowSet& r) {
     int rc = gemm_any(c, c->y, c->wqkv[l], c->qkv, r.M, qkv_w, d, EPI_STORE_F32, c->bf16);
     if (rc) return rc;
     LAUNCH(c, launch_rope_append(s, c->qkv, nullptr, 0, 0, r.row_pos, r.row_seq, c->d_cos, c->d_sin, c->qb, pool,
-                                 c->d_table, c->max_blocks, r.M, Hq, Hkv, h, c->bf16), "rope_append");
+                                 c->d_table, c->max_blocks, c->n_blocks, r.M, Hq, Hkv, h, c->bf16), "rope_append");
     if (!c->bf16) {
-      LAUNCH(c, launch_attn_f32(s, (const float*)c->qb, (const float*)pool, c->d_table, c->max_blocks, r.row_pos,
+      LAUNCH(c, launch_attn_f32(s, (const float*)c->qb, (const float*)pool, c->d_table, c->max_blocks, c->n_blocks, r.row_pos,
                                 r.row_seq, (float*)c->ab, r.M, Hq, Hkv, h), "attn_f32");
     } else if (r.prefill) {
-      LAUNCH(c, launch_attn_prefill_h16(s, c->qb, pool, c->d_table, c->max_blocks, r.cu, r.seq_ids, c->ab, r.nseq,
+      LAUNCH(c, launch_attn_prefill_h16(s, c->qb, pool, c->d_table, c->max_blocks, c->n_blocks, r.cu, r.seq_ids, c->ab, r.nseq,
                                          r.max_len, Hq, Hkv), "attn_prefill");
     } else {
-      LAUNCH(c, launch_attn_decode_h16(s, c->qb, pool, c->d_table, c->max_blocks, c->d_seq_len, c->ab, r.M, Hq, Hkv),
+      LAUNCH(c, launch_attn_decode_h16(s, c->qb, pool, c->d_table, c->max_blocks, c->n_blocks, c->d_seq_len, c->ab, r.M, Hq, Hkv),
              "attn_decode");
     }
     rc = gemm_any(c, c->ab, c->wo[l], c->x, r.M, d, Hq * h, EPI_RESID_F32, c->bf16);
@@ -266,10 +266,10 @@ int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
     prof_mark(c, RLHF_GEN_PROF_GEMM_QKV);
     size_t st = (size_t)B * qkv_w;
     LAUNCH(c, launch_rope_append(s, c->part, c->ks_qkv > 1 ? c->part + st : nullptr, c->ks_qkv - 1, st, c->d_seq_len,
-                                 nullptr, c->d_cos, c->d_sin, c->qb, pool, c->d_table, c->max_blocks, B, Hq, Hkv, h, 1),
+                                 nullptr, c->d_cos, c->d_sin, c->qb, pool, c->d_table, c->max_blocks, c->n_blocks, B, Hq, Hkv, h, 1),
            "rope_append");
     prof_mark(c, RLHF_GEN_PROF_ROPE);
-    LAUNCH(c, launch_attn_decode_h16(s, c->qb, pool, c->d_table, c->max_blocks, c->d_seq_len, c->ab, B, Hq, Hkv),
+    LAUNCH(c, launch_attn_decode_h16(s, c->qb, pool, c->d_table, c->max_blocks, c->n_blocks, c->d_seq_len, c->ab, B, Hq, Hkv),
            "attn_decode");
     prof_mark(c, RLHF_GEN_PROF_ATTN);
     LAUNCH(c, launch_gemm_skinny_h16(s, c->ab, c->wo[l], c->part, B, d, Hq * h, c->ks_wo, 1), "gemm_skinny wo");
@@ -875,28 +875,29 @@ int rlhf_gen_op_gemm(void* stream, int kind, const void* A, const void* W, void*
 
 int rlhf_gen_op_rope_append(void* stream, const float* qkv, const int32_t* row_pos, const int32_t* row_seq,
                             const float* cos_t, const float* sin_t, void* q_out, void* kv_pool,
-                            const int32_t* block_table, int32_t max_blocks, int32_t M, int32_t Hq, int32_t Hkv,
-                            int32_t head_dim, int32_t half16) {
+                            const int32_t* block_table, int32_t max_blocks, int32_t n_blocks, int32_t M, int32_t Hq,
+                            int32_t Hkv, int32_t head_dim, int32_t half16) {
   if (!qkv || !row_pos || !cos_t || !sin_t || !q_out || !kv_pool || !block_table) return RLHF_GEN_E_INVALID;
   hipError_t e = launch_rope_append((hipStream_t)stream, qkv, nullptr, 0, 0, row_pos, row_seq, cos_t, sin_t, q_out, kv_pool,
-                                    block_table, max_blocks, M, Hq, Hkv, head_dim, half16);
+                                    block_table, max_blocks, n_blocks, M, Hq, Hkv, head_dim, half16);
   if (e == hipErrorInvalidValue) return RLHF_GEN_E_UNSUPPORTED;
   return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;
 }
 
 int rlhf_gen_op_attn_decode(void* stream, const void* q, const void* kv_pool, const int32_t* block_table,
-                            int32_t max_blocks, const int32_t* seq_len, void* out, int32_t B, int32_t Hq, int32_t Hkv) {
+                            int32_t max_blocks, int32_t n_blocks, const int32_t* seq_len, void* out, int32_t B, int32_t Hq,
+                            int32_t Hkv) {
   if (!q || !kv_pool || !block_table || !seq_len || !out) return RLHF_GEN_E_INVALID;
-  hipError_t e = launch_attn_decode_h16((hipStream_t)stream, q, kv_pool, block_table, max_blocks, seq_len, out, B, Hq, Hkv);
+  hipError_t e = launch_attn_decode_h16((hipStream_t)stream, q, kv_pool, block_table, max_blocks, n_blocks, seq_len, out, B, Hq, Hkv);
   if (e == hipErrorInvalidValue) return RLHF_GEN_E_UNSUPPORTED;
   return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;
 }
 
 int rlhf_gen_op_attn_prefill(void* stream, const void* q, const void* kv_pool, const int32_t* block_table,
-                             int32_t max_blocks, const int32_t* cu_seqlens, const int32_t* seq_ids, void* out,
+                             int32_t max_blocks, int32_t n_blocks, const int32_t* cu_seqlens, const int32_t* seq_ids, void* out,
                              int32_t nseq, int32_t max_len, int32_t Hq, int32_t Hkv) {
   if (!q || !kv_pool || !block_table || !cu_seqlens || !seq_ids || !out) return RLHF_GEN_E_INVALID;
-  hipError_t e = launch_attn_prefill_h16((hipStream_t)stream, q, kv_pool, block_table, max_blocks, cu_seqlens, seq_ids, out,
+  hipError_t e = launch_attn_prefill_h16((hipStream_t)stream, q, kv_pool, block_table, max_blocks, n_blocks, cu_seqlens, seq_ids, out,
                                           nseq, max_len, Hq, Hkv);
   if (e == hipErrorInvalidValue) return RLHF_GEN_E_UNSUPPORTED;
   return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;

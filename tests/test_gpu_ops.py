@@ -138,22 +138,22 @@ def test_attention_prefill_then_decode(B, Hq, Hkv, lens):
     row_seq = torch.tensor([b for b, L in enumerate(lens) for _ in range(L)], dtype=torch.int32)
     row_pos = torch.tensor([p for L in lens for p in range(L)], dtype=torch.int32)
     cu = torch.tensor([0] + list(torch.tensor(lens).cumsum(0)), dtype=torch.int32)
-    pool = torch.zeros(n_blocks, Hkv, 8192, dtype=torch.uint8, device="cuda")
+    pool = torch.zeros(Hkv, n_blocks, 8192, dtype=torch.uint8, device="cuda")
     dev = lambda t: t.cuda().contiguous()
     qkv_d, cos_d, sin_d, table_d = dev(qkv), dev(cos_t), dev(sin_t), dev(table)
     q_out = torch.zeros(T, Hq, 2, h, dtype=torch.float16, device="cuda")
     assert B.rlhf_gen_op_rope_append(qkv_d[:T].contiguous(), dev(row_pos), dev(row_seq), cos_d, sin_d, q_out, pool,
-                                     table_d, max_blocks, T, Hq, Hkv, h, True) == 0
+                                     table_d, max_blocks, n_blocks, T, Hq, Hkv, h, True) == 0
     out = torch.zeros(T, 2, Hq * h, dtype=torch.float16, device="cuda")
     seq_ids = torch.arange(nseq, dtype=torch.int32, device="cuda")
-    assert B.rlhf_gen_op_attn_prefill(q_out, pool, table_d, max_blocks, dev(cu), seq_ids, out, nseq, max(lens), Hq, Hkv) == 0
+    assert B.rlhf_gen_op_attn_prefill(q_out, pool, table_d, max_blocks, n_blocks, dev(cu), seq_ids, out, nseq, max(lens), Hq, Hkv) == 0
     # decode row for each sequence at position len
     qd = torch.zeros(nseq, Hq, 2, h, dtype=torch.float16, device="cuda")
     seq_len = torch.tensor(lens, dtype=torch.int32, device="cuda")
     assert B.rlhf_gen_op_rope_append(qkv_d[T:].contiguous(), seq_len, None, cos_d, sin_d, qd, pool, table_d, max_blocks,
-                                     nseq, Hq, Hkv, h, True) == 0
+                                     n_blocks, nseq, Hq, Hkv, h, True) == 0
     outd = torch.zeros(nseq, 2, Hq * h, dtype=torch.float16, device="cuda")
-    assert B.rlhf_gen_op_attn_decode(qd, pool, table_d, max_blocks, seq_len, outd, nseq, Hq, Hkv) == 0
+    assert B.rlhf_gen_op_attn_decode(qd, pool, table_d, max_blocks, n_blocks, seq_len, outd, nseq, Hq, Hkv) == 0
     torch.cuda.synchronize()
     # CPU definition on the unrounded fp32 inputs
     scale = 1.0 / math.sqrt(h)
