@@ -181,12 +181,14 @@ hipError_t launch_large_dma(hipStream_t s, const void* A, const void* W, void* o
 constexpr int SK = 128;                 // k extent of one staged activation slice
 constexpr int SK_ROW = SK * 2 + 16;     // bytes per LDS row (padded)
 
-// grid (Nw / 64, nsplit), 256 threads; wavefront w owns W rows n0 + 16 w .. +16 and all M (<= 16 MB) columns.
+// grid (Nw / (16 NW), nsplit), 64 NW threads; wavefront w owns W rows n0 + 16 w .. +16 and all M (<= 16 MB) columns.
+// Measured on MI355X the kernel's time follows (weight bytes + activation-slice bytes requested from L2) / ~6.5 TB/s,
+// so the slice re-reads matter as much as the weights: eight wavefronts per workgroup (128 rows of W) halve them.
 // Loads run D - 1 k-steps ahead of the MFMAs through a register ring (weights and the activation slice alike:
 // the memory counter retires in order, so both must share one prefetch distance); the activation slice then
 // passes through a double-buffered LDS tile that the four wavefronts share.
-template <int MB, int D, bool GLU, bool DUAL>
-__global__ __launch_bounds__(256) void gemm_skinny_kernel(const h16_t* __restrict__ X, const h16_t* __restrict__ W,
+template <int MB, int D, bool GLU, bool DUAL, int NW>
+__global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __restrict__ X, const h16_t* __restrict__ W,
                                                           float* __restrict__ part, int M, int Nw, int K,
                                                           int steps_per_split) {
   static_assert(D == 2 || D == 4, "ring depth 2 or 4");
@@ -195,11 +197,14 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const h16_t* __restric
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int XR = DUAL ? 2 * MB : MB;   // 16-row blocks of the staged slice
   constexpr int XBYTES = 16 * XR * SK_ROW;
+  constexpr int NT = 64 * NW;
+  constexpr int XL = 256 * XR / NT;        // 16-byte chunks of the slice each thread moves per k-step
+  static_assert(XL * NT == 256 * XR, "slice chunks must divide evenly over the threads");
   const int ldx = DUAL ? 2 * K : K;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, t = lane & 15, g = lane >> 4;
   // GLU: W = [gate rows | up rows] of F = Nw / 2 features each; the workgroup owns 32 features, each wavefront
   // 8 of them with the gate rows in MFMA rows 0..7 and the matching up rows in 8..15.
-  const int n0 = GLU ? blockIdx.x * 32 : blockIdx.x * 64;
+  const int n0 = GLU ? blockIdx.x * (8 * NW) : blockIdx.x * (16 * NW);
   const int nsteps_total = K / SK;
   const int s0 = blockIdx.y * steps_per_split;
   const int s1 = min(nsteps_total, s0 + steps_per_split);
@@ -212,11 +217,11 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const h16_t* __restric
   const h16_t* wp = W + (size_t)wrow * K + 8 * g;
   // Activation slice: 16 MB rows x 16 chunks of 16 B per k-step, MB chunks per thread.  Rows beyond M are read
   // from row M - 1 instead: they only feed output columns that are never stored.
-  const h16_t* xp[XR];
-  int xo[XR];
+  const h16_t* xp[XL];
+  int xo[XL];
 #pragma unroll
-  for (int it = 0; it < XR; ++it) {
-    int c = it * 256 + tid, r = c >> 4, kc = c & 15;   // r in [0, 16 XR): rows >= 16 MB are the lo parts
+  for (int it = 0; it < XL; ++it) {
+    int c = it * NT + tid, r = c >> 4, kc = c & 15;   // r in [0, 16 XR): rows >= 16 MB are the lo parts
     int rr = DUAL ? r % (16 * MB) : r;
     xp[it] = X + (size_t)min(rr, M - 1) * ldx + ((DUAL && r >= 16 * MB) ? K : 0) + kc * 8;
     xo[it] = r * SK_ROW + kc * 16;
@@ -225,6 +230,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const h16_t* __restric
   // touch the same columns of W at the same time.
   const int nst = s1 - s0;
   const int rot = nst > 0 ? (int)((blockIdx.x * 5u + blockIdx.y * 3u) % (unsigned)nst) : 0;
+  (void)NT;
   // Loads are issued without any branch around them (a step index past the end re-reads the last step, which
   // hits in cache): with straight-line code the compiler can keep D - 1 steps of loads in flight and wait only
   // for the oldest.
@@ -234,19 +240,19 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const h16_t* __restric
     return (size_t)(s0 + r) * SK;
   };
   // Ring of D named slots (separate variables, so that they live in registers).
-  struct Slot { uint4 w[4]; uint4 x[XR]; };
+  struct Slot { uint4 w[4]; uint4 x[XL]; };
   Slot r0, r1, r2, r3;
 #define SKINNY_LOAD(S, I)                                                                                \
   {                                                                                                      \
     const size_t ko = step_off(I);                                                                       \
     _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) S.w[kk] = *(const uint4*)(wp + ko + kk * 32);       \
-    _Pragma("unroll") for (int it = 0; it < XR; ++it) S.x[it] = *(const uint4*)(xp[it] + ko);            \
+    _Pragma("unroll") for (int it = 0; it < XL; ++it) S.x[it] = *(const uint4*)(xp[it] + ko);            \
   }
   // one k-step on slot S (LDS buffer PAR)
 #define SKINNY_STEP(S, PAR)                                                                              \
   {                                                                                                      \
     char* buf = smem + (PAR) * XBYTES;                                                                   \
-    _Pragma("unroll") for (int it = 0; it < XR; ++it) *(uint4*)(buf + xo[it]) = S.x[it];                 \
+    _Pragma("unroll") for (int it = 0; it < XL; ++it) *(uint4*)(buf + xo[it]) = S.x[it];                 \
     __syncthreads();                                                                                     \
     uint4 xf[2][XR];                                                                                     \
     _Pragma("unroll") for (int mb = 0; mb < XR; ++mb)                                                    \
@@ -327,36 +333,65 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const h16_t* __restric
   }
 }
 
-template <int MB>
-hipError_t launch_skinny(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K, int nsplit,
-                         int a_dual, bool configure_only = false) {
+inline bool skinny_force_narrow() {
+  static const bool v = getenv("RLHF_SKINNY_NARROW") && atoi(getenv("RLHF_SKINNY_NARROW"));
+  return v;
+}
+
+template <int MB, int NW>
+hipError_t launch_skinny_nw(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K, int nsplit,
+                            int a_dual, bool configure_only) {
   constexpr int SMEM = 2 * 16 * MB * SK_ROW;
   constexpr int D = MB <= 4 ? 4 : 2;
-  constexpr bool HAS_DUAL = MB <= 8;   // the doubled slice of the largest variant would not fit in LDS
+  constexpr bool HAS_DUAL = MB <= 8;          // the doubled slice of the largest variant would not fit in LDS
+  constexpr bool HAS_SINGLE = 4 * MB >= NW;   // at least one slice chunk per thread
   if (configure_only) {
     hipError_t e;
-    if ((e = hipFuncSetAttribute((const void*)gemm_skinny_kernel<MB, D, false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute((const void*)gemm_skinny_kernel<MB, D, true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM)) != hipSuccess) return e;
+    if constexpr (HAS_SINGLE) {
+      if ((e = hipFuncSetAttribute((const void*)gemm_skinny_kernel<MB, D, false, false, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM)) != hipSuccess) return e;
+      if ((e = hipFuncSetAttribute((const void*)gemm_skinny_kernel<MB, D, true, false, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM)) != hipSuccess) return e;
+    }
     if constexpr (HAS_DUAL)
-      if ((e = hipFuncSetAttribute((const void*)gemm_skinny_kernel<MB, 2, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * SMEM)) != hipSuccess) return e;
+      if ((e = hipFuncSetAttribute((const void*)gemm_skinny_kernel<MB, 2, false, true, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * SMEM)) != hipSuccess) return e;
     return hipSuccess;
   }
+  const int rows_per_wg = 16 * NW;
   if (nsplit == 0) {  // fused SwiGLU: W = [2F, K], output fp16 [M, F], no split
     if (a_dual) return hipErrorInvalidValue;
-    gemm_skinny_kernel<MB, D, true, false><<<dim3(Nw / 64, 1), 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, K / SK);
+    if constexpr (HAS_SINGLE)
+      gemm_skinny_kernel<MB, D, true, false, NW><<<dim3(Nw / rows_per_wg, 1), 64 * NW, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, K / SK);
+    else
+      return hipErrorInvalidValue;
     return hipGetLastError();
   }
   int steps = K / SK;
   int per = (steps + nsplit - 1) / nsplit;
   if (a_dual) {
     if constexpr (HAS_DUAL)
-      gemm_skinny_kernel<MB, 2, false, true><<<dim3(Nw / 64, nsplit), 256, 2 * SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, per);
+      gemm_skinny_kernel<MB, 2, false, true, NW><<<dim3(Nw / rows_per_wg, nsplit), 64 * NW, 2 * SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, per);
     else
       return hipErrorInvalidValue;
   } else {
-    gemm_skinny_kernel<MB, D, false, false><<<dim3(Nw / 64, nsplit), 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, per);
+    if constexpr (HAS_SINGLE)
+      gemm_skinny_kernel<MB, D, false, false, NW><<<dim3(Nw / rows_per_wg, nsplit), 64 * NW, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, per);
+    else
+      return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+template <int MB>
+hipError_t launch_skinny(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K, int nsplit,
+                         int a_dual, bool configure_only = false) {
+  if (configure_only) {
+    hipError_t e = launch_skinny_nw<MB, 4>(s, A, W, part, M, Nw, K, nsplit, a_dual, true);
+    if (e != hipSuccess) return e;
+    return launch_skinny_nw<MB, 8>(s, A, W, part, M, Nw, K, nsplit, a_dual, true);
+  }
+  // eight wavefronts (128 rows of W per workgroup) when the shape allows: half the activation-slice traffic
+  const bool wide = Nw % 128 == 0 && (a_dual ? true : 4 * MB >= 8) && MB <= 8 && !skinny_force_narrow();
+  return wide ? launch_skinny_nw<MB, 8>(s, A, W, part, M, Nw, K, nsplit, a_dual, false)
+              : launch_skinny_nw<MB, 4>(s, A, W, part, M, Nw, K, nsplit, a_dual, false);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -414,8 +449,8 @@ hipError_t gemm_configure() {
 
 int gemm_skinny_pick_split(int M, int Nw, int K) {
   (void)M;
-  int tiles = Nw / 64, steps = K / SK;
-  int want = (512 + tiles - 1) / tiles;
+  int tiles = (Nw % 128 == 0 && !skinny_force_narrow()) ? Nw / 128 : Nw / 64, steps = K / SK;
+  int want = (768 + tiles - 1) / tiles;
   if (want > 8) want = 8;
   if (want > steps) want = steps;
   if (want < 1) want = 1;
