@@ -53,6 +53,7 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=0, help="override the depth (debugging only; invalidates the metric)")
     ap.add_argument("--resp-len", type=int, default=0, help="override R (debugging only; invalidates the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-score", action="store_true")
     ap.add_argument("--profile-every", type=int, default=64)
     ap.add_argument("--flags", type=int, default=0)
     args = ap.parse_args()
@@ -140,6 +141,20 @@ def main() -> int:
         roofline["attn_decode_GBps"] = attn_bytes / attn_s / 1e9 if attn_s > 0 else None
         roofline["gemm_skinny_GBps"] = gemm_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else None
 
+    # scoring pass over the rollout just produced (Actor.forward of Alg. 1), outside the timed region
+    score = None
+    if not args.no_score:
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        sc = ctx.rlhf_gen_score(toks_d, lens.tolist(), out_t)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t1
+        fed = lsum + B * (R - 1)
+        sflop = 2 * layer_mm * shape.n_layers * fed + 2 * B * R * shape.vocab * shape.d_model \
+            + sum(2 * (int(l) + R - 1) ** 2 * shape.n_heads * shape.head_dim * shape.n_layers for l in lens)
+        score = {"ms": dt * 1e3, "scored_tokens_per_s": B * R / dt, "mfma_bf16_frac": sflop / dt / MFMA_BF16_PEAK,
+                 "max_abs_diff_vs_rollout_logprobs": float((sc - out_lp).abs().max())}
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(wl if not args.layers else synth.dataclasses.replace(wl, shape=shape), w, toks, lens)
@@ -157,6 +172,7 @@ def main() -> int:
         "prefill": {"ms": pre_ms, "mfma_bf16_frac": pre_frac, "flop": pre_flop + pre_flop_attn},
         "roofline": roofline,
         "kernels_sampled": kernels,
+        "score_pass": score,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))

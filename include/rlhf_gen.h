@@ -143,6 +143,18 @@ int rlhf_gen_generate(rlhf_gen_ctx* ctx, const int32_t* query_tokens, const int3
                       int32_t Lmax, int32_t max_resp_len, const rlhf_gen_sampling* sampling,
                       int32_t* resp_tokens, float* resp_logprobs);
 
+/* Teacher-forced scoring pass: the raw-model log-probability of every token of given responses, by one forward over
+ * query ++ response per sequence - `ActorOutput <- Actor.forward(Query, Response)` of Alg. 1 (the same call scores the
+ * Ref model).  logprobs_out[b, t] = log softmax(logits at position lengths[b] - 1 + t)[resp_tokens[b, t]]; for a
+ * rollout produced by rlhf_gen_generate with logprob_mode 0 it reproduces the log-probs returned there (up to the
+ * rounding of the 16-bit path).  The [rows, vocab] logits are produced and consumed in blocks of 1024 rows inside the
+ * library and never written out.  Replaces the batch held by the context (a following decode_step fails with E_STATE).
+ *   query_tokens device int32 [B, Lmax]; lengths HOST int32 [B]; resp_tokens device int32 [B, R];
+ *   lengths[b] + R - 1 <= max_seq; logprobs_out device float [B, R], valid after the stream is synchronised.
+ * Errors as for rlhf_gen_prefill. */
+int rlhf_gen_score(rlhf_gen_ctx* ctx, const int32_t* query_tokens, const int32_t* lengths, int32_t B, int32_t Lmax,
+                   const int32_t* resp_tokens, int32_t R, float* logprobs_out);
+
 /* Copy the fp32 logits [B, vocab] that the last prefill/decode step sampled from into a device
  * buffer (parity checks).  E_STATE if no step has run. */
 int rlhf_gen_get_logits(rlhf_gen_ctx* ctx, float* out);

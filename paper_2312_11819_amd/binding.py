@@ -27,7 +27,7 @@ PROF_CLASSES = ["embed", "norm", "gemm_qkv", "rope_append", "attn_decode", "gemm
                 "gemm_down", "lm_head", "sampler"]
 
 EXPORTS = [
-    "rlhf_gen_init", "rlhf_gen_prefill", "rlhf_gen_decode_step", "rlhf_gen_generate", "rlhf_gen_get_logits",
+    "rlhf_gen_init", "rlhf_gen_prefill", "rlhf_gen_decode_step", "rlhf_gen_generate", "rlhf_gen_score", "rlhf_gen_get_logits",
     "rlhf_gen_last_timing", "rlhf_gen_set_profile", "rlhf_gen_get_profile", "rlhf_gen_last_error", "rlhf_gen_destroy",
     "rlhf_gen_op_gemm", "rlhf_gen_op_rope_append", "rlhf_gen_op_attn_decode", "rlhf_gen_op_attn_prefill",
     "rlhf_gen_op_sample",
@@ -76,6 +76,8 @@ def lib() -> C.CDLL:
         L.rlhf_gen_decode_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.rlhf_gen_generate.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_int32,
                                         C.POINTER(Sampling), C.c_void_p, C.c_void_p]
+        L.rlhf_gen_score.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_void_p,
+                                     C.c_int32, C.c_void_p]
         L.rlhf_gen_get_logits.argtypes = [C.c_void_p, C.c_void_p]
         L.rlhf_gen_last_timing.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_int32)]
         L.rlhf_gen_set_profile.argtypes = [C.c_void_p, C.c_int32]
@@ -171,6 +173,17 @@ class Context:
                                                 C.byref(sampling), _ptr(toks), _ptr(lps)))
         self.B = B
         return toks, lps
+
+    def rlhf_gen_score(self, query_tokens: torch.Tensor, lengths: Sequence[int], resp_tokens: torch.Tensor) -> torch.Tensor:
+        B, Lmax = query_tokens.shape
+        R = resp_tokens.shape[1]
+        lens = (C.c_int32 * B)(*[int(x) for x in lengths])
+        out = torch.empty(B, R, dtype=torch.float32, device=self.device)
+        self.stream.wait_stream(torch.cuda.current_stream(self.device))
+        _check(self._h, lib().rlhf_gen_score(self._h, _ptr(query_tokens), lens, B, Lmax, _ptr(resp_tokens), R, _ptr(out)))
+        self.synchronize()
+        self.B = 0
+        return out
 
     def rlhf_gen_get_logits(self) -> torch.Tensor:
         out = torch.empty(self.B, self.shape.vocab, dtype=torch.float32, device=self.device)

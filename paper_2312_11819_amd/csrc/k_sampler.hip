@@ -261,7 +261,46 @@ __global__ __launch_bounds__(ST) void sampler_kernel(const float* __restrict__ l
   (void)Zn;
 }
 
+// Raw-model log-probability of a given token per row of logits: lp = logit[tok] - max - log(sum exp(logit - max)).
+// Row r belongs to flat response slot slot[r]; the token is resp_tokens[slot[r]] and the result goes to out[slot[r]].
+__global__ __launch_bounds__(ST) void logprob_gather_kernel(const float* __restrict__ logits, int V,
+                                                            const int* __restrict__ slot,
+                                                            const int* __restrict__ resp_tokens, float* __restrict__ out,
+                                                            int* __restrict__ err_flag) {
+  __shared__ Shared sh;
+  const int r = blockIdx.x, tid = threadIdx.x;
+  const float* row = logits + (size_t)r * V;
+  float vloc = -INFINITY;
+  int iloc = 0x7fffffff;
+  for (int i = tid; i < V; i += ST) {
+    float v = row[i];
+    if (v > vloc) { vloc = v; iloc = i; }
+  }
+  float vmax;
+  int imax;
+  block_argmax(vloc, iloc, sh, vmax, imax);
+  double sraw = 0.0;
+  for (int i = tid; i < V; i += ST) sraw += (double)expf(row[i] - vmax);
+  const double Z = block_sum_d(sraw, sh);
+  if (tid == 0) {
+    const int sl = slot[r];
+    int tok = resp_tokens[sl];
+    if (tok < 0 || tok >= V) {
+      *err_flag = 1;
+      tok = tok < 0 ? 0 : V - 1;
+    }
+    out[sl] = (float)((double)(row[tok] - vmax) - log(Z));
+  }
+}
+
 }  // namespace
+
+hipError_t launch_logprob_gather(hipStream_t s, const float* logits, int rows, int V, const int* slot,
+                                 const int* resp_tokens, float* out, int* err_flag) {
+  if (rows <= 0) return hipSuccess;
+  logprob_gather_kernel<<<rows, ST, 0, s>>>(logits, V, slot, resp_tokens, out, err_flag);
+  return hipGetLastError();
+}
 
 hipError_t launch_sampler(hipStream_t s, const float* logits, int B, int V, SamplerParams p, const int* step_ptr,
                           int out_stride, int use_step_col, int* tok_out, float* lp_out, int* cur_tok) {

@@ -17,6 +17,32 @@ __global__ void pack_tokens_kernel(const int* __restrict__ query_tokens, int Lma
   ids_out[i] = id;
 }
 
+// Scoring pass: the fed sequence of row b is its query followed by its response; position p < qlen[b] reads the
+// query, later positions the response.
+__global__ void pack_tokens2_kernel(const int* __restrict__ query_tokens, int Lmax, const int* __restrict__ resp_tokens,
+                                    int R, const int* __restrict__ qlen, const int* __restrict__ tok_seq,
+                                    const int* __restrict__ tok_pos, int T, int vocab, int* __restrict__ ids_out,
+                                    int* __restrict__ err_flag) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= T) return;
+  int b = tok_seq[i], p = tok_pos[i], ql = qlen[b];
+  int id = p < ql ? query_tokens[(size_t)b * Lmax + p] : resp_tokens[(size_t)b * R + (p - ql)];
+  if (id < 0 || id >= vocab) {
+    *err_flag = 1;
+    id = id < 0 ? 0 : vocab - 1;
+  }
+  ids_out[i] = id;
+}
+
+hipError_t launch_pack_tokens2(hipStream_t s, const int* query_tokens, int Lmax, const int* resp_tokens, int R,
+                               const int* qlen, const int* tok_seq, const int* tok_pos, int T, int vocab, int* ids_out,
+                               int* err_flag) {
+  if (T <= 0) return hipSuccess;
+  pack_tokens2_kernel<<<(T + 255) / 256, 256, 0, s>>>(query_tokens, Lmax, resp_tokens, R, qlen, tok_seq, tok_pos, T, vocab,
+                                                      ids_out, err_flag);
+  return hipGetLastError();
+}
+
 hipError_t launch_pack_tokens(hipStream_t s, const int* query_tokens, int Lmax, const int* tok_seq, const int* tok_pos,
                               int T, int vocab, int* ids_out, int* err_flag) {
   if (T <= 0) return hipSuccess;

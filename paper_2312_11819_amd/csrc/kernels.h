@@ -28,6 +28,9 @@ hipError_t gemm_configure();
 // ---- elementwise / small kernels (act_bf16 != 0: 16-bit (fp16) activations, else fp32) ----
 hipError_t launch_pack_tokens(hipStream_t s, const int* query_tokens, int Lmax, const int* tok_seq, const int* tok_pos,
                               int T, int vocab, int* ids_out, int* err_flag);
+hipError_t launch_pack_tokens2(hipStream_t s, const int* query_tokens, int Lmax, const int* resp_tokens, int R,
+                               const int* qlen, const int* tok_seq, const int* tok_pos, int T, int vocab, int* ids_out,
+                               int* err_flag);
 hipError_t launch_embed(hipStream_t s, const int* ids, const void* table, int w_bf16, float* x, int M, int d, int vocab,
                         int* err_flag);
 // x[m] += sum_{s<nsplit} part[s][m][:] (if part), then y = rmsnorm(x) * gain.  rows[m] (optional) selects
@@ -64,7 +67,9 @@ hipError_t launch_attn_f32(hipStream_t s, const float* q, const float* kv_pool_l
 // ---- fp32 GEMM (plain ALU) ----
 hipError_t launch_gemm_f32(hipStream_t s, const float* A, const float* W, float* out, int M, int N, int K, int accumulate);
 
-// ---- sampler ----
+// ---- sampler / log-prob gather ----
+hipError_t launch_logprob_gather(hipStream_t s, const float* logits, int rows, int V, const int* slot,
+                                 const int* resp_tokens, float* out, int* err_flag);
 struct SamplerParams {
   float temperature, top_p;
   uint64_t seed;

@@ -52,6 +52,11 @@ struct rlhf_gen_ctx {
   float *d_cos = nullptr, *d_sin = nullptr;
   int *d_tok_seq = nullptr, *d_tok_pos = nullptr, *d_ids = nullptr, *d_cu = nullptr, *d_seq_ids = nullptr,
       *d_last_rows = nullptr;
+  // scoring pass scratch: gathered rows, their response slots, and a block of logits
+  int score_cap = 0;
+  int *d_srows = nullptr, *d_sslot = nullptr, *h_srows = nullptr, *h_sslot = nullptr;
+  void* ys = nullptr;
+  float* slogits = nullptr;
   int act_rows = 0;  // row capacity of the activation buffers
   float *x = nullptr, *qkv = nullptr, *logits = nullptr, *part = nullptr;
   void *y = nullptr, *yl = nullptr, *qb = nullptr, *ab = nullptr, *hb = nullptr;
@@ -461,6 +466,128 @@ int prefill_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* le
   return RLHF_GEN_OK;
 }
 
+// Teacher-forced forward over query ++ response[0 .. R-2] and log-softmax gather at the R positions that predict the
+// response tokens.  Uses the same kernels as prefill; replaces the batch held by the context.
+int score_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* lengths, int32_t B, int32_t Lmax,
+               const int32_t* resp_tokens, int32_t R, float* lp_out) {
+  const rlhf_gen_cfg& g = c->cfg;
+  if (!query_tokens || !lengths || !resp_tokens || !lp_out) return fail(c, RLHF_GEN_E_INVALID, "NULL pointer argument");
+  if (B < 1 || B > g.max_batch) return fail(c, RLHF_GEN_E_INVALID, "B = %d outside [1, max_batch = %d]", B, g.max_batch);
+  if (Lmax < 1 || R < 1) return fail(c, RLHF_GEN_E_INVALID, "Lmax and R must be positive");
+  long need_blocks = 0;
+  for (int b = 0; b < B; ++b) {
+    if (lengths[b] < 1 || lengths[b] > Lmax)
+      return fail(c, RLHF_GEN_E_INVALID, "lengths[%d] = %d outside [1, Lmax = %d]", b, lengths[b], Lmax);
+    if (lengths[b] + R - 1 > g.max_seq)
+      return fail(c, RLHF_GEN_E_INVALID, "sequence %d: %d query + %d response tokens exceed max_seq = %d", b, lengths[b], R,
+                  g.max_seq);
+    need_blocks += blocks_for(lengths[b] + R - 1);
+  }
+  if (need_blocks > c->n_blocks)
+    return fail(c, RLHF_GEN_E_NOMEM, "KV pool has %d pages, the batch needs %ld", c->n_blocks, need_blocks);
+  HIP_TRY(c, hipSetDevice(g.device));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  c->have_batch = false;
+  c->have_logits = false;
+  c->B = B;
+  reset_free_list(c);
+  int T = 0;
+  for (int b = 0; b < B; ++b) {
+    const int fed = lengths[b] + R - 1;
+    c->h_len[b] = fed;
+    grow_seq(c, b, fed);
+    for (int p = 0; p < fed; ++p) {
+      c->h_tok_seq[T] = b;
+      c->h_tok_pos[T] = p;
+      ++T;
+    }
+    c->h_lenbuf[b] = lengths[b];
+    c->h_seq_ids[b] = b;
+  }
+  hipStream_t s = c->stream;
+  HIP_TRY(c, hipMemcpyAsync(c->d_table, c->h_table, sizeof(int) * (size_t)g.max_batch * c->max_blocks,
+                            hipMemcpyHostToDevice, s));
+  HIP_TRY(c, hipMemcpyAsync(c->d_tok_seq, c->h_tok_seq, sizeof(int) * T, hipMemcpyHostToDevice, s));
+  HIP_TRY(c, hipMemcpyAsync(c->d_tok_pos, c->h_tok_pos, sizeof(int) * T, hipMemcpyHostToDevice, s));
+  HIP_TRY(c, hipMemcpyAsync(c->d_seq_len, c->h_lenbuf, sizeof(int) * B, hipMemcpyHostToDevice, s));  // query lengths
+  HIP_TRY(c, hipMemcpyAsync(c->d_seq_ids, c->h_seq_ids, sizeof(int) * B, hipMemcpyHostToDevice, s));
+  c->h_misc[0] = 0;
+  HIP_TRY(c, hipMemcpyAsync(c->d_err, &c->h_misc[0], sizeof(int), hipMemcpyHostToDevice, s));
+  LAUNCH(c, launch_pack_tokens2(s, query_tokens, Lmax, resp_tokens, R, c->d_seq_len, c->d_tok_seq, c->d_tok_pos, T,
+                                g.vocab, c->d_ids, c->d_err), "pack_tokens2");
+  HIP_TRY(c, hipMemcpyAsync(&c->h_misc[2], c->d_err, sizeof(int), hipMemcpyDeviceToHost, s));
+  HIP_TRY(c, hipStreamSynchronize(s));
+  if (c->h_misc[2]) return fail(c, RLHF_GEN_E_INVALID, "a token id lies outside [0, vocab = %d)", g.vocab);
+
+  std::vector<int> chunk_begin;
+  {
+    int rows = 0;
+    chunk_begin.push_back(0);
+    for (int b = 0; b < B; ++b) {
+      const int fed = lengths[b] + R - 1;
+      if (rows + fed > c->act_rows) {
+        chunk_begin.push_back(b);
+        rows = 0;
+      }
+      rows += fed;
+    }
+    chunk_begin.push_back(B);
+  }
+  // per chunk: local row offsets; for every response slot (b, t) the chunk-local row that predicts it
+  int cu_fill = 0, sfill = 0;
+  std::vector<int> cu_at(chunk_begin.size() - 1), s_at(chunk_begin.size());
+  for (size_t ci = 0; ci + 1 < chunk_begin.size(); ++ci) {
+    cu_at[ci] = cu_fill;
+    s_at[ci] = sfill;
+    int rows = 0;
+    c->h_cu[cu_fill++] = 0;
+    for (int b = chunk_begin[ci]; b < chunk_begin[ci + 1]; ++b) {
+      for (int t = 0; t < R; ++t) {
+        c->h_srows[sfill] = rows + lengths[b] - 1 + t;
+        c->h_sslot[sfill] = b * R + t;
+        ++sfill;
+      }
+      rows += lengths[b] + R - 1;
+      c->h_cu[cu_fill++] = rows;
+    }
+  }
+  s_at[chunk_begin.size() - 1] = sfill;
+  HIP_TRY(c, hipMemcpyAsync(c->d_cu, c->h_cu, sizeof(int) * cu_fill, hipMemcpyHostToDevice, s));
+  HIP_TRY(c, hipMemcpyAsync(c->d_srows, c->h_srows, sizeof(int) * sfill, hipMemcpyHostToDevice, s));
+  HIP_TRY(c, hipMemcpyAsync(c->d_sslot, c->h_sslot, sizeof(int) * sfill, hipMemcpyHostToDevice, s));
+
+  int row0 = 0;
+  for (size_t ci = 0; ci + 1 < chunk_begin.size(); ++ci) {
+    int b0 = chunk_begin[ci], b1 = chunk_begin[ci + 1];
+    RowSet r;
+    r.prefill = true;
+    r.nseq = b1 - b0;
+    for (int b = b0; b < b1; ++b) {
+      r.M += lengths[b] + R - 1;
+      r.max_len = std::max(r.max_len, (int)lengths[b] + R - 1);
+    }
+    r.ids = c->d_ids + row0;
+    r.row_pos = c->d_tok_pos + row0;
+    r.row_seq = c->d_tok_seq + row0;
+    r.cu = c->d_cu + cu_at[ci];
+    r.seq_ids = c->d_seq_ids + b0;
+    int rc = forward_layers_generic(c, r);
+    if (rc) return rc;
+    // LM head + log-softmax gather over the chunk's scoring rows, score_cap rows at a time (logits never leave the scratch)
+    for (int q0 = s_at[ci]; q0 < s_at[ci + 1]; q0 += c->score_cap) {
+      const int n = std::min(c->score_cap, s_at[ci + 1] - q0);
+      LAUNCH(c, launch_rmsnorm(s, c->x, nullptr, 0, 0, c->final_norm, c->bf16, c->ys, c->bf16, n, g.d_model, g.rms_eps,
+                               c->d_srows + q0, 0), "final rmsnorm");
+      rc = gemm_any(c, c->ys, c->lm_head, c->slogits, n, g.vocab, g.d_model, EPI_STORE_F32);
+      if (rc) return rc;
+      LAUNCH(c, launch_logprob_gather(s, c->slogits, n, g.vocab, c->d_sslot + q0, resp_tokens, lp_out, c->d_err),
+             "logprob_gather");
+    }
+    row0 += r.M;
+  }
+  return RLHF_GEN_OK;
+}
+
 int decode_checks(rlhf_gen_ctx* c) {
   if (!c->have_batch) return fail(c, RLHF_GEN_E_STATE, "decode_step before a successful prefill");
   long need = 0;
@@ -641,6 +768,11 @@ int rlhf_gen_init(const rlhf_gen_weights* w, const rlhf_gen_cfg* cfg, rlhf_gen_c
   A_(dev_alloc(c, &c->ab, 2 * as * rows * g.n_heads * g.head_dim, true));
   A_(dev_alloc(c, &c->hb, as * rows * g.d_ffn, true));
   A_(dev_alloc(c, &c->logits, 4 * (size_t)g.max_batch * g.vocab, true));
+  c->score_cap = 1024;
+  A_(dev_alloc(c, &c->d_srows, sizeof(int) * total_tok, true));
+  A_(dev_alloc(c, &c->d_sslot, sizeof(int) * total_tok, true));
+  A_(dev_alloc(c, &c->ys, as * ((size_t)c->score_cap + 256) * g.d_model, true));
+  A_(dev_alloc(c, &c->slogits, 4 * (size_t)c->score_cap * g.vocab, true));
   if (c->bf16) {
     const int Bm = std::min(g.max_batch, 128);
     c->ks_qkv = gemm_skinny_pick_split(Bm, qkv_w, g.d_model);
@@ -659,6 +791,8 @@ int rlhf_gen_init(const rlhf_gen_weights* w, const rlhf_gen_cfg* cfg, rlhf_gen_c
   A_(host_alloc(c, &c->h_table, sizeof(int) * (size_t)g.max_batch * c->max_blocks));
   A_(host_alloc(c, &c->h_lenbuf, sizeof(int) * g.max_batch));
   A_(host_alloc(c, &c->h_misc, sizeof(int) * 8));
+  A_(host_alloc(c, &c->h_srows, sizeof(int) * total_tok));
+  A_(host_alloc(c, &c->h_sslot, sizeof(int) * total_tok));
 #undef A_
   {
     // rotation tables in double, rounded once to fp32: angle = pos * theta^(-2i/h)
@@ -785,6 +919,12 @@ int rlhf_gen_generate(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_
   return RLHF_GEN_OK;
 }
 
+int rlhf_gen_score(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* lengths, int32_t B, int32_t Lmax,
+                   const int32_t* resp_tokens, int32_t R, float* logprobs_out) {
+  if (!c) return RLHF_GEN_E_INVALID;
+  return score_impl(c, query_tokens, lengths, B, Lmax, resp_tokens, R, logprobs_out);
+}
+
 int rlhf_gen_get_logits(rlhf_gen_ctx* c, float* out) {
   if (!c) return RLHF_GEN_E_INVALID;
   if (!out) return fail(c, RLHF_GEN_E_INVALID, "NULL output pointer");
@@ -842,7 +982,8 @@ void rlhf_gen_destroy(rlhf_gen_ctx* c) {
   if (c->stream || !c->allocs.empty()) (void)hipStreamSynchronize(c->stream);
   drop_graph(c);
   for (void* p : c->allocs) (void)hipFree(p);
-  int* pinned[] = {c->h_tok_seq, c->h_tok_pos, c->h_cu, c->h_seq_ids, c->h_last_rows, c->h_table, c->h_lenbuf, c->h_misc};
+  int* pinned[] = {c->h_tok_seq, c->h_tok_pos, c->h_cu, c->h_seq_ids, c->h_last_rows, c->h_table, c->h_lenbuf, c->h_misc,
+                   c->h_srows, c->h_sslot};
   for (int* p : pinned)
     if (p) (void)hipHostFree(p);
   for (int i = 0; i < 3; ++i)

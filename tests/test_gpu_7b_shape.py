@@ -93,3 +93,23 @@ def test_70b_width_gqa_2_layers(B):
     shape = synth.with_layers(synth.LLAMA_70B_GQA, 2)
     dl, dlp, frac = _run(B, shape, 32, 200, 520, [0, 17], 4, dict(temperature=1.0, top_p=0.9, seed=5), 5, 5)
     assert dl <= 3e-2 and dlp <= 2e-2 and frac <= 0.5
+
+
+def test_7b_width_score_pass(B):
+    """rlhf_gen_score at the 7B width (2 layers, 16 sequences of 300 + 40 tokens) against the oracle's score()."""
+    from oracle.generate import score as oracle_score
+    shape = synth.with_layers(synth.LLAMA_7B, 2)
+    w = synth.make_weights(shape, 7, "bf16", "cuda")
+    toks, lens = synth.make_queries(shape.vocab, 16, 100, 300, 8)
+    g = torch.Generator().manual_seed(9)
+    resp = torch.randint(0, shape.vocab, (16, 40), generator=g, dtype=torch.int32)
+    ctx = B.Context(w, shape, "bf16", 16, 340)
+    got = ctx.rlhf_gen_score(toks.cuda(), lens.tolist(), resp.cuda()).cpu().double()
+    w_cpu = synth.weights_to(w, "cpu")
+    worst = 0.0
+    for b in (0, 15):
+        want = oracle_score(w_cpu, shape, toks[b, : lens[b]].tolist(), resp[b].tolist())
+        worst = max(worst, float((got[b] - want).abs().max()))
+    print(f"\n[score, 2 layers] max|dlogprob|={worst:.4f}", flush=True)
+    assert worst <= 2e-2
+    ctx.rlhf_gen_destroy()
