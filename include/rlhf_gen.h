@@ -50,6 +50,8 @@ enum {
   RLHF_GEN_FLAG_SHUFFLE_BLOCKS = 1u, /* hand out KV blocks in a scrambled order (tests: results must not depend on placement) */
   RLHF_GEN_FLAG_NO_GRAPH = 2u,       /* generate launches every decode step kernel by kernel instead of replaying a captured graph */
   RLHF_GEN_FLAG_GENERIC_GEMM = 4u,   /* decode uses the large-tile GEMM instead of the weight-streaming one (cross-check) */
+  RLHF_GEN_FLAG_FUSED_ROPE = 16u,    /* decode folds RoPE + KV append into the attention kernel (one launch fewer per layer;
+                                        measured 2 % slower per step on MI355X at the 7B shape, so it is off by default) */
   RLHF_GEN_FLAG_CONVERT_IN_PLACE = 8u /* bf16 mode: rewrite the caller's projection matrices and LM head to fp16 in place
                                          instead of allocating working copies (for models that fill the card; the
                                          buffers then no longer hold bf16 and must not be reused as such) */

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "librlhf_gen.so")
 
 OK, E_INVALID, E_NOMEM, E_STATE, E_DEVICE, E_UNSUPPORTED = 0, -1, -2, -3, -4, -5
 DTYPE_FP32, DTYPE_BF16 = 0, 1
-FLAG_SHUFFLE_BLOCKS, FLAG_NO_GRAPH, FLAG_GENERIC_GEMM, FLAG_CONVERT_IN_PLACE = 1, 2, 4, 8
+FLAG_SHUFFLE_BLOCKS, FLAG_NO_GRAPH, FLAG_GENERIC_GEMM, FLAG_CONVERT_IN_PLACE, FLAG_FUSED_ROPE = 1, 2, 4, 8, 16
 GEMM_TILED, GEMM_STREAMING, GEMM_FP32 = 0, 1, 2
 EPI_STORE_F32, EPI_RESID_F32, EPI_SWIGLU, EPI_STORE_H16 = 0, 1, 2, 3
 

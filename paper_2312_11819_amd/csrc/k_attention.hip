@@ -87,41 +87,132 @@ __device__ __forceinline__ void init_state(AttnState& st) {
   st.l = 0.f;
 }
 
-// grid (Hkv, B), 256 threads.  q [B, Hq, 2, 128] fp16 (hi | lo per head), out [B, 2, Hq*128] fp16 (hi | lo).  seq_len[b] = tokens cached BEFORE
-// this step; the step's own key/value has already been appended, so seq_len[b] + 1 tokens are visible.
-__global__ __launch_bounds__(256) void attn_decode_kernel(const h16_t* __restrict__ q, const char* __restrict__ pool,
+// grid (Hkv, B), 256 threads.  out [B, 2, Hq*128] fp16 (hi | lo).  seq_len[b] = tokens cached BEFORE this step.
+//   FUSED = false: q [B, Hq, 2, 128] fp16 (hi | lo per head) is given and the step's own key/value has already been
+//     appended, so seq_len[b] + 1 tokens are read from the cache.
+//   FUSED = true: the kernel starts from the QKV projection's split-K partial sums (qkv_part[s][b][qkv_w], s < nsplit):
+//     it adds them, rotates q and k by the position, writes the new key/value into the cache page for later steps,
+//     attends over the seq_len[b] cached tokens from HBM and folds the new token in from LDS at the merge.  This
+//     removes the separate RoPE/append kernel from the decode step.
+struct FusedArgs {
+  const float* qkv_part;
+  int nsplit;
+  size_t part_stride;
+  int qkv_w;
+  const float* cos_t;
+  const float* sin_t;
+};
+
+template <bool FUSED>
+__global__ __launch_bounds__(256) void attn_decode_kernel(const h16_t* __restrict__ q, char* __restrict__ pool,
                                                           const int* __restrict__ block_table, int max_blocks, int n_blocks,
                                                           const int* __restrict__ seq_len, h16_t* __restrict__ out,
-                                                          int Hq, int Hkv, float scale_log2) {
+                                                          int Hq, int Hkv, float scale_log2, FusedArgs fa) {
   __shared__ float m_s[4][16];
   __shared__ float l_s[4][16];
   __shared__ float o_s[4][16][132];
+  __shared__ __attribute__((aligned(16))) h16_t q_s[FUSED ? 16 : 1][256];  // [row][hi 128 | lo 128]
+  __shared__ h16_t kn_s[FUSED ? 128 : 1], vn_s[FUSED ? 128 : 1];
+  __shared__ float snew_s[16];
   const int kvh = blockIdx.x, b = blockIdx.y;
   const int group = Hq / Hkv;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, t = lane & 15, g = lane >> 4;
-  const int L = seq_len[b] + 1;
+  const int pos = seq_len[b];                  // position of the step's token = tokens already cached
+  const int L = FUSED ? pos : pos + 1;         // tokens read from the cache
   const int npages = (L + 15) >> 4;
+  const int* bt = block_table + (size_t)b * max_blocks;
   uint4 qf[8];
+  // block-table entries of this wavefront's first 64 pages and its first page: issued before anything else
+  const int last = npages - 1;
+  const int my_blk0 = npages > 0 ? bt[min(w + 4 * lane, last)] : 0;
+  uint4 ka[4], va[4], kb[4], vb[4];
+  load_page(pool + ((size_t)kvh * n_blocks + __shfl(my_blk0, 0)) * KV_PAGE_BYTES, lane, ka, va);
+  if (FUSED) {
+    const float* row = fa.qkv_part + (size_t)b * fa.qkv_w;
+    const float* cs = fa.cos_t + (size_t)pos * 64;
+    const float* sn = fa.sin_t + (size_t)pos * 64;
+    char* page = pool + ((size_t)kvh * n_blocks + bt[pos >> 4]) * KV_PAGE_BYTES;
+    const int slot = pos & 15;
+    // tasks: (group + 2) vectors of 128 (the group's query heads, the key, the value), 64 dimension pairs each
+    for (int task = threadIdx.x; task < (group + 2) * 64; task += 256) {
+      const int vec = task >> 6, i = task & 63;
+      int col;  // column of dimension i of this vector in the fused qkv row
+      if (vec < group) col = (kvh * group + vec) * 128 + i;
+      else if (vec == group) col = (Hq + kvh) * 128 + i;
+      else col = (Hq + Hkv + kvh) * 128 + i;
+      // up to 8 partial sums, all loads in flight at once, added in split order
+      float av[8], bv[8];
 #pragma unroll
-  for (int kk = 0; kk < 8; ++kk) {
-    qf[kk] = make_uint4(0, 0, 0, 0);
-    if (t < group)
-      qf[kk] = *(const uint4*)(q + ((size_t)b * Hq + kvh * group + t) * 256 + (kk >> 2) * 128 + 8 * (4 * (kk & 3) + g));
+      for (int s8 = 0; s8 < 8; ++s8) {
+        const size_t so = (size_t)min(s8, fa.nsplit - 1) * fa.part_stride;
+        av[s8] = row[so + col];
+        bv[s8] = row[so + col + 64];
+      }
+      float a = 0.f, bb = 0.f;
+#pragma unroll
+      for (int s8 = 0; s8 < 8; ++s8)
+        if (s8 < fa.nsplit) { a += av[s8]; bb += bv[s8]; }
+      if (vec <= group) {  // queries and the key are rotated
+        const float c = cs[i], sv = sn[i];
+        const float r0 = a * c - bb * sv, r1 = bb * c + a * sv;
+        a = r0;
+        bb = r1;
+      }
+      if (vec < group) {
+        split_h16(a, q_s[vec][i], q_s[vec][128 + i]);
+        split_h16(bb, q_s[vec][i + 64], q_s[vec][128 + i + 64]);
+      } else if (vec == group) {
+        const h16_t k0 = f32_to_h16(a), k1 = f32_to_h16(bb);
+        kn_s[i] = k0;
+        kn_s[i + 64] = k1;
+        *(h16_t*)(page + kpage_offset(slot, i)) = k0;
+        *(h16_t*)(page + kpage_offset(slot, i + 64)) = k1;
+      } else {
+        const h16_t v0 = f32_to_h16(a), v1 = f32_to_h16(bb);
+        vn_s[i] = v0;
+        vn_s[i + 64] = v1;
+        *(h16_t*)(page + vpage_offset(slot, i)) = v0;
+        *(h16_t*)(page + vpage_offset(slot, i + 64)) = v1;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      qf[kk] = make_uint4(0, 0, 0, 0);
+      if (t < group) qf[kk] = *(const uint4*)(&q_s[t][(kk >> 2) * 128 + 8 * (4 * (kk & 3) + g)]);
+    }
+    // score of the new token against each query row (same fp16 values a later step will read from the cache)
+    for (int r = w; r < group; r += 4) {
+      float acc = 0.f;
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int d = 2 * lane + e;
+        acc += (h16_to_f32(q_s[r][d]) + h16_to_f32(q_s[r][128 + d])) * h16_to_f32(kn_s[d]);
+      }
+      acc = wave_sum(acc);
+      if (lane == 0) snew_s[r] = acc * scale_log2;
+    }
+  } else {
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      qf[kk] = make_uint4(0, 0, 0, 0);
+      if (t < group)
+        qf[kk] = *(const uint4*)(q + ((size_t)b * Hq + kvh * group + t) * 256 + (kk >> 2) * 128 + 8 * (4 * (kk & 3) + g));
+    }
   }
   AttnState st;
   init_state(st);
-  const int* bt = block_table + (size_t)b * max_blocks;
   // This wavefront takes pages w, w + 4, w + 8, ...  Their block-table entries are fetched up front, 64 at a time
   // (lane i holds the entry of page w + 4 i), and broadcast from registers inside the loop.  Page loads are issued
   // with no branch around them (an index past the end re-reads the last page), so that the loads of the next page
   // stay in flight while the current one is consumed.
-  const int last = npages - 1;
   for (int base = w; base < npages; base += 256) {
-    const int mine = min(base + 4 * lane, last);
-    const int my_blk = bt[mine];
+    int my_blk = my_blk0;
+    if (base != w) {  // beyond 4096 tokens: next batch of 64 pages
+      my_blk = bt[min(base + 4 * lane, last)];
+      load_page(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, 0)) * KV_PAGE_BYTES, lane, ka, va);
+    }
     const int cnt = min(64, (npages - base + 3) >> 2);  // pages of this wavefront in this batch
-    uint4 ka[4], va[4], kb[4], vb[4];
-    load_page(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, 0)) * KV_PAGE_BYTES, lane, ka, va);
     int i = 0;
     for (; i + 2 <= cnt; i += 2) {
       load_page(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, i + 1)) * KV_PAGE_BYTES, lane, kb, vb);
@@ -145,6 +236,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const h16_t* __restric
   for (int idx = threadIdx.x; idx < group * 128; idx += 256) {
     int r = idx >> 7, dim = idx & 127;
     float M = fmaxf(fmaxf(m_s[0][r], m_s[1][r]), fmaxf(m_s[2][r], m_s[3][r]));
+    if (FUSED) M = fmaxf(M, snew_s[r]);
     float num = 0.f, den = 0.f;
 #pragma unroll
     for (int ww = 0; ww < 4; ++ww) {
@@ -152,6 +244,11 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const h16_t* __restric
       float a = (mw == -INFINITY) ? 0.f : exp2f(mw - M);
       num += a * o_s[ww][r][dim];
       den += a * l_s[ww][r];
+    }
+    if (FUSED) {  // the new token: weight exp2(s_new - M), value from LDS
+      float a = exp2f(snew_s[r] - M);
+      num += a * h16_to_f32(vn_s[dim]);
+      den += a;
     }
     h16_t* orow = out + (size_t)b * 2 * Hq * 128 + (kvh * group + r) * 128 + dim;
     split_h16(num / den, orow[0], orow[Hq * 128]);
@@ -267,8 +364,22 @@ hipError_t launch_attn_decode_h16(hipStream_t s, const void* q, const void* kv_p
   if (B <= 0) return hipSuccess;
   if (Hq % Hkv || Hq / Hkv > 16) return hipErrorInvalidValue;
   float scale_log2 = LOG2E / sqrtf((float)KV_HEAD_DIM);
-  attn_decode_kernel<<<dim3(Hkv, B), 256, 0, s>>>((const h16_t*)q, (const char*)kv_pool_layer, block_table, max_blocks,
-                                                  n_blocks, seq_len, (h16_t*)out, Hq, Hkv, scale_log2);
+  FusedArgs fa{};
+  attn_decode_kernel<false><<<dim3(Hkv, B), 256, 0, s>>>((const h16_t*)q, (char*)const_cast<void*>(kv_pool_layer), block_table,
+                                                         max_blocks, n_blocks, seq_len, (h16_t*)out, Hq, Hkv, scale_log2, fa);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_decode_fused_h16(hipStream_t s, const float* qkv_part, int nsplit, size_t part_stride,
+                                        const float* cos_t, const float* sin_t, void* kv_pool_layer,
+                                        const int* block_table, int max_blocks, int n_blocks, const int* seq_len, void* out,
+                                        int B, int Hq, int Hkv) {
+  if (B <= 0) return hipSuccess;
+  if (Hq % Hkv || Hq / Hkv > 16 || nsplit < 1 || nsplit > 8) return hipErrorInvalidValue;
+  float scale_log2 = LOG2E / sqrtf((float)KV_HEAD_DIM);
+  FusedArgs fa{qkv_part, nsplit, part_stride, (Hq + 2 * Hkv) * KV_HEAD_DIM, cos_t, sin_t};
+  attn_decode_kernel<true><<<dim3(Hkv, B), 256, 0, s>>>(nullptr, (char*)kv_pool_layer, block_table, max_blocks, n_blocks,
+                                                        seq_len, (h16_t*)out, Hq, Hkv, scale_log2, fa);
   return hipGetLastError();
 }
 

@@ -56,6 +56,12 @@ hipError_t launch_bf16_to_h16(hipStream_t s, const void* src, void* dst, size_t 
 // ---- attention over the paged cache (16-bit mode: q [rows, Hq, 2, 128] hi|lo pairs, out [rows, 2, Hq*128] hi|lo) ----
 hipError_t launch_attn_decode_h16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
                                    int max_blocks, int n_blocks, const int* seq_len, void* out, int B, int Hq, int Hkv);
+// Decode attention that starts from the QKV projection's partial sums: adds them, applies RoPE, appends the new
+// key/value to the cache and attends (no separate rope_append launch).
+hipError_t launch_attn_decode_fused_h16(hipStream_t s, const float* qkv_part, int nsplit, size_t part_stride,
+                                        const float* cos_t, const float* sin_t, void* kv_pool_layer,
+                                        const int* block_table, int max_blocks, int n_blocks, const int* seq_len, void* out,
+                                        int B, int Hq, int Hkv);
 hipError_t launch_attn_prefill_h16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
                                     int max_blocks, int n_blocks, const int* cu_seqlens, const int* seq_ids, void* out, int nseq,
                                     int max_len, int Hq, int Hkv);

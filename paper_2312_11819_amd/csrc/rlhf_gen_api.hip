@@ -270,12 +270,17 @@ int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
     LAUNCH(c, launch_gemm_skinny_h16(s, c->y, c->wqkv[l], c->part, B, qkv_w, d, c->ks_qkv, 1), "gemm_skinny qkv");
     prof_mark(c, RLHF_GEN_PROF_GEMM_QKV);
     size_t st = (size_t)B * qkv_w;
-    LAUNCH(c, launch_rope_append(s, c->part, c->ks_qkv > 1 ? c->part + st : nullptr, c->ks_qkv - 1, st, c->d_seq_len,
-                                 nullptr, c->d_cos, c->d_sin, c->qb, pool, c->d_table, c->max_blocks, c->n_blocks, B, Hq, Hkv, h, 1),
-           "rope_append");
-    prof_mark(c, RLHF_GEN_PROF_ROPE);
-    LAUNCH(c, launch_attn_decode_h16(s, c->qb, pool, c->d_table, c->max_blocks, c->n_blocks, c->d_seq_len, c->ab, B, Hq, Hkv),
-           "attn_decode");
+    if (!(c->cfg.flags & RLHF_GEN_FLAG_FUSED_ROPE)) {
+      LAUNCH(c, launch_rope_append(s, c->part, c->ks_qkv > 1 ? c->part + st : nullptr, c->ks_qkv - 1, st, c->d_seq_len,
+                                   nullptr, c->d_cos, c->d_sin, c->qb, pool, c->d_table, c->max_blocks, c->n_blocks, B, Hq,
+                                   Hkv, h, 1), "rope_append");
+      prof_mark(c, RLHF_GEN_PROF_ROPE);
+      LAUNCH(c, launch_attn_decode_h16(s, c->qb, pool, c->d_table, c->max_blocks, c->n_blocks, c->d_seq_len, c->ab, B, Hq,
+                                       Hkv), "attn_decode");
+    } else {
+      LAUNCH(c, launch_attn_decode_fused_h16(s, c->part, c->ks_qkv, st, c->d_cos, c->d_sin, pool, c->d_table, c->max_blocks,
+                                             c->n_blocks, c->d_seq_len, c->ab, B, Hq, Hkv), "attn_decode_fused");
+    }
     prof_mark(c, RLHF_GEN_PROF_ATTN);
     LAUNCH(c, launch_gemm_skinny_h16(s, c->ab, c->wo[l], c->part, B, d, Hq * h, c->ks_wo, 1), "gemm_skinny wo");
     prof_mark(c, RLHF_GEN_PROF_GEMM_WO);

@@ -106,7 +106,8 @@ def test_tiny_fp32_ragged_sampling(B, shape_name, flags):
     assert frac < 0.1
 
 
-@pytest.mark.parametrize("shape,flags", [(BF16_SMALL, 0), (BF16_SMALL, 4), (BF16_SMALL_GQA, 1), (BF16_SMALL_GQA, 4 | 2)])
+@pytest.mark.parametrize("shape,flags", [(BF16_SMALL, 0), (BF16_SMALL, 4), (BF16_SMALL_GQA, 1), (BF16_SMALL_GQA, 4 | 2),
+                                         (BF16_SMALL, 16), (BF16_SMALL_GQA, 16 | 2)])
 def test_small_bf16_teacher_forced(B, shape, flags):
     w = synth.make_weights(shape, 5, "bf16")
     synth.randomize_norm_gains(w, 6)
