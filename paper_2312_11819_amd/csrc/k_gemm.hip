@@ -16,9 +16,10 @@ namespace {
 // Large-tile GEMM: the operand tiles go from global memory straight into LDS (LDS-DMA loads, no staging
 // registers), 256x256x64 block tile, two LDS stages of 64 KB, 8 wavefronts of 128x64, 32x32x16 MFMA.
 //   * A wavefront-wide DMA load writes lane i's 16 bytes to LDS base + 16 i, so one instruction fills eight
-//     128-byte tile rows.  To keep the later 16-byte MFMA operand reads free of bank conflicts the 16-byte chunk
-//     c of row r is stored at slot c ^ (r & 7); the permutation is applied on the global side (lane i fetches
-//     chunk (i & 7) ^ (i >> 3) of its row), so global reads stay whole 128-byte rows.
+//     128-byte tile rows.  To keep the later 16-byte MFMA operand reads free of bank conflicts (64 banks: sixteen
+//     lanes, i.e. sixteen consecutive rows, are served per cycle and must cover 256 distinct bytes) the 16-byte
+//     chunk c of row r is stored at slot c ^ ((r >> 1) & 7); the permutation is applied on the global side (each
+//     lane fetches the chunk that belongs in its slot), so global reads stay whole 128-byte rows.
 //   * The compiler would wait for every outstanding DMA load before any LDS read it knows about, which would
 //     serialise the pipeline, so the operand reads are issued as inline ds_read_b128 and their completion is
 //     awaited explicitly (s_waitcnt lgkmcnt), two k-steps of fragments in flight.
@@ -73,7 +74,7 @@ __global__ __launch_bounds__(512) void gemm_h16_dma_kernel(const h16_t* __restri
   for (int it = 0; it < 8; ++it) {
     int row = 8 * ((wave & 3) * 8 + it) + (lane >> 3);
     int grow = loads_a ? min(m0 + row, M - 1) : wrow(row);
-    go[it] = (uint32_t)grow * (uint32_t)(loads_a && a_dual ? 2 * K : K) * 2u + (uint32_t)(((lane & 7) ^ (lane >> 3)) * 16);
+    go[it] = (uint32_t)grow * (uint32_t)(loads_a && a_dual ? 2 * K : K) * 2u + (uint32_t)(((lane & 7) ^ ((row >> 1) & 7)) * 16);
   }
   const int nkw = K / 64;                       // k-tiles of W
   const int nk = a_dual ? 2 * nkw : nkw;        // k-tiles of the product
@@ -96,9 +97,9 @@ __global__ __launch_bounds__(512) void gemm_h16_dma_kernel(const h16_t* __restri
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  // operand read addresses: row (lane & 31) of a 32-row block, chunk 2 ks + (lane >> 5), stored at slot chunk ^ (row & 7)
+  // operand read addresses: row (lane & 31) of a 32-row block, chunk 2 ks + (lane >> 5), stored at slot chunk ^ ((row >> 1) & 7)
   const uint32_t lds0 = (uint32_t)(size_t)smem;
-  const uint32_t y = (uint32_t)((lane >> 5) ^ (lane & 7));
+  const uint32_t y = (uint32_t)((lane >> 5) ^ ((lane >> 1) & 7));
   uint32_t a_rd[4], b_rd[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {

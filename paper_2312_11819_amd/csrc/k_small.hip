@@ -109,6 +109,14 @@ __global__ __launch_bounds__(NT) void rmsnorm_kernel(float* __restrict__ x, cons
       if (nsplit > 0) {
         const float* pp = part + (size_t)m * d + i;
         int sidx = 0;
+        if (nsplit == 8) {  // the usual split count: eight independent loads in flight, added in order
+          float4 pv[8];
+#pragma unroll
+          for (int s8 = 0; s8 < 8; ++s8) pv[s8] = *(const float4*)(pp + (size_t)s8 * part_stride);
+#pragma unroll
+          for (int s8 = 0; s8 < 8; ++s8) { a.x += pv[s8].x; a.y += pv[s8].y; a.z += pv[s8].z; a.w += pv[s8].w; }
+          sidx = 8;
+        }
         for (; sidx + 4 <= nsplit; sidx += 4) {  // four independent loads in flight, added in order
           float4 p0 = *(const float4*)(pp + (size_t)(sidx + 0) * part_stride);
           float4 p1 = *(const float4*)(pp + (size_t)(sidx + 1) * part_stride);
@@ -214,9 +222,22 @@ __global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict
   if (head < Hq + Hkv) {
     for (int i = threadIdx.x; i < half; i += 64) {
       float a = row[i], bb = row[i + half];
-      for (int sidx = 0; sidx < nsplit; ++sidx) {
-        a += prow[sidx * part_stride + i];
-        bb += prow[sidx * part_stride + i + half];
+      {
+        // up to 8 further partial sums with all loads in flight at once, added in split order
+        float av[8], bv[8];
+#pragma unroll
+        for (int s8 = 0; s8 < 8; ++s8) {
+          const size_t so = (size_t)min(s8, max(nsplit - 1, 0)) * part_stride;
+          av[s8] = prow[so + i];
+          bv[s8] = prow[so + i + half];
+        }
+#pragma unroll
+        for (int s8 = 0; s8 < 8; ++s8)
+          if (s8 < nsplit) { a += av[s8]; bb += bv[s8]; }
+        for (int sidx = 8; sidx < nsplit; ++sidx) {
+          a += prow[sidx * part_stride + i];
+          bb += prow[sidx * part_stride + i + half];
+        }
       }
       float c = cos_t[(size_t)pos * half + i], sv = sin_t[(size_t)pos * half + i];
       float r0 = a * c - bb * sv, r1 = bb * c + a * sv;
@@ -247,7 +268,15 @@ __global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict
     const int kvh = head - Hq - Hkv;
     for (int dim = threadIdx.x; dim < h; dim += 64) {
       float v = row[dim];
-      for (int sidx = 0; sidx < nsplit; ++sidx) v += prow[sidx * part_stride + dim];
+      {
+        float vv[8];
+#pragma unroll
+        for (int s8 = 0; s8 < 8; ++s8) vv[s8] = prow[(size_t)min(s8, max(nsplit - 1, 0)) * part_stride + dim];
+#pragma unroll
+        for (int s8 = 0; s8 < 8; ++s8)
+          if (s8 < nsplit) v += vv[s8];
+        for (int sidx = 8; sidx < nsplit; ++sidx) v += prow[sidx * part_stride + dim];
+      }
       if (A16) {
         char* page = (char*)pool + ((size_t)kvh * n_blocks + blk) * KV_PAGE_BYTES;
         *(h16_t*)(page + vpage_offset(slot, dim)) = f32_to_h16(v);
