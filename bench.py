@@ -155,6 +155,18 @@ def main() -> int:
         score = {"ms": dt * 1e3, "scored_tokens_per_s": B * R / dt, "mfma_bf16_frac": sflop / dt / MFMA_BF16_PEAK,
                  "max_abs_diff_vs_rollout_logprobs": float((sc - out_lp).abs().max())}
 
+    # weight refresh of the shadow Actor (the parameter synchronisation of Alg. 2), outside the timed region:
+    # every projection matrix and the LM head is read as bf16 and rewritten as fp16
+    refresh = None
+    if wl.dtype == "bf16" and not args.no_score and not (args.flags & 8):   # in place, the sources no longer hold bf16
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ctx.rlhf_gen_update_weights(ctx._weights)
+        ctx.synchronize()
+        dt = time.perf_counter() - t1
+        moved = 2 * (wb - (2 * shape.n_layers + 1) * shape.d_model * 2)
+        refresh = {"ms": dt * 1e3, "GBps_read_plus_write": moved / dt / 1e9}
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(wl if not args.layers else synth.dataclasses.replace(wl, shape=shape), w, toks, lens)
@@ -173,6 +185,7 @@ def main() -> int:
         "roofline": roofline,
         "kernels_sampled": kernels,
         "score_pass": score,
+        "weight_refresh": refresh,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))

@@ -157,6 +157,37 @@ int rlhf_gen_generate(rlhf_gen_ctx* ctx, const int32_t* query_tokens, const int3
 int rlhf_gen_score(rlhf_gen_ctx* ctx, const int32_t* query_tokens, const int32_t* lengths, int32_t B, int32_t Lmax,
                    const int32_t* resp_tokens, int32_t R, float* logprobs_out);
 
+/* Low-rank adapters to fold into the weights at a refresh (the paper trains the Actor with LoRA adapters of
+ * dimension 4, Sec. V-A "Hyperparameters"): the effective matrix is W + scale * B A. */
+typedef struct {
+  const void* a;  /* device bf16 [rank, in_features]; NULL = no adapter on this matrix */
+  const void* b;  /* device bf16 [out_features, rank] */
+  int32_t rank;   /* 1..64 (an adapter on a fused matrix such as wqkv stacks its parts: rank = sum of their ranks) */
+} rlhf_gen_lora_pair;
+typedef struct {
+  float scale;                          /* alpha / rank of the usual parametrisation */
+  const rlhf_gen_lora_pair* wqkv;       /* HOST arrays of n_layers entries, or NULL for "none on these matrices" */
+  const rlhf_gen_lora_pair* wo;
+  const rlhf_gen_lora_pair* w_gate_up;
+  const rlhf_gen_lora_pair* w_down;
+  rlhf_gen_lora_pair lm_head;
+} rlhf_gen_lora;
+
+/* Refresh the replica's weights from the trainer's current ones - the periodic parameter synchronisation of the
+ * shadow Actor in Alg. 2 (parameters of the shadow models are synchronised with the training models after each round of PPO training, Sec. IV-A, Disaggregated strategy) - without
+ * allocating.  weights has the meaning it has in rlhf_gen_init (same shapes and dtype; the pointers may be the ones
+ * given at init, whose contents the caller has overwritten, or other buffers).  bf16 mode: every projection matrix
+ * and the LM head is converted again into the fp16 working copies made at init (with
+ * RLHF_GEN_FLAG_CONVERT_IN_PLACE: rewritten in place, so the buffers must hold bf16 again when this is called), and
+ * where lora names an adapter the update W + scale * B A is formed in fp32 on the way (one rounding to fp16).
+ * lora may be NULL.  fp32 mode: the pointers are adopted; adapters are E_UNSUPPORTED there.
+ * The work is enqueued on cfg.stream; the sources may be reused once it has completed.  The batch held by the context
+ * is dropped (its KV cache belongs to the old weights): the next call must be prefill, generate or score.  A
+ * captured decode graph stays valid unless an address the kernels read directly changed (token embedding, norm gains,
+ * any matrix in fp32 or in-place mode); then it is recorded again by the next rlhf_gen_generate.
+ * Errors: E_INVALID (NULL pointers, rank out of range), E_UNSUPPORTED, E_DEVICE. */
+int rlhf_gen_update_weights(rlhf_gen_ctx* ctx, const rlhf_gen_weights* weights, const rlhf_gen_lora* lora);
+
 /* Copy the fp32 logits [B, vocab] that the last prefill/decode step sampled from into a device
  * buffer (parity checks).  E_STATE if no step has run. */
 int rlhf_gen_get_logits(rlhf_gen_ctx* ctx, float* out);

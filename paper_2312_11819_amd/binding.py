@@ -27,7 +27,8 @@ PROF_CLASSES = ["embed", "norm", "gemm_qkv", "rope_append", "attn_decode", "gemm
                 "gemm_down", "lm_head", "sampler"]
 
 EXPORTS = [
-    "rlhf_gen_init", "rlhf_gen_prefill", "rlhf_gen_decode_step", "rlhf_gen_generate", "rlhf_gen_score", "rlhf_gen_get_logits",
+    "rlhf_gen_init", "rlhf_gen_prefill", "rlhf_gen_decode_step", "rlhf_gen_generate", "rlhf_gen_score", "rlhf_gen_update_weights",
+    "rlhf_gen_get_logits",
     "rlhf_gen_last_timing", "rlhf_gen_set_profile", "rlhf_gen_get_profile", "rlhf_gen_last_error", "rlhf_gen_destroy",
     "rlhf_gen_op_gemm", "rlhf_gen_op_rope_append", "rlhf_gen_op_attn_decode", "rlhf_gen_op_attn_prefill",
     "rlhf_gen_op_sample",
@@ -46,6 +47,15 @@ class Weights(C.Structure):
                 ("attn_norm", C.POINTER(C.c_void_p)), ("wqkv", C.POINTER(C.c_void_p)), ("wo", C.POINTER(C.c_void_p)),
                 ("ffn_norm", C.POINTER(C.c_void_p)), ("w_gate_up", C.POINTER(C.c_void_p)),
                 ("w_down", C.POINTER(C.c_void_p))]
+
+
+class LoraPair(C.Structure):
+    _fields_ = [("a", C.c_void_p), ("b", C.c_void_p), ("rank", C.c_int32)]
+
+
+class Lora(C.Structure):
+    _fields_ = [("scale", C.c_float), ("wqkv", C.POINTER(LoraPair)), ("wo", C.POINTER(LoraPair)),
+                ("w_gate_up", C.POINTER(LoraPair)), ("w_down", C.POINTER(LoraPair)), ("lm_head", LoraPair)]
 
 
 class Sampling(C.Structure):
@@ -78,6 +88,7 @@ def lib() -> C.CDLL:
                                         C.POINTER(Sampling), C.c_void_p, C.c_void_p]
         L.rlhf_gen_score.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_void_p,
                                      C.c_int32, C.c_void_p]
+        L.rlhf_gen_update_weights.argtypes = [C.c_void_p, C.POINTER(Weights), C.POINTER(Lora)]
         L.rlhf_gen_get_logits.argtypes = [C.c_void_p, C.c_void_p]
         L.rlhf_gen_last_timing.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_int32)]
         L.rlhf_gen_set_profile.argtypes = [C.c_void_p, C.c_int32]
@@ -126,13 +137,7 @@ class Context:
         L = lib()
         self.shape, self.dtype, self.device = shape, dtype, torch.device("cuda", device)
         self.stream = stream if stream is not None else torch.cuda.Stream(device=self.device)
-        self._weights = weights  # borrowed by the library: keep alive
-        n = shape.n_layers
-        arr = lambda key: (C.c_void_p * n)(*[_ptr(lw[key]) for lw in weights["layers"]])
-        self._arrs = {k: arr(k) for k in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")}
-        w = Weights(_ptr(weights["tok_emb"]), _ptr(weights["lm_head"]), _ptr(weights["final_norm"]),
-                    *[C.cast(self._arrs[k], C.POINTER(C.c_void_p)) for k in
-                      ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")])
+        w = self._marshal_weights(weights)
         cfg = Cfg(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
                   shape.vocab, shape.rms_eps, shape.rope_theta, DTYPE_BF16 if dtype == "bf16" else DTYPE_FP32,
                   max_batch, max_seq, 16, kv_pool_blocks, device, self.stream.cuda_stream, flags)
@@ -143,7 +148,42 @@ class Context:
         self._h = h
         self.B = 0
 
+    def _marshal_weights(self, weights: dict) -> Weights:
+        self._weights = weights  # borrowed by the library: keep alive
+        n = self.shape.n_layers
+        arr = lambda key: (C.c_void_p * n)(*[_ptr(lw[key]) for lw in weights["layers"]])
+        self._arrs = {k: arr(k) for k in ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")}
+        return Weights(_ptr(weights["tok_emb"]), _ptr(weights["lm_head"]), _ptr(weights["final_norm"]),
+                       *[C.cast(self._arrs[k], C.POINTER(C.c_void_p)) for k in
+                         ("attn_norm", "wqkv", "wo", "ffn_norm", "w_gate_up", "w_down")])
+
     # -- the C entry points ------------------------------------------------------------------
+    def rlhf_gen_update_weights(self, weights: dict, lora: Optional[dict] = None) -> None:
+        """weights as for the constructor.  lora: {"scale": s, "layers": [{"wqkv": (A, B), ...}, ...], "lm_head": (A, B)}
+        with any entry optional; A is [rank, in], B is [out, rank]."""
+        w = self._marshal_weights(weights)
+        lp = None
+        if lora is not None:
+            n = self.shape.n_layers
+            self._lora = lora  # keep the adapter tensors alive until the conversion has run
+            def pairs(key):
+                arr = (LoraPair * n)()
+                for l, lw in enumerate(lora.get("layers", [{}] * n)):
+                    if lw.get(key) is not None:
+                        a, b = lw[key]
+                        arr[l] = LoraPair(_ptr(a), _ptr(b), a.shape[0])
+                return arr
+            self._lora_arrs = {k: pairs(k) for k in ("wqkv", "wo", "w_gate_up", "w_down")}
+            head = LoraPair()
+            if lora.get("lm_head") is not None:
+                a, b = lora["lm_head"]
+                head = LoraPair(_ptr(a), _ptr(b), a.shape[0])
+            lp = Lora(float(lora.get("scale", 1.0)), *[C.cast(self._lora_arrs[k], C.POINTER(LoraPair)) for k in
+                                                        ("wqkv", "wo", "w_gate_up", "w_down")], head)
+        self.stream.wait_stream(torch.cuda.current_stream(self.device))
+        _check(self._h, lib().rlhf_gen_update_weights(self._h, C.byref(w), C.byref(lp) if lp is not None else None))
+        self.B = 0
+
     def rlhf_gen_prefill(self, query_tokens: torch.Tensor, lengths: Sequence[int], sampling: Sampling):
         B, Lmax = query_tokens.shape
         lens = (C.c_int32 * B)(*[int(x) for x in lengths])

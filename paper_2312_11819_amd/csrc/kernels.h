@@ -50,6 +50,9 @@ hipError_t launch_swiglu(hipStream_t s, const float* gu, int nsplit, size_t part
 hipError_t launch_advance(hipStream_t s, int* seq_len, int* step, int B);
 // bf16 -> fp16 copy of n elements (working copies of the weight matrices).
 hipError_t launch_bf16_to_h16(hipStream_t s, const void* src, void* dst, size_t n);
+// dst = fp16(src + scale * B A): src/dst [rows, cols] (may alias), A bf16 [rank, cols], B bf16 [rows, rank]
+hipError_t launch_bf16_lora_to_h16(hipStream_t s, const void* src, void* dst, int rows, int cols, const void* A,
+                                   const void* B, int rank, float scale);
 
 // One layer's pool is [Hkv][n_blocks] pages: the pages a sequence gets from consecutive block ids are contiguous per
 // KV head, so a workgroup streams one contiguous region and different workgroups spread over the memory channels.

@@ -981,6 +981,81 @@ int rlhf_gen_get_profile(const rlhf_gen_ctx* c, double* ms, int64_t* launches, i
 
 const char* rlhf_gen_last_error(const rlhf_gen_ctx* c) { return c ? c->err.c_str() : g_init_error.c_str(); }
 
+int rlhf_gen_update_weights(rlhf_gen_ctx* c, const rlhf_gen_weights* w, const rlhf_gen_lora* lora) {
+  if (!c) return RLHF_GEN_E_INVALID;
+  if (!w) return fail(c, RLHF_GEN_E_INVALID, "NULL weights");
+  const rlhf_gen_cfg& g = c->cfg;
+  if (!w->tok_emb || !w->lm_head || !w->final_norm || !w->attn_norm || !w->wqkv || !w->wo || !w->ffn_norm ||
+      !w->w_gate_up || !w->w_down)
+    return fail(c, RLHF_GEN_E_INVALID, "NULL weight pointer");
+  for (int l = 0; l < g.n_layers; ++l)
+    if (!w->attn_norm[l] || !w->wqkv[l] || !w->wo[l] || !w->ffn_norm[l] || !w->w_gate_up[l] || !w->w_down[l])
+      return fail(c, RLHF_GEN_E_INVALID, "NULL weight pointer in layer %d", l);
+  // adapters: validate everything before the first kernel is enqueued
+  auto pair_of = [&](const rlhf_gen_lora_pair* arr, int l) -> const rlhf_gen_lora_pair* {
+    return (lora && arr && arr[l].a) ? &arr[l] : nullptr;
+  };
+  bool any_lora = false;
+  if (lora) {
+    const rlhf_gen_lora_pair* arrs[4] = {lora->wqkv, lora->wo, lora->w_gate_up, lora->w_down};
+    for (int l = 0; l <= g.n_layers; ++l)
+      for (int m = 0; m < (l < g.n_layers ? 4 : 1); ++m) {
+        const rlhf_gen_lora_pair* pr = l < g.n_layers ? pair_of(arrs[m], l) : (lora->lm_head.a ? &lora->lm_head : nullptr);
+        if (!pr) continue;
+        if (!pr->b) return fail(c, RLHF_GEN_E_INVALID, "adapter with A but no B");
+        if (pr->rank < 1 || pr->rank > 64) return fail(c, RLHF_GEN_E_INVALID, "adapter rank must be in 1..64 (got %d)", pr->rank);
+        any_lora = true;
+      }
+    if (any_lora && !(lora->scale == lora->scale)) return fail(c, RLHF_GEN_E_INVALID, "adapter scale is NaN");
+  }
+  if (any_lora && !c->bf16)
+    return fail(c, RLHF_GEN_E_UNSUPPORTED, "the fp32 path reads the caller's matrices in place and cannot fold adapters");
+  HIP_TRY(c, hipSetDevice(g.device));
+
+  bool moved = c->tok_emb != w->tok_emb || c->final_norm != w->final_norm;
+  for (int l = 0; l < g.n_layers; ++l) moved = moved || c->attn_norm[l] != w->attn_norm[l] || c->ffn_norm[l] != w->ffn_norm[l];
+  const int qkv_w = (g.n_heads + 2 * g.n_kv_heads) * g.head_dim;
+  if (c->bf16) {
+    const bool in_place = (g.flags & RLHF_GEN_FLAG_CONVERT_IN_PLACE) != 0;
+    auto refresh = [&](const void* src, const void** work, int rows, int cols, const rlhf_gen_lora_pair* pr) -> int {
+      void* dst = in_place ? const_cast<void*>(src) : const_cast<void*>(*work);
+      hipError_t e = pr ? launch_bf16_lora_to_h16(c->stream, src, dst, rows, cols, pr->a, pr->b, pr->rank, lora->scale)
+                        : launch_bf16_to_h16(c->stream, src, dst, (size_t)rows * cols);
+      if (e != hipSuccess) return fail(c, RLHF_GEN_E_DEVICE, "weight conversion kernel failed: %s", hipGetErrorString(e));
+      if (*work != dst) moved = true;
+      *work = dst;
+      return RLHF_GEN_OK;
+    };
+    int rc;
+    for (int l = 0; l < g.n_layers; ++l) {
+      if ((rc = refresh(w->wqkv[l], &c->wqkv[l], qkv_w, g.d_model, pair_of(lora ? lora->wqkv : nullptr, l)))) return rc;
+      if ((rc = refresh(w->wo[l], &c->wo[l], g.d_model, g.n_heads * g.head_dim, pair_of(lora ? lora->wo : nullptr, l)))) return rc;
+      if ((rc = refresh(w->w_gate_up[l], &c->w_gate_up[l], 2 * g.d_ffn, g.d_model, pair_of(lora ? lora->w_gate_up : nullptr, l)))) return rc;
+      if ((rc = refresh(w->w_down[l], &c->w_down[l], g.d_model, g.d_ffn, pair_of(lora ? lora->w_down : nullptr, l)))) return rc;
+      c->src_wqkv[l] = w->wqkv[l]; c->src_wo[l] = w->wo[l]; c->src_w_gate_up[l] = w->w_gate_up[l]; c->src_w_down[l] = w->w_down[l];
+    }
+    if ((rc = refresh(w->lm_head, &c->lm_head, g.vocab, g.d_model, (lora && lora->lm_head.a) ? &lora->lm_head : nullptr))) return rc;
+    c->src_lm_head = w->lm_head;
+  } else {
+    moved = moved || c->lm_head != w->lm_head;
+    for (int l = 0; l < g.n_layers; ++l) {
+      moved = moved || c->wqkv[l] != w->wqkv[l] || c->wo[l] != w->wo[l] || c->w_gate_up[l] != w->w_gate_up[l] ||
+              c->w_down[l] != w->w_down[l];
+      c->wqkv[l] = w->wqkv[l]; c->wo[l] = w->wo[l]; c->w_gate_up[l] = w->w_gate_up[l]; c->w_down[l] = w->w_down[l];
+    }
+    c->lm_head = w->lm_head;
+  }
+  c->tok_emb = w->tok_emb;
+  c->final_norm = w->final_norm;
+  for (int l = 0; l < g.n_layers; ++l) { c->attn_norm[l] = w->attn_norm[l]; c->ffn_norm[l] = w->ffn_norm[l]; }
+  // a captured decode graph holds the addresses it was recorded with: it survives unless one of them changed
+  if (moved) drop_graph(c);
+  // whatever the KV cache holds was computed with the old weights
+  c->have_batch = false;
+  c->have_logits = false;
+  return RLHF_GEN_OK;
+}
+
 void rlhf_gen_destroy(rlhf_gen_ctx* c) {
   if (!c) return;
   (void)hipSetDevice(c->cfg.device);

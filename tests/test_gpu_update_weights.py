@@ -1,0 +1,144 @@
+"""rlhf_gen_update_weights: the refreshed replica must behave like a context created with the new weights, and a
+refresh with adapters like the oracle run on the merged matrices."""
+import pytest
+import torch
+
+from oracle.generate import generate as oracle_generate
+from oracle.sampling import Sampling as OSampling
+from oracle import lora as OL
+from paper_2312_11819_amd import synth
+from tests.gpu_util import need_gpu
+from tests.test_gpu_rollout import BF16_SMALL, BF16_SMALL_GQA, _queries, _teacher_forced, _compare
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    need_gpu()
+    from paper_2312_11819_amd import binding
+    binding.lib()
+    return binding
+
+
+def _copy_into(dst: dict, src: dict) -> None:
+    """Overwrite the tensors of dst with the values of src, keeping dst's addresses."""
+    for k, v in src.items():
+        if k != "layers":
+            dst[k].copy_(v)
+    for dl, sl in zip(dst["layers"], src["layers"]):
+        for k, v in sl.items():
+            dl[k].copy_(v)
+
+
+@pytest.mark.parametrize("flags", [0, 8])
+def test_refresh_equals_fresh_context(B, flags):
+    shape = BF16_SMALL_GQA
+    w1 = synth.make_weights(shape, 31, "bf16"); synth.randomize_norm_gains(w1, 32)
+    w2 = synth.make_weights(shape, 33, "bf16"); synth.randomize_norm_gains(w2, 34)
+    toks, lens = synth.make_queries(shape.vocab, 5, 2, 50, 35, pad_token=2)
+    sp = B.make_sampling(temperature=0.9, top_p=0.9, seed=5)
+    args = (toks.cuda(), lens.tolist(), 24, sp)
+    fresh = lambda w: B.Context(synth.weights_to(w, "cuda"), shape, "bf16", 8, 96, flags=flags)
+    want1 = [t.clone() for t in fresh(w1).rlhf_gen_generate(*args)]
+    want2 = [t.clone() for t in fresh(w2).rlhf_gen_generate(*args)]
+    assert not torch.equal(want1[0], want2[0])
+
+    d1 = synth.weights_to(w1, "cuda")
+    ctx = B.Context(d1, shape, "bf16", 8, 96, flags=flags)
+    got = ctx.rlhf_gen_generate(*args)
+    assert torch.equal(got[0], want1[0]) and torch.equal(got[1], want1[1])
+    # (a) new buffers
+    ctx.rlhf_gen_update_weights(synth.weights_to(w2, "cuda"))
+    with pytest.raises(B.RlhfGenError) as e:
+        ctx.rlhf_gen_decode_step()                       # the old batch is gone
+    assert e.value.status == B.E_STATE
+    got = ctx.rlhf_gen_generate(*args)
+    assert torch.equal(got[0], want2[0]) and torch.equal(got[1], want2[1])
+    # (b) the trainer overwrote the buffers given at init: same addresses, the recorded decode graph is replayed
+    ctx2 = B.Context(d1, shape, "bf16", 8, 96, flags=flags) if flags == 0 else None
+    if ctx2 is not None:
+        got = ctx2.rlhf_gen_generate(*args)
+        assert torch.equal(got[0], want1[0])
+        _copy_into(d1, synth.weights_to(w2, "cuda"))
+        ctx2.rlhf_gen_update_weights(d1)
+        got = ctx2.rlhf_gen_generate(*args)
+        assert torch.equal(got[0], want2[0]) and torch.equal(got[1], want2[1])
+        # and back again
+        _copy_into(d1, synth.weights_to(w1, "cuda"))
+        ctx2.rlhf_gen_update_weights(d1)
+        got = ctx2.rlhf_gen_generate(*args)
+        assert torch.equal(got[0], want1[0]) and torch.equal(got[1], want1[1])
+
+
+def _make_lora(shape, seed, rank, std=0.06):
+    g = torch.Generator().manual_seed(seed)
+    mk = lambda r, c: (torch.randn(r, c, generator=g) * std).bfloat16()
+    d, qkv, hq, F = shape.d_model, shape.qkv_rows, shape.n_heads * shape.head_dim, shape.d_ffn
+    layers = []
+    for l in range(shape.n_layers):
+        la = {"wqkv": (mk(3 * rank, d), mk(qkv, 3 * rank)), "wo": (mk(rank, hq), mk(d, rank))}
+        if l % 2 == 0:
+            la["w_gate_up"] = (mk(2 * rank, d), mk(2 * F, 2 * rank))
+            la["w_down"] = (mk(rank, F), mk(d, rank))
+        layers.append(la)
+    return {"scale": 1.5, "layers": layers, "lm_head": (mk(rank, d), mk(shape.vocab, rank))}
+
+
+def _lora_to(lora, dev):
+    mv = lambda p: None if p is None else (p[0].to(dev), p[1].to(dev))
+    return {"scale": lora["scale"], "layers": [{k: mv(v) for k, v in la.items()} for la in lora["layers"]],
+            "lm_head": mv(lora.get("lm_head"))}
+
+
+@pytest.mark.parametrize("shape,flags", [(BF16_SMALL, 0), (BF16_SMALL_GQA, 8)])
+def test_lora_refresh_matches_oracle_on_merged_weights(B, shape, flags):
+    w = synth.make_weights(shape, 41, "bf16"); synth.randomize_norm_gains(w, 42)
+    lora = _make_lora(shape, 43, rank=4)
+    merged = OL.fold_weights(w, lora)
+    toks, lens = synth.make_queries(shape.vocab, 6, 1, 60, 44, pad_token=3)
+    cfgs = dict(temperature=1.0, top_p=0.95, seed=11)
+    osp = OSampling(**cfgs)
+    ref = oracle_generate(merged, shape, _queries(toks, lens), 10, osp)
+    base = oracle_generate(w, shape, _queries(toks, lens), 10, osp, forced=ref["tokens"])
+    # the adapters move the logits by far more than the tolerance, so ignoring them cannot pass
+    assert float((base["logits"] - ref["logits"]).abs().max()) > 0.3
+    ctx = B.Context(synth.weights_to(w, "cuda"), shape, "bf16", 8, 96, flags=flags)
+    ctx.rlhf_gen_update_weights(synth.weights_to(w, "cuda"), _lora_to(lora, "cuda"))
+    t, lp, lg = _teacher_forced(B, ctx, toks, lens, ref["tokens"], B.make_sampling(**cfgs))
+    frac = _compare(ref, t, lp, lg, osp, 3e-2, 2e-2, 6e-2)
+    assert frac < 0.2
+    # a refresh without adapters returns to the base model
+    ctx.rlhf_gen_update_weights(synth.weights_to(w, "cuda"))
+    t, lp, lg = _teacher_forced(B, ctx, toks, lens, ref["tokens"], B.make_sampling(**cfgs))
+    assert float((lg - base["logits"]).abs().max()) <= 3e-2
+
+
+def test_fp32_refresh_and_error_paths(B):
+    shape = synth.TINY
+    w1, w2 = synth.make_weights(shape, 51), synth.make_weights(shape, 52)
+    toks, lens = synth.make_queries(shape.vocab, 3, 2, 9, 53)
+    sp = B.make_sampling(greedy=True)
+    ctx = B.Context(synth.weights_to(w1, "cuda"), shape, "fp32", 4, 32)
+    ctx.rlhf_gen_generate(toks.cuda(), lens.tolist(), 8, sp)
+    ctx.rlhf_gen_update_weights(synth.weights_to(w2, "cuda"))
+    gt, glp = ctx.rlhf_gen_generate(toks.cuda(), lens.tolist(), 8, sp)
+    ref = oracle_generate(w2, shape, _queries(toks, lens), 8, OSampling(greedy=True))
+    top2 = ref["logits"].topk(2, dim=-1).values
+    assert float((top2[..., 0] - top2[..., 1]).min()) > 2e-4      # this seed has no near-tie
+    assert torch.equal(gt.cpu().long(), ref["tokens"])
+    assert (glp.cpu().double() - ref["logprobs"]).abs().max() < 1e-4
+    lora = {"scale": 1.0, "layers": [{"wo": (torch.zeros(2, shape.n_heads * shape.head_dim).cuda(),
+                                             torch.zeros(shape.d_model, 2).cuda())}] + [{}] * (shape.n_layers - 1)}
+    with pytest.raises(B.RlhfGenError) as e:
+        ctx.rlhf_gen_update_weights(synth.weights_to(w2, "cuda"), lora)
+    assert e.value.status == B.E_UNSUPPORTED
+    # rank out of range on the 16-bit path
+    shape = BF16_SMALL
+    wb = synth.weights_to(synth.make_weights(shape, 54, "bf16"), "cuda")
+    cb = B.Context(wb, shape, "bf16", 2, 48)
+    bad = {"scale": 1.0, "layers": [{"wo": (torch.zeros(65, shape.n_heads * shape.head_dim, dtype=torch.bfloat16).cuda(),
+                                            torch.zeros(shape.d_model, 65, dtype=torch.bfloat16).cuda())}, {}]}
+    with pytest.raises(B.RlhfGenError) as e:
+        cb.rlhf_gen_update_weights(wb, bad)
+    assert e.value.status == B.E_INVALID
