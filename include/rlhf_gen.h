@@ -188,6 +188,27 @@ typedef struct {
  * Errors: E_INVALID (NULL pointers, rank out of range), E_UNSUPPORTED, E_DEVICE. */
 int rlhf_gen_update_weights(rlhf_gen_ctx* ctx, const rlhf_gen_weights* weights, const rlhf_gen_lora* lora);
 
+/* Capacity planning.  The paper sizes every run by memory: the batch is the largest that does not run out of memory
+ * (Sec. V-A "Hyperparameters"), and its guideline is to raise the batch while memory is spare and stop before 95 % of
+ * the capacity (Sec. IV-C).  This call answers that question for one replica without allocating: the largest
+ * max_batch for which a context created from cfg (cfg.max_batch is ignored, cfg.kv_pool_blocks must be 0, cfg.max_seq
+ * = query + response length of the longest sequence) fits into fraction * capacity_bytes - reserved_bytes.  The
+ * footprint is computed by the same code that performs the allocations in rlhf_gen_init (KV pool of
+ * max_batch * ceil(max_seq / 16) pages per layer, fp16 working copies of the matrices unless
+ * RLHF_GEN_FLAG_CONVERT_IN_PLACE, activations, logits, split-K workspace), as the sum of the sizes requested.
+ *   capacity_bytes   memory of the card; 0 = ask HIP for the total memory of cfg.device (the only case that touches a GPU)
+ *   fraction         in (0, 1], e.g. 0.95
+ *   reserved_bytes   memory others hold on the card; a negative value stands for "the caller's copy of this model in
+ *                    cfg.dtype", which rlhf_gen_init borrows
+ *   *max_batch_out   the answer, 0 if not even one sequence fits; *context_bytes_out (may be NULL) the device bytes
+ *                    such a context allocates
+ * Errors: E_INVALID, E_UNSUPPORTED (as rlhf_gen_init for the shape), E_DEVICE. */
+int rlhf_gen_plan_capacity(const rlhf_gen_cfg* cfg, int64_t capacity_bytes, double fraction, int64_t reserved_bytes,
+                           int32_t* max_batch_out, int64_t* context_bytes_out);
+
+/* Device bytes the context requested from HIP in rlhf_gen_init (what rlhf_gen_plan_capacity predicts). */
+int64_t rlhf_gen_context_bytes(const rlhf_gen_ctx* ctx);
+
 /* Copy the fp32 logits [B, vocab] that the last prefill/decode step sampled from into a device
  * buffer (parity checks).  E_STATE if no step has run. */
 int rlhf_gen_get_logits(rlhf_gen_ctx* ctx, float* out);

@@ -28,6 +28,7 @@ PROF_CLASSES = ["embed", "norm", "gemm_qkv", "rope_append", "attn_decode", "gemm
 
 EXPORTS = [
     "rlhf_gen_init", "rlhf_gen_prefill", "rlhf_gen_decode_step", "rlhf_gen_generate", "rlhf_gen_score", "rlhf_gen_update_weights",
+    "rlhf_gen_plan_capacity", "rlhf_gen_context_bytes",
     "rlhf_gen_get_logits",
     "rlhf_gen_last_timing", "rlhf_gen_set_profile", "rlhf_gen_get_profile", "rlhf_gen_last_error", "rlhf_gen_destroy",
     "rlhf_gen_op_gemm", "rlhf_gen_op_rope_append", "rlhf_gen_op_attn_decode", "rlhf_gen_op_attn_prefill",
@@ -89,6 +90,10 @@ def lib() -> C.CDLL:
         L.rlhf_gen_score.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_void_p,
                                      C.c_int32, C.c_void_p]
         L.rlhf_gen_update_weights.argtypes = [C.c_void_p, C.POINTER(Weights), C.POINTER(Lora)]
+        L.rlhf_gen_plan_capacity.argtypes = [C.POINTER(Cfg), C.c_int64, C.c_double, C.c_int64, C.POINTER(C.c_int32),
+                                             C.POINTER(C.c_int64)]
+        L.rlhf_gen_context_bytes.argtypes = [C.c_void_p]
+        L.rlhf_gen_context_bytes.restype = C.c_int64
         L.rlhf_gen_get_logits.argtypes = [C.c_void_p, C.c_void_p]
         L.rlhf_gen_last_timing.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_int32)]
         L.rlhf_gen_set_profile.argtypes = [C.c_void_p, C.c_int32]
@@ -117,6 +122,18 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
         return None
     assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous CUDA/HIP tensors"
     return t.data_ptr()
+
+
+def rlhf_gen_plan_capacity(shape, dtype: str, max_seq: int, capacity_bytes: int, fraction: float = 0.95,
+                           reserved_bytes: int = -1, flags: int = 0, device: int = 0):
+    """Largest batch a context of this shape can hold, and the device bytes it would allocate."""
+    cfg = Cfg(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
+              shape.vocab, shape.rms_eps, shape.rope_theta, DTYPE_BF16 if dtype == "bf16" else DTYPE_FP32,
+              1, max_seq, 16, 0, device, None, flags)
+    b, n = C.c_int32(), C.c_int64()
+    _check(None, lib().rlhf_gen_plan_capacity(C.byref(cfg), int(capacity_bytes), float(fraction), int(reserved_bytes),
+                                              C.byref(b), C.byref(n)))
+    return b.value, n.value
 
 
 def make_sampling(temperature=1.0, top_p=1.0, seed=0, greedy=False, logprob_mode=0) -> Sampling:
@@ -224,6 +241,9 @@ class Context:
         self.synchronize()
         self.B = 0
         return out
+
+    def rlhf_gen_context_bytes(self) -> int:
+        return int(lib().rlhf_gen_context_bytes(self._h))
 
     def rlhf_gen_get_logits(self) -> torch.Tensor:
         out = torch.empty(self.B, self.shape.vocab, dtype=torch.float32, device=self.device)

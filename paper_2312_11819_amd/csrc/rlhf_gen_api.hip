@@ -45,6 +45,8 @@ struct rlhf_gen_ctx {
 
   // device memory owned by the context
   std::vector<void*> allocs;
+  size_t dev_bytes = 0;   // sum of the device allocations requested
+  bool dry_run = false;   // capacity planning: walk the allocation sequence without allocating
   char* kv_pool = nullptr;
   size_t layer_pool_bytes = 0;
   int n_blocks = 0, max_blocks = 0;
@@ -115,6 +117,11 @@ template <typename T>
 int dev_alloc(rlhf_gen_ctx* c, T** p, size_t bytes, bool zero) {
   void* q = nullptr;
   if (bytes == 0) bytes = 16;
+  c->dev_bytes += bytes;
+  if (c->dry_run) {
+    *p = nullptr;
+    return RLHF_GEN_OK;
+  }
   hipError_t e = hipMalloc(&q, bytes);
   if (e != hipSuccess) {
     (void)hipGetLastError();
@@ -129,6 +136,10 @@ int dev_alloc(rlhf_gen_ctx* c, T** p, size_t bytes, bool zero) {
 template <typename T>
 int host_alloc(rlhf_gen_ctx* c, T** p, size_t bytes) {
   void* q = nullptr;
+  if (c->dry_run) {
+    *p = nullptr;
+    return RLHF_GEN_OK;
+  }
   HIP_TRY(c, hipHostMalloc(&q, bytes ? bytes : 16, hipHostMallocDefault));
   memset(q, 0, bytes ? bytes : 16);
   *p = (T*)q;
@@ -628,9 +639,8 @@ void drop_graph(rlhf_gen_ctx* c) {
 
 extern "C" {
 
-int rlhf_gen_init(const rlhf_gen_weights* w, const rlhf_gen_cfg* cfg, rlhf_gen_ctx** out) {
-  if (out) *out = nullptr;
-  if (!w || !cfg || !out) return fail(nullptr, RLHF_GEN_E_INVALID, "NULL argument to rlhf_gen_init");
+// Shape and capacity checks shared by rlhf_gen_init and the capacity planner.
+static int validate_cfg(const rlhf_gen_cfg* cfg) {
   const rlhf_gen_cfg& g = *cfg;
   if (g.n_layers < 1 || g.d_model < 1 || g.n_heads < 1 || g.n_kv_heads < 1 || g.head_dim < 1 || g.d_ffn < 1 || g.vocab < 1)
     return fail(nullptr, RLHF_GEN_E_INVALID, "model dimensions must be positive");
@@ -654,59 +664,15 @@ int rlhf_gen_init(const rlhf_gen_weights* w, const rlhf_gen_cfg* cfg, rlhf_gen_c
     if (g.head_dim != 32 && g.head_dim != 64 && g.head_dim != 128)
       return fail(nullptr, RLHF_GEN_E_UNSUPPORTED, "fp32 path supports head_dim 32, 64 or 128");
   }
-  if (!w->tok_emb || !w->lm_head || !w->final_norm || !w->attn_norm || !w->wqkv || !w->wo || !w->ffn_norm ||
-      !w->w_gate_up || !w->w_down)
-    return fail(nullptr, RLHF_GEN_E_INVALID, "NULL weight pointer");
-  for (int l = 0; l < g.n_layers; ++l)
-    if (!w->attn_norm[l] || !w->wqkv[l] || !w->wo[l] || !w->ffn_norm[l] || !w->w_gate_up[l] || !w->w_down[l])
-      return fail(nullptr, RLHF_GEN_E_INVALID, "NULL weight pointer in layer %d", l);
+  return RLHF_GEN_OK;
+}
 
-  int ndev = 0;
-  if (hipGetDeviceCount(&ndev) != hipSuccess || g.device < 0 || g.device >= ndev) {
-    (void)hipGetLastError();
-    return fail(nullptr, RLHF_GEN_E_DEVICE, "HIP device %d is not available (%d devices)", g.device, ndev);
-  }
-  rlhf_gen_ctx* c = new rlhf_gen_ctx();
-  c->cfg = g;
-  c->bf16 = g.dtype == RLHF_GEN_DTYPE_BF16;
-  c->stream = (hipStream_t)g.stream;
-  c->tok_emb = w->tok_emb;
-  c->lm_head = w->lm_head;
-  c->final_norm = w->final_norm;
-  for (int l = 0; l < g.n_layers; ++l) {
-    c->attn_norm.push_back(w->attn_norm[l]);
-    c->wqkv.push_back(w->wqkv[l]);
-    c->wo.push_back(w->wo[l]);
-    c->ffn_norm.push_back(w->ffn_norm[l]);
-    c->w_gate_up.push_back(w->w_gate_up[l]);
-    c->w_down.push_back(w->w_down[l]);
-  }
-  c->src_wqkv = c->wqkv; c->src_wo = c->wo; c->src_w_gate_up = c->w_gate_up; c->src_w_down = c->w_down;
-  c->src_lm_head = c->lm_head;
-  auto bail = [&](int code) {
-    g_init_error = c->err;
-    rlhf_gen_destroy(c);
-    return code;
-  };
-  if (hipSetDevice(g.device) != hipSuccess) {
-    (void)hipGetLastError();
-    c->err = "hipSetDevice failed";
-    return bail(RLHF_GEN_E_DEVICE);
-  }
-  if (!c->stream) {
-    // the legacy default stream cannot be captured into a graph: use a stream of our own (default priority)
-    if (hipStreamCreate(&c->stream) != hipSuccess) {
-      c->err = "hipStreamCreate failed";
-      c->stream = nullptr;
-      return bail(RLHF_GEN_E_DEVICE);
-    }
-    c->own_stream = true;
-  }
-  if (gemm_configure() != hipSuccess) {
-    (void)hipGetLastError();
-    c->err = "kernel attribute setup failed";
-    return bail(RLHF_GEN_E_DEVICE);
-  }
+// Every device and pinned-host allocation of a context, in one place.  With c->dry_run set nothing is allocated or
+// launched and c->dev_bytes ends up as the context's device footprint.
+static int allocate_all(rlhf_gen_ctx* c) {
+  const rlhf_gen_cfg& g = c->cfg;
+  const int qkv_w = (g.n_heads + 2 * g.n_kv_heads) * g.head_dim;
+  auto bail = [&](int code) { return code; };
   c->max_blocks = blocks_for(g.max_seq);
   c->n_blocks = g.kv_pool_blocks ? g.kv_pool_blocks : g.max_batch * c->max_blocks;
   const size_t page_bytes = c->bf16 ? 8192 : (size_t)2 * 16 * g.head_dim * 4;
@@ -716,7 +682,7 @@ int rlhf_gen_init(const rlhf_gen_weights* w, const rlhf_gen_cfg* cfg, rlhf_gen_c
   // activation rows: a prefill chunk holds whole sequences, so at least max_seq rows; 16384 keeps the
   // large GEMMs in their efficient regime while bounding the scratch
   c->act_rows = std::max(std::max(g.max_seq, g.max_batch), 16384);
-  c->act_rows = std::min(c->act_rows, std::max(g.max_batch * g.max_seq, g.max_batch));
+  c->act_rows = (int)std::min<long long>(c->act_rows, std::max<long long>((long long)g.max_batch * g.max_seq, g.max_batch));
   c->act_rows = (c->act_rows + 255) / 256 * 256;
   const size_t rows = c->act_rows, as = act_size(c);
   const size_t total_tok = (size_t)g.max_batch * g.max_seq;
@@ -734,7 +700,7 @@ int rlhf_gen_init(const rlhf_gen_weights* w, const rlhf_gen_cfg* cfg, rlhf_gen_c
         if (r) return r;
         d = fresh;
       }
-      if (launch_bf16_to_h16(c->stream, src, d, n) != hipSuccess) {
+      if (!c->dry_run && launch_bf16_to_h16(c->stream, src, d, n) != hipSuccess) {
         c->err = "weight conversion kernel failed to launch";
         return RLHF_GEN_E_DEVICE;
       }
@@ -799,6 +765,75 @@ int rlhf_gen_init(const rlhf_gen_weights* w, const rlhf_gen_cfg* cfg, rlhf_gen_c
   A_(host_alloc(c, &c->h_srows, sizeof(int) * total_tok));
   A_(host_alloc(c, &c->h_sslot, sizeof(int) * total_tok));
 #undef A_
+  return RLHF_GEN_OK;
+}
+
+int rlhf_gen_init(const rlhf_gen_weights* w, const rlhf_gen_cfg* cfg, rlhf_gen_ctx** out) {
+  if (out) *out = nullptr;
+  if (!w || !cfg || !out) return fail(nullptr, RLHF_GEN_E_INVALID, "NULL argument to rlhf_gen_init");
+  {
+    int vrc = validate_cfg(cfg);
+    if (vrc) return vrc;
+  }
+  const rlhf_gen_cfg& g = *cfg;
+  if (!w->tok_emb || !w->lm_head || !w->final_norm || !w->attn_norm || !w->wqkv || !w->wo || !w->ffn_norm ||
+      !w->w_gate_up || !w->w_down)
+    return fail(nullptr, RLHF_GEN_E_INVALID, "NULL weight pointer");
+  for (int l = 0; l < g.n_layers; ++l)
+    if (!w->attn_norm[l] || !w->wqkv[l] || !w->wo[l] || !w->ffn_norm[l] || !w->w_gate_up[l] || !w->w_down[l])
+      return fail(nullptr, RLHF_GEN_E_INVALID, "NULL weight pointer in layer %d", l);
+
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || g.device < 0 || g.device >= ndev) {
+    (void)hipGetLastError();
+    return fail(nullptr, RLHF_GEN_E_DEVICE, "HIP device %d is not available (%d devices)", g.device, ndev);
+  }
+  rlhf_gen_ctx* c = new rlhf_gen_ctx();
+  c->cfg = g;
+  c->bf16 = g.dtype == RLHF_GEN_DTYPE_BF16;
+  c->stream = (hipStream_t)g.stream;
+  c->tok_emb = w->tok_emb;
+  c->lm_head = w->lm_head;
+  c->final_norm = w->final_norm;
+  for (int l = 0; l < g.n_layers; ++l) {
+    c->attn_norm.push_back(w->attn_norm[l]);
+    c->wqkv.push_back(w->wqkv[l]);
+    c->wo.push_back(w->wo[l]);
+    c->ffn_norm.push_back(w->ffn_norm[l]);
+    c->w_gate_up.push_back(w->w_gate_up[l]);
+    c->w_down.push_back(w->w_down[l]);
+  }
+  c->src_wqkv = c->wqkv; c->src_wo = c->wo; c->src_w_gate_up = c->w_gate_up; c->src_w_down = c->w_down;
+  c->src_lm_head = c->lm_head;
+  auto bail = [&](int code) {
+    g_init_error = c->err;
+    rlhf_gen_destroy(c);
+    return code;
+  };
+  if (hipSetDevice(g.device) != hipSuccess) {
+    (void)hipGetLastError();
+    c->err = "hipSetDevice failed";
+    return bail(RLHF_GEN_E_DEVICE);
+  }
+  if (!c->stream) {
+    // the legacy default stream cannot be captured into a graph: use a stream of our own (default priority)
+    if (hipStreamCreate(&c->stream) != hipSuccess) {
+      c->err = "hipStreamCreate failed";
+      c->stream = nullptr;
+      return bail(RLHF_GEN_E_DEVICE);
+    }
+    c->own_stream = true;
+  }
+  if (gemm_configure() != hipSuccess) {
+    (void)hipGetLastError();
+    c->err = "kernel attribute setup failed";
+    return bail(RLHF_GEN_E_DEVICE);
+  }
+  {
+    int arc = allocate_all(c);
+    if (arc) return bail(arc);
+  }
+  const int half = g.head_dim / 2;
   {
     // rotation tables in double, rounded once to fp32: angle = pos * theta^(-2i/h)
     std::vector<float> cs((size_t)(g.max_seq + 1) * half), sn((size_t)(g.max_seq + 1) * half);
@@ -980,6 +1015,64 @@ int rlhf_gen_get_profile(const rlhf_gen_ctx* c, double* ms, int64_t* launches, i
 }
 
 const char* rlhf_gen_last_error(const rlhf_gen_ctx* c) { return c ? c->err.c_str() : g_init_error.c_str(); }
+
+int64_t rlhf_gen_context_bytes(const rlhf_gen_ctx* c) { return c ? (int64_t)c->dev_bytes : 0; }
+
+int rlhf_gen_plan_capacity(const rlhf_gen_cfg* cfg, int64_t capacity_bytes, double fraction, int64_t reserved_bytes,
+                           int32_t* max_batch_out, int64_t* context_bytes_out) {
+  if (!cfg || !max_batch_out) return fail(nullptr, RLHF_GEN_E_INVALID, "NULL argument to rlhf_gen_plan_capacity");
+  if (!(fraction > 0.0) || fraction > 1.0) return fail(nullptr, RLHF_GEN_E_INVALID, "fraction must be in (0, 1]");
+  if (capacity_bytes < 0) return fail(nullptr, RLHF_GEN_E_INVALID, "capacity_bytes must not be negative");
+  rlhf_gen_cfg g = *cfg;
+  g.max_batch = 1;
+  int rc = validate_cfg(&g);
+  if (rc) return rc;
+  if (g.kv_pool_blocks != 0)
+    return fail(nullptr, RLHF_GEN_E_INVALID, "the planner sizes the KV pool itself: kv_pool_blocks must be 0");
+  if (capacity_bytes == 0) {
+    size_t free_b = 0, total_b = 0;
+    if (hipSetDevice(g.device) != hipSuccess || hipMemGetInfo(&free_b, &total_b) != hipSuccess) {
+      (void)hipGetLastError();
+      return fail(nullptr, RLHF_GEN_E_DEVICE, "cannot query the memory of HIP device %d", g.device);
+    }
+    capacity_bytes = (int64_t)total_b;
+  }
+  if (reserved_bytes < 0) {
+    // the caller's own copy of the model in cfg.dtype
+    const size_t es = g.dtype == RLHF_GEN_DTYPE_BF16 ? 2 : 4;
+    const size_t qkv_w = (size_t)(g.n_heads + 2 * g.n_kv_heads) * g.head_dim;
+    const size_t per_layer = qkv_w * g.d_model + (size_t)g.d_model * g.n_heads * g.head_dim + (size_t)3 * g.d_ffn * g.d_model +
+                             (size_t)2 * g.d_model;
+    reserved_bytes = (int64_t)(es * (per_layer * g.n_layers + (size_t)2 * g.vocab * g.d_model + g.d_model));
+  }
+  const double budget = fraction * (double)capacity_bytes - (double)reserved_bytes;
+  auto footprint = [&](int B) -> int64_t {
+    rlhf_gen_ctx tmp;
+    tmp.cfg = g;
+    tmp.cfg.max_batch = B;
+    tmp.bf16 = g.dtype == RLHF_GEN_DTYPE_BF16;
+    tmp.dry_run = true;
+    tmp.src_wqkv.assign(g.n_layers, nullptr); tmp.src_wo = tmp.src_w_gate_up = tmp.src_w_down = tmp.src_wqkv;
+    tmp.wqkv = tmp.wo = tmp.w_gate_up = tmp.w_down = tmp.src_wqkv;
+    if (allocate_all(&tmp)) return INT64_MAX;
+    return (int64_t)tmp.dev_bytes;
+  };
+  // the footprint grows with B: bisect for the largest batch within the budget
+  const int blocks = (g.max_seq + 15) / 16;
+  int hi = (int)std::min<long long>(1 << 20, std::min<long long>((1ll << 30) / g.max_seq, (1ll << 30) / blocks));
+  int lo = 0;  // largest batch known to fit (0: none)
+  if ((double)footprint(1) <= budget) {
+    lo = 1;
+    if ((double)footprint(hi) <= budget) lo = hi;
+    while (hi - lo > 1 && lo != hi) {
+      int mid = lo + (hi - lo) / 2;
+      if ((double)footprint(mid) <= budget) lo = mid; else hi = mid;
+    }
+  }
+  *max_batch_out = lo;
+  if (context_bytes_out) *context_bytes_out = lo ? footprint(lo) : 0;
+  return RLHF_GEN_OK;
+}
 
 int rlhf_gen_update_weights(rlhf_gen_ctx* c, const rlhf_gen_weights* w, const rlhf_gen_lora* lora) {
   if (!c) return RLHF_GEN_E_INVALID;
