@@ -145,6 +145,30 @@ int rlhf_gen_generate(rlhf_gen_ctx* ctx, const int32_t* query_tokens, const int3
                       int32_t Lmax, int32_t max_resp_len, const rlhf_gen_sampling* sampling,
                       int32_t* resp_tokens, float* resp_logprobs);
 
+/* Micro-batched rollout.  The paper hides the hand-off between stages by micro-batching: the forward stage (and the
+ * transfer that feeds it) of one micro-batch starts when its generation ends, not when the whole batch has been
+ * generated, and the transfers run on a stream of their own beside the computation (Sec. IV-A: Interleaving strategy,
+ * "computation and communication occupy different streams"; Disaggregated strategy, "bubbles are nearly hidden through
+ * micro-batching"; Sec. IV-C item 3).  This call generates rows [0, B) in micro-batches of micro_batch rows, one after
+ * the other on cfg.stream, and tells the caller when each is finished:
+ *   - after micro-batch i (rows row0 = i * micro_batch .. row0 + rows) is complete, done_events[i] (a hipEvent_t the
+ *     caller created; done_events is a HOST array of ceil(B / micro_batch) entries, or NULL) is recorded on cfg.stream;
+ *   - then on_ready(user, i, row0, rows, done_events[i]) (or NULL) is called on the calling thread, before micro-batch
+ *     i + 1 is enqueued: work the callback enqueues on another stream behind hipStreamWaitEvent(stream, event) - a copy
+ *     of the finished rows to the host or to a peer, a scoring pass on another context - overlaps with the generation of
+ *     the following micro-batches.
+ * Row b draws the same random numbers as in rlhf_gen_generate over the whole batch, and the kernels accumulate every
+ * output element in an order that does not depend on the number of rows while micro_batch <= 128, so the result then
+ * equals rlhf_gen_generate's bit for bit.  Only min(micro_batch, B) <= cfg.max_batch is required (the KV pool is reused by each
+ * micro-batch), so a context can be sized for the micro-batch.  rlhf_gen_last_timing reports the sums over the
+ * micro-batches.  Other arguments and errors as for rlhf_gen_generate; on an error the remaining micro-batches are
+ * not generated. */
+typedef void (*rlhf_gen_microbatch_fn)(void* user, int32_t index, int32_t row0, int32_t rows, void* done_event);
+int rlhf_gen_generate_stream(rlhf_gen_ctx* ctx, const int32_t* query_tokens, const int32_t* lengths, int32_t B,
+                             int32_t Lmax, int32_t max_resp_len, const rlhf_gen_sampling* sampling, int32_t* resp_tokens,
+                             float* resp_logprobs, int32_t micro_batch, void* const* done_events,
+                             rlhf_gen_microbatch_fn on_ready, void* user);
+
 /* Teacher-forced scoring pass: the raw-model log-probability of every token of given responses, by one forward over
  * query ++ response per sequence - `ActorOutput <- Actor.forward(Query, Response)` of Alg. 1 (the same call scores the
  * Ref model).  logprobs_out[b, t] = log softmax(logits at position lengths[b] - 1 + t)[resp_tokens[b, t]]; for a

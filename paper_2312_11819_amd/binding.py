@@ -27,7 +27,7 @@ PROF_CLASSES = ["embed", "norm", "gemm_qkv", "rope_append", "attn_decode", "gemm
                 "gemm_down", "lm_head", "sampler"]
 
 EXPORTS = [
-    "rlhf_gen_init", "rlhf_gen_prefill", "rlhf_gen_decode_step", "rlhf_gen_generate", "rlhf_gen_score", "rlhf_gen_update_weights",
+    "rlhf_gen_init", "rlhf_gen_prefill", "rlhf_gen_decode_step", "rlhf_gen_generate", "rlhf_gen_generate_stream", "rlhf_gen_score", "rlhf_gen_update_weights",
     "rlhf_gen_plan_capacity", "rlhf_gen_context_bytes",
     "rlhf_gen_get_logits",
     "rlhf_gen_last_timing", "rlhf_gen_set_profile", "rlhf_gen_get_profile", "rlhf_gen_last_error", "rlhf_gen_destroy",
@@ -71,6 +71,8 @@ class RlhfGenError(RuntimeError):
         self.message = message
 
 
+MICROBATCH_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p)
+
 _lib = None
 
 
@@ -87,6 +89,9 @@ def lib() -> C.CDLL:
         L.rlhf_gen_decode_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.rlhf_gen_generate.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_int32,
                                         C.POINTER(Sampling), C.c_void_p, C.c_void_p]
+        L.rlhf_gen_generate_stream.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_int32,
+                                               C.POINTER(Sampling), C.c_void_p, C.c_void_p, C.c_int32,
+                                               C.POINTER(C.c_void_p), MICROBATCH_FN, C.c_void_p]
         L.rlhf_gen_score.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_void_p,
                                      C.c_int32, C.c_void_p]
         L.rlhf_gen_update_weights.argtypes = [C.c_void_p, C.POINTER(Weights), C.POINTER(Lora)]
@@ -230,6 +235,41 @@ class Context:
                                                 C.byref(sampling), _ptr(toks), _ptr(lps)))
         self.B = B
         return toks, lps
+
+    def rlhf_gen_generate_stream(self, query_tokens: torch.Tensor, lengths: Sequence[int], max_resp_len: int,
+                                 sampling: Sampling, micro_batch: int, on_ready=None,
+                                 out_tokens: Optional[torch.Tensor] = None, out_logprobs: Optional[torch.Tensor] = None):
+        """on_ready(index, row0, rows, event) runs on this thread right after micro-batch `index` has been generated and
+        `event` (a torch.cuda.Event recorded on the context's stream) marks its rows complete.
+        Returns (tokens, logprobs, events)."""
+        B, Lmax = query_tokens.shape
+        lens = (C.c_int32 * B)(*[int(x) for x in lengths])
+        toks = out_tokens if out_tokens is not None else torch.empty(B, max_resp_len, dtype=torch.int32, device=self.device)
+        lps = out_logprobs if out_logprobs is not None else torch.empty(B, max_resp_len, dtype=torch.float32, device=self.device)
+        n_mb = -(-B // max(micro_batch, 1))
+        events = [torch.cuda.Event(enable_timing=True) for _ in range(n_mb)]
+        with torch.cuda.stream(self.stream):
+            for e in events:
+                e.record()          # torch creates the HIP event at its first record
+        handles = (C.c_void_p * n_mb)(*[e.cuda_event for e in events])
+        failure = []
+
+        def trampoline(_user, index, row0, rows, _ev):
+            try:
+                if on_ready is not None:
+                    on_ready(index, row0, rows, events[index])
+            except BaseException as exc:   # never unwind through the C frames
+                failure.append(exc)
+
+        cb = MICROBATCH_FN(trampoline)
+        self.stream.wait_stream(torch.cuda.current_stream(self.device))
+        _check(self._h, lib().rlhf_gen_generate_stream(self._h, _ptr(query_tokens), lens, B, Lmax, max_resp_len,
+                                                       C.byref(sampling), _ptr(toks), _ptr(lps), micro_batch, handles, cb,
+                                                       None))
+        if failure:
+            raise failure[0]
+        self.B = min(micro_batch, B)
+        return toks, lps, events
 
     def rlhf_gen_score(self, query_tokens: torch.Tensor, lengths: Sequence[int], resp_tokens: torch.Tensor) -> torch.Tensor:
         B, Lmax = query_tokens.shape

@@ -230,7 +230,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __res
   // Workgroups walk their k range from different starting points (wrapping around), so that they do not all
   // touch the same columns of W at the same time.
   const int nst = s1 - s0;
-  const int rot = nst > 0 ? (int)((blockIdx.x * 5u + blockIdx.y * 3u) % (unsigned)nst) : 0;
+  // The starting point is a function of the rows, not of the workgroup shape, so that every output element is
+  // accumulated in the same order whichever instantiation (4 or 8 wavefronts, any batch width) computes it.
+  const unsigned grp = GLU ? (unsigned)n0 >> 6 : (unsigned)n0 >> 7;
+  const int rot = nst > 0 ? (int)((grp * 5u + blockIdx.y * 3u) % (unsigned)nst) : 0;
   (void)NT;
   // Loads are issued without any branch around them (a step index past the end re-reads the last step, which
   // hits in cache): with straight-line code the compiler can keep D - 1 steps of loads in flight and wait only

@@ -223,7 +223,7 @@ __global__ __launch_bounds__(ST) void sampler_kernel(const float* __restrict__ l
   }
   double total;
   double excl = block_excl_scan_d(local, sh, total);
-  const uint64_t key = p.seed ^ ((uint64_t)b * 0x9E3779B97F4A7C15ull) ^ ((uint64_t)t * 0xBF58476D1CE4E5B9ull);
+  const uint64_t key = p.seed ^ ((uint64_t)(b + p.row0) * 0x9E3779B97F4A7C15ull) ^ ((uint64_t)t * 0xBF58476D1CE4E5B9ull);
   const double u = (double)(mix64(key) >> 40) * (1.0 / 16777216.0);
   const double target = u * total;
   if (tid == 0) { sh.found = 0x7fffffff; sh.last = -1; }

@@ -83,6 +83,8 @@ struct SamplerParams {
   float temperature, top_p;
   uint64_t seed;
   int greedy, logprob_mode;
+  int row0;   // batch row of logits row 0 (a micro-batch keeps the random stream of its rows in the full batch)
+  int pad_;
 };
 // One workgroup per row of logits [B, V].  Response index t = *step_ptr + step_add; results go to
 // tok_out[b*out_stride + col], col = use_step_col ? t : 0; cur_tok[b] receives the token too.

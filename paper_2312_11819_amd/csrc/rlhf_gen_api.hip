@@ -74,6 +74,7 @@ struct rlhf_gen_ctx {
   bool have_batch = false, have_logits = false;
   int h_step = 0;
   int reserve_extra = 0;  // tokens beyond the query that prefill must reserve pages for
+  int row_offset = 0;     // batch row of row 0 of the current (micro-)batch, for the sampler's random stream
   SamplerParams sp{};
   std::string err;
 
@@ -386,6 +387,8 @@ int prefill_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* le
   c->sp.seed = sampling->seed;
   c->sp.greedy = sampling->greedy;
   c->sp.logprob_mode = sampling->logprob_mode;
+  c->sp.row0 = c->row_offset;
+  c->sp.pad_ = 0;
   reset_free_list(c);
   int T = 0;
   for (int b = 0; b < B; ++b) {
@@ -884,9 +887,8 @@ int rlhf_gen_decode_step(rlhf_gen_ctx* c, const int32_t* forced_tokens, int32_t*
   return RLHF_GEN_OK;
 }
 
-int rlhf_gen_generate(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* lengths, int32_t B, int32_t Lmax,
-                      int32_t R, const rlhf_gen_sampling* sampling, int32_t* resp_tokens, float* resp_logprobs) {
-  if (!c) return RLHF_GEN_E_INVALID;
+static int generate_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* lengths, int32_t B, int32_t Lmax,
+                         int32_t R, const rlhf_gen_sampling* sampling, int32_t* resp_tokens, float* resp_logprobs) {
   if (R < 1) return fail(c, RLHF_GEN_E_INVALID, "max_resp_len = %d must be positive", R);
   HIP_TRY(c, hipSetDevice(c->cfg.device));
   c->reserve_extra = R - 1;
@@ -956,6 +958,42 @@ int rlhf_gen_generate(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_
   }
   c->prof_used = 0;
   if (c->h_misc[2]) return fail(c, RLHF_GEN_E_INVALID, "a token id outside [0, vocab) reached the embedding");
+  return RLHF_GEN_OK;
+}
+
+int rlhf_gen_generate(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* lengths, int32_t B, int32_t Lmax,
+                      int32_t R, const rlhf_gen_sampling* sampling, int32_t* resp_tokens, float* resp_logprobs) {
+  if (!c) return RLHF_GEN_E_INVALID;
+  c->row_offset = 0;
+  return generate_impl(c, query_tokens, lengths, B, Lmax, R, sampling, resp_tokens, resp_logprobs);
+}
+
+int rlhf_gen_generate_stream(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* lengths, int32_t B, int32_t Lmax,
+                             int32_t R, const rlhf_gen_sampling* sampling, int32_t* resp_tokens, float* resp_logprobs,
+                             int32_t micro_batch, void* const* done_events, rlhf_gen_microbatch_fn on_ready, void* user) {
+  if (!c) return RLHF_GEN_E_INVALID;
+  if (!query_tokens || !lengths || !resp_tokens || !resp_logprobs) return fail(c, RLHF_GEN_E_INVALID, "NULL argument");
+  if (B < 1 || Lmax < 1) return fail(c, RLHF_GEN_E_INVALID, "B = %d and Lmax = %d must be positive", B, Lmax);
+  if (micro_batch < 1) return fail(c, RLHF_GEN_E_INVALID, "micro_batch = %d must be positive", micro_batch);
+  micro_batch = std::min(micro_batch, B);
+  if (micro_batch > c->cfg.max_batch)
+    return fail(c, RLHF_GEN_E_INVALID, "micro-batches of %d rows exceed max_batch = %d", micro_batch, c->cfg.max_batch);
+  HIP_TRY(c, hipSetDevice(c->cfg.device));
+  float pre = 0.f, dec = 0.f;
+  int steps = 0, rc = RLHF_GEN_OK, index = 0;
+  for (int row0 = 0; row0 < B; row0 += micro_batch, ++index) {
+    const int rows = std::min(micro_batch, B - row0);
+    c->row_offset = row0;
+    rc = generate_impl(c, query_tokens + (size_t)row0 * Lmax, lengths + row0, rows, Lmax, R, sampling,
+                       resp_tokens + (size_t)row0 * R, resp_logprobs + (size_t)row0 * R);
+    c->row_offset = 0;
+    if (rc) return rc;
+    pre += c->prefill_ms; dec += c->decode_ms; steps += c->decode_steps;
+    void* ev = done_events ? done_events[index] : nullptr;
+    if (ev) HIP_TRY(c, hipEventRecord((hipEvent_t)ev, c->stream));
+    if (on_ready) on_ready(user, index, row0, rows, ev);
+  }
+  c->prefill_ms = pre; c->decode_ms = dec; c->decode_steps = steps;
   return RLHF_GEN_OK;
 }
 
@@ -1220,7 +1258,7 @@ int rlhf_gen_op_attn_prefill(void* stream, const void* q, const void* kv_pool, c
 int rlhf_gen_op_sample(void* stream, const float* logits, int32_t B, int32_t V, const rlhf_gen_sampling* sp,
                        const int32_t* step, int32_t* tok_out, float* logprob_out, int32_t* scratch_tok) {
   if (!logits || !sp || !step || !tok_out || !logprob_out || !scratch_tok || B < 1 || V < 1) return RLHF_GEN_E_INVALID;
-  SamplerParams p;
+  SamplerParams p{};
   p.temperature = sp->temperature; p.top_p = sp->top_p; p.seed = sp->seed; p.greedy = sp->greedy; p.logprob_mode = sp->logprob_mode;
   hipError_t e = launch_sampler((hipStream_t)stream, logits, B, V, p, step, 1, 0, tok_out, logprob_out, scratch_tok);
   return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;
