@@ -54,6 +54,7 @@ def main() -> int:
     ap.add_argument("--resp-len", type=int, default=0, help="override R (debugging only; invalidates the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-score", action="store_true")
+    ap.add_argument("--micro-batch", type=int, default=16, help="rows per micro-batch of the streaming leg (0 = skip)")
     ap.add_argument("--profile-every", type=int, default=64)
     ap.add_argument("--flags", type=int, default=0)
     args = ap.parse_args()
@@ -93,6 +94,7 @@ def main() -> int:
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     prof = ctx.rlhf_gen_get_profile()
+    ctx.rlhf_gen_set_profile(0)
     assert bool(torch.isfinite(out_lp).all()) and int(out_t.min()) >= 0 and int(out_t.max()) < shape.vocab
 
     K = args.steps
@@ -155,6 +157,21 @@ def main() -> int:
         score = {"ms": dt * 1e3, "scored_tokens_per_s": B * R / dt, "mfma_bf16_frac": sflop / dt / MFMA_BF16_PEAK,
                  "max_abs_diff_vs_rollout_logprobs": float((sc - out_lp).abs().max())}
 
+    # micro-batched rollout of the same batch (the pipelining of Sec. IV-A), outside the timed region: when is the first
+    # micro-batch available to the next stage, and what does the smaller decode batch cost in throughput
+    micro = None
+    if args.micro_batch > 0 and not args.no_score and args.micro_batch < B:
+        ready = []
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        mt, mlp, _ = ctx.rlhf_gen_generate_stream(toks_d, lens.tolist(), R, sp, args.micro_batch,
+                                                  lambda i, r0, n, ev: ready.append(time.perf_counter() - t1))
+        ctx.synchronize()
+        dt = time.perf_counter() - t1
+        micro = {"micro_batch": args.micro_batch, "ms": dt * 1e3, "tokens_per_s": B * R / dt,
+                 "first_micro_batch_ready_ms": ready[0] * 1e3, "ready_ms": [r * 1e3 for r in ready],
+                 "equals_whole_batch_rollout": bool(torch.equal(mt, out_t) and torch.equal(mlp, out_lp))}
+
     # weight refresh of the shadow Actor (the parameter synchronisation of Alg. 2), outside the timed region:
     # every projection matrix and the LM head is read as bf16 and rewritten as fp16
     refresh = None
@@ -185,6 +202,7 @@ def main() -> int:
         "roofline": roofline,
         "kernels_sampled": kernels,
         "score_pass": score,
+        "micro_batched": micro,
         "weight_refresh": refresh,
         "cpu_baseline": cpu,
     }
