@@ -1,6 +1,6 @@
 // GEMMs of the rollout, out = A[M,K] * W[N,K]^T with both operands K-contiguous.
-//   gemm_h16_dma_kernel : large-tile fp16 MFMA GEMM for prefill (M = thousands of tokens): 256x256x64 block tile,
-//                         8 wavefronts of 128x64, LDS double buffer filled by LDS-DMA loads, 32x32x16 MFMA.
+//   gemm_h16_dma_kernel : large-tile fp16 MFMA GEMM for prefill (M = thousands of tokens): 256x256x32 block tile,
+//                         4 wavefronts of 128x128, LDS ring filled by LDS-DMA loads, 32x32x16 MFMA.
 //   gemm_skinny_kernel  : weight-streaming GEMM for decode (M = batch <= 256): W is the MFMA row operand read
 //                         straight from HBM into registers exactly once, the activation slice is staged in LDS,
 //                         split-K partial sums go to a workspace that the consumer kernel adds up in a fixed order.
@@ -13,17 +13,27 @@
 namespace {
 
 // ---------------------------------------------------------------------------------------------------
-// Large-tile GEMM: the operand tiles go from global memory straight into LDS (LDS-DMA loads, no staging
-// registers), 256x256x64 block tile, two LDS stages of 64 KB, 8 wavefronts of 128x64, 32x32x16 MFMA.
-//   * A wavefront-wide DMA load writes lane i's 16 bytes to LDS base + 16 i, so one instruction fills eight
-//     128-byte tile rows.  To keep the later 16-byte MFMA operand reads free of bank conflicts (64 banks: sixteen
-//     lanes, i.e. sixteen consecutive rows, are served per cycle and must cover 256 distinct bytes) the 16-byte
-//     chunk c of row r is stored at slot c ^ ((r >> 1) & 7); the permutation is applied on the global side (each
-//     lane fetches the chunk that belongs in its slot), so global reads stay whole 128-byte rows.
+// Large-tile GEMM: 256x256 block tile, four wavefronts (one per SIMD) of 128x128, 32x32x16 MFMA with the 256
+// accumulator registers of a wavefront in AGPRs, k-tiles of 32 that travel global memory -> LDS by LDS-DMA loads
+// (no staging registers) through a ring of NS stages of 32 KB.
+//   * A wavefront-wide DMA load writes lane i's 16 bytes to LDS base + 16 i, so one instruction fills sixteen
+//     64-byte tile rows.  To keep the later 16-byte MFMA operand reads free of bank conflicts (64 banks: sixteen
+//     lanes, i.e. sixteen consecutive rows, are served together and must cover 256 distinct bytes) the 16-byte chunk c
+//     of row r is stored at slot c ^ ((r >> 2) & 3); the permutation is applied on the global side (each lane
+//     fetches the chunk that belongs in its slot).
 //   * The compiler would wait for every outstanding DMA load before any LDS read it knows about, which would
 //     serialise the pipeline, so the operand reads are issued as inline ds_read_b128 and their completion is
-//     awaited explicitly (s_waitcnt lgkmcnt), two k-steps of fragments in flight.
-constexpr int DMA_STAGE = 65536;
+//     awaited explicitly (s_waitcnt lgkmcnt); the barrier is the bare s_barrier for the same reason.
+//   * One wavefront per SIMD has nobody to hide its issue slots behind: the sixteen operand reads and eight DMA
+//     loads of a k-tile are interleaved by hand between pairs of MFMAs (scheduling barriers pin the order), and the
+//     reads of the next half-tile are in flight while the current one multiplies.
+//   * Rows of the W tile are permuted on the way in: MFMA column c of the 32-column blocks j = 2 jp and 2 jp + 1
+//     holds output columns 2 c and 2 c + 1 of a 64-column group, so a lane owns two adjacent outputs and a store
+//     instruction writes whole 128-byte (fp16) or 256-byte (fp32) row segments.
+//   * Measured on MI355X: the k loop alone sustains about 1.0-1.1 PFLOP/s on random fp16 data (the MFMA pipe itself,
+//     fed from registers, 1.6 PFLOP/s on such data and 2.3-2.5 on zeros: the clock follows the data).
+constexpr int DMA_NS = 4;            // LDS stages
+constexpr int DMA_STAGE = 512 * 64;  // bytes per stage: 256 A rows + 256 W rows of 32 halves
 
 typedef unsigned __attribute__((ext_vector_type(4))) u32x4_t;  // native vector: can live in an asm "v" operand
 template <int OFF>
@@ -35,131 +45,162 @@ __device__ __forceinline__ u32x4_t lds_read128(uint32_t addr) {
 __device__ __forceinline__ f32x16_t mfma_32x32x16_v(u32x4_t a, u32x4_t b, f32x16_t c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
 }
-#define LDS_WAIT6(N, f0, f1, f2, f3, f4, f5) \
-  asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(f0), "+v"(f1), "+v"(f2), "+v"(f3), "+v"(f4), "+v"(f5))
+#define LDS_WAIT8(N, f0, f1, f2, f3, f4, f5, f6, f7) \
+  asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(f0), "+v"(f1), "+v"(f2), "+v"(f3), "+v"(f4), "+v"(f5), "+v"(f6), "+v"(f7))
 
 template <int EPI>
-__global__ __launch_bounds__(512) void gemm_h16_dma_kernel(const h16_t* __restrict__ A, const h16_t* __restrict__ W,
+__global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restrict__ A, const h16_t* __restrict__ W,
                                                             void* __restrict__ out, int M, int N, int K, int tilesM,
                                                             int tilesN, int a_dual) {
   // a_dual: A rows are [hi (K) | lo (K)]; the k loop then runs over 2K columns of A against W's K columns twice.
-  constexpr int BM = 256, BN = 256, WN = 64;
+  constexpr int NS = DMA_NS, DIST = NS - 1, LPT = 8;  // LPT: DMA loads per thread and k-tile
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   int pid = blockIdx.x;
   const int total = tilesM * tilesN;
-  if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
+  if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);  // consecutive tiles on one XCD (shared L2)
   const int band = 8 * tilesN;
   const int first_m = (pid / band) * 8;
   const int gsz = min(tilesM - first_m, 8);
   const int tm = first_m + (pid % band) % gsz;
   const int tn = (pid % band) / gsz;
-  const int m0 = tm * BM;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 2, wn = wave & 3;
+  const int m0 = tm * 256;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
 
-  auto wrow = [&](int r) -> int {
-    if (EPI == EPI_SWIGLU) {
-      int wv = r / WN, qd = r % WN;
-      int half = qd / (WN / 2), j = qd % (WN / 2);
-      return half * N + tn * (BN / 2) + wv * (WN / 2) + j;
-    }
-    return tn * BN + r;
+  // global row of W behind row R (0..255) of the LDS tile: wavefront half wn, 32-column block j, MFMA column c
+  auto wrow = [&](int R) -> int {
+    const int wv = R >> 7, j = (R >> 5) & 3, c = R & 31;
+    if (EPI == EPI_SWIGLU) return (j >> 1) * N + tn * 128 + wv * 64 + 2 * c + (j & 1);  // gate blocks 0,1; up blocks 2,3
+    return tn * 256 + wv * 128 + 64 * (j >> 1) + 2 * c + (j & 1);
   };
 
-  // DMA sources: wavefronts 0-3 bring the A tile (32 row groups of 8), 4-7 the W tile
-  const bool loads_a = wave < 4;
+  // DMA sources: wavefronts 0,1 bring the A rows (16 row groups of 16 each), 2,3 the W rows
+  const bool loads_a = wave < 2;
   const char* gbase = loads_a ? (const char*)A : (const char*)W;
-  uint32_t go[8];
+  uint32_t go[LPT];
 #pragma unroll
-  for (int it = 0; it < 8; ++it) {
-    int row = 8 * ((wave & 3) * 8 + it) + (lane >> 3);
-    int grow = loads_a ? min(m0 + row, M - 1) : wrow(row);
-    go[it] = (uint32_t)grow * (uint32_t)(loads_a && a_dual ? 2 * K : K) * 2u + (uint32_t)(((lane & 7) ^ ((row >> 1) & 7)) * 16);
+  for (int it = 0; it < LPT; ++it) {
+    const int row = 16 * ((wave & 1) * 8 + it) + (lane >> 2);
+    const int grow = loads_a ? min(m0 + row, M - 1) : wrow(row);
+    go[it] = (uint32_t)grow * (uint32_t)(loads_a && a_dual ? 2 * K : K) * 2u + (uint32_t)(((lane & 3) ^ ((row >> 2) & 3)) * 16);
   }
-  const int nkw = K / 64;                       // k-tiles of W
-  const int nk = a_dual ? 2 * nkw : nkw;        // k-tiles of the product
+  const int nkw = K / 32;                 // k-tiles of W
+  const int nk = a_dual ? 2 * nkw : nkw;  // k-tiles of the product
   typedef __attribute__((address_space(3))) void lds_void;
   typedef const __attribute__((address_space(1))) void g_void;
-  char* dma_dst = smem + wave * 8192;  // + stage * DMA_STAGE + it * 1024
-#define DMA_ISSUE(KT, STAGE)                                                                              \
-  {                                                                                                       \
-    const char* src = gbase + (size_t)(loads_a ? (KT) : ((KT) >= nkw ? (KT) - nkw : (KT))) * 128;        \
-    _Pragma("unroll") for (int it = 0; it < 8; ++it)                                                      \
-        __builtin_amdgcn_global_load_lds((g_void*)(src + go[it]),                                         \
-                                         (lds_void*)(dma_dst + (STAGE) * DMA_STAGE + it * 1024), 16, 0, 0); \
-  }
+  char* dma_dst = smem + wave * 8192;
+  // tile KT of this wavefront's operand (past the end: the last tile again, into a stage nobody reads any more)
+  auto tile_src = [&](int kt) -> const char* {
+    kt = min(kt, nk - 1);
+    return gbase + (size_t)(loads_a ? kt : (kt >= nkw ? kt - nkw : kt)) * 64;
+  };
+#define DMA1(SRC, SOFF, IT) \
+  __builtin_amdgcn_global_load_lds((g_void*)((SRC) + go[IT]), (lds_void*)(dma_dst + (SOFF) + (IT) * 1024), 16, 0, 0);
 
-  f32x16_t acc[4][2];
+  f32x16_t acc[4][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  // operand read addresses: row (lane & 31) of a 32-row block, chunk 2 ks + (lane >> 5), stored at slot chunk ^ ((row >> 1) & 7)
+  // operand read addresses: row (lane & 31) of a 32-row block, chunk 2 ks + (lane >> 5), stored at slot chunk ^ ((row >> 2) & 3)
   const uint32_t lds0 = (uint32_t)(size_t)smem;
-  const uint32_t y = (uint32_t)((lane >> 5) ^ ((lane >> 1) & 7));
-  uint32_t a_rd[4], b_rd[4];
+  const uint32_t sw = (uint32_t)((lane >> 2) & 3);
+  uint32_t a_rd[2], b_rd[2];
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) {
-    uint32_t slot = (uint32_t)(2 * ks) ^ y;
-    a_rd[ks] = lds0 + (uint32_t)((wm * 128 + (lane & 31)) * 128) + slot * 16;
-    b_rd[ks] = lds0 + (uint32_t)((BM + wn * 64 + (lane & 31)) * 128) + slot * 16;
+  for (int ks = 0; ks < 2; ++ks) {
+    const uint32_t slot = (uint32_t)(2 * ks + (lane >> 5)) ^ sw;
+    a_rd[ks] = lds0 + (uint32_t)((wm * 128 + (lane & 31)) * 64) + slot * 16;
+    b_rd[ks] = lds0 + (uint32_t)((256 + wn * 128 + (lane & 31)) * 64) + slot * 16;
   }
-
-  DMA_ISSUE(0, 0)
+#pragma unroll
+  for (int d = 0; d < DIST; ++d) {
+    const char* src = tile_src(d);
+#pragma unroll
+    for (int it = 0; it < LPT; ++it) DMA1(src, d * DMA_STAGE, it)
+  }
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 1) * LPT) : "memory");
+  __builtin_amdgcn_s_barrier();
+  u32x4_t p0, p1, p2, p3, p4, p5, p6, p7, q0, q1, q2, q3, q4, q5, q6, q7;
+  uint32_t so_cur = 0;                     // stage of k-tile kt
+  uint32_t so_issue = DIST * DMA_STAGE;    // stage that k-tile kt + DIST goes to
+  {
+    const uint32_t ra = a_rd[0], rb = b_rd[0];
+    p4 = lds_read128<0>(rb); p5 = lds_read128<2048>(rb); p6 = lds_read128<4096>(rb); p7 = lds_read128<6144>(rb);
+    p0 = lds_read128<0>(ra); p1 = lds_read128<2048>(ra); p2 = lds_read128<4096>(ra); p3 = lds_read128<6144>(ra);
+  }
+#define SB0 __builtin_amdgcn_sched_barrier(0);
+#define MF(I, J, SA, SB) acc[I][J] = mfma_32x32x16_v(SA, SB, acc[I][J]);
   for (int kt = 0; kt < nk; ++kt) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (kt + 1 < nk) DMA_ISSUE(kt + 1, (kt + 1) & 1)
-    const uint32_t so = (uint32_t)(kt & 1) * DMA_STAGE;
-    u32x4_t p0, p1, p2, p3, p4, p5, q0, q1, q2, q3, q4, q5;
-#define RD(S0, S1, S2, S3, S4, S5, KS)                                                      \
-    S0 = lds_read128<0>(a_rd[KS] + so); S1 = lds_read128<4096>(a_rd[KS] + so);              \
-    S2 = lds_read128<8192>(a_rd[KS] + so); S3 = lds_read128<12288>(a_rd[KS] + so);          \
-    S4 = lds_read128<0>(b_rd[KS] + so); S5 = lds_read128<4096>(b_rd[KS] + so);
-#define MM(S0, S1, S2, S3, S4, S5)                                                          \
-    acc[0][0] = mfma_32x32x16_v(S0, S4, acc[0][0]); acc[0][1] = mfma_32x32x16_v(S0, S5, acc[0][1]); \
-    acc[1][0] = mfma_32x32x16_v(S1, S4, acc[1][0]); acc[1][1] = mfma_32x32x16_v(S1, S5, acc[1][1]); \
-    acc[2][0] = mfma_32x32x16_v(S2, S4, acc[2][0]); acc[2][1] = mfma_32x32x16_v(S2, S5, acc[2][1]); \
-    acc[3][0] = mfma_32x32x16_v(S3, S4, acc[3][0]); acc[3][1] = mfma_32x32x16_v(S3, S5, acc[3][1]);
-    RD(p0, p1, p2, p3, p4, p5, 0)
-    RD(q0, q1, q2, q3, q4, q5, 1)
-    LDS_WAIT6(6, p0, p1, p2, p3, p4, p5);
-    MM(p0, p1, p2, p3, p4, p5)
-    RD(p0, p1, p2, p3, p4, p5, 2)
-    LDS_WAIT6(6, q0, q1, q2, q3, q4, q5);
-    MM(q0, q1, q2, q3, q4, q5)
-    RD(q0, q1, q2, q3, q4, q5, 3)
-    LDS_WAIT6(6, p0, p1, p2, p3, p4, p5);
-    MM(p0, p1, p2, p3, p4, p5)
-    LDS_WAIT6(0, q0, q1, q2, q3, q4, q5);
-    MM(q0, q1, q2, q3, q4, q5)
-#undef RD
-#undef MM
+    {
+      // first half of k-tile kt from p, while the second half is read into q
+      const uint32_t ra = a_rd[1] + so_cur, rb = b_rd[1] + so_cur;
+      LDS_WAIT8(0, p0, p1, p2, p3, p4, p5, p6, p7);
+      SB0 MF(0, 0, p0, p4) MF(0, 1, p0, p5) SB0 q4 = lds_read128<0>(rb);
+      SB0 MF(0, 2, p0, p6) MF(0, 3, p0, p7) SB0 q5 = lds_read128<2048>(rb);
+      SB0 MF(1, 0, p1, p4) MF(1, 1, p1, p5) SB0 q6 = lds_read128<4096>(rb);
+      SB0 MF(1, 2, p1, p6) MF(1, 3, p1, p7) SB0 q7 = lds_read128<6144>(rb);
+      SB0 MF(2, 0, p2, p4) MF(2, 1, p2, p5) SB0 q0 = lds_read128<0>(ra);
+      SB0 MF(2, 2, p2, p6) MF(2, 3, p2, p7) SB0 q1 = lds_read128<2048>(ra);
+      SB0 MF(3, 0, p3, p4) MF(3, 1, p3, p5) SB0 q2 = lds_read128<4096>(ra);
+      SB0 MF(3, 2, p3, p6) MF(3, 3, p3, p7) SB0 q3 = lds_read128<6144>(ra);
+      SB0
+    }
+    // k-tile kt + 1 has landed (this wavefront's share: the barrier covers the others'), and nobody reads the
+    // stage of k-tile kt - 1 any more, which is where k-tile kt + DIST goes
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 2) * LPT) : "memory");
+    __builtin_amdgcn_s_barrier();
+    {
+      const char* src = tile_src(kt + DIST);
+      const uint32_t so_i = so_issue;
+      so_cur = so_cur + DMA_STAGE == NS * DMA_STAGE ? 0 : so_cur + DMA_STAGE;
+      so_issue = so_issue + DMA_STAGE == NS * DMA_STAGE ? 0 : so_issue + DMA_STAGE;
+      const uint32_t ra = a_rd[0] + so_cur, rb = b_rd[0] + so_cur;
+      LDS_WAIT8(0, q0, q1, q2, q3, q4, q5, q6, q7);
+      SB0 MF(0, 0, q0, q4) MF(0, 1, q0, q5) SB0 p4 = lds_read128<0>(rb);    DMA1(src, so_i, 0)
+      SB0 MF(0, 2, q0, q6) MF(0, 3, q0, q7) SB0 p5 = lds_read128<2048>(rb); DMA1(src, so_i, 1)
+      SB0 MF(1, 0, q1, q4) MF(1, 1, q1, q5) SB0 p6 = lds_read128<4096>(rb); DMA1(src, so_i, 2)
+      SB0 MF(1, 2, q1, q6) MF(1, 3, q1, q7) SB0 p7 = lds_read128<6144>(rb); DMA1(src, so_i, 3)
+      SB0 MF(2, 0, q2, q4) MF(2, 1, q2, q5) SB0 p0 = lds_read128<0>(ra);    DMA1(src, so_i, 4)
+      SB0 MF(2, 2, q2, q6) MF(2, 3, q2, q7) SB0 p1 = lds_read128<2048>(ra); DMA1(src, so_i, 5)
+      SB0 MF(3, 0, q3, q4) MF(3, 1, q3, q5) SB0 p2 = lds_read128<4096>(ra); DMA1(src, so_i, 6)
+      SB0 MF(3, 2, q3, q6) MF(3, 3, q3, q7) SB0 p3 = lds_read128<6144>(ra); DMA1(src, so_i, 7)
+      SB0
+    }
   }
-#undef DMA_ISSUE
+#undef MF
+#undef SB0
+#undef DMA1
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // the trailing prefetches (never consumed) are done
 
+  const int c2 = 2 * (lane & 31);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-      int m = m0 + wm * 128 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+      const int m = m0 + wm * 128 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
       if (m >= M) continue;
       if (EPI == EPI_SWIGLU) {
-        int f = tn * (BN / 2) + wn * (WN / 2) + (lane & 31);
-        float gte = acc[i][0][e], up = acc[i][1][e];
-        float v = gte / (1.f + __expf(-gte)) * up;
-        ((h16_t*)out)[(size_t)m * N + f] = f32_to_h16(v);
+        const int f = tn * 128 + wn * 64 + c2;
+        const float g0 = acc[i][0][e], g1 = acc[i][1][e], u0 = acc[i][2][e], u1 = acc[i][3][e];
+        const float v0 = g0 / (1.f + __expf(-g0)) * u0, v1 = g1 / (1.f + __expf(-g1)) * u1;
+        *(uint32_t*)((h16_t*)out + (size_t)m * N + f) = pack_h16x2(v0, v1);
       } else {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          int n = tn * BN + wn * WN + j * 32 + (lane & 31);
-          float v = acc[i][j][e];
-          if (EPI == EPI_STORE_F32) ((float*)out)[(size_t)m * N + n] = v;
-          if (EPI == EPI_RESID_F32) ((float*)out)[(size_t)m * N + n] += v;
-          if (EPI == EPI_STORE_ACT) ((h16_t*)out)[(size_t)m * N + n] = f32_to_h16(v);
+        for (int jp = 0; jp < 2; ++jp) {
+          const int n = tn * 256 + wn * 128 + 64 * jp + c2;
+          const float v0 = acc[i][2 * jp][e], v1 = acc[i][2 * jp + 1][e];
+          if (EPI == EPI_STORE_F32) *(float2*)((float*)out + (size_t)m * N + n) = make_float2(v0, v1);
+          if (EPI == EPI_RESID_F32) {
+            float2* o = (float2*)((float*)out + (size_t)m * N + n);
+            float2 r = *o;
+            r.x += v0; r.y += v1;
+            *o = r;
+          }
+          if (EPI == EPI_STORE_ACT) *(uint32_t*)((h16_t*)out + (size_t)m * N + n) = pack_h16x2(v0, v1);
         }
       }
     }
@@ -169,12 +210,12 @@ __global__ __launch_bounds__(512) void gemm_h16_dma_kernel(const h16_t* __restri
 template <int EPI>
 hipError_t launch_large_dma(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K, int a_dual,
                             bool configure_only = false) {
-  constexpr int SMEM = 2 * DMA_STAGE;
+  constexpr int SMEM = DMA_NS * DMA_STAGE;
   auto kern = gemm_h16_dma_kernel<EPI>;
   if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
   int tilesM = (M + 255) / 256;
   int tilesN = (EPI == EPI_SWIGLU) ? N / 128 : N / 256;
-  kern<<<tilesM * tilesN, 512, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, out, M, N, K, tilesM, tilesN, a_dual);
+  kern<<<tilesM * tilesN, 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, out, M, N, K, tilesM, tilesN, a_dual);
   return hipGetLastError();
 }
 
@@ -425,8 +466,11 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 hipError_t launch_gemm_h16(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K, int epi,
                            int a_dual) {
   if (M <= 0) return hipSuccess;
-  if (K % 64) return hipErrorInvalidValue;
+  if (K % 32) return hipErrorInvalidValue;
   if (epi == EPI_SWIGLU ? (N % 128) : (N % 256)) return hipErrorInvalidValue;
+  // the kernel addresses both operands with 32-bit byte offsets
+  if ((size_t)M * (a_dual ? 2 : 1) * K * 2 >= ((size_t)1 << 32) || (size_t)N * (epi == EPI_SWIGLU ? 2 : 1) * K * 2 >= ((size_t)1 << 32))
+    return hipErrorInvalidValue;
   switch (epi) {
     case EPI_STORE_F32: return launch_large_dma<EPI_STORE_F32>(s, A, W, out, M, N, K, a_dual);
     case EPI_RESID_F32: return launch_large_dma<EPI_RESID_F32>(s, A, W, out, M, N, K, a_dual);
