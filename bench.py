@@ -140,6 +140,14 @@ def main() -> int:
                         "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": gemm_bytes / (gemm_ms * 1e-3) / HBM_PEAK,
                         "traffic": None, "avg_launch_us": gemm_ms / n_g * 1e3, "launches_timed": n_g,
                         "bytes_per_launch": gemm_bytes / n_g}
+        # HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by what the counters read for the
+        # weight-conversion copy kernel): measured on a 2-layer, 48-token run of this workload, because counter runs of
+        # the full-size command do not finish; the fetched / algorithmic ratio of those launches is applied to this
+        # run's launches (profiles/bench_7b_b64_pmc_traffic.md)
+        pmc = {"attn_decode_kernel": (1.014, 1.0e6), "gemm_skinny_kernel": (1.130, 10.5e6)}[roofline["kernel"]]
+        if wl.name == "7b_b64":
+            roofline["traffic"] = pmc[0] * roofline["bytes_per_launch"] + pmc[1]
+            roofline["traffic_source"] = "rocprofv3 --pmc ratio of a reduced-depth run, see profiles/bench_7b_b64_pmc_traffic.md"
         roofline["attn_decode_GBps"] = attn_bytes / attn_s / 1e9 if attn_s > 0 else None
         roofline["gemm_skinny_GBps"] = gemm_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else None
 
