@@ -17,6 +17,16 @@ __device__ __forceinline__ h16_t f32_to_h16(float f) {
   _Float16 h = (_Float16)fminf(fmaxf(f, -65504.f), 65504.f);
   return __builtin_bit_cast(uint16_t, h);
 }
+// 16-byte load of data that is read exactly once and in whole cache lines per instruction (cached K/V pages in
+// decode): the nontemporal hint keeps it from displacing reusable lines in L2 and measures 10-12 % faster than a
+// plain load on MI355X for read-only streams (6.7 vs 6.0 TB/s).  Not for the decode GEMM's weights: there one
+// instruction takes half a line per row and the other half would be fetched from HBM again.
+typedef unsigned u32x4_native_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+  u32x4_native_t v = __builtin_nontemporal_load((const u32x4_native_t*)p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 __device__ __forceinline__ uint32_t pack_h16x2(float lo, float hi) {
   return (uint32_t)f32_to_h16(lo) | ((uint32_t)f32_to_h16(hi) << 16);
 }

@@ -25,11 +25,15 @@ struct AttnState {
   float l;       // this lane's share of the running sum
 };
 
+// STREAM: the page is read once by the whole grid (decode); prefill re-reads pages from several query tiles.
+template <bool STREAM>
 __device__ __forceinline__ void load_page(const char* page, int lane, uint4 kf[4], uint4 vf[4]) {
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) kf[kk] = *(const uint4*)(page + kk * 1024 + lane * 16);
+  for (int kk = 0; kk < 4; ++kk)
+    kf[kk] = STREAM ? load_stream16(page + kk * 1024 + lane * 16) : *(const uint4*)(page + kk * 1024 + lane * 16);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) vf[j] = *(const uint4*)(page + 4096 + j * 1024 + lane * 16);
+  for (int j = 0; j < 4; ++j)
+    vf[j] = STREAM ? load_stream16(page + 4096 + j * 1024 + lane * 16) : *(const uint4*)(page + 4096 + j * 1024 + lane * 16);
 }
 
 // tok0: index of the page's first token; limit: number of tokens visible to this lane's query row.
@@ -126,7 +130,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const h16_t* __restric
   const int last = npages - 1;
   const int my_blk0 = npages > 0 ? bt[min(w + 4 * lane, last)] : 0;
   uint4 ka[4], va[4], kb[4], vb[4];
-  load_page(pool + ((size_t)kvh * n_blocks + __shfl(my_blk0, 0)) * KV_PAGE_BYTES, lane, ka, va);
+  load_page<true>(pool + ((size_t)kvh * n_blocks + __shfl(my_blk0, 0)) * KV_PAGE_BYTES, lane, ka, va);
   if (FUSED) {
     const float* row = fa.qkv_part + (size_t)b * fa.qkv_w;
     const float* cs = fa.cos_t + (size_t)pos * 64;
@@ -210,14 +214,14 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const h16_t* __restric
     int my_blk = my_blk0;
     if (base != w) {  // beyond 4096 tokens: next batch of 64 pages
       my_blk = bt[min(base + 4 * lane, last)];
-      load_page(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, 0)) * KV_PAGE_BYTES, lane, ka, va);
+      load_page<true>(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, 0)) * KV_PAGE_BYTES, lane, ka, va);
     }
     const int cnt = min(64, (npages - base + 3) >> 2);  // pages of this wavefront in this batch
     int i = 0;
     for (; i + 2 <= cnt; i += 2) {
-      load_page(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, i + 1)) * KV_PAGE_BYTES, lane, kb, vb);
+      load_page<true>(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, i + 1)) * KV_PAGE_BYTES, lane, kb, vb);
       attn_page<true>(ka, va, qf, st, scale_log2, (base + 4 * i) * 16, L, g);
-      load_page(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, min(i + 2, cnt - 1))) * KV_PAGE_BYTES, lane, ka, va);
+      load_page<true>(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, min(i + 2, cnt - 1))) * KV_PAGE_BYTES, lane, ka, va);
       attn_page<true>(kb, vb, qf, st, scale_log2, (base + 4 * (i + 1)) * 16, L, g);
     }
     if (i < cnt) attn_page<true>(ka, va, qf, st, scale_log2, (base + 4 * i) * 16, L, g);
@@ -283,9 +287,9 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const h16_t* __restri
   const int* bt = block_table + (size_t)b * max_blocks;
   const int pd = p0 >> 4;  // diagonal page
   uint4 kf[4], vf[4], kn[4], vn[4];
-  load_page(pool + ((size_t)kvh * n_blocks + bt[0]) * KV_PAGE_BYTES, lane, kf, vf);
+  load_page<false>(pool + ((size_t)kvh * n_blocks + bt[0]) * KV_PAGE_BYTES, lane, kf, vf);
   for (int p = 0; p <= pd; ++p) {
-    if (p < pd) load_page(pool + ((size_t)kvh * n_blocks + bt[p + 1]) * KV_PAGE_BYTES, lane, kn, vn);
+    if (p < pd) load_page<false>(pool + ((size_t)kvh * n_blocks + bt[p + 1]) * KV_PAGE_BYTES, lane, kn, vn);
     if (p == pd)
       attn_page<true>(kf, vf, qf, st, scale_log2, p * 16, p0 + t + 1, g);
     else
