@@ -378,11 +378,6 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __res
   }
 }
 
-inline bool skinny_force_narrow() {
-  static const bool v = getenv("RLHF_SKINNY_NARROW") && atoi(getenv("RLHF_SKINNY_NARROW"));
-  return v;
-}
-
 template <int MB, int NW>
 hipError_t launch_skinny_nw(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K, int nsplit,
                             int a_dual, bool configure_only) {
@@ -434,7 +429,7 @@ hipError_t launch_skinny(hipStream_t s, const void* A, const void* W, float* par
     return launch_skinny_nw<MB, 8>(s, A, W, part, M, Nw, K, nsplit, a_dual, true);
   }
   // eight wavefronts (128 rows of W per workgroup) when the shape allows: half the activation-slice traffic
-  const bool wide = Nw % 128 == 0 && (a_dual ? true : 4 * MB >= 8) && MB <= 8 && !skinny_force_narrow();
+  const bool wide = Nw % 128 == 0 && (a_dual ? true : 4 * MB >= 8) && MB <= 8;
   return wide ? launch_skinny_nw<MB, 8>(s, A, W, part, M, Nw, K, nsplit, a_dual, false)
               : launch_skinny_nw<MB, 4>(s, A, W, part, M, Nw, K, nsplit, a_dual, false);
 }
@@ -497,7 +492,7 @@ hipError_t gemm_configure() {
 
 int gemm_skinny_pick_split(int M, int Nw, int K) {
   (void)M;
-  int tiles = (Nw % 128 == 0 && !skinny_force_narrow()) ? Nw / 128 : Nw / 64, steps = K / SK;
+  int tiles = Nw % 128 == 0 ? Nw / 128 : Nw / 64, steps = K / SK;
   int want = (768 + tiles - 1) / tiles;
   if (want > 8) want = 8;
   if (want > steps) want = steps;
