@@ -21,11 +21,18 @@ enum { RLHF_GEN_GEMM_TILED = 0, RLHF_GEN_GEMM_STREAMING = 1, RLHF_GEN_GEMM_FP32 
 /* epilogues of the tiled GEMM */
 enum { RLHF_GEN_EPI_STORE_F32 = 0, RLHF_GEN_EPI_RESID_F32 = 1, RLHF_GEN_EPI_SWIGLU = 2, RLHF_GEN_EPI_STORE_H16 = 3 };
 
+/* Re-order an fp16 weight matrix W [N, K] (row-major) into the library's working layout, which the 16-bit GEMMs below
+ * expect (rlhf_gen_init does the same to the Actor's matrices while converting them from bf16): tiles of 16 rows x
+ * 128 columns, 4 KB each, stored row-block major, and inside a tile the halves in the order
+ * [k/32 % 4][row % 16][k % 32].  N % 16 == 0, K % 128 == 0; the two buffers must not overlap. */
+int rlhf_gen_op_tile_weights(void* stream, const void* w_rowmajor, void* w_tiled, int32_t N, int32_t K);
+
 /* out = A[M,K] * W[N,K]^T (the projections of a decoder layer, y = x W^T).
- * 16-bit operands are IEEE fp16 (the library's working format; bf16 weights are converted at init).
+ * 16-bit operands are IEEE fp16 (the library's working format; bf16 weights are converted at init); for the TILED and
+ * STREAMING kinds W must be in the working layout made by rlhf_gen_op_tile_weights (A is plain row-major).
  *   TILED     fp16 A and W; epilogue selects out: fp32 [M,N] store, fp32 [M,N] accumulate, fp16 [M,N] store, or
  *             SWIGLU where W is [2N, K] (gate rows then up rows) and out is fp16 [M,N] = silu(gate) * up.
- *             N % 256 == 0 (N % 128 for SWIGLU), K % 64 == 0.
+ *             N % 256 == 0 (N % 128 for SWIGLU), K % 128 == 0.
  *   STREAMING fp16 A and W, M <= 256, N % 64 == 0, K % 128 == 0; out is fp32 [nsplit, M, N] partial sums whose
  *             sum over the first axis is the product.  nsplit in [1, K/128].  With epilogue SWIGLU instead: W is
  *             [2N, K] (gate rows then up rows), N % 32 == 0, no split, out is fp16 [M, N] = silu(gate) * up.

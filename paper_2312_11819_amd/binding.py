@@ -31,7 +31,7 @@ EXPORTS = [
     "rlhf_gen_plan_capacity", "rlhf_gen_context_bytes",
     "rlhf_gen_get_logits",
     "rlhf_gen_last_timing", "rlhf_gen_set_profile", "rlhf_gen_get_profile", "rlhf_gen_last_error", "rlhf_gen_destroy",
-    "rlhf_gen_op_gemm", "rlhf_gen_op_rope_append", "rlhf_gen_op_attn_decode", "rlhf_gen_op_attn_prefill",
+    "rlhf_gen_op_tile_weights", "rlhf_gen_op_gemm", "rlhf_gen_op_rope_append", "rlhf_gen_op_attn_decode", "rlhf_gen_op_attn_prefill",
     "rlhf_gen_op_sample",
 ]
 
@@ -108,6 +108,7 @@ def lib() -> C.CDLL:
         L.rlhf_gen_last_error.restype = C.c_char_p
         L.rlhf_gen_destroy.argtypes = [C.c_void_p]
         L.rlhf_gen_destroy.restype = None
+        L.rlhf_gen_op_tile_weights.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32]
         L.rlhf_gen_op_gemm.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                        C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         L.rlhf_gen_op_rope_append.argtypes = [C.c_void_p] * 9 + [C.c_int32] * 7
@@ -323,6 +324,11 @@ class Context:
 
 
 # -- single-operation entry points -------------------------------------------------------------------
+def rlhf_gen_op_tile_weights(w_rowmajor: torch.Tensor, w_tiled: torch.Tensor) -> int:
+    N, K = w_rowmajor.shape
+    return lib().rlhf_gen_op_tile_weights(None, _ptr(w_rowmajor), _ptr(w_tiled), N, K)
+
+
 def rlhf_gen_op_gemm(kind, A, W, out, M, N, K, epilogue=0, nsplit=1, a_pairs=0) -> int:
     return lib().rlhf_gen_op_gemm(None, kind, _ptr(A), _ptr(W), _ptr(out), M, N, K, epilogue, nsplit, a_pairs)
 

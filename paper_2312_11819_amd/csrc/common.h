@@ -18,9 +18,9 @@ __device__ __forceinline__ h16_t f32_to_h16(float f) {
   return __builtin_bit_cast(uint16_t, h);
 }
 // 16-byte load of data that is read exactly once and in whole cache lines per instruction (cached K/V pages in
-// decode): the nontemporal hint keeps it from displacing reusable lines in L2 and measures 10-12 % faster than a
-// plain load on MI355X for read-only streams (6.7 vs 6.0 TB/s).  Not for the decode GEMM's weights: there one
-// instruction takes half a line per row and the other half would be fetched from HBM again.
+// decode, the tiled weights of the decode GEMM): the nontemporal hint keeps it from displacing reusable lines in L2
+// and measures 10-12 % faster than a plain load on MI355X for read-only streams (6.7 vs 6.0 TB/s).  It loses when
+// one instruction takes only part of a line and another instruction the rest (the line is fetched twice).
 typedef unsigned u32x4_native_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 load_stream16(const void* p) {
   u32x4_native_t v = __builtin_nontemporal_load((const u32x4_native_t*)p);
@@ -75,6 +75,15 @@ __device__ __forceinline__ float wave_max(float v) {
 //   keys:   16 B chunk (kk, lane) at kk*1024 + lane*16 holds K[token lane&15][dims 8*(4kk + (lane>>4)) .. +8]
 //   values: 16 B chunk (j, lane) at 4096 + j*1024 + lane*16 holds, for tokens 4*(lane>>4) .. +4,
 //           V[token][dim 32j + (lane&15)] in its first 8 B and V[token][dim 32j + 16 + (lane&15)] in the rest
+// Working layout of a 16-bit weight matrix W [N, K] (N % 16 == 0, K % 128 == 0): tiles of 16 rows x 128 columns,
+// 4 KB each, row-block major ([N/16][K/128] tiles); inside a tile the halves are ordered [k/32 % 4][row % 16][k/8 % 4][k % 8].
+// A wavefront of the weight-streaming GEMM then takes one k-step of its 16 rows with four loads of 1 KB of
+// consecutive bytes (whole cache lines, so the nontemporal hint pays), and the large-tile GEMM finds the 64 bytes
+// of one (row, 32-column k-tile) together.  Offset in halves of element (n, k):
+__host__ __device__ __forceinline__ size_t wtile_offset(int n, int k, int K) {
+  return ((size_t)(n >> 4) * (size_t)(K >> 7) + (size_t)(k >> 7)) * 2048 + (size_t)(((k >> 5) & 3) * 512 + (n & 15) * 32 + (k & 31));
+}
+
 constexpr int KV_PAGE_TOKENS = 16;
 constexpr int KV_HEAD_DIM = 128;
 constexpr int KV_PAGE_BYTES = 8192;

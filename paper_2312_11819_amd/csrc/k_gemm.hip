@@ -83,7 +83,11 @@ __global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restri
   for (int it = 0; it < LPT; ++it) {
     const int row = 16 * ((wave & 1) * 8 + it) + (lane >> 2);
     const int grow = loads_a ? min(m0 + row, M - 1) : wrow(row);
-    go[it] = (uint32_t)grow * (uint32_t)(loads_a && a_dual ? 2 * K : K) * 2u + (uint32_t)(((lane & 3) ^ ((row >> 2) & 3)) * 16);
+    const uint32_t chunk = (uint32_t)((lane & 3) ^ ((row >> 2) & 3));
+    // A is row-major; W is in the tiled working layout (16-row x 128-column tiles of 4 KB, a row's 64 bytes of one
+    // k-tile together)
+    go[it] = loads_a ? (uint32_t)grow * (uint32_t)(a_dual ? 2 * K : K) * 2u + chunk * 16u
+                     : (uint32_t)(wtile_offset(grow, 0, K) * 2) + chunk * 16u;
   }
   const int nkw = K / 32;                 // k-tiles of W
   const int nk = a_dual ? 2 * nkw : nkw;  // k-tiles of the product
@@ -93,7 +97,9 @@ __global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restri
   // tile KT of this wavefront's operand (past the end: the last tile again, into a stage nobody reads any more)
   auto tile_src = [&](int kt) -> const char* {
     kt = min(kt, nk - 1);
-    return gbase + (size_t)(loads_a ? kt : (kt >= nkw ? kt - nkw : kt)) * 64;
+    if (loads_a) return gbase + (size_t)kt * 64;
+    const int kw = kt >= nkw ? kt - nkw : kt;
+    return gbase + (size_t)(kw >> 2) * 4096 + (size_t)(kw & 3) * 1024;
   };
 #define DMA1(SRC, SOFF, IT) \
   __builtin_amdgcn_global_load_lds((g_void*)((SRC) + go[IT]), (lds_void*)(dma_dst + (SOFF) + (IT) * 1024), 16, 0, 0);
@@ -256,7 +262,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __res
   for (int i = 0; i < MB; ++i) acc[i] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
   const int wrow = GLU ? ((t < 8) ? n0 + 8 * w + t : (Nw >> 1) + n0 + 8 * w + (t - 8)) : n0 + 16 * w + t;
-  const h16_t* wp = W + (size_t)wrow * K + 8 * g;
+  const h16_t* wp = W + wtile_offset(wrow, 8 * g, K);   // W is in the tiled working layout: 2048 halves per k-step
   // Activation slice: 16 MB rows x 16 chunks of 16 B per k-step, MB chunks per thread.  Rows beyond M are read
   // from row M - 1 instead: they only feed output columns that are never stored.
   const h16_t* xp[XL];
@@ -290,7 +296,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __res
 #define SKINNY_LOAD(S, I)                                                                                \
   {                                                                                                      \
     const size_t ko = step_off(I);                                                                       \
-    _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) S.w[kk] = *(const uint4*)(wp + ko + kk * 32);       \
+    _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) S.w[kk] = load_stream16(wp + ko * 16 + kk * 512);       \
     _Pragma("unroll") for (int it = 0; it < XL; ++it) S.x[it] = *(const uint4*)(xp[it] + ko);            \
   }
   // one k-step on slot S (LDS buffer PAR)
@@ -461,7 +467,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 hipError_t launch_gemm_h16(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K, int epi,
                            int a_dual) {
   if (M <= 0) return hipSuccess;
-  if (K % 32) return hipErrorInvalidValue;
+  if (K % 128) return hipErrorInvalidValue;   // W comes in 128-column tiles
   if (epi == EPI_SWIGLU ? (N % 128) : (N % 256)) return hipErrorInvalidValue;
   // the kernel addresses both operands with 32-bit byte offsets
   if ((size_t)M * (a_dual ? 2 : 1) * K * 2 >= ((size_t)1 << 32) || (size_t)N * (epi == EPI_SWIGLU ? 2 : 1) * K * 2 >= ((size_t)1 << 32))

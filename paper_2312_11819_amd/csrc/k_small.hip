@@ -348,67 +348,57 @@ hipError_t launch_advance(hipStream_t s, int* seq_len, int* step, int B) {
   return hipGetLastError();
 }
 
-// One-time conversion of a bf16 weight matrix to the fp16 working format (exact unless |w| < 2^-17, where fp16
-// subnormals keep an absolute accuracy of 2^-25; saturates beyond 65504).
-__global__ void bf16_to_h16_kernel(const bf16_t* src, h16_t* dst, size_t n) {  // src == dst is allowed
-  size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 8;
-  if (i + 8 <= n) {
-    uint4 v = *(const uint4*)(src + i);
-    uint4 o;
-    o.x = pack_h16x2(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u));
-    o.y = pack_h16x2(__uint_as_float(v.y << 16), __uint_as_float(v.y & 0xffff0000u));
-    o.z = pack_h16x2(__uint_as_float(v.z << 16), __uint_as_float(v.z & 0xffff0000u));
-    o.w = pack_h16x2(__uint_as_float(v.w << 16), __uint_as_float(v.w & 0xffff0000u));
-    *(uint4*)(dst + i) = o;
-  } else {
-    for (; i < n; ++i) dst[i] = f32_to_h16(bf16_to_f32(src[i]));
-  }
-}
-
-// The same conversion with a low-rank update folded in: dst[n, k] = fp16(src[n, k] + scale * sum_r B[n, r] A[r, k])
-// (LoRA adapters of the trainable Actor, Sec. V-A "Hyperparameters"; the sum runs over r ascending in fp32).
-// One thread owns eight consecutive k of one row, so src == dst is allowed.  cols must be a multiple of 8.
-__global__ void bf16_lora_to_h16_kernel(const bf16_t* src, h16_t* dst, int rows, int cols,
-                                        const bf16_t* __restrict__ A, const bf16_t* __restrict__ Bm, int rank,
-                                        float scale) {
+// Conversion of a bf16 weight matrix [rows, cols] to the fp16 working format in the tiled working layout of
+// common.h (exact unless |w| < 2^-17, where fp16 subnormals keep an absolute accuracy of 2^-25; saturates beyond
+// 65504).  One thread moves eight consecutive columns of one row.  With A != nullptr a low-rank update is folded in:
+// dst[n, k] = fp16(src[n, k] + scale * sum_r B[row0 + n, r] A[r, k]) (LoRA adapters of the trainable Actor, Sec. V-A
+// "Hyperparameters"; the sum runs over r ascending in fp32).  src and dst must not overlap (the layouts differ).
+// SRC16: 0 = bf16 source, 1 = fp16 source (already in the working format, only re-tiled).
+template <int SRC16>
+__global__ void to_h16_tiled_kernel(const uint16_t* __restrict__ src, h16_t* __restrict__ dst, int rows, int cols,
+                                    const bf16_t* __restrict__ A, const bf16_t* __restrict__ Bm, int rank, float scale,
+                                    int row0) {
   const int cpr = cols >> 3;
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (size_t)rows * cpr) return;
   const int n = (int)(idx / cpr), k = (int)(idx % cpr) * 8;
-  float d[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  for (int r = 0; r < rank; ++r) {
-    const float b = bf16_to_f32(Bm[(size_t)n * rank + r]);
-    uint4 a = *(const uint4*)(A + (size_t)r * cols + k);
-    const uint32_t aw[4] = {a.x, a.y, a.z, a.w};
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      d[2 * j] = fmaf(b, __uint_as_float(aw[j] << 16), d[2 * j]);
-      d[2 * j + 1] = fmaf(b, __uint_as_float(aw[j] & 0xffff0000u), d[2 * j + 1]);
-    }
-  }
   uint4 v = *(const uint4*)(src + (size_t)n * cols + k);
-  const uint32_t vw[4] = {v.x, v.y, v.z, v.w};
-  uint32_t ow[4];
+  uint4 o = v;
+  if (SRC16 == 0) {
+    float d[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (A != nullptr) {
+      for (int r = 0; r < rank; ++r) {
+        const float b = bf16_to_f32(Bm[(size_t)(row0 + n) * rank + r]);
+        uint4 a = *(const uint4*)(A + (size_t)r * cols + k);
+        const uint32_t aw[4] = {a.x, a.y, a.z, a.w};
 #pragma unroll
-  for (int j = 0; j < 4; ++j)
-    ow[j] = pack_h16x2(fmaf(scale, d[2 * j], __uint_as_float(vw[j] << 16)),
-                       fmaf(scale, d[2 * j + 1], __uint_as_float(vw[j] & 0xffff0000u)));
-  *(uint4*)(dst + (size_t)n * cols + k) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+        for (int j = 0; j < 4; ++j) {
+          d[2 * j] = fmaf(b, __uint_as_float(aw[j] << 16), d[2 * j]);
+          d[2 * j + 1] = fmaf(b, __uint_as_float(aw[j] & 0xffff0000u), d[2 * j + 1]);
+        }
+      }
+    }
+    const uint32_t vw[4] = {v.x, v.y, v.z, v.w};
+    uint32_t ow[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      ow[j] = pack_h16x2(fmaf(scale, d[2 * j], __uint_as_float(vw[j] << 16)),
+                         fmaf(scale, d[2 * j + 1], __uint_as_float(vw[j] & 0xffff0000u)));
+    o = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+  }
+  *(uint4*)(dst + wtile_offset(n, k, cols)) = o;
 }
 
-hipError_t launch_bf16_lora_to_h16(hipStream_t s, const void* src, void* dst, int rows, int cols, const void* A,
-                                   const void* B, int rank, float scale) {
+hipError_t launch_to_h16_tiled(hipStream_t s, const void* src, int src_is_h16, void* dst, int rows, int cols, const void* A,
+                               const void* B, int rank, float scale, int row0) {
   if (rows <= 0 || cols <= 0) return hipSuccess;
-  if (cols % 8 || rank < 1) return hipErrorInvalidValue;
+  if (rows % 16 || cols % 128 || (A != nullptr && (rank < 1 || B == nullptr))) return hipErrorInvalidValue;
   size_t threads = (size_t)rows * (cols / 8);
-  bf16_lora_to_h16_kernel<<<(unsigned)((threads + 255) / 256), 256, 0, s>>>((const bf16_t*)src, (h16_t*)dst, rows, cols,
-                                                                         (const bf16_t*)A, (const bf16_t*)B, rank, scale);
-  return hipGetLastError();
-}
-
-hipError_t launch_bf16_to_h16(hipStream_t s, const void* src, void* dst, size_t n) {
-  if (n == 0) return hipSuccess;
-  size_t threads = (n + 7) / 8;
-  bf16_to_h16_kernel<<<(unsigned)((threads + 255) / 256), 256, 0, s>>>((const bf16_t*)src, (h16_t*)dst, n);
+  unsigned grid = (unsigned)((threads + 255) / 256);
+  if (src_is_h16)
+    to_h16_tiled_kernel<1><<<grid, 256, 0, s>>>((const uint16_t*)src, (h16_t*)dst, rows, cols, nullptr, nullptr, 0, 0.f, 0);
+  else
+    to_h16_tiled_kernel<0><<<grid, 256, 0, s>>>((const uint16_t*)src, (h16_t*)dst, rows, cols, (const bf16_t*)A,
+                                               (const bf16_t*)B, rank, A ? scale : 0.f, row0);
   return hipGetLastError();
 }

@@ -49,10 +49,11 @@ hipError_t launch_swiglu(hipStream_t s, const float* gu, int nsplit, size_t part
                          int M, int F);
 hipError_t launch_advance(hipStream_t s, int* seq_len, int* step, int B);
 // bf16 -> fp16 copy of n elements (working copies of the weight matrices).
-hipError_t launch_bf16_to_h16(hipStream_t s, const void* src, void* dst, size_t n);
-// dst = fp16(src + scale * B A): src/dst [rows, cols] (may alias), A bf16 [rank, cols], B bf16 [rows, rank]
-hipError_t launch_bf16_lora_to_h16(hipStream_t s, const void* src, void* dst, int rows, int cols, const void* A,
-                                   const void* B, int rank, float scale);
+// dst (tiled working layout, see common.h) = fp16(src + scale * B[row0.., :] A): src row-major [rows, cols], bf16 or
+// (src_is_h16) fp16; A bf16 [rank, cols] and B bf16 [.., rank] may be NULL (plain conversion).  rows % 16 == 0,
+// cols % 128 == 0; src and dst must not overlap.
+hipError_t launch_to_h16_tiled(hipStream_t s, const void* src, int src_is_h16, void* dst, int rows, int cols, const void* A,
+                               const void* B, int rank, float scale, int row0);
 
 // One layer's pool is [Hkv][n_blocks] pages: the pages a sequence gets from consecutive block ids are contiguous per
 // KV head, so a workgroup streams one contiguous region and different workgroups spread over the memory channels.

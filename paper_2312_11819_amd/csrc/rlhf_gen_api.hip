@@ -47,6 +47,7 @@ struct rlhf_gen_ctx {
   std::vector<void*> allocs;
   size_t dev_bytes = 0;   // sum of the device allocations requested
   bool dry_run = false;   // capacity planning: walk the allocation sequence without allocating
+  char* conv_tmp = nullptr;  // in-place mode: staging buffer of the weight conversion (one slab of rows)
   char* kv_pool = nullptr;
   size_t layer_pool_bytes = 0;
   int n_blocks = 0, max_blocks = 0;
@@ -670,6 +671,31 @@ static int validate_cfg(const rlhf_gen_cfg* cfg) {
   return RLHF_GEN_OK;
 }
 
+// One weight matrix [rows, cols] from the caller's bf16 row-major storage into the fp16 tiled working layout at dst,
+// optionally with an adapter folded in.  dst == src (in-place mode) goes through the staging buffer in slabs of
+// whole 16-row blocks: a slab's tiled image occupies exactly the bytes of its row-major rows.
+constexpr int CONV_SLAB_ROWS = 1024;
+static int convert_matrix(rlhf_gen_ctx* c, const void* src, void* dst, int rows, int cols, const rlhf_gen_lora_pair* pr,
+                          float scale) {
+  const void* A = pr ? pr->a : nullptr;
+  const void* Bm = pr ? pr->b : nullptr;
+  const int rank = pr ? pr->rank : 0;
+  hipError_t e = hipSuccess;
+  if (dst != src) {
+    e = launch_to_h16_tiled(c->stream, src, 0, dst, rows, cols, A, Bm, rank, scale, 0);
+  } else {
+    if (!c->conv_tmp) return fail(c, RLHF_GEN_E_STATE, "in-place conversion without a staging buffer");
+    for (int r0 = 0; r0 < rows && e == hipSuccess; r0 += CONV_SLAB_ROWS) {
+      const int nr = std::min(CONV_SLAB_ROWS, rows - r0);
+      char* slab = (char*)const_cast<void*>(src) + (size_t)r0 * cols * 2;
+      e = launch_to_h16_tiled(c->stream, slab, 0, c->conv_tmp, nr, cols, A, Bm, rank, scale, r0);
+      if (e == hipSuccess) e = hipMemcpyAsync(slab, c->conv_tmp, (size_t)nr * cols * 2, hipMemcpyDeviceToDevice, c->stream);
+    }
+  }
+  if (e != hipSuccess) return fail(c, RLHF_GEN_E_DEVICE, "weight conversion failed: %s", hipGetErrorString(e));
+  return RLHF_GEN_OK;
+}
+
 // Every device and pinned-host allocation of a context, in one place.  With c->dry_run set nothing is allocated or
 // launched and c->dev_bytes ends up as the context's device footprint.
 static int allocate_all(rlhf_gen_ctx* c) {
@@ -695,30 +721,28 @@ static int allocate_all(rlhf_gen_ctx* c) {
   if (c->bf16) {
     // fp16 working copies of the projection matrices (or an in-place rewrite if the caller allows it)
     const bool in_place = (g.flags & RLHF_GEN_FLAG_CONVERT_IN_PLACE) != 0;
-    auto convert = [&](const void* src, const void** dst, size_t n) -> int {
+    if (in_place) {
+      const int widest = std::max(std::max(g.d_model, g.d_ffn), g.n_heads * g.head_dim);
+      A_(dev_alloc(c, &c->conv_tmp, (size_t)CONV_SLAB_ROWS * widest * 2, false));
+    }
+    auto convert = [&](const void* src, const void** dst, int rows, int cols) -> int {
       void* d = const_cast<void*>(src);
       if (!in_place) {
         char* fresh = nullptr;
-        int r = dev_alloc(c, &fresh, n * 2, false);
+        int r = dev_alloc(c, &fresh, (size_t)rows * cols * 2, false);
         if (r) return r;
         d = fresh;
       }
-      if (!c->dry_run && launch_bf16_to_h16(c->stream, src, d, n) != hipSuccess) {
-        c->err = "weight conversion kernel failed to launch";
-        return RLHF_GEN_E_DEVICE;
-      }
       *dst = d;
-      return RLHF_GEN_OK;
+      return c->dry_run ? RLHF_GEN_OK : convert_matrix(c, src, d, rows, cols, nullptr, 0.f);
     };
-    const size_t dq = (size_t)qkv_w * g.d_model, dw = (size_t)g.d_model * g.n_heads * g.head_dim,
-                 dg = (size_t)2 * g.d_ffn * g.d_model, dd = (size_t)g.d_model * g.d_ffn;
     for (int l = 0; l < g.n_layers; ++l) {
-      A_(convert(c->src_wqkv[l], &c->wqkv[l], dq));
-      A_(convert(c->src_wo[l], &c->wo[l], dw));
-      A_(convert(c->src_w_gate_up[l], &c->w_gate_up[l], dg));
-      A_(convert(c->src_w_down[l], &c->w_down[l], dd));
+      A_(convert(c->src_wqkv[l], &c->wqkv[l], qkv_w, g.d_model));
+      A_(convert(c->src_wo[l], &c->wo[l], g.d_model, g.n_heads * g.head_dim));
+      A_(convert(c->src_w_gate_up[l], &c->w_gate_up[l], 2 * g.d_ffn, g.d_model));
+      A_(convert(c->src_w_down[l], &c->w_down[l], g.d_model, g.d_ffn));
     }
-    A_(convert(c->src_lm_head, &c->lm_head, (size_t)g.vocab * g.d_model));
+    A_(convert(c->src_lm_head, &c->lm_head, g.vocab, g.d_model));
   }
   A_(dev_alloc(c, &c->kv_pool, c->layer_pool_bytes * g.n_layers, true));
   A_(dev_alloc(c, &c->d_table, sizeof(int) * (size_t)g.max_batch * c->max_blocks, true));
@@ -1150,9 +1174,8 @@ int rlhf_gen_update_weights(rlhf_gen_ctx* c, const rlhf_gen_weights* w, const rl
     const bool in_place = (g.flags & RLHF_GEN_FLAG_CONVERT_IN_PLACE) != 0;
     auto refresh = [&](const void* src, const void** work, int rows, int cols, const rlhf_gen_lora_pair* pr) -> int {
       void* dst = in_place ? const_cast<void*>(src) : const_cast<void*>(*work);
-      hipError_t e = pr ? launch_bf16_lora_to_h16(c->stream, src, dst, rows, cols, pr->a, pr->b, pr->rank, lora->scale)
-                        : launch_bf16_to_h16(c->stream, src, dst, (size_t)rows * cols);
-      if (e != hipSuccess) return fail(c, RLHF_GEN_E_DEVICE, "weight conversion kernel failed: %s", hipGetErrorString(e));
+      int r = convert_matrix(c, src, dst, rows, cols, pr, lora ? lora->scale : 0.f);
+      if (r) return r;
       if (*work != dst) moved = true;
       *work = dst;
       return RLHF_GEN_OK;
@@ -1205,6 +1228,12 @@ void rlhf_gen_destroy(rlhf_gen_ctx* c) {
 }
 
 // ---- single-operation entry points (kernel parity tests) ----------------------------------------
+int rlhf_gen_op_tile_weights(void* stream, const void* w_rowmajor, void* w_tiled, int32_t N, int32_t K) {
+  if (!w_rowmajor || !w_tiled || w_rowmajor == w_tiled || N < 16 || K < 128 || N % 16 || K % 128) return RLHF_GEN_E_INVALID;
+  hipError_t e = launch_to_h16_tiled((hipStream_t)stream, w_rowmajor, 1, w_tiled, N, K, nullptr, nullptr, 0, 0.f, 0);
+  return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;
+}
+
 int rlhf_gen_op_gemm(void* stream, int kind, const void* A, const void* W, void* out, int32_t M, int32_t N, int32_t K,
                      int32_t epilogue, int32_t nsplit, int32_t a_pairs) {
   hipStream_t s = (hipStream_t)stream;

@@ -19,16 +19,37 @@ def B():
     return binding
 
 
+def _tiled(B, w: torch.Tensor) -> torch.Tensor:
+    """Device copy of the fp16 matrix w [N, K] in the working layout of the 16-bit GEMMs."""
+    src = w.cuda().contiguous()
+    dst = torch.empty_like(src)
+    assert B.rlhf_gen_op_tile_weights(src, dst) == 0
+    return dst
+
+
+def test_tile_weights_layout(B):
+    """Tiles of 16 rows x 128 columns, row-block major; inside a tile [k/32 % 4][row % 16][k % 32]."""
+    N, K = 48, 384
+    w = torch.arange(N * K, dtype=torch.int32).remainder(30000).to(torch.int16).view(N, K)
+    got = _tiled(B, w.view(torch.float16)).cpu().view(torch.int16).flatten()
+    want = w.view(N // 16, 16, K // 128, 4, 32).permute(0, 2, 3, 1, 4).contiguous().flatten()
+    assert torch.equal(got, want)
+    t = torch.zeros(16, 128, dtype=torch.float16, device="cuda")
+    assert B.rlhf_gen_op_tile_weights(t, t) == B.E_INVALID                   # in place is not possible
+    assert B.rlhf_gen_op_tile_weights(torch.zeros(8, 128, dtype=torch.float16, device="cuda"),
+                                      torch.zeros(8, 128, dtype=torch.float16, device="cuda")) == B.E_INVALID
+
+
 def _rand(shape, seed, scale=1.0, dtype=torch.float16):
     g = torch.Generator().manual_seed(seed)
     return (torch.randn(*shape, generator=g) * scale).to(dtype)
 
 
-@pytest.mark.parametrize("M,N,K", [(300, 512, 256), (1024, 256, 448), (7, 256, 64), (513, 768, 1024)])
+@pytest.mark.parametrize("M,N,K", [(300, 512, 256), (1024, 256, 384), (7, 256, 128), (513, 768, 1024)])
 def test_gemm_tiled_store_and_accumulate(B, M, N, K):
     a, w = _rand((M, K), 1), _rand((N, K), 2, 0.05)
     ref = a.double() @ w.double().T
-    A, W = a.cuda(), w.cuda()
+    A, W = a.cuda(), _tiled(B, w)
     out = torch.full((M, N), 7.0, dtype=torch.float32, device="cuda")
     assert B.rlhf_gen_op_gemm(B.GEMM_TILED, A, W, out, M, N, K, B.EPI_STORE_F32) == 0
     torch.cuda.synchronize()
@@ -49,7 +70,7 @@ def test_gemm_tiled_swiglu(B, M, F, K):
     gu = a.double() @ w.double().T
     ref = OT.silu(gu[:, :F]) * gu[:, F:]
     out = torch.zeros((M, F), dtype=torch.float16, device="cuda")
-    assert B.rlhf_gen_op_gemm(B.GEMM_TILED, a.cuda(), w.cuda(), out, M, F, K, B.EPI_SWIGLU) == 0
+    assert B.rlhf_gen_op_gemm(B.GEMM_TILED, a.cuda(), _tiled(B, w), out, M, F, K, B.EPI_SWIGLU) == 0
     torch.cuda.synchronize()
     err = (out.cpu().double() - ref).abs()
     assert (err <= ref.abs() * 2 ** -11 + 1e-4).all()
@@ -61,7 +82,7 @@ def test_gemm_streaming(B, M, N, K, ns):
     a, w = _rand((M, K), 5), _rand((N, K), 6, 0.05)
     ref = a.double() @ w.double().T
     part = torch.full((ns, M, N), float("nan"), dtype=torch.float32, device="cuda")
-    assert B.rlhf_gen_op_gemm(B.GEMM_STREAMING, a.cuda(), w.cuda(), part, M, N, K, 0, ns) == 0
+    assert B.rlhf_gen_op_gemm(B.GEMM_STREAMING, a.cuda(), _tiled(B, w), part, M, N, K, 0, ns) == 0
     torch.cuda.synchronize()
     got = part.cpu().double().sum(0)
     assert (got - ref).abs().max() < 1e-5 * math.sqrt(K) + 1e-6
@@ -73,13 +94,13 @@ def test_gemm_streaming_swiglu(B, M, F, K):
     gu = a.double() @ w.double().T
     ref = OT.silu(gu[:, :F]) * gu[:, F:]
     out = torch.zeros((M, F), dtype=torch.float16, device="cuda")
-    assert B.rlhf_gen_op_gemm(B.GEMM_STREAMING, a.cuda(), w.cuda(), out, M, F, K, B.EPI_SWIGLU, 1) == 0
+    assert B.rlhf_gen_op_gemm(B.GEMM_STREAMING, a.cuda(), _tiled(B, w), out, M, F, K, B.EPI_SWIGLU, 1) == 0
     torch.cuda.synchronize()
     err = (out.cpu().double() - ref).abs()
     assert (err <= ref.abs() * 2 ** -11 + 1e-4).all()
 
 
-@pytest.mark.parametrize("kind,M,N,K,ns", [("tiled", 300, 512, 256, 1), ("tiled", 1024, 256, 192, 1),
+@pytest.mark.parametrize("kind,M,N,K,ns", [("tiled", 300, 512, 256, 1), ("tiled", 1024, 256, 384, 1),
                                             ("stream", 64, 256, 512, 2), ("stream", 17, 128, 128, 1), ("stream", 128, 192, 1024, 3)])
 def test_gemm_with_activation_pairs(B, kind, M, N, K, ns):
     g = torch.Generator().manual_seed(31)
@@ -91,11 +112,11 @@ def test_gemm_with_activation_pairs(B, kind, M, N, K, ns):
     a = torch.cat([hi, lo], dim=1).contiguous().cuda()                      # [M, 2K]
     if kind == "tiled":
         out = torch.zeros((M, N), dtype=torch.float32, device="cuda")
-        assert B.rlhf_gen_op_gemm(B.GEMM_TILED, a, w.cuda(), out, M, N, K, B.EPI_STORE_F32, 1, 1) == 0
+        assert B.rlhf_gen_op_gemm(B.GEMM_TILED, a, _tiled(B, w), out, M, N, K, B.EPI_STORE_F32, 1, 1) == 0
         got = out.cpu().double()
     else:
         part = torch.zeros((ns, M, N), dtype=torch.float32, device="cuda")
-        assert B.rlhf_gen_op_gemm(B.GEMM_STREAMING, a, w.cuda(), part, M, N, K, 0, ns, 1) == 0
+        assert B.rlhf_gen_op_gemm(B.GEMM_STREAMING, a, _tiled(B, w), part, M, N, K, 0, ns, 1) == 0
         got = part.cpu().double().sum(0)
     torch.cuda.synchronize()
     # the pair carries ~22 bits, so the result is far more accurate than a single fp16 operand would allow
