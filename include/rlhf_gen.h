@@ -52,9 +52,10 @@ enum {
   RLHF_GEN_FLAG_GENERIC_GEMM = 4u,   /* decode uses the large-tile GEMM instead of the weight-streaming one (cross-check) */
   RLHF_GEN_FLAG_FUSED_ROPE = 16u,    /* decode folds RoPE + KV append into the attention kernel (one launch fewer per layer;
                                         measured 2 % slower per step on MI355X at the 7B shape, so it is off by default) */
-  RLHF_GEN_FLAG_CONVERT_IN_PLACE = 8u /* bf16 mode: rewrite the caller's projection matrices and LM head to fp16 in place
-                                         instead of allocating working copies (for models that fill the card; the
-                                         buffers then no longer hold bf16 and must not be reused as such) */
+  RLHF_GEN_FLAG_CONVERT_IN_PLACE = 8u /* bf16 mode: rewrite the caller's projection matrices and LM head in place into
+                                         the fp16 working format (tiled layout) instead of allocating working copies
+                                         (for models that fill the card; the buffers then no longer hold row-major
+                                         bf16 and must not be reused as such); costs a 1024-row staging buffer */
 };
 
 /* Model and capacity description.  Architecture: pre-norm decoder, RMSNorm (eps inside the
@@ -65,7 +66,7 @@ typedef struct {
   int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
   float rms_eps, rope_theta;
   int32_t dtype;          /* RLHF_GEN_DTYPE_*: storage type of the caller's weights.  bf16: the projection matrices are
-                             converted once to fp16 working copies (exact unless |w| < 2^-17), every MFMA operand,
+                             converted once to fp16 working copies in a tiled layout (exact unless |w| < 2^-17), every MFMA operand,
                              activation and the KV cache is fp16 (bf16's 8 significant bits cannot meet the parity
                              tolerance over 32 layers), accumulation / residual / softmax / logits are fp32.  Like any
                              fp16 inference it assumes activations within +-65504 (they saturate there).  fp32 is a
