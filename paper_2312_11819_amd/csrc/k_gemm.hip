@@ -238,7 +238,7 @@ constexpr int SK_ROW = SK * 2 + 16;     // bytes per LDS row (padded)
 template <int MB, int D, bool GLU, bool DUAL, int NW>
 __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __restrict__ X, const h16_t* __restrict__ W,
                                                           float* __restrict__ part, int M, int Nw, int K,
-                                                          int steps_per_split) {
+                                                          int steps_per_split, int plane_rows) {
   static_assert(D == 2 || D == 4, "ring depth 2 or 4");
   // DUAL: X rows are [hi (K) | lo (K)] fp16 pairs; the LDS tile holds the hi rows followed by the lo rows and every
   // weight fragment is multiplied with both.
@@ -376,7 +376,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __res
     }
     return;
   }
-  float* dst = part + (size_t)blockIdx.y * M * Nw;
+  // split-K plane s holds plane_rows rows (>= M: the caller may compute a taller output in several row slabs)
+  float* dst = part + (size_t)blockIdx.y * plane_rows * Nw;
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
     int m = mb * 16 + t;
@@ -386,7 +387,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __res
 
 template <int MB, int NW>
 hipError_t launch_skinny_nw(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K, int nsplit,
-                            int a_dual, bool configure_only) {
+                            int a_dual, int plane_rows, bool configure_only) {
   constexpr int SMEM = 2 * 16 * MB * SK_ROW;
   constexpr int D = MB <= 4 ? 4 : 2;
   constexpr bool HAS_DUAL = MB <= 8;          // the doubled slice of the largest variant would not fit in LDS
@@ -405,7 +406,7 @@ hipError_t launch_skinny_nw(hipStream_t s, const void* A, const void* W, float* 
   if (nsplit == 0) {  // fused SwiGLU: W = [2F, K], output fp16 [M, F], no split
     if (a_dual) return hipErrorInvalidValue;
     if constexpr (HAS_SINGLE)
-      gemm_skinny_kernel<MB, D, true, false, NW><<<dim3(Nw / rows_per_wg, 1), 64 * NW, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, K / SK);
+      gemm_skinny_kernel<MB, D, true, false, NW><<<dim3(Nw / rows_per_wg, 1), 64 * NW, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, K / SK, plane_rows);
     else
       return hipErrorInvalidValue;
     return hipGetLastError();
@@ -414,12 +415,12 @@ hipError_t launch_skinny_nw(hipStream_t s, const void* A, const void* W, float* 
   int per = (steps + nsplit - 1) / nsplit;
   if (a_dual) {
     if constexpr (HAS_DUAL)
-      gemm_skinny_kernel<MB, 2, false, true, NW><<<dim3(Nw / rows_per_wg, nsplit), 64 * NW, 2 * SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, per);
+      gemm_skinny_kernel<MB, 2, false, true, NW><<<dim3(Nw / rows_per_wg, nsplit), 64 * NW, 2 * SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, per, plane_rows);
     else
       return hipErrorInvalidValue;
   } else {
     if constexpr (HAS_SINGLE)
-      gemm_skinny_kernel<MB, D, false, false, NW><<<dim3(Nw / rows_per_wg, nsplit), 64 * NW, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, per);
+      gemm_skinny_kernel<MB, D, false, false, NW><<<dim3(Nw / rows_per_wg, nsplit), 64 * NW, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, per, plane_rows);
     else
       return hipErrorInvalidValue;
   }
@@ -428,16 +429,16 @@ hipError_t launch_skinny_nw(hipStream_t s, const void* A, const void* W, float* 
 
 template <int MB>
 hipError_t launch_skinny(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K, int nsplit,
-                         int a_dual, bool configure_only = false) {
+                         int a_dual, int plane_rows, bool configure_only = false) {
   if (configure_only) {
-    hipError_t e = launch_skinny_nw<MB, 4>(s, A, W, part, M, Nw, K, nsplit, a_dual, true);
+    hipError_t e = launch_skinny_nw<MB, 4>(s, A, W, part, M, Nw, K, nsplit, a_dual, plane_rows, true);
     if (e != hipSuccess) return e;
-    return launch_skinny_nw<MB, 8>(s, A, W, part, M, Nw, K, nsplit, a_dual, true);
+    return launch_skinny_nw<MB, 8>(s, A, W, part, M, Nw, K, nsplit, a_dual, plane_rows, true);
   }
   // eight wavefronts (128 rows of W per workgroup) when the shape allows: half the activation-slice traffic
   const bool wide = Nw % 128 == 0 && (a_dual ? true : 4 * MB >= 8) && MB <= 8;
-  return wide ? launch_skinny_nw<MB, 8>(s, A, W, part, M, Nw, K, nsplit, a_dual, false)
-              : launch_skinny_nw<MB, 4>(s, A, W, part, M, Nw, K, nsplit, a_dual, false);
+  return wide ? launch_skinny_nw<MB, 8>(s, A, W, part, M, Nw, K, nsplit, a_dual, plane_rows, false)
+              : launch_skinny_nw<MB, 4>(s, A, W, part, M, Nw, K, nsplit, a_dual, plane_rows, false);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -488,11 +489,11 @@ hipError_t gemm_configure() {
   if ((e = launch_large_dma<EPI_RESID_F32>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, true)) != hipSuccess) return e;
   if ((e = launch_large_dma<EPI_SWIGLU>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, true)) != hipSuccess) return e;
   if ((e = launch_large_dma<EPI_STORE_ACT>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, true)) != hipSuccess) return e;
-  if ((e = launch_skinny<1>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, true)) != hipSuccess) return e;
-  if ((e = launch_skinny<2>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, true)) != hipSuccess) return e;
-  if ((e = launch_skinny<4>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, true)) != hipSuccess) return e;
-  if ((e = launch_skinny<8>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, true)) != hipSuccess) return e;
-  if ((e = launch_skinny<16>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, true)) != hipSuccess) return e;
+  if ((e = launch_skinny<1>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, 0, true)) != hipSuccess) return e;
+  if ((e = launch_skinny<2>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, 0, true)) != hipSuccess) return e;
+  if ((e = launch_skinny<4>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, 0, true)) != hipSuccess) return e;
+  if ((e = launch_skinny<8>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, 0, true)) != hipSuccess) return e;
+  if ((e = launch_skinny<16>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, 0, true)) != hipSuccess) return e;
   return hipSuccess;
 }
 
@@ -508,14 +509,15 @@ int gemm_skinny_pick_split(int M, int Nw, int K) {
 }
 
 hipError_t launch_gemm_skinny_h16(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K,
-                                  int nsplit, int a_dual) {
+                                  int nsplit, int a_dual, int plane_rows) {
   if (M <= 0) return hipSuccess;
-  if (K % SK || Nw % 64 || M > 256 || nsplit < 0) return hipErrorInvalidValue;
-  if (M <= 16) return launch_skinny<1>(s, A, W, part, M, Nw, K, nsplit, a_dual);
-  if (M <= 32) return launch_skinny<2>(s, A, W, part, M, Nw, K, nsplit, a_dual);
-  if (M <= 64) return launch_skinny<4>(s, A, W, part, M, Nw, K, nsplit, a_dual);
-  if (M <= 128) return launch_skinny<8>(s, A, W, part, M, Nw, K, nsplit, a_dual);
-  return launch_skinny<16>(s, A, W, part, M, Nw, K, nsplit, a_dual);
+  if (plane_rows <= 0) plane_rows = M;
+  if (K % SK || Nw % 64 || M > 256 || nsplit < 0 || plane_rows < M) return hipErrorInvalidValue;
+  if (M <= 16) return launch_skinny<1>(s, A, W, part, M, Nw, K, nsplit, a_dual, plane_rows);
+  if (M <= 32) return launch_skinny<2>(s, A, W, part, M, Nw, K, nsplit, a_dual, plane_rows);
+  if (M <= 64) return launch_skinny<4>(s, A, W, part, M, Nw, K, nsplit, a_dual, plane_rows);
+  if (M <= 128) return launch_skinny<8>(s, A, W, part, M, Nw, K, nsplit, a_dual, plane_rows);
+  return launch_skinny<16>(s, A, W, part, M, Nw, K, nsplit, a_dual, plane_rows);
 }
 
 hipError_t launch_gemm_f32(hipStream_t s, const float* A, const float* W, float* out, int M, int N, int K,

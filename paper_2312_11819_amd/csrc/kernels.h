@@ -12,15 +12,17 @@ enum GemmEpilogue {
 
 // ---- 16-bit MFMA path (fp16 operands, fp32 accumulation) ----
 // Large-tile GEMM: out = A[M,K] (fp16) * W[N,K]^T (fp16).  Needs N % 256 == 0 (F % 128 == 0 for SWIGLU),
-// K % 64 == 0; rows of A beyond M are never read.  a_dual: A is [M, 2K], each row = [hi (K) | lo (K)], and
+// K % 128 == 0, W in the tiled working layout (common.h); rows of A beyond M are never read.  a_dual: A is [M, 2K], each row = [hi (K) | lo (K)], and
 // out = (hi + lo) W^T.
 hipError_t launch_gemm_h16(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K, int epi,
                            int a_dual);
 // Weight-streaming GEMM for M <= 256 rows: writes fp32 partial sums part[ks][M][Nw] (Nw = rows of W)
 // for ks < nsplit; the consumer kernel adds them.  nsplit = 0 selects the fused SwiGLU form: W = [2F, K]
 // (gate rows, then up rows; Nw = 2F), no split, and `part` receives fp16 [M, F] = silu(gate) * up.
+// plane_rows (0 = M): rows per split-K plane of `part`, for callers that fill a taller output in row slabs.
+// W is in the tiled working layout (common.h); with a_dual M is at most 128.
 hipError_t launch_gemm_skinny_h16(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K,
-                                  int nsplit, int a_dual);
+                                  int nsplit, int a_dual, int plane_rows = 0);
 int gemm_skinny_pick_split(int M, int Nw, int K);
 // Per-device one-time kernel attribute setup; call before the first launch and outside any stream capture.
 hipError_t gemm_configure();

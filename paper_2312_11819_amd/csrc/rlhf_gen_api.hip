@@ -266,6 +266,17 @@ int forward_layers_generic(rlhf_gen_ctx* c, const RowSet& r) {
 
 // Decode step on the weight-streaming GEMM: every projection writes split-K partial sums, and the next
 // small kernel (RoPE+append, RMSNorm+residual, SwiGLU) adds them up while doing its own work.
+// Projection whose input travels as hi|lo pairs: the streaming kernel takes up to 128 such rows, taller batches go
+// in slabs of 128 rows that share the split-K planes of `part` (the weights are then streamed once per slab).
+static int skinny_pairs(rlhf_gen_ctx* c, const void* A, const void* W, int B, int Nw, int K, int nsplit, const char* what) {
+  for (int r0 = 0; r0 < B; r0 += 128) {
+    const int rows = std::min(128, B - r0);
+    LAUNCH(c, launch_gemm_skinny_h16(c->stream, (const uint16_t*)A + (size_t)r0 * 2 * K, W, c->part + (size_t)r0 * Nw, rows, Nw,
+                                     K, nsplit, 1, B), what);
+  }
+  return RLHF_GEN_OK;
+}
+
 int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
   const rlhf_gen_cfg& g = c->cfg;
   const int d = g.d_model, Hq = g.n_heads, Hkv = g.n_kv_heads, h = g.head_dim, F = g.d_ffn;
@@ -280,7 +291,7 @@ int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
     LAUNCH(c, launch_rmsnorm(s, c->x, pending ? c->part : nullptr, pending, (size_t)B * d, c->attn_norm[l], 1, c->y, 1,
                              B, d, g.rms_eps, nullptr, 1), "rmsnorm");
     prof_mark(c, RLHF_GEN_PROF_NORM);
-    LAUNCH(c, launch_gemm_skinny_h16(s, c->y, c->wqkv[l], c->part, B, qkv_w, d, c->ks_qkv, 1), "gemm_skinny qkv");
+    if (int rc = skinny_pairs(c, c->y, c->wqkv[l], B, qkv_w, d, c->ks_qkv, "gemm_skinny qkv")) return rc;
     prof_mark(c, RLHF_GEN_PROF_GEMM_QKV);
     size_t st = (size_t)B * qkv_w;
     if (!(c->cfg.flags & RLHF_GEN_FLAG_FUSED_ROPE)) {
@@ -295,7 +306,7 @@ int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
                                              c->n_blocks, c->d_seq_len, c->ab, B, Hq, Hkv), "attn_decode_fused");
     }
     prof_mark(c, RLHF_GEN_PROF_ATTN);
-    LAUNCH(c, launch_gemm_skinny_h16(s, c->ab, c->wo[l], c->part, B, d, Hq * h, c->ks_wo, 1), "gemm_skinny wo");
+    if (int rc = skinny_pairs(c, c->ab, c->wo[l], B, d, Hq * h, c->ks_wo, "gemm_skinny wo")) return rc;
     prof_mark(c, RLHF_GEN_PROF_GEMM_WO);
     LAUNCH(c, launch_rmsnorm(s, c->x, c->part, c->ks_wo, (size_t)B * d, c->ffn_norm[l], 1, c->y, 1, B, d, g.rms_eps,
                              nullptr, 0), "rmsnorm");
@@ -315,8 +326,9 @@ int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
 }
 
 bool use_streaming(const rlhf_gen_ctx* c, int B) {
-  // the weight-streaming GEMM takes hi|lo activation pairs up to 128 rows; larger batches use the tiled GEMM
-  return c->bf16 && !(c->cfg.flags & RLHF_GEN_FLAG_GENERIC_GEMM) && B <= 128;
+  // the weight-streaming GEMM takes up to 256 rows (hi|lo activation pairs in slabs of 128); larger batches use the
+  // tiled GEMM
+  return c->bf16 && !(c->cfg.flags & RLHF_GEN_FLAG_GENERIC_GEMM) && B <= 256;
 }
 
 // Kernels of one decode step, in order, ending with the sampler and the counter update.
@@ -772,7 +784,7 @@ static int allocate_all(rlhf_gen_ctx* c) {
   A_(dev_alloc(c, &c->ys, as * ((size_t)c->score_cap + 256) * g.d_model, true));
   A_(dev_alloc(c, &c->slogits, 4 * (size_t)c->score_cap * g.vocab, true));
   if (c->bf16) {
-    const int Bm = std::min(g.max_batch, 128);
+    const int Bm = std::min(g.max_batch, 256);
     c->ks_qkv = gemm_skinny_pick_split(Bm, qkv_w, g.d_model);
     c->ks_wo = gemm_skinny_pick_split(Bm, g.d_model, g.n_heads * g.head_dim);
     c->ks_gu = gemm_skinny_pick_split(Bm, 2 * g.d_ffn, g.d_model);
