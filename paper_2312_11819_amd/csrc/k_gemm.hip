@@ -7,6 +7,8 @@
 //   gemm_f32_kernel     : plain-ALU fp32 GEMM for the small fp32 configuration.
 #include <stdlib.h>
 
+#include <algorithm>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -280,7 +282,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __res
   // The starting point is a function of the rows, not of the workgroup shape, so that every output element is
   // accumulated in the same order whichever instantiation (4 or 8 wavefronts, any batch width) computes it.
   const unsigned grp = GLU ? (unsigned)n0 >> 6 : (unsigned)n0 >> 7;
-  const int rot = nst > 0 ? (int)((grp * 5u + blockIdx.y * 3u) % (unsigned)nst) : 0;
+  // (the pair-input variant walks k in order, like the resident-slice kernel that serves the same GEMMs at <= 64 rows)
+  const int rot = (nst > 0 && !DUAL) ? (int)((grp * 5u + blockIdx.y * 3u) % (unsigned)nst) : 0;
   (void)NT;
   // Loads are issued without any branch around them (a step index past the end re-reads the last step, which
   // hits in cache): with straight-line code the compiler can keep D - 1 steps of loads in flight and wait only
@@ -388,6 +391,132 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __res
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Weight-streaming GEMM with the activation slice resident in LDS, for pair-input projections of up to 64 rows
+// whose K is a multiple of 512 (QKV and output projection at d_model 4096 / 5120).  Grid (G, ns), ns = K / 512:
+// workgroup (j, s) loads the slice X[:, 512 s .. 512 s + 512) (hi rows, then lo rows: 128 x 1 KB for 64 batch rows)
+// into LDS once and then streams the k-range of the 128-row weight tiles j, j + G, j + 2 G, ... against it, writing
+// one [M, 128] partial tile per weight tile into split plane s.  Compared with gemm_skinny_kernel the slice is
+// fetched once per workgroup instead of once per weight tile (the counters showed those re-reads missing L2 under
+// the weight stream and adding a quarter to the HBM traffic of these GEMMs), there is no barrier in the k loop, and
+// the register ring of weight loads runs on across tile boundaries.  Accumulation order per output element is the
+// same as in gemm_skinny_kernel<.., DUAL = true> (k ascending inside the split, hi then lo), so the two give
+// identical bits.
+constexpr int XRES_KS = 512;                  // k extent of a resident slice
+constexpr int XRES_ROW = XRES_KS * 2 + 16;    // bytes per LDS row (padded: 16 lanes x 16 B cover all 64 banks)
+
+template <int MB>
+__global__ __launch_bounds__(512) void gemm_skinny_xres_kernel(const h16_t* __restrict__ X, const h16_t* __restrict__ W,
+                                                               float* __restrict__ part, int M, int Nw, int K,
+                                                               int plane_rows) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  constexpr int XROWS = 32 * MB;              // hi rows of 16 MB batch rows, then their lo rows
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, t = lane & 15, g = lane >> 4;
+  const int j = blockIdx.x, G = gridDim.x, s = blockIdx.y;
+  const int T = Nw >> 7;                      // 128-row weight tiles
+  const int ntiles = j < T ? (T - 1 - j) / G + 1 : 0;
+  const int F = 4 * ntiles;                   // k-steps of this workgroup, tile after tile
+  const int nsteps = K >> 7;
+
+  // weight fragment of flattened step f: tile j + (f / 4) G, 16-row block w of it, k-step 4 s + f % 4
+  const h16_t* wlane = W + (size_t)(t * 32 + g * 8);
+  auto w_off = [&](int f) -> size_t {
+    f = min(f, F - 1);
+    return ((size_t)((j + (f >> 2) * G) * 8 + w) * nsteps + (size_t)(4 * s + (f & 3))) * 2048;
+  };
+  struct Slot { uint4 w[4]; };
+  Slot r0, r1, r2, r3;
+#define XRES_LOAD(S, FI)                                                                              \
+  {                                                                                                   \
+    const h16_t* p_ = wlane + w_off(FI);                                                              \
+    _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) S.w[kk] = *(const uint4*)(p_ + kk * 512);        \
+  }
+  if (F > 0) {
+    XRES_LOAD(r0, 0)
+    XRES_LOAD(r1, 1)
+    XRES_LOAD(r2, 2)
+  }
+  // stage the slice: XROWS rows of 64 chunks (16 bytes each); rows beyond M repeat row M - 1 (never stored)
+  {
+    constexpr int NCH = XROWS * 64, PER = NCH / 512;
+    uint4 v[PER];
+#pragma unroll
+    for (int it = 0; it < PER; ++it) {
+      const int c = it * 512 + tid, r = c >> 6, kc = c & 63;
+      const int rb = r % (16 * MB);
+      v[it] = *(const uint4*)(X + (size_t)min(rb, M - 1) * 2 * K + (r >= 16 * MB ? K : 0) + (size_t)s * XRES_KS + kc * 8);
+    }
+#pragma unroll
+    for (int it = 0; it < PER; ++it) {
+      const int c = it * 512 + tid, r = c >> 6, kc = c & 63;
+      *(uint4*)(smem + r * XRES_ROW + kc * 16) = v[it];
+    }
+  }
+  __syncthreads();
+
+  f32x4_t acc[MB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i) acc[i] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+  const char* xlane = smem + t * XRES_ROW + g * 16;
+  // one k-step (ST = 0..3 inside the slice) on slot S
+#define XRES_STEP(S, ST)                                                                              \
+  {                                                                                                   \
+    /* the slice never changes, so its fragments are loop invariant: keep the compiler from hoisting */ \
+    /* all of them out of the tile loop into registers it does not have */                            \
+    asm volatile("" ::: "memory");                                                                    \
+    _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                                \
+      uint4 xf[2 * MB];                                                                               \
+      _Pragma("unroll") for (int mb = 0; mb < 2 * MB; ++mb)                                           \
+          xf[mb] = *(const uint4*)(xlane + mb * 16 * XRES_ROW + (ST) * 256 + kk * 64);                \
+      _Pragma("unroll") for (int mb = 0; mb < 2 * MB; ++mb)                                           \
+          acc[mb % MB] = mfma_16x16x32(S.w[kk], xf[mb], acc[mb % MB]);                                \
+    }                                                                                                 \
+  }
+  for (int ti = 0; ti < ntiles; ++ti) {
+    const int f = 4 * ti;
+    XRES_LOAD(r3, f + 3)
+    XRES_STEP(r0, 0)
+    XRES_LOAD(r0, f + 4)
+    XRES_STEP(r1, 1)
+    XRES_LOAD(r1, f + 5)
+    XRES_STEP(r2, 2)
+    XRES_LOAD(r2, f + 6)
+    XRES_STEP(r3, 3)
+    float* dst = part + (size_t)s * plane_rows * Nw + (size_t)(j + ti * G) * 128 + 16 * w + 4 * g;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      const int m = mb * 16 + t;
+      if (m < M) *(float4*)(dst + (size_t)m * Nw) = make_float4(acc[mb][0], acc[mb][1], acc[mb][2], acc[mb][3]);
+      acc[mb] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+    }
+  }
+#undef XRES_STEP
+#undef XRES_LOAD
+}
+
+int g_num_cu = 256;  // compute units of the device, set by gemm_configure
+
+template <int MB>
+hipError_t launch_skinny_xres(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K, int plane_rows,
+                              bool configure_only = false) {
+  constexpr int SMEM = 32 * MB * XRES_ROW;
+  auto kern = gemm_skinny_xres_kernel<MB>;
+  if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+  const int ns = K / XRES_KS, T = Nw / 128;
+  const int G = std::max(1, std::min(T, g_num_cu / ns));
+  kern<<<dim3(G, ns), 512, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, Nw, K, plane_rows);
+  return hipGetLastError();
+}
+
+// the shapes the resident-slice kernel takes (and the split count it implies)
+// (with a single weight tile per workgroup nothing is reused and the up-front staging only delays the first MFMA:
+// measured slower than gemm_skinny_kernel, so at least two tiles per workgroup are required)
+inline bool skinny_xres_ok(int M, int Nw, int K, int nsplit) {
+  if (!(M <= 64 && Nw % 128 == 0 && K % XRES_KS == 0 && K / XRES_KS == nsplit && nsplit <= 16)) return false;
+  const int T = Nw / 128, G = std::max(1, std::min(T, g_num_cu / nsplit));
+  return T >= 2 * G;
+}
+
 template <int MB, int NW>
 hipError_t launch_skinny_nw(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K, int nsplit,
                             int a_dual, int plane_rows, bool configure_only) {
@@ -492,6 +621,15 @@ hipError_t gemm_configure() {
   if ((e = launch_large_dma<EPI_RESID_F32>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, true)) != hipSuccess) return e;
   if ((e = launch_large_dma<EPI_SWIGLU>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, true)) != hipSuccess) return e;
   if ((e = launch_large_dma<EPI_STORE_ACT>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, true)) != hipSuccess) return e;
+  {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+      g_num_cu = prop.multiProcessorCount;
+  }
+  if ((e = launch_skinny_xres<1>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, true)) != hipSuccess) return e;
+  if ((e = launch_skinny_xres<2>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, true)) != hipSuccess) return e;
+  if ((e = launch_skinny_xres<4>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, true)) != hipSuccess) return e;
   if ((e = launch_skinny<1>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, 0, true)) != hipSuccess) return e;
   if ((e = launch_skinny<2>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, 0, true)) != hipSuccess) return e;
   if ((e = launch_skinny<4>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, 0, true)) != hipSuccess) return e;
@@ -500,8 +638,10 @@ hipError_t gemm_configure() {
   return hipSuccess;
 }
 
-int gemm_skinny_pick_split(int M, int Nw, int K) {
+int gemm_skinny_pick_split(int M, int Nw, int K, int a_dual) {
   (void)M;
+  // pair-input projections: the split of the resident-slice kernel (512 columns per split) where it applies
+  if (a_dual && Nw % 128 == 0 && K % XRES_KS == 0 && K / XRES_KS <= 10) return K / XRES_KS;
   int tiles = Nw % 128 == 0 ? Nw / 128 : Nw / 64, steps = K / SK;
   int want = (768 + tiles - 1) / tiles;
   if (want > 8) want = 8;
@@ -516,6 +656,11 @@ hipError_t launch_gemm_skinny_h16(hipStream_t s, const void* A, const void* W, f
   if (M <= 0) return hipSuccess;
   if (plane_rows <= 0) plane_rows = M;
   if (K % SK || Nw % 64 || M > 256 || nsplit < 0 || plane_rows < M) return hipErrorInvalidValue;
+  if (a_dual && skinny_xres_ok(M, Nw, K, nsplit)) {
+    if (M <= 16) return launch_skinny_xres<1>(s, A, W, part, M, Nw, K, plane_rows);
+    if (M <= 32) return launch_skinny_xres<2>(s, A, W, part, M, Nw, K, plane_rows);
+    return launch_skinny_xres<4>(s, A, W, part, M, Nw, K, plane_rows);
+  }
   if (M <= 16) return launch_skinny<1>(s, A, W, part, M, Nw, K, nsplit, a_dual, plane_rows);
   if (M <= 32) return launch_skinny<2>(s, A, W, part, M, Nw, K, nsplit, a_dual, plane_rows);
   if (M <= 64) return launch_skinny<4>(s, A, W, part, M, Nw, K, nsplit, a_dual, plane_rows);

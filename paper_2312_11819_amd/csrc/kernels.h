@@ -23,7 +23,7 @@ hipError_t launch_gemm_h16(hipStream_t s, const void* A, const void* W, void* ou
 // W is in the tiled working layout (common.h); with a_dual M is at most 128.
 hipError_t launch_gemm_skinny_h16(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K,
                                   int nsplit, int a_dual, int plane_rows = 0);
-int gemm_skinny_pick_split(int M, int Nw, int K);
+int gemm_skinny_pick_split(int M, int Nw, int K, int a_dual = 0);
 // Per-device one-time kernel attribute setup; call before the first launch and outside any stream capture.
 hipError_t gemm_configure();
 

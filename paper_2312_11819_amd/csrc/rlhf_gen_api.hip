@@ -785,8 +785,8 @@ static int allocate_all(rlhf_gen_ctx* c) {
   A_(dev_alloc(c, &c->slogits, 4 * (size_t)c->score_cap * g.vocab, true));
   if (c->bf16) {
     const int Bm = std::min(g.max_batch, 256);
-    c->ks_qkv = gemm_skinny_pick_split(Bm, qkv_w, g.d_model);
-    c->ks_wo = gemm_skinny_pick_split(Bm, g.d_model, g.n_heads * g.head_dim);
+    c->ks_qkv = gemm_skinny_pick_split(Bm, qkv_w, g.d_model, 1);
+    c->ks_wo = gemm_skinny_pick_split(Bm, g.d_model, g.n_heads * g.head_dim, 1);
     c->ks_gu = gemm_skinny_pick_split(Bm, 2 * g.d_ffn, g.d_model);
     c->ks_down = gemm_skinny_pick_split(Bm, g.d_model, g.d_ffn);
     size_t pe = std::max(std::max((size_t)c->ks_qkv * qkv_w, (size_t)c->ks_wo * g.d_model),

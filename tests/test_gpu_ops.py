@@ -101,7 +101,11 @@ def test_gemm_streaming_swiglu(B, M, F, K):
 
 
 @pytest.mark.parametrize("kind,M,N,K,ns", [("tiled", 300, 512, 256, 1), ("tiled", 1024, 256, 384, 1),
-                                            ("stream", 64, 256, 512, 2), ("stream", 17, 128, 128, 1), ("stream", 128, 192, 1024, 3)])
+                                            ("stream", 64, 256, 512, 2), ("stream", 17, 128, 128, 1), ("stream", 128, 192, 1024, 3),
+                                            ("stream", 64, 256, 1024, 2), ("stream", 20, 384, 2048, 4), ("stream", 9, 128, 512, 1),
+                                            # K / 512 splits, <= 64 rows and at least two 128-row tiles per workgroup:
+                                            # the resident-slice kernel
+                                            ("stream", 64, 8192, 4096, 8), ("stream", 20, 12288, 4096, 8), ("stream", 7, 8320, 2048, 4)])
 def test_gemm_with_activation_pairs(B, kind, M, N, K, ns):
     g = torch.Generator().manual_seed(31)
     x = torch.randn(M, K, generator=g, dtype=torch.float64)
@@ -122,6 +126,27 @@ def test_gemm_with_activation_pairs(B, kind, M, N, K, ns):
     # the pair carries ~22 bits, so the result is far more accurate than a single fp16 operand would allow
     assert (got - ref).abs().max() < 2e-5 * math.sqrt(K)
     assert (got - hi.double() @ w.double().T).abs().max() > (got - ref).abs().max()
+
+
+def test_gemm_pairs_same_bits_for_any_row_count(B):
+    """The pair-input streaming GEMM accumulates every output element in the same order whichever kernel serves the
+    row count (resident-slice kernel up to 64 rows, ring kernel above): a row's partial sums do not depend on how
+    many other rows are in the call."""
+    N, K, ns = 8320, 4096, 8          # 65 tiles over 32 workgroups per split: 2 or 3 tiles each
+    g = torch.Generator().manual_seed(41)
+    x = torch.randn(100, K, generator=g, dtype=torch.float64)
+    hi = x.to(torch.float16)
+    lo = (x - hi.double()).to(torch.float16)
+    a = torch.cat([hi, lo], dim=1).contiguous().cuda()
+    w = _tiled(B, _rand((N, K), 42, 0.05))
+    outs = {}
+    for M in (100, 64, 40, 16, 7):
+        part = torch.zeros((ns, M, N), dtype=torch.float32, device="cuda")
+        assert B.rlhf_gen_op_gemm(B.GEMM_STREAMING, a[:M].contiguous(), w, part, M, N, K, 0, ns, 1) == 0
+        torch.cuda.synchronize()
+        outs[M] = part.cpu()
+    for M in (64, 40, 16, 7):
+        assert torch.equal(outs[M], outs[100][:, :M])
 
 
 def test_gemm_fp32(B):
