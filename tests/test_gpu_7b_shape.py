@@ -113,3 +113,34 @@ def test_7b_width_score_pass(B):
     print(f"\n[score, 2 layers] max|dlogprob|={worst:.4f}", flush=True)
     assert worst <= 2e-2
     ctx.rlhf_gen_destroy()
+
+
+def test_7b_width_sampler_agrees_with_oracle_on_every_row(B):
+    """At the benchmark's batch and vocabulary (2 layers of the 7B width): on the logits the GPU itself produced, the
+    oracle's sampler must pick the token the GPU picked for every one of the 64 rows and steps (same stateless random
+    numbers, same nucleus), and the returned log-prob must be the log-softmax of those logits at that token.  This
+    isolates the sampling path from the model's 16-bit rounding."""
+    shape = synth.with_layers(synth.LLAMA_7B, 2)
+    w = synth.make_weights(shape, 9, "bf16", "cuda")
+    toks, lens = synth.make_queries(shape.vocab, 64, 512, 512, 9)
+    for cfgs in (dict(temperature=1.0, top_p=1.0, seed=77), dict(temperature=0.7, top_p=0.8, seed=78)):
+        osp = OSampling(**cfgs)
+        ctx = B.Context(w, shape, "bf16", 64, 512 + 8)
+        tok, lp = ctx.rlhf_gen_prefill(toks.cuda(), lens.tolist(), B.make_sampling(**cfgs))
+        mismatches = 0
+        for t in range(4):
+            lg = ctx.rlhf_gen_get_logits().cpu().double()
+            ctx.synchronize()
+            ref_lp = torch.log_softmax(lg, dim=-1)
+            for b in range(64):
+                want, _, info = OS.sample(lg[b], osp, b, t)
+                got = int(tok[b])
+                if got != want:
+                    # only a draw within rounding distance of a CDF edge (fp32 weights on the GPU) may differ
+                    assert OS.cdf_margin(info, want) < 1e-5, (b, t, got, want)
+                    mismatches += 1
+                assert abs(float(lp[b]) - float(ref_lp[b, got])) < 2e-5, (b, t)
+            if t < 3:
+                tok, lp = ctx.rlhf_gen_decode_step()
+        assert mismatches <= 1
+        ctx.rlhf_gen_destroy()
