@@ -95,6 +95,15 @@ def test_70b_width_gqa_2_layers(B):
     assert dl <= 3e-2 and dlp <= 2e-2 and frac <= 0.5
 
 
+def test_13b_width_ragged_2_layers(B):
+    # d_model 5120: ten 512-column splits in the QKV projection, 108 k-steps in the down projection
+    shape = synth.with_layers(synth.LLAMA_13B, 2)
+    toks, lens = synth.make_queries(shape.vocab, 32, 64, 700, 6)
+    rows = [int(lens.argmax()), int(lens.argmin()), 11]
+    dl, dlp, frac = _run(B, shape, 32, 64, 700, rows, 4, dict(temperature=1.0, top_p=0.9, seed=6), 6, 6)
+    assert dl <= 3e-2 and dlp <= 2e-2 and frac <= 0.5
+
+
 def test_7b_width_score_pass(B):
     """rlhf_gen_score at the 7B width (2 layers, 16 sequences of 300 + 40 tokens) against the oracle's score()."""
     from oracle.generate import score as oracle_score
