@@ -72,7 +72,8 @@ typedef struct {
                              fp16 inference it assumes activations within +-65504 (they saturate there).  fp32 is a
                              plain-ALU path meant for small models */
   int32_t max_batch;      /* largest B any call will pass */
-  int32_t max_seq;        /* largest query length + response length of one sequence */
+  int32_t max_seq;        /* most tokens one sequence holds in the cache: query length + response length - 1 (the last
+                             token drawn is not fed back) */
   int32_t kv_block;       /* tokens per KV page; must be 16 */
   int32_t kv_pool_blocks; /* pages in the pool (shared by all sequences, one set per layer);
                              0 = max_batch * ceil(max_seq / kv_block) */

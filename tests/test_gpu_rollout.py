@@ -185,3 +185,46 @@ def test_error_paths_on_device(B):
         ctx.rlhf_gen_decode_step()                                          # both need a second page, one is left
     assert e.value.status == B.E_NOMEM
     ctx.synchronize()
+
+
+@pytest.mark.parametrize("dtype,shape", [("fp32", synth.TINY), ("bf16", BF16_SMALL)])
+def test_degenerate_shapes(B, dtype, shape):
+    """One sequence of one token; responses of 1, 2 and 3 tokens (no decode step, one step without a graph, the
+    shortest graph-replayed rollout); queries that end exactly on a page boundary; a rollout that ends exactly at
+    max_seq and one token more, which must be refused."""
+    w = synth.make_weights(shape, 91, dtype)
+    synth.randomize_norm_gains(w, 92)
+    wd = synth.weights_to(w, "cuda")
+    sp = B.make_sampling(greedy=True)
+    osp = OSampling(greedy=True)
+    tol_l, tol_p, gap = (1e-4, 1e-4, 2e-4) if dtype == "fp32" else (3e-2, 2e-2, 6e-2)
+
+    def check(toks, lens, R, max_seq):
+        ctx = B.Context(wd, shape, dtype, toks.shape[0], max_seq)
+        gt, glp = ctx.rlhf_gen_generate(toks.cuda(), lens.tolist(), R, sp)
+        ref = oracle_generate(w, shape, _queries(toks, lens), R, osp)
+        # free-running greedy: compare up to the first near-tie of each row
+        for b in range(toks.shape[0]):
+            for t in range(R):
+                top2 = ref["logits"][b, t].topk(2).values
+                if float(top2[0] - top2[1]) < gap:
+                    break
+                assert int(gt[b, t]) == int(ref["tokens"][b, t]), (b, t)
+                assert abs(float(glp[b, t]) - float(ref["logprobs"][b, t])) <= tol_p, (b, t)
+        ctx.rlhf_gen_destroy()
+
+    one = torch.tensor([[5]], dtype=torch.int32)
+    for R in (1, 2, 3):
+        check(one, torch.tensor([1], dtype=torch.int32), R, 8)
+    toks, lens = synth.make_queries(shape.vocab, 3, 16, 16, 93)          # exactly one page each
+    check(toks, lens, 17, 33)
+    toks, lens = synth.make_queries(shape.vocab, 2, 32, 32, 94)
+    # the last token drawn is not fed back, so a rollout caches lengths + R - 1 tokens: this one fills max_seq exactly
+    check(toks, lens, 3, 34)
+    ctx = B.Context(wd, shape, dtype, 2, 34)
+    with pytest.raises(B.RlhfGenError) as e:
+        ctx.rlhf_gen_generate(toks.cuda(), lens.tolist(), 4, sp)          # 32 + 4 - 1 > 34
+    assert e.value.status == B.E_INVALID
+    with pytest.raises(B.RlhfGenError) as e:
+        ctx.rlhf_gen_generate(toks.cuda(), lens.tolist(), 0, sp)
+    assert e.value.status == B.E_INVALID
