@@ -26,6 +26,63 @@ def weight_bytes(shape, elt=2):
     return (synth.param_count(shape) - shape.vocab * shape.d_model) * elt   # the embedding table is gathered, not streamed
 
 
+def _time_gpu(fn, reps=5, warm=2):
+    import torch
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps * 1e-3
+
+
+def hardware_probes(binding, dev):
+    """What the card sustains with nothing in the way: a read-only stream over 1 GiB (plain and nontemporal loads) and
+    the fp16 MFMA pipe on register-resident operands (random values in [-1, 1], and zeros: the clock follows the data)."""
+    import torch
+    scratch = torch.zeros(1024, dtype=torch.uint8, device=dev)
+    buf = torch.empty(1 << 28, dtype=torch.int32, device=dev).random_()
+    out = {}
+    for name, nt in (("hbm_read_plain_GBps", False), ("hbm_read_nontemporal_GBps", True)):
+        t = _time_gpu(lambda: binding.rlhf_gen_op_probe_stream_read(buf, nt, scratch))
+        out[name] = buf.numel() * 4 / t / 1e9
+    del buf
+    wgs, iters = 512, 20000
+    flop = wgs * 4 * 8 * iters * 32768.0
+    for name, ops in (("mfma_f16_random_operands_TFLOPs", (torch.rand(8192, device=dev) * 2 - 1).half()),
+                      ("mfma_f16_zero_operands_TFLOPs", torch.zeros(8192, device=dev, dtype=torch.float16))):
+        t = _time_gpu(lambda: binding.rlhf_gen_op_probe_mfma_loop(ops, wgs, iters, scratch), reps=3, warm=1)
+        out[name] = flop / t / 1e12
+    return out
+
+
+def prefill_gemm_shapes(binding, shape, rows, dev):
+    """The four projection GEMMs of one layer at the prefill chunk size, one by one through the kernel entry point:
+    time, flop rate of the product (2 M N K; x 2 for the fused gate/up pair) and of what the kernel executes (the
+    QKV and output projections take hi|lo activation pairs, i.e. twice the flops)."""
+    import torch
+    d, F, hq = shape.d_model, shape.d_ffn, shape.n_heads * shape.head_dim
+    out = {}
+    for name, N, K, epi, dual in (("qkv", shape.qkv_rows, d, 0, 1), ("attn_out", d, hq, 1, 1), ("gate_up_swiglu", F, d, 2, 0),
+                                  ("down", d, F, 1, 0)):
+        a = torch.randn(rows, K * (2 if dual else 1), device=dev).half()
+        w0 = (torch.randn(N * (2 if epi == 2 else 1), K, device=dev) * 0.02).half()
+        w = torch.empty_like(w0)
+        binding.rlhf_gen_op_tile_weights(w0, w)
+        o = torch.zeros(rows, N, device=dev, dtype=torch.float16 if epi == 2 else torch.float32)
+        t = _time_gpu(lambda: binding.rlhf_gen_op_gemm(binding.GEMM_TILED, a, w, o, rows, N, K, epi, 1, dual))
+        flop = 2.0 * rows * N * K * (2 if epi == 2 else 1)
+        out[name] = {"M": rows, "N": N * (2 if epi == 2 else 1), "K": K, "ms": t * 1e3, "TFLOPs": flop / t / 1e12,
+                     "executed_TFLOPs": flop * (2 if dual else 1) / t / 1e12,
+                     "executed_frac_of_mfma_peak": flop * (2 if dual else 1) / t / MFMA_BF16_PEAK}
+        del a, w0, w, o
+    return out
+
+
 def cpu_baseline(wl, w_dev, toks, lens, decode_steps=2):
     """The oracle as it stands, fp32 mode, on one sequence of the batch: full prefill + a few decode steps."""
     import torch
@@ -192,6 +249,14 @@ def main() -> int:
         moved = 2 * (wb - (2 * shape.n_layers + 1) * shape.d_model * 2)
         refresh = {"ms": dt * 1e3, "GBps_read_plus_write": moved / dt / 1e9}
 
+    probes = gemm_shapes = None
+    if wl.dtype == "bf16" and not args.no_score:
+        probes = hardware_probes(binding, dev)
+        gemm_shapes = prefill_gemm_shapes(binding, shape, min(16384, lsum), dev)
+        if roofline is not None:   # the same achieved rate against what a bare read-only stream sustains on this card
+            roofline["measured_peak"] = probes["hbm_read_nontemporal_GBps"]
+            roofline["frac_of_measured_peak"] = roofline["achieved"] / probes["hbm_read_nontemporal_GBps"]
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(wl if not args.layers else synth.dataclasses.replace(wl, shape=shape), w, toks, lens)
@@ -211,6 +276,8 @@ def main() -> int:
         "kernels_sampled": kernels,
         "score_pass": score,
         "micro_batched": micro,
+        "prefill_gemm_shapes": gemm_shapes,
+        "measured_peaks": probes,
         "weight_refresh": refresh,
         "cpu_baseline": cpu,
     }

@@ -21,6 +21,15 @@ enum { RLHF_GEN_GEMM_TILED = 0, RLHF_GEN_GEMM_STREAMING = 1, RLHF_GEN_GEMM_FP32 
 /* epilogues of the tiled GEMM */
 enum { RLHF_GEN_EPI_STORE_F32 = 0, RLHF_GEN_EPI_RESID_F32 = 1, RLHF_GEN_EPI_SWIGLU = 2, RLHF_GEN_EPI_STORE_H16 = 3 };
 
+/* Hardware probes for the benchmark's roofline report (Sec. III-B names generation, a memory-bound stage, as the
+ * bottleneck: the report quotes the kernels against what the card sustains as well as against datasheet peaks).
+ * stream_read: one read-only pass over buf (bytes rounded down to a multiple of 8192) with 16-byte loads, plain or
+ * nontemporal; nothing is written unless a checksum hits one value in 2^32 (scratch: 1 KB device buffer).
+ * mfma_loop: workgroups * 4 wavefronts each issue 8 * iters v_mfma_f32_32x32x16_f16 (32768 flop each) on operand
+ * registers filled from `operands` (device, 16 KB of fp16 values); no memory traffic inside the loop. */
+int rlhf_gen_op_probe_stream_read(void* stream, const void* buf, int64_t bytes, int32_t nontemporal, void* scratch);
+int rlhf_gen_op_probe_mfma_loop(void* stream, const void* operands, int32_t workgroups, int32_t iters, void* scratch);
+
 /* Re-order an fp16 weight matrix W [N, K] (row-major) into the library's working layout, which the 16-bit GEMMs below
  * expect (rlhf_gen_init does the same to the Actor's matrices while converting them from bf16): tiles of 16 rows x
  * 128 columns, 4 KB each, stored row-block major, and inside a tile the halves in the order

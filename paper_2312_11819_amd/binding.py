@@ -31,7 +31,7 @@ EXPORTS = [
     "rlhf_gen_plan_capacity", "rlhf_gen_context_bytes",
     "rlhf_gen_get_logits",
     "rlhf_gen_last_timing", "rlhf_gen_set_profile", "rlhf_gen_get_profile", "rlhf_gen_last_error", "rlhf_gen_destroy",
-    "rlhf_gen_op_tile_weights", "rlhf_gen_op_gemm", "rlhf_gen_op_rope_append", "rlhf_gen_op_attn_decode", "rlhf_gen_op_attn_prefill",
+    "rlhf_gen_op_probe_stream_read", "rlhf_gen_op_probe_mfma_loop", "rlhf_gen_op_tile_weights", "rlhf_gen_op_gemm", "rlhf_gen_op_rope_append", "rlhf_gen_op_attn_decode", "rlhf_gen_op_attn_prefill",
     "rlhf_gen_op_sample",
 ]
 
@@ -108,6 +108,8 @@ def lib() -> C.CDLL:
         L.rlhf_gen_last_error.restype = C.c_char_p
         L.rlhf_gen_destroy.argtypes = [C.c_void_p]
         L.rlhf_gen_destroy.restype = None
+        L.rlhf_gen_op_probe_stream_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]
+        L.rlhf_gen_op_probe_mfma_loop.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         L.rlhf_gen_op_tile_weights.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32]
         L.rlhf_gen_op_gemm.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                        C.c_int32, C.c_int32, C.c_int32, C.c_int32]
@@ -324,6 +326,14 @@ class Context:
 
 
 # -- single-operation entry points -------------------------------------------------------------------
+def rlhf_gen_op_probe_stream_read(buf: torch.Tensor, nontemporal: bool, scratch: torch.Tensor) -> int:
+    return lib().rlhf_gen_op_probe_stream_read(None, _ptr(buf), buf.numel() * buf.element_size(), int(nontemporal), _ptr(scratch))
+
+
+def rlhf_gen_op_probe_mfma_loop(operands: torch.Tensor, workgroups: int, iters: int, scratch: torch.Tensor) -> int:
+    return lib().rlhf_gen_op_probe_mfma_loop(None, _ptr(operands), workgroups, iters, _ptr(scratch))
+
+
 def rlhf_gen_op_tile_weights(w_rowmajor: torch.Tensor, w_tiled: torch.Tensor) -> int:
     N, K = w_rowmajor.shape
     return lib().rlhf_gen_op_tile_weights(None, _ptr(w_rowmajor), _ptr(w_tiled), N, K)

@@ -93,3 +93,9 @@ struct SamplerParams {
 // tok_out[b*out_stride + col], col = use_step_col ? t : 0; cur_tok[b] receives the token too.
 hipError_t launch_sampler(hipStream_t s, const float* logits, int B, int V, SamplerParams p, const int* step_ptr,
                           int out_stride, int use_step_col, int* tok_out, float* lp_out, int* cur_tok);
+
+// Hardware probes (k_probe.hip).  stream_read: reads bytes / 8192 chunks of 8 KB from buf (plain or nontemporal 16-byte
+// loads), scratch >= 1 KB.  mfma_loop: `workgroups` x 4 wavefronts each issue 8 * iters v_mfma_f32_32x32x16_f16
+// (32768 flop each) on operands taken from a 16 KB buffer; scratch >= 1 KB.
+hipError_t launch_probe_stream_read(hipStream_t s, const void* buf, size_t bytes, int nontemporal, void* scratch);
+hipError_t launch_probe_mfma_loop(hipStream_t s, const void* operands, int workgroups, int iters, void* scratch);

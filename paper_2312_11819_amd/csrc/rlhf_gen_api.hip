@@ -1240,6 +1240,18 @@ void rlhf_gen_destroy(rlhf_gen_ctx* c) {
 }
 
 // ---- single-operation entry points (kernel parity tests) ----------------------------------------
+int rlhf_gen_op_probe_stream_read(void* stream, const void* buf, int64_t bytes, int32_t nontemporal, void* scratch) {
+  if (!buf || !scratch || bytes < 8192) return RLHF_GEN_E_INVALID;
+  return launch_probe_stream_read((hipStream_t)stream, buf, (size_t)bytes, nontemporal, scratch) == hipSuccess ? RLHF_GEN_OK
+                                                                                                             : RLHF_GEN_E_DEVICE;
+}
+
+int rlhf_gen_op_probe_mfma_loop(void* stream, const void* operands, int32_t workgroups, int32_t iters, void* scratch) {
+  if (!operands || !scratch || workgroups < 1 || iters < 1) return RLHF_GEN_E_INVALID;
+  return launch_probe_mfma_loop((hipStream_t)stream, operands, workgroups, iters, scratch) == hipSuccess ? RLHF_GEN_OK
+                                                                                                         : RLHF_GEN_E_DEVICE;
+}
+
 int rlhf_gen_op_tile_weights(void* stream, const void* w_rowmajor, void* w_tiled, int32_t N, int32_t K) {
   if (!w_rowmajor || !w_tiled || w_rowmajor == w_tiled || N < 16 || K < 128 || N % 16 || K % 128) return RLHF_GEN_E_INVALID;
   hipError_t e = launch_to_h16_tiled((hipStream_t)stream, w_rowmajor, 1, w_tiled, N, K, nullptr, nullptr, 0, 0.f, 0);
