@@ -248,3 +248,16 @@ def test_sampler(B, mode):
                 assert not osp.greedy and OS.cdf_margin(info, want_tok) < 1e-3, (b, t, got, want_tok)
                 continue
             assert abs(float(lp[b]) - want_lp) < 1e-4, (b, t, float(lp[b]), want_lp)
+
+
+def test_hardware_probes_run(B):
+    scratch = torch.zeros(1024, dtype=torch.uint8, device="cuda")
+    buf = torch.zeros(1 << 20, dtype=torch.int32, device="cuda")
+    assert B.rlhf_gen_op_probe_stream_read(buf, False, scratch) == 0
+    assert B.rlhf_gen_op_probe_stream_read(buf, True, scratch) == 0
+    assert B.rlhf_gen_op_probe_stream_read(buf[:16], True, scratch) == B.E_INVALID        # less than one 8 KB chunk
+    ops = torch.ones(8192, dtype=torch.float16, device="cuda")
+    assert B.rlhf_gen_op_probe_mfma_loop(ops, 4, 10, scratch) == 0
+    assert B.rlhf_gen_op_probe_mfma_loop(ops, 0, 10, scratch) == B.E_INVALID
+    torch.cuda.synchronize()
+    assert int(scratch.sum()) == 0                                                           # the probes write nothing
