@@ -151,6 +151,7 @@ def main() -> int:
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     prof = ctx.rlhf_gen_get_profile()
+    step_ms = ctx.rlhf_gen_last_step_ms()
     ctx.rlhf_gen_set_profile(0)
     assert bool(torch.isfinite(out_lp).all()) and int(out_t.min()) >= 0 and int(out_t.max()) < shape.vocab
 
@@ -168,6 +169,13 @@ def main() -> int:
         ctx_tokens = lsum + B * t          # cached tokens the step reads, its own included
         dec_bytes += wb + ctx_tokens * kv_tok + B * kv_tok
     dec_frac = dec_bytes / (dec_ms * 1e-3) / HBM_PEAK if dec_ms > 0 else None
+    # the same per step: every step's own context lengths against its own time (steps that were run kernel by kernel
+    # for the per-kernel timing carry the event overhead and are left out)
+    step_fracs = []
+    every = args.profile_every
+    for t, ms in enumerate(step_ms, start=1):
+        if ms > 0 and not (every > 0 and t % every == 0):
+            step_fracs.append((wb + (lsum + B * t) * kv_tok + B * kv_tok) / (ms * 1e-3) / HBM_PEAK)
     # prefill flops: projections over all query tokens + causal attention + LM head on B rows
     layer_mm = (shape.qkv_rows * shape.d_model + shape.d_model * shape.n_heads * shape.head_dim
                 + 3 * shape.d_ffn * shape.d_model)
@@ -270,7 +278,10 @@ def main() -> int:
                    "query_len": [wl.len_lo, wl.len_hi], "resp_len": R, "temperature": wl.temperature, "top_p": wl.top_p,
                    "kv_block": 16, "valid": not args.layers and not args.resp_len},
         "decode": {"ms_per_decode_step": dec_ms / max(R - 1, 1), "tokens_per_s_decode_only": B * (R - 1) / (dec_ms * 1e-3) if dec_ms else None,
-                   "hbm_roofline_frac_per_decode_step": dec_frac, "algorithmic_GB_per_step_mean": dec_bytes / max(R - 1, 1) / 1e9},
+                   "hbm_roofline_frac_per_decode_step": dec_frac, "algorithmic_GB_per_step_mean": dec_bytes / max(R - 1, 1) / 1e9,
+                   "hbm_roofline_frac_step_min": min(step_fracs) if step_fracs else None,
+                   "hbm_roofline_frac_step_max": max(step_fracs) if step_fracs else None,
+                   "hbm_roofline_frac_step_mean": sum(step_fracs) / len(step_fracs) if step_fracs else None},
         "prefill": {"ms": pre_ms, "mfma_bf16_frac": pre_frac, "flop": pre_flop + pre_flop_attn},
         "roofline": roofline,
         "kernels_sampled": kernels,

@@ -243,6 +243,11 @@ int rlhf_gen_get_logits(rlhf_gen_ctx* ctx, float* out);
  * prefill_ms, decode_ms (all decode steps together) and the number of decode steps. */
 int rlhf_gen_last_timing(const rlhf_gen_ctx* ctx, float* prefill_ms, float* decode_ms, int32_t* decode_steps);
 
+/* Time of every decode step of the last rlhf_gen_generate (HIP events on cfg.stream, one after each step): ms_out
+ * receives min(capacity, *n_out) values, step t = 1 first; *n_out the number of steps.  Host pointers, either may be
+ * NULL.  After rlhf_gen_generate_stream: the steps of the last micro-batch. */
+int rlhf_gen_last_step_ms(const rlhf_gen_ctx* ctx, float* ms_out, int32_t capacity, int32_t* n_out);
+
 /* Per-kernel timing of the decode loop, for roofline reports.  With every > 0, rlhf_gen_generate runs decode
  * step t kernel by kernel (instead of replaying its graph) whenever t % every == 0 and brackets each kernel with
  * HIP events on cfg.stream; at most 16 steps per call are sampled.  every = 0 switches it off.  Counters

@@ -30,7 +30,7 @@ EXPORTS = [
     "rlhf_gen_init", "rlhf_gen_prefill", "rlhf_gen_decode_step", "rlhf_gen_generate", "rlhf_gen_generate_stream", "rlhf_gen_score", "rlhf_gen_update_weights",
     "rlhf_gen_plan_capacity", "rlhf_gen_context_bytes",
     "rlhf_gen_get_logits",
-    "rlhf_gen_last_timing", "rlhf_gen_set_profile", "rlhf_gen_get_profile", "rlhf_gen_last_error", "rlhf_gen_destroy",
+    "rlhf_gen_last_timing", "rlhf_gen_last_step_ms", "rlhf_gen_set_profile", "rlhf_gen_get_profile", "rlhf_gen_last_error", "rlhf_gen_destroy",
     "rlhf_gen_op_probe_stream_read", "rlhf_gen_op_probe_mfma_loop", "rlhf_gen_op_tile_weights", "rlhf_gen_op_gemm", "rlhf_gen_op_rope_append", "rlhf_gen_op_attn_decode", "rlhf_gen_op_attn_prefill",
     "rlhf_gen_op_sample",
 ]
@@ -101,6 +101,7 @@ def lib() -> C.CDLL:
         L.rlhf_gen_context_bytes.restype = C.c_int64
         L.rlhf_gen_get_logits.argtypes = [C.c_void_p, C.c_void_p]
         L.rlhf_gen_last_timing.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_int32)]
+        L.rlhf_gen_last_step_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)]
         L.rlhf_gen_set_profile.argtypes = [C.c_void_p, C.c_int32]
         L.rlhf_gen_get_profile.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_int64),
                                            C.POINTER(C.c_int32)]
@@ -298,6 +299,13 @@ class Context:
         a, b, n = C.c_float(), C.c_float(), C.c_int32()
         _check(self._h, lib().rlhf_gen_last_timing(self._h, C.byref(a), C.byref(b), C.byref(n)))
         return a.value, b.value, n.value
+
+    def rlhf_gen_last_step_ms(self):
+        n = C.c_int32()
+        _check(self._h, lib().rlhf_gen_last_step_ms(self._h, None, 0, C.byref(n)))
+        buf = (C.c_float * max(n.value, 1))()
+        _check(self._h, lib().rlhf_gen_last_step_ms(self._h, buf, n.value, C.byref(n)))
+        return [buf[i] for i in range(n.value)]
 
     def rlhf_gen_set_profile(self, every: int) -> None:
         _check(self._h, lib().rlhf_gen_set_profile(self._h, every))

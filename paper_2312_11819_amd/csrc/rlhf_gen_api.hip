@@ -93,6 +93,8 @@ struct rlhf_gen_ctx {
   hipGraphExec_t graph_exec = nullptr;
   GraphKey graph_key;
   hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+  std::vector<hipEvent_t> step_ev;   // one event after every decode step of the last rollout
+  std::vector<float> step_ms;
   float prefill_ms = 0.f, decode_ms = 0.f;
   int decode_steps = 0;
 };
@@ -977,6 +979,12 @@ static int generate_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int
       }
     }
     after_step(c);
+    if ((int)c->step_ev.size() < t) {
+      hipEvent_t e = nullptr;
+      HIP_TRY(c, hipEventCreate(&e));
+      c->step_ev.push_back(e);
+    }
+    HIP_TRY(c, hipEventRecord(c->step_ev[t - 1], s));
   }
   HIP_TRY(c, hipEventRecord(c->ev[2], s));
   HIP_TRY(c, hipMemcpyAsync(&c->h_misc[2], c->d_err, sizeof(int), hipMemcpyDeviceToHost, s));
@@ -984,6 +992,9 @@ static int generate_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int
   HIP_TRY(c, hipEventElapsedTime(&c->prefill_ms, c->ev[0], c->ev[1]));
   HIP_TRY(c, hipEventElapsedTime(&c->decode_ms, c->ev[1], c->ev[2]));
   c->decode_steps = R - 1;
+  c->step_ms.assign(R - 1, 0.f);
+  for (int t = 1; t < R; ++t)
+    HIP_TRY(c, hipEventElapsedTime(&c->step_ms[t - 1], t == 1 ? c->ev[1] : c->step_ev[t - 2], c->step_ev[t - 1]));
   for (int i = 1; i < c->prof_used; ++i) {
     if (c->prof_cls[i] < 0) continue;
     float ms = 0.f;
@@ -1052,6 +1063,15 @@ int rlhf_gen_last_timing(const rlhf_gen_ctx* c, float* prefill_ms, float* decode
   if (prefill_ms) *prefill_ms = c->prefill_ms;
   if (decode_ms) *decode_ms = c->decode_ms;
   if (decode_steps) *decode_steps = c->decode_steps;
+  return RLHF_GEN_OK;
+}
+
+int rlhf_gen_last_step_ms(const rlhf_gen_ctx* c, float* ms_out, int32_t capacity, int32_t* n_out) {
+  if (!c) return RLHF_GEN_E_INVALID;
+  const int n = (int)c->step_ms.size();
+  if (n_out) *n_out = n;
+  if (ms_out)
+    for (int i = 0; i < n && i < capacity; ++i) ms_out[i] = c->step_ms[i];
   return RLHF_GEN_OK;
 }
 
@@ -1235,6 +1255,7 @@ void rlhf_gen_destroy(rlhf_gen_ctx* c) {
   for (int i = 0; i < 3; ++i)
     if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
   for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
+  for (hipEvent_t e : c->step_ev) (void)hipEventDestroy(e);
   if (c->own_stream && c->stream) (void)hipStreamDestroy(c->stream);
   delete c;
 }

@@ -124,6 +124,11 @@ def test_small_bf16_teacher_forced(B, shape, flags):
     g2 = ctx.rlhf_gen_generate(toks.cuda(), lens.tolist(), 12, B.make_sampling(**cfgs))
     assert torch.equal(g1[0], g2[0]) and torch.equal(g1[1], g2[1])
     assert torch.equal(g1[0][:, 0].cpu().long(), t[:, 0])
+    # timing getters: one entry per decode step, all positive, adding up to the decode time
+    pre_ms, dec_ms, nsteps = ctx.rlhf_gen_last_timing()
+    steps = ctx.rlhf_gen_last_step_ms()
+    assert nsteps == 11 and len(steps) == 11 and all(x > 0 for x in steps)
+    assert abs(sum(steps) - dec_ms) <= 0.05 * dec_ms + 0.05
 
 
 @pytest.mark.parametrize("batch", [17, 100, 200, 300])
