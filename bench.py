@@ -104,7 +104,7 @@ def cpu_baseline(wl, w_dev, toks, lens, decode_steps=2):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="7b_b64")
     ap.add_argument("--layers", type=int, default=0, help="override the depth (debugging only; invalidates the metric)")
