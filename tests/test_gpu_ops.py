@@ -220,6 +220,57 @@ def test_attention_prefill_then_decode(B, Hq, Hkv, lens):
     assert worst < 3e-3, worst   # fp16 rounding of k and v on values of order 1
 
 
+def test_attention_long_context(B):
+    """Contexts beyond 4096 tokens: a wavefront's pages no longer fit one batch of 64 block-table entries (decode),
+    and the prefill tiles walk hundreds of pages.  Sampled rows against the CPU definition."""
+    Hq, Hkv, h = 4, 2, 128
+    lens = [4400, 130]
+    nseq, T = len(lens), sum(lens)
+    width = (Hq + 2 * Hkv) * h
+    maxpos = max(lens) + 1
+    max_blocks = (maxpos + 15) // 16
+    n_blocks = nseq * max_blocks + 5
+    g = torch.Generator().manual_seed(12)
+    table = torch.randperm(n_blocks, generator=g)[: nseq * max_blocks].reshape(nseq, max_blocks).to(torch.int32)
+    qkv = torch.randn(T + nseq, width, generator=g)
+    cos_t, sin_t = rope_tables(maxpos, h)
+    row_seq = torch.tensor([b for b, L in enumerate(lens) for _ in range(L)], dtype=torch.int32)
+    row_pos = torch.tensor([p for L in lens for p in range(L)], dtype=torch.int32)
+    cu = torch.tensor([0] + list(torch.tensor(lens).cumsum(0)), dtype=torch.int32)
+    pool = torch.zeros(Hkv, n_blocks, 8192, dtype=torch.uint8, device="cuda")
+    dev = lambda t: t.cuda().contiguous()
+    qkv_d, cos_d, sin_d, table_d = dev(qkv), dev(cos_t), dev(sin_t), dev(table)
+    q_out = torch.zeros(T, Hq, 2, h, dtype=torch.float16, device="cuda")
+    assert B.rlhf_gen_op_rope_append(qkv_d[:T].contiguous(), dev(row_pos), dev(row_seq), cos_d, sin_d, q_out, pool,
+                                     table_d, max_blocks, n_blocks, T, Hq, Hkv, h, True) == 0
+    out = torch.zeros(T, 2, Hq * h, dtype=torch.float16, device="cuda")
+    seq_ids = torch.arange(nseq, dtype=torch.int32, device="cuda")
+    assert B.rlhf_gen_op_attn_prefill(q_out, pool, table_d, max_blocks, n_blocks, dev(cu), seq_ids, out, nseq, max(lens), Hq, Hkv) == 0
+    qd = torch.zeros(nseq, Hq, 2, h, dtype=torch.float16, device="cuda")
+    seq_len = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    assert B.rlhf_gen_op_rope_append(qkv_d[T:].contiguous(), seq_len, None, cos_d, sin_d, qd, pool, table_d, max_blocks,
+                                     n_blocks, nseq, Hq, Hkv, h, True) == 0
+    outd = torch.zeros(nseq, 2, Hq * h, dtype=torch.float16, device="cuda")
+    assert B.rlhf_gen_op_attn_decode(qd, pool, table_d, max_blocks, n_blocks, seq_len, outd, nseq, Hq, Hkv) == 0
+    torch.cuda.synchronize()
+    scale = 1.0 / math.sqrt(h)
+    worst = 0.0
+    for b, L in enumerate(lens):
+        rows = torch.cat([qkv[cu[b]: cu[b] + L], qkv[T + b: T + b + 1]]).double()
+        pos = torch.arange(L + 1)
+        q = OT.rope(rows[:, : Hq * h].reshape(L + 1, Hq, h), pos, 10000.0)
+        k = OT.rope(rows[:, Hq * h: (Hq + Hkv) * h].reshape(L + 1, Hkv, h), pos, 10000.0)
+        v = rows[:, (Hq + Hkv) * h:].reshape(L + 1, Hkv, h)
+        for i in sorted({0, 15, 16, L // 2, L - 1, L}):          # L = the decode row
+            for j in range(Hq):
+                kv = j // (Hq // Hkv)
+                want = oracle_attention_rows(q[i, j], k[: i + 1, kv], v[: i + 1, kv], scale)
+                src = out[cu[b] + i] if i < L else outd[b]
+                got = src[:, j * h:(j + 1) * h].cpu().double().sum(0)
+                worst = max(worst, float((got - want).abs().max()))
+    assert worst < 3e-3, worst
+
+
 @pytest.mark.parametrize("mode", ["greedy", "plain", "nucleus", "nucleus_lp1", "tight"])
 def test_sampler(B, mode):
     V, rows = 32000, 6
