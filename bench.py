@@ -139,6 +139,7 @@ def main() -> int:
 
     for _ in range(args.warmup):
         ctx.rlhf_gen_generate(toks_d, lens.tolist(), R, sp, out_t, out_lp)
+    first = (out_t.clone(), out_lp.clone()) if args.warmup > 0 else None   # same inputs and seed: must repeat exactly
     ctx.rlhf_gen_set_profile(args.profile_every)
     torch.cuda.synchronize()
     pre_ms = dec_ms = 0.0
@@ -154,6 +155,7 @@ def main() -> int:
     step_ms = ctx.rlhf_gen_last_step_ms()
     ctx.rlhf_gen_set_profile(0)
     assert bool(torch.isfinite(out_lp).all()) and int(out_t.min()) >= 0 and int(out_t.max()) < shape.vocab
+    repeatable = None if first is None else bool(torch.equal(first[0], out_t) and torch.equal(first[1], out_lp))
 
     K = args.steps
     ms_per_step = wall / K * 1e3
@@ -276,7 +278,8 @@ def main() -> int:
         "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": wl.name, "layers": shape.n_layers, "d_model": shape.d_model, "batch": B,
                    "query_len": [wl.len_lo, wl.len_hi], "resp_len": R, "temperature": wl.temperature, "top_p": wl.top_p,
-                   "kv_block": 16, "valid": not args.layers and not args.resp_len},
+                   "kv_block": 16, "valid": not args.layers and not args.resp_len,
+                   "rollouts_bit_identical": repeatable},
         "decode": {"ms_per_decode_step": dec_ms / max(R - 1, 1), "tokens_per_s_decode_only": B * (R - 1) / (dec_ms * 1e-3) if dec_ms else None,
                    "hbm_roofline_frac_per_decode_step": dec_frac, "algorithmic_GB_per_step_mean": dec_bytes / max(R - 1, 1) / 1e9,
                    "hbm_roofline_frac_step_min": min(step_fracs) if step_fracs else None,
