@@ -188,9 +188,16 @@ def main() -> int:
     roofline = None
     kernels = {}
     if prof["steps"] > 0:
+        hq = shape.n_heads * shape.head_dim
+        wbytes = {"gemm_qkv": shape.qkv_rows * shape.d_model * 2, "gemm_wo": shape.d_model * hq * 2,
+                  "gemm_gate_up": 2 * shape.d_ffn * shape.d_model * 2, "gemm_down": shape.d_model * shape.d_ffn * 2,
+                  "lm_head": shape.vocab * shape.d_model * 2}
         for k in binding.PROF_CLASSES:
             if prof["launches"][k]:
-                kernels[k] = {"ms_per_sampled_step": prof["ms"][k] / prof["steps"], "launches": prof["launches"][k]}
+                kernels[k] = {"ms_per_sampled_step": prof["ms"][k] / prof["steps"], "launches": prof["launches"][k],
+                              "us_per_launch": prof["ms"][k] / prof["launches"][k] * 1e3}
+                if k in wbytes and prof["ms"][k] > 0:   # weight bytes streamed per second by this projection
+                    kernels[k]["weight_GBps"] = wbytes[k] * prof["launches"][k] / (prof["ms"][k] * 1e-3) / 1e9
         n_attn = prof["launches"]["attn_decode"]
         attn_bytes = prof["attn_tokens"] * 2 * shape.n_kv_heads * shape.head_dim * 2 * shape.n_layers  # all sampled launches
         attn_s = prof["ms"]["attn_decode"] * 1e-3
