@@ -1,7 +1,8 @@
 // Fused softmax / temperature / top-p / seeded draw / log-prob gather: one 1024-thread workgroup per
-// row of fp32 logits.  The row (128 KB at V = 32000) is re-read from L2 in each pass; the passes are
-// bandwidth-trivial next to a decode step.  Sums are kept in double and reduced in a fixed order, so a
-// row's result is reproducible bit for bit.
+// row of fp32 logits.  The first pass copies the row into LDS (128 KB at V = 32000, padded by one float per 32 so that
+// the per-thread contiguous chunks of the draw passes hit distinct banks) and the later passes read it from there;
+// rows that do not fit are re-read from L2 instead.  Sums are kept in double and reduced in a fixed order, so a
+// row's result is reproducible bit for bit, and both variants compute the same bits.
 #include <math.h>
 
 #include "common.h"
@@ -121,23 +122,55 @@ __device__ unsigned block_excl_scan_u(unsigned v, Shared& sh) {
   return base + inc - v;
 }
 
+template <bool CACHE>
 __global__ __launch_bounds__(ST) void sampler_kernel(const float* __restrict__ logits, int V, SamplerParams p,
                                                      const int* __restrict__ step_ptr, int out_stride,
                                                      int use_step_col, int* __restrict__ tok_out,
                                                      float* __restrict__ lp_out, int* __restrict__ cur_tok) {
   __shared__ Shared sh;
+  extern __shared__ float row_s[];   // CACHE: the row, element i at i + i / 32
   const int b = blockIdx.x;
   const int tid = threadIdx.x;
-  const float* row = logits + (size_t)b * V;
+  const float* grow = logits + (size_t)b * V;
   const int t = *step_ptr;
   const size_t out_idx = (size_t)b * out_stride + (use_step_col ? t : 0);
+  struct Row {
+    const float* g;
+    const float* s;
+    __device__ __forceinline__ float operator[](int i) const { return CACHE ? s[i + (i >> 5)] : g[i]; }
+  } row{grow, row_s};
 
   // pass 1: raw maximum and its lowest index
   float vloc = -INFINITY;
   int iloc = 0x7fffffff;
-  for (int i = tid; i < V; i += ST) {
-    float v = row[i];
-    if (v > vloc) { vloc = v; iloc = i; }
+  if ((V & 3) == 0) {
+    // 16-byte loads, eight in flight per thread: one memory round trip for rows up to 32768 entries instead of a
+    // chain of dependent 4-byte loads.  A thread sees its indices in ascending order, so `>` keeps the lowest.
+    const int nvec = V >> 2;
+    for (int j0 = tid; j0 < nvec; j0 += 8 * ST) {
+      float4 q[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) q[u] = *(const float4*)(grow + 4 * (size_t)min(j0 + u * ST, nvec - 1));
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int j = j0 + u * ST;
+        if (j < nvec) {
+          const float e4[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const int i = 4 * j + c;
+            if (CACHE) row_s[i + (i >> 5)] = e4[c];
+            if (e4[c] > vloc) { vloc = e4[c]; iloc = i; }
+          }
+        }
+      }
+    }
+  } else {
+    for (int i = tid; i < V; i += ST) {
+      float v = grow[i];
+      if (CACHE) row_s[i + (i >> 5)] = v;
+      if (v > vloc) { vloc = v; iloc = i; }
+    }
   }
   float vmax;
   int imax;
@@ -148,9 +181,17 @@ __global__ __launch_bounds__(ST) void sampler_kernel(const float* __restrict__ l
   double sraw = 0.0, stmp = 0.0;
   for (int i = tid; i < V; i += ST) {
     float v = row[i];
-    sraw += (double)expf(v - vmax);
-    if (!p.greedy) stmp += (double)expf((v - vmax) * invT);
+    const float eraw = expf(v - vmax);
+    sraw += (double)eraw;
+    if (!p.greedy) {
+      // (v - vmax) * 1.0f is v - vmax exactly, so at temperature 1 the two weights are the same value
+      const float e = invT == 1.f ? eraw : expf((v - vmax) * invT);
+      stmp += (double)e;
+      if (CACHE) row_s[i + (i >> 5)] = e;   // from here on the cached row holds the tempered weights
+    }
   }
+  // tempered weight of token i: read back from the cache, or recomputed (same expression, same bits)
+  auto wgt = [&](int i) -> float { return CACHE ? row_s[i + (i >> 5)] : expf((grow[i] - vmax) * invT); };
   const double Zraw = block_sum_d(sraw, sh);
   if (p.greedy) {
     if (tid == 0) {
@@ -178,7 +219,7 @@ __global__ __launch_bounds__(ST) void sampler_kernel(const float* __restrict__ l
       float fm = __uint_as_float(mid);
       double part = 0.0;
       for (int i = tid; i < V; i += ST) {
-        float e = expf((row[i] - vmax) * invT);
+        float e = wgt(i);
         if (e >= fm) part += (double)e;
       }
       double mass = block_sum_d(part, sh);
@@ -188,7 +229,7 @@ __global__ __launch_bounds__(ST) void sampler_kernel(const float* __restrict__ l
     double pgt = 0.0;
     unsigned ceq = 0;
     for (int i = tid; i < V; i += ST) {
-      float e = expf((row[i] - vmax) * invT);
+      float e = wgt(i);
       if (e > tau) pgt += (double)e;
       else if (e == tau) ceq++;
     }
@@ -208,14 +249,14 @@ __global__ __launch_bounds__(ST) void sampler_kernel(const float* __restrict__ l
   if (ktie != 0xffffffffu) {
     unsigned c = 0;
     for (int i = i0; i < i1; ++i)
-      if (expf((row[i] - vmax) * invT) == tau) c++;
+      if (wgt(i) == tau) c++;
     tie_before = block_excl_scan_u(c, sh);
   }
   double local = 0.0;
   {
     unsigned tr = tie_before;
     for (int i = i0; i < i1; ++i) {
-      float e = expf((row[i] - vmax) * invT);
+      float e = wgt(i);
       bool mem = !truncated || e > tau || (e == tau && (ktie == 0xffffffffu || tr < ktie));
       if (e == tau) tr++;
       if (mem) local += (double)e;
@@ -234,7 +275,7 @@ __global__ __launch_bounds__(ST) void sampler_kernel(const float* __restrict__ l
     int mylast = -1;
     bool done = false;
     for (int i = i0; i < i1; ++i) {
-      float e = expf((row[i] - vmax) * invT);
+      float e = wgt(i);
       bool mem = !truncated || e > tau || (e == tau && (ktie == 0xffffffffu || tr < ktie));
       if (e == tau) tr++;
       if (mem) {
@@ -248,7 +289,7 @@ __global__ __launch_bounds__(ST) void sampler_kernel(const float* __restrict__ l
   __syncthreads();
   if (tid == 0) {
     int tok = sh.found != 0x7fffffff ? sh.found : sh.last;
-    float v = row[tok];
+    float v = grow[tok];
     float lp;
     if (p.logprob_mode == 0)
       lp = (float)((double)(v - vmax) - log(Zraw));
@@ -302,9 +343,20 @@ hipError_t launch_logprob_gather(hipStream_t s, const float* logits, int rows, i
   return hipGetLastError();
 }
 
+constexpr int SAMPLER_MAX_CACHED_V = 36864;   // 36864 * 33 / 32 floats = 148.5 KB of LDS
+
+hipError_t sampler_configure() {
+  return hipFuncSetAttribute((const void*)sampler_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (SAMPLER_MAX_CACHED_V + SAMPLER_MAX_CACHED_V / 32) * 4);
+}
+
 hipError_t launch_sampler(hipStream_t s, const float* logits, int B, int V, SamplerParams p, const int* step_ptr,
                           int out_stride, int use_step_col, int* tok_out, float* lp_out, int* cur_tok) {
   if (B <= 0) return hipSuccess;
-  sampler_kernel<<<B, ST, 0, s>>>(logits, V, p, step_ptr, out_stride, use_step_col, tok_out, lp_out, cur_tok);
+  if (V <= SAMPLER_MAX_CACHED_V)
+    sampler_kernel<true><<<B, ST, (size_t)(V + V / 32 + 1) * 4, s>>>(logits, V, p, step_ptr, out_stride, use_step_col, tok_out,
+                                                                     lp_out, cur_tok);
+  else
+    sampler_kernel<false><<<B, ST, 0, s>>>(logits, V, p, step_ptr, out_stride, use_step_col, tok_out, lp_out, cur_tok);
   return hipGetLastError();
 }

@@ -26,6 +26,7 @@ hipError_t launch_gemm_skinny_h16(hipStream_t s, const void* A, const void* W, f
 int gemm_skinny_pick_split(int M, int Nw, int K, int a_dual = 0);
 // Per-device one-time kernel attribute setup; call before the first launch and outside any stream capture.
 hipError_t gemm_configure();
+hipError_t sampler_configure();   // likewise for the sampler's LDS row cache
 
 // ---- elementwise / small kernels (act_bf16 != 0: 16-bit (fp16) activations, else fp32) ----
 hipError_t launch_pack_tokens(hipStream_t s, const int* query_tokens, int Lmax, const int* tok_seq, const int* tok_pos,

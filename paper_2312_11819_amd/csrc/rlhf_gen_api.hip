@@ -865,7 +865,7 @@ int rlhf_gen_init(const rlhf_gen_weights* w, const rlhf_gen_cfg* cfg, rlhf_gen_c
     }
     c->own_stream = true;
   }
-  if (gemm_configure() != hipSuccess) {
+  if (gemm_configure() != hipSuccess || sampler_configure() != hipSuccess) {
     (void)hipGetLastError();
     c->err = "kernel attribute setup failed";
     return bail(RLHF_GEN_E_DEVICE);
@@ -1332,6 +1332,11 @@ int rlhf_gen_op_attn_prefill(void* stream, const void* q, const void* kv_pool, c
 int rlhf_gen_op_sample(void* stream, const float* logits, int32_t B, int32_t V, const rlhf_gen_sampling* sp,
                        const int32_t* step, int32_t* tok_out, float* logprob_out, int32_t* scratch_tok) {
   if (!logits || !sp || !step || !tok_out || !logprob_out || !scratch_tok || B < 1 || V < 1) return RLHF_GEN_E_INVALID;
+  static bool configured = false;
+  if (!configured) {
+    if (sampler_configure() != hipSuccess) return RLHF_GEN_E_DEVICE;
+    configured = true;
+  }
   SamplerParams p{};
   p.temperature = sp->temperature; p.top_p = sp->top_p; p.seed = sp->seed; p.greedy = sp->greedy; p.logprob_mode = sp->logprob_mode;
   hipError_t e = launch_sampler((hipStream_t)stream, logits, B, V, p, step, 1, 0, tok_out, logprob_out, scratch_tok);
