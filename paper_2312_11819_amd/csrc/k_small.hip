@@ -222,7 +222,7 @@ __global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict
   if (head < Hq + Hkv) {
     for (int i = threadIdx.x; i < half; i += 64) {
       float a = row[i], bb = row[i + half];
-      {
+      if (nsplit > 0) {   // (prefill passes complete sums: nothing to add, nothing to load)
         // up to 8 further partial sums with all loads in flight at once, added in split order
         float av[8], bv[8];
 #pragma unroll
@@ -268,7 +268,7 @@ __global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict
     const int kvh = head - Hq - Hkv;
     for (int dim = threadIdx.x; dim < h; dim += 64) {
       float v = row[dim];
-      {
+      if (nsplit > 0) {
         float vv[8];
 #pragma unroll
         for (int s8 = 0; s8 < 8; ++s8) vv[s8] = prow[(size_t)min(s8, max(nsplit - 1, 0)) * part_stride + dim];
