@@ -285,18 +285,35 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const h16_t* __restri
   AttnState st;
   init_state(st);
   const int* bt = block_table + (size_t)b * max_blocks;
-  const int pd = p0 >> 4;  // diagonal page
-  uint4 kf[4], vf[4], kn[4], vn[4];
-  load_page<false>(pool + ((size_t)kvh * n_blocks + bt[0]) * KV_PAGE_BYTES, lane, kf, vf);
-  for (int p = 0; p <= pd; ++p) {
-    if (p < pd) load_page<false>(pool + ((size_t)kvh * n_blocks + bt[p + 1]) * KV_PAGE_BYTES, lane, kn, vn);
-    if (p == pd)
-      attn_page<true>(kf, vf, qf, st, scale_log2, p * 16, p0 + t + 1, g);
-    else
-      attn_page<false>(kf, vf, qf, st, scale_log2, p * 16, 0, g);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { kf[i] = kn[i]; vf[i] = vn[i]; }
+  const int pd = p0 >> 4;  // diagonal page = last page this tile reads
+  // Pages 0 .. pd in order.  As in the decode kernel the block-table entries are fetched 64 at a time (lane i holds
+  // the entry of page base + i) and broadcast from registers, and the page loads are issued with no branch around
+  // them (an index past the end re-reads the last page), so the next page is in flight while this one is consumed.
+  const int my_blk0 = bt[min(lane, pd)];
+  uint4 ka[4], va[4], kb[4], vb[4];
+  load_page<false>(pool + ((size_t)kvh * n_blocks + __shfl(my_blk0, 0)) * KV_PAGE_BYTES, lane, ka, va);
+#define PREFILL_PAGE(KF, VF, P)                                                              \
+  if ((P) == pd)                                                                             \
+    attn_page<true>(KF, VF, qf, st, scale_log2, (P) * 16, p0 + t + 1, g);                    \
+  else                                                                                       \
+    attn_page<false>(KF, VF, qf, st, scale_log2, (P) * 16, 0, g);
+  for (int base = 0; base <= pd; base += 64) {
+    int my_blk = my_blk0;
+    if (base != 0) {
+      my_blk = bt[min(base + lane, pd)];
+      load_page<false>(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, 0)) * KV_PAGE_BYTES, lane, ka, va);
+    }
+    const int cnt = min(64, pd + 1 - base);
+    int i = 0;
+    for (; i + 2 <= cnt; i += 2) {
+      load_page<false>(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, i + 1)) * KV_PAGE_BYTES, lane, kb, vb);
+      PREFILL_PAGE(ka, va, base + i)
+      load_page<false>(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, min(i + 2, cnt - 1))) * KV_PAGE_BYTES, lane, ka, va);
+      PREFILL_PAGE(kb, vb, base + i + 1)
+    }
+    if (i < cnt) PREFILL_PAGE(ka, va, base + i)
   }
+#undef PREFILL_PAGE
   float lt = st.l;
   lt += __shfl_xor(lt, 16);
   lt += __shfl_xor(lt, 32);
