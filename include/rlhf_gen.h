@@ -149,9 +149,9 @@ int rlhf_gen_generate(rlhf_gen_ctx* ctx, const int32_t* query_tokens, const int3
 
 /* Micro-batched rollout.  The paper hides the hand-off between stages by micro-batching: the forward stage (and the
  * transfer that feeds it) of one micro-batch starts when its generation ends, not when the whole batch has been
- * generated, and the transfers run on a stream of their own beside the computation (Sec. IV-A: Interleaving strategy,
- * "computation and communication occupy different streams"; Disaggregated strategy, "bubbles are nearly hidden through
- * micro-batching"; Sec. IV-C item 3).  This call generates rows [0, B) in micro-batches of micro_batch rows, one after
+ * generated, and the transfers run on a stream of their own beside the computation (Sec. IV-A: the Interleaving
+ * strategy puts communication and computation on separate streams, the Disaggregated strategy pipelines micro-batches
+ * to hide the idle time of the hand-off; Sec. IV-C, third recommendation of the second guideline).  This call generates rows [0, B) in micro-batches of micro_batch rows, one after
  * the other on cfg.stream, and tells the caller when each is finished:
  *   - after micro-batch i (rows row0 = i * micro_batch .. row0 + rows) is complete, done_events[i] (a hipEvent_t the
  *     caller created; done_events is a HOST array of ceil(B / micro_batch) entries, or NULL) is recorded on cfg.stream;
@@ -160,7 +160,7 @@ int rlhf_gen_generate(rlhf_gen_ctx* ctx, const int32_t* query_tokens, const int3
  *     of the finished rows to the host or to a peer, a scoring pass on another context - overlaps with the generation of
  *     the following micro-batches.
  * Row b draws the same random numbers as in rlhf_gen_generate over the whole batch, and the kernels accumulate every
- * output element in an order that does not depend on the number of rows while micro_batch <= 128, so the result then
+ * output element in an order that does not depend on the number of rows up to 256 rows per call, so the result then
  * equals rlhf_gen_generate's bit for bit.  Only min(micro_batch, B) <= cfg.max_batch is required (the KV pool is reused by each
  * micro-batch), so a context can be sized for the micro-batch.  rlhf_gen_last_timing reports the sums over the
  * micro-batches.  Other arguments and errors as for rlhf_gen_generate; on an error the remaining micro-batches are
