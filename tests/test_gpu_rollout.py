@@ -183,6 +183,18 @@ def test_error_paths_on_device(B):
     with pytest.raises(B.RlhfGenError) as e:
         ctx.rlhf_gen_generate(toks.cuda(), lens.tolist(), 16, sp)           # needs 2 * 2 pages, pool has 3
     assert e.value.status == B.E_NOMEM
+    with pytest.raises(B.RlhfGenError) as e:                                # an empty query
+        ctx.rlhf_gen_prefill(toks.cuda(), [0, 8], sp)
+    assert e.value.status == B.E_INVALID
+    with pytest.raises(B.RlhfGenError) as e:                                # an empty batch
+        ctx.rlhf_gen_prefill(toks[:0].cuda(), [], sp)
+    assert e.value.status == B.E_INVALID
+    with pytest.raises(B.RlhfGenError) as e:                                # more rows than max_batch
+        ctx.rlhf_gen_prefill(torch.cat([toks, toks]).cuda(), lens.tolist() * 2, sp)
+    assert e.value.status == B.E_INVALID
+    with pytest.raises(B.RlhfGenError) as e:
+        ctx.rlhf_gen_prefill(toks.cuda(), lens.tolist(), B.make_sampling(temperature=0.0))
+    assert e.value.status == B.E_INVALID
     ctx.rlhf_gen_prefill(toks.cuda(), lens.tolist(), sp)                    # 1 page each: fits
     for _ in range(8):
         ctx.rlhf_gen_decode_step()                                          # fills the first page of both
