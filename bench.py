@@ -282,10 +282,12 @@ def main() -> int:
         "metric": "generated tokens/sec + % HBM roofline per decode step, 7B-shape bf16 B=64",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
+        "dtype": "f16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": wl.name, "layers": shape.n_layers, "d_model": shape.d_model, "batch": B,
                    "query_len": [wl.len_lo, wl.len_hi], "resp_len": R, "temperature": wl.temperature, "top_p": wl.top_p,
-                   "kv_block": 16, "valid": not args.layers and not args.resp_len,
+                   "kv_block": 16,
+                   "weights": "bf16 at the boundary; fp16 MFMA operands (exact conversion), fp32 accumulation" if wl.dtype == "bf16" else "fp32",
+                   "valid": not args.layers and not args.resp_len,
                    "rollouts_bit_identical": repeatable},
         "decode": {"ms_per_decode_step": dec_ms / max(R - 1, 1), "tokens_per_s_decode_only": B * (R - 1) / (dec_ms * 1e-3) if dec_ms else None,
                    "hbm_roofline_frac_per_decode_step": dec_frac, "algorithmic_GB_per_step_mean": dec_bytes / max(R - 1, 1) / 1e9,
