@@ -160,8 +160,9 @@ int rlhf_gen_generate(rlhf_gen_ctx* ctx, const int32_t* query_tokens, const int3
  *     of the finished rows to the host or to a peer, a scoring pass on another context - overlaps with the generation of
  *     the following micro-batches.
  * Row b draws the same random numbers as in rlhf_gen_generate over the whole batch, and the kernels accumulate every
- * output element in an order that does not depend on the number of rows up to 256 rows per call, so the result then
- * equals rlhf_gen_generate's bit for bit.  Only min(micro_batch, B) <= cfg.max_batch is required (the KV pool is reused by each
+ * output element in an order that does not depend on the number of rows up to 128 rows per call (larger decode
+ * batches take a tile GEMM with another summation order), so for B <= 128 the result equals rlhf_gen_generate's bit
+ * for bit; for larger B it equals it within the rounding differences of the two GEMMs.  Only min(micro_batch, B) <= cfg.max_batch is required (the KV pool is reused by each
  * micro-batch), so a context can be sized for the micro-batch.  rlhf_gen_last_timing reports the sums over the
  * micro-batches.  Other arguments and errors as for rlhf_gen_generate; on an error the remaining micro-batches are
  * not generated. */

@@ -41,7 +41,9 @@ int rlhf_gen_op_tile_weights(void* stream, const void* w_rowmajor, void* w_tiled
  * STREAMING kinds W must be in the working layout made by rlhf_gen_op_tile_weights (A is plain row-major).
  *   TILED     fp16 A and W; epilogue selects out: fp32 [M,N] store, fp32 [M,N] accumulate, fp16 [M,N] store, or
  *             SWIGLU where W is [2N, K] (gate rows then up rows) and out is fp16 [M,N] = silu(gate) * up.
- *             N % 256 == 0 (N % 128 for SWIGLU), K % 128 == 0.
+ *             N % 256 == 0 (N % 128 for SWIGLU), K % 128 == 0.  With epilogue STORE_F32 and nsplit > 1: split-K
+ *             form for a few hundred rows, out is fp32 [nsplit, M, N] partial sums as for STREAMING; nsplit must
+ *             leave no split empty (ceil(K/32 / ceil(K/32 / nsplit)) == nsplit), else UNSUPPORTED.
  *   STREAMING fp16 A and W, M <= 256, N % 64 == 0, K % 128 == 0; out is fp32 [nsplit, M, N] partial sums whose
  *             sum over the first axis is the product.  nsplit in [1, K/128].  With epilogue SWIGLU instead: W is
  *             [2N, K] (gate rows then up rows), N % 32 == 0, no split, out is fp16 [M, N] = silu(gate) * up.

@@ -50,16 +50,25 @@ __device__ __forceinline__ f32x16_t mfma_32x32x16_v(u32x4_t a, u32x4_t b, f32x16
 #define LDS_WAIT8(N, f0, f1, f2, f3, f4, f5, f6, f7) \
   asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(f0), "+v"(f1), "+v"(f2), "+v"(f3), "+v"(f4), "+v"(f5), "+v"(f6), "+v"(f7))
 
-template <int EPI>
+// SPLIT: split-K form for a few hundred rows (large decode batches), where the output tiles alone cannot fill the
+// chip: workgroup (tile, split) contracts k-tiles [kw0, kw1) of W only and stores its fp32 tile into plane `split` of
+// `out` (plane_stride floats apart); the consumer kernel adds the planes in a fixed order.  With hi|lo inputs the
+// split walks (k-tile, hi), (k-tile, lo), ... so that the W tile fetched for the hi half is still in L2 for the lo half.
+template <int EPI, bool SPLIT>
 __global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restrict__ A, const h16_t* __restrict__ W,
                                                             void* __restrict__ out, int M, int N, int K, int tilesM,
-                                                            int tilesN, int a_dual) {
+                                                            int tilesN, int a_dual, int nsplit, size_t plane_stride) {
   // a_dual: A rows are [hi (K) | lo (K)]; the k loop then runs over 2K columns of A against W's K columns twice.
   constexpr int NS = DMA_NS, DIST = NS - 1, LPT = 8;  // LPT: DMA loads per thread and k-tile
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   int pid = blockIdx.x;
+  int split = 0;
+  if (SPLIT) {
+    split = pid % nsplit;
+    pid /= nsplit;
+  }
   const int total = tilesM * tilesN;
-  if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);  // consecutive tiles on one XCD (shared L2)
+  if (!SPLIT && (total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);  // consecutive tiles on one XCD (shared L2)
   const int band = 8 * tilesN;
   const int first_m = (pid / band) * 8;
   const int gsz = min(tilesM - first_m, 8);
@@ -92,13 +101,24 @@ __global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restri
                      : (uint32_t)(wtile_offset(grow, 0, K) * 2) + chunk * 16u;
   }
   const int nkw = K / 32;                 // k-tiles of W
-  const int nk = a_dual ? 2 * nkw : nkw;  // k-tiles of the product
+  int kw0 = 0, kw1 = nkw;                 // this workgroup's k-tiles of W
+  if (SPLIT) {
+    const int per = (nkw + nsplit - 1) / nsplit;
+    kw0 = split * per;
+    kw1 = min(nkw, kw0 + per);
+  }
+  const int nk = SPLIT ? (kw1 - kw0) * (a_dual ? 2 : 1) : (a_dual ? 2 * nkw : nkw);  // k-tiles of the product
   typedef __attribute__((address_space(3))) void lds_void;
   typedef const __attribute__((address_space(1))) void g_void;
   char* dma_dst = smem + wave * 8192;
   // tile KT of this wavefront's operand (past the end: the last tile again, into a stage nobody reads any more)
   auto tile_src = [&](int kt) -> const char* {
     kt = min(kt, nk - 1);
+    if (SPLIT) {
+      const int kw = kw0 + (a_dual ? kt >> 1 : kt);
+      if (loads_a) return gbase + ((a_dual && (kt & 1)) ? (size_t)K * 2 : (size_t)0) + (size_t)kw * 64;
+      return gbase + (size_t)(kw >> 2) * 4096 + (size_t)(kw & 3) * 1024;
+    }
     if (loads_a) return gbase + (size_t)kt * 64;
     const int kw = kt >= nkw ? kt - nkw : kt;
     return gbase + (size_t)(kw >> 2) * 4096 + (size_t)(kw & 3) * 1024;
@@ -201,7 +221,8 @@ __global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restri
         for (int jp = 0; jp < 2; ++jp) {
           const int n = tn * 256 + wn * 128 + 64 * jp + c2;
           const float v0 = acc[i][2 * jp][e], v1 = acc[i][2 * jp + 1][e];
-          if (EPI == EPI_STORE_F32) *(float2*)((float*)out + (size_t)m * N + n) = make_float2(v0, v1);
+          if (EPI == EPI_STORE_F32)
+            *(float2*)((float*)out + (SPLIT ? (size_t)split * plane_stride : (size_t)0) + (size_t)m * N + n) = make_float2(v0, v1);
           if (EPI == EPI_RESID_F32) {
             float2* o = (float2*)((float*)out + (size_t)m * N + n);
             float2 r = *o;
@@ -219,11 +240,23 @@ template <int EPI>
 hipError_t launch_large_dma(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K, int a_dual,
                             bool configure_only = false) {
   constexpr int SMEM = DMA_NS * DMA_STAGE;
-  auto kern = gemm_h16_dma_kernel<EPI>;
+  auto kern = gemm_h16_dma_kernel<EPI, false>;
   if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
   int tilesM = (M + 255) / 256;
   int tilesN = (EPI == EPI_SWIGLU) ? N / 128 : N / 256;
-  kern<<<tilesM * tilesN, 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, out, M, N, K, tilesM, tilesN, a_dual);
+  kern<<<tilesM * tilesN, 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, out, M, N, K, tilesM, tilesN, a_dual, 1, 0);
+  return hipGetLastError();
+}
+
+// split-K form: fp32 partial planes part[split][plane_rows][N]
+hipError_t launch_large_dma_split(hipStream_t s, const void* A, const void* W, float* part, int M, int N, int K, int a_dual,
+                                  int nsplit, int plane_rows, bool configure_only = false) {
+  constexpr int SMEM = DMA_NS * DMA_STAGE;
+  auto kern = gemm_h16_dma_kernel<EPI_STORE_F32, true>;
+  if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+  const int tilesM = (M + 255) / 256, tilesN = N / 256;
+  kern<<<tilesM * tilesN * nsplit, 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, N, K, tilesM, tilesN, a_dual,
+                                                   nsplit, (size_t)plane_rows * N);
   return hipGetLastError();
 }
 
@@ -614,6 +647,26 @@ hipError_t launch_gemm_h16(hipStream_t s, const void* A, const void* W, void* ou
   return hipErrorInvalidValue;
 }
 
+int gemm_tiled_pick_split(int M, int N, int K) {
+  // as many splits as it takes to give every compute unit one workgroup, none of them empty
+  const int tiles = ((M + 255) / 256) * (N / 256), nkw = K / 32;
+  int want = std::max(1, std::min(g_num_cu / std::max(tiles, 1), 16));
+  want = std::min(want, nkw);
+  const int per = (nkw + want - 1) / want;
+  return (nkw + per - 1) / per;
+}
+
+hipError_t launch_gemm_h16_splitk(hipStream_t s, const void* A, const void* W, float* part, int M, int N, int K, int a_dual,
+                                  int nsplit, int plane_rows) {
+  if (M <= 0) return hipSuccess;
+  if (plane_rows <= 0) plane_rows = M;
+  if (K % 128 || N % 256 || nsplit < 1 || plane_rows < M) return hipErrorInvalidValue;
+  const int nkw = K / 32, per = (nkw + nsplit - 1) / nsplit;
+  if ((nkw + per - 1) / per != nsplit) return hipErrorInvalidValue;   // a split would be empty
+  if ((size_t)M * (a_dual ? 2 : 1) * K * 2 >= ((size_t)1 << 32) || (size_t)N * K * 2 >= ((size_t)1 << 32)) return hipErrorInvalidValue;
+  return launch_large_dma_split(s, A, W, part, M, N, K, a_dual, nsplit, plane_rows);
+}
+
 // Raise the dynamic-LDS limit of every instantiation once per device (must not happen inside a stream capture).
 hipError_t gemm_configure() {
   hipError_t e;
@@ -621,6 +674,7 @@ hipError_t gemm_configure() {
   if ((e = launch_large_dma<EPI_RESID_F32>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, true)) != hipSuccess) return e;
   if ((e = launch_large_dma<EPI_SWIGLU>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, true)) != hipSuccess) return e;
   if ((e = launch_large_dma<EPI_STORE_ACT>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, true)) != hipSuccess) return e;
+  if ((e = launch_large_dma_split(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, 1, 0, true)) != hipSuccess) return e;
   {
     int dev = 0;
     hipDeviceProp_t prop;

@@ -64,6 +64,10 @@ struct rlhf_gen_ctx {
   float *x = nullptr, *qkv = nullptr, *logits = nullptr, *part = nullptr;
   void *y = nullptr, *yl = nullptr, *qb = nullptr, *ab = nullptr, *hb = nullptr;
   int ks_qkv = 1, ks_wo = 1, ks_gu = 1, ks_down = 1;
+  // split counts of the split-K tile GEMM that takes decode batches of 129..256 rows (tile_ok: every projection
+  // has a width the 256-column tiles divide)
+  bool tile_ok = false;
+  int kt_qkv = 1, kt_wo = 1, kt_gu = 1, kt_down = 1;
 
   // pinned host staging
   int *h_tok_seq = nullptr, *h_tok_pos = nullptr, *h_cu = nullptr, *h_seq_ids = nullptr, *h_last_rows = nullptr,
@@ -279,11 +283,21 @@ static int skinny_pairs(rlhf_gen_ctx* c, const void* A, const void* W, int B, in
   return RLHF_GEN_OK;
 }
 
+// Batches of more than 128 rows are past the point where the weight stream bounds the projections (at 256 rows the
+// MFMA time of a projection exceeds its weight-streaming time), and the streaming kernel, in which every wavefront
+// reads the whole activation slice, falls behind: measured at 256 rows on the 7B shapes, QKV 115 -> 62 us,
+// output projection 43 -> 28 us, gate/up 180 -> 74 + 12 us (un-fused, two splits), down 75 -> 42 us with the
+// split-K form of the large-tile GEMM.  At 128 rows and below the streaming kernels are faster.
+static bool decode_uses_tiles(const rlhf_gen_ctx* c, int B) { return c->tile_ok && B > 128; }
+
 int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
   const rlhf_gen_cfg& g = c->cfg;
   const int d = g.d_model, Hq = g.n_heads, Hkv = g.n_kv_heads, h = g.head_dim, F = g.d_ffn;
   const int qkv_w = (Hq + 2 * Hkv) * h;
   hipStream_t s = c->stream;
+  const bool tiles = decode_uses_tiles(c, B);
+  const int ks_qkv = tiles ? c->kt_qkv : c->ks_qkv, ks_wo = tiles ? c->kt_wo : c->ks_wo;
+  const int ks_down = tiles ? c->kt_down : c->ks_down;
   prof_mark(c, -1);
   LAUNCH(c, launch_embed(s, c->d_cur_tok, c->tok_emb, 1, c->x, B, d, g.vocab, c->d_err), "embed");
   prof_mark(c, RLHF_GEN_PROF_EMBED);
@@ -293,31 +307,49 @@ int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
     LAUNCH(c, launch_rmsnorm(s, c->x, pending ? c->part : nullptr, pending, (size_t)B * d, c->attn_norm[l], 1, c->y, 1,
                              B, d, g.rms_eps, nullptr, 1), "rmsnorm");
     prof_mark(c, RLHF_GEN_PROF_NORM);
-    if (int rc = skinny_pairs(c, c->y, c->wqkv[l], B, qkv_w, d, c->ks_qkv, "gemm_skinny qkv")) return rc;
+    if (tiles) {
+      LAUNCH(c, launch_gemm_h16_splitk(s, c->y, c->wqkv[l], c->part, B, qkv_w, d, 1, ks_qkv, B), "gemm_splitk qkv");
+    } else if (int rc = skinny_pairs(c, c->y, c->wqkv[l], B, qkv_w, d, ks_qkv, "gemm_skinny qkv")) {
+      return rc;
+    }
     prof_mark(c, RLHF_GEN_PROF_GEMM_QKV);
     size_t st = (size_t)B * qkv_w;
     if (!(c->cfg.flags & RLHF_GEN_FLAG_FUSED_ROPE)) {
-      LAUNCH(c, launch_rope_append(s, c->part, c->ks_qkv > 1 ? c->part + st : nullptr, c->ks_qkv - 1, st, c->d_seq_len,
+      LAUNCH(c, launch_rope_append(s, c->part, ks_qkv > 1 ? c->part + st : nullptr, ks_qkv - 1, st, c->d_seq_len,
                                    nullptr, c->d_cos, c->d_sin, c->qb, pool, c->d_table, c->max_blocks, c->n_blocks, B, Hq,
                                    Hkv, h, 1), "rope_append");
       prof_mark(c, RLHF_GEN_PROF_ROPE);
       LAUNCH(c, launch_attn_decode_h16(s, c->qb, pool, c->d_table, c->max_blocks, c->n_blocks, c->d_seq_len, c->ab, B, Hq,
                                        Hkv), "attn_decode");
     } else {
-      LAUNCH(c, launch_attn_decode_fused_h16(s, c->part, c->ks_qkv, st, c->d_cos, c->d_sin, pool, c->d_table, c->max_blocks,
+      LAUNCH(c, launch_attn_decode_fused_h16(s, c->part, ks_qkv, st, c->d_cos, c->d_sin, pool, c->d_table, c->max_blocks,
                                              c->n_blocks, c->d_seq_len, c->ab, B, Hq, Hkv), "attn_decode_fused");
     }
     prof_mark(c, RLHF_GEN_PROF_ATTN);
-    if (int rc = skinny_pairs(c, c->ab, c->wo[l], B, d, Hq * h, c->ks_wo, "gemm_skinny wo")) return rc;
+    if (tiles) {
+      LAUNCH(c, launch_gemm_h16_splitk(s, c->ab, c->wo[l], c->part, B, d, Hq * h, 1, ks_wo, B), "gemm_splitk wo");
+    } else if (int rc = skinny_pairs(c, c->ab, c->wo[l], B, d, Hq * h, ks_wo, "gemm_skinny wo")) {
+      return rc;
+    }
     prof_mark(c, RLHF_GEN_PROF_GEMM_WO);
-    LAUNCH(c, launch_rmsnorm(s, c->x, c->part, c->ks_wo, (size_t)B * d, c->ffn_norm[l], 1, c->y, 1, B, d, g.rms_eps,
+    LAUNCH(c, launch_rmsnorm(s, c->x, c->part, ks_wo, (size_t)B * d, c->ffn_norm[l], 1, c->y, 1, B, d, g.rms_eps,
                              nullptr, 0), "rmsnorm");
     prof_mark(c, RLHF_GEN_PROF_NORM);
-    LAUNCH(c, launch_gemm_skinny_h16(s, c->y, c->w_gate_up[l], (float*)c->hb, B, 2 * F, d, 0, 0), "gemm_skinny gate_up");
+    if (tiles) {
+      // gate and up as plain partial sums (the fused SwiGLU epilogue cannot be split), combined by a small kernel
+      LAUNCH(c, launch_gemm_h16_splitk(s, c->y, c->w_gate_up[l], c->part, B, 2 * F, d, 0, c->kt_gu, B), "gemm_splitk gate_up");
+      LAUNCH(c, launch_swiglu(s, c->part, c->kt_gu, (size_t)B * 2 * F, c->hb, 1, B, F), "swiglu");
+    } else {
+      LAUNCH(c, launch_gemm_skinny_h16(s, c->y, c->w_gate_up[l], (float*)c->hb, B, 2 * F, d, 0, 0), "gemm_skinny gate_up");
+    }
     prof_mark(c, RLHF_GEN_PROF_GEMM_GATE_UP);
-    LAUNCH(c, launch_gemm_skinny_h16(s, c->hb, c->w_down[l], c->part, B, d, F, c->ks_down, 0), "gemm_skinny down");
+    if (tiles) {
+      LAUNCH(c, launch_gemm_h16_splitk(s, c->hb, c->w_down[l], c->part, B, d, F, 0, ks_down, B), "gemm_splitk down");
+    } else {
+      LAUNCH(c, launch_gemm_skinny_h16(s, c->hb, c->w_down[l], c->part, B, d, F, ks_down, 0), "gemm_skinny down");
+    }
     prof_mark(c, RLHF_GEN_PROF_GEMM_DOWN);
-    pending = c->ks_down;
+    pending = ks_down;
   }
   LAUNCH(c, launch_rmsnorm(s, c->x, pending ? c->part : nullptr, pending, (size_t)B * d, c->final_norm, 1, c->yl, 1, B,
                            d, g.rms_eps, nullptr, 0), "final rmsnorm");
@@ -793,6 +825,18 @@ static int allocate_all(rlhf_gen_ctx* c) {
     c->ks_down = gemm_skinny_pick_split(Bm, g.d_model, g.d_ffn);
     size_t pe = std::max(std::max((size_t)c->ks_qkv * qkv_w, (size_t)c->ks_wo * g.d_model),
                          std::max((size_t)c->ks_gu * 2 * g.d_ffn, (size_t)c->ks_down * g.d_model));
+    const int attn_w = g.n_heads * g.head_dim;
+    c->tile_ok = Bm > 128 && qkv_w % 256 == 0 && g.d_model % 256 == 0 && (2 * g.d_ffn) % 256 == 0 && attn_w % 128 == 0 &&
+                 g.d_ffn % 128 == 0 && (size_t)2 * g.d_ffn * g.d_model * 2 < ((size_t)1 << 32) &&
+                 (size_t)g.d_model * g.d_ffn * 2 < ((size_t)1 << 32) && (size_t)qkv_w * g.d_model * 2 < ((size_t)1 << 32);
+    if (c->tile_ok) {
+      c->kt_qkv = gemm_tiled_pick_split(Bm, qkv_w, g.d_model);
+      c->kt_wo = gemm_tiled_pick_split(Bm, g.d_model, attn_w);
+      c->kt_gu = gemm_tiled_pick_split(Bm, 2 * g.d_ffn, g.d_model);
+      c->kt_down = gemm_tiled_pick_split(Bm, g.d_model, g.d_ffn);
+      pe = std::max(pe, std::max(std::max((size_t)c->kt_qkv * qkv_w, (size_t)c->kt_wo * g.d_model),
+                                 std::max((size_t)c->kt_gu * 2 * g.d_ffn, (size_t)c->kt_down * g.d_model)));
+    }
     A_(dev_alloc(c, &c->part, 4 * pe * Bm, true));
   }
   A_(host_alloc(c, &c->h_tok_seq, sizeof(int) * total_tok));
@@ -1289,7 +1333,9 @@ int rlhf_gen_op_gemm(void* stream, int kind, const void* A, const void* W, void*
     if (gemm_configure() != hipSuccess) return RLHF_GEN_E_DEVICE;
     configured = true;
   }
-  if (kind == RLHF_GEN_GEMM_TILED) e = launch_gemm_h16(s, A, W, out, M, N, K, epilogue, a_pairs);
+  if (kind == RLHF_GEN_GEMM_TILED)
+    e = (nsplit > 1 && epilogue == EPI_STORE_F32) ? launch_gemm_h16_splitk(s, A, W, (float*)out, M, N, K, a_pairs, nsplit, 0)
+                                                  : launch_gemm_h16(s, A, W, out, M, N, K, epilogue, a_pairs);
   else if (kind == RLHF_GEN_GEMM_STREAMING)
     e = launch_gemm_skinny_h16(s, A, W, (float*)out, M, epilogue == EPI_SWIGLU ? 2 * N : N, K,
                                epilogue == EPI_SWIGLU ? 0 : nsplit, a_pairs);

@@ -160,6 +160,36 @@ def test_gemm_fp32(B):
     assert (out.cpu().double() - 2 * ref).abs().max() < 1e-5
 
 
+@pytest.mark.parametrize("M,N,K,ns,pairs", [(256, 512, 1024, 4, 0), (200, 768, 384, 3, 1), (129, 256, 128, 2, 0),
+                                             (256, 256, 1408, 16, 0), (300, 512, 512, 5, 1), (256, 12288, 4096, 5, 1)])
+def test_gemm_tiled_split_k(B, M, N, K, ns, pairs):
+    """Split-K form of the tiled GEMM (decode batches of 129..256 rows): the planes add up to the product; a split
+    count that would leave a split empty is refused."""
+    nkw = K // 32
+    per = -(-nkw // ns)
+    ns = -(-nkw // per)                                                      # the nearest count with no empty split
+    g = torch.Generator().manual_seed(41)
+    x = torch.randn(M, K, generator=g, dtype=torch.float64)
+    hi = x.to(torch.float16)
+    w = _rand((N, K), 42, 0.05)
+    if pairs:
+        lo = (x - hi.double()).to(torch.float16)
+        a = torch.cat([hi, lo], dim=1).contiguous().cuda()
+        ref = (hi.double() + lo.double()) @ w.double().T
+    else:
+        a = hi.cuda()
+        ref = hi.double() @ w.double().T
+    part = torch.full((ns, M, N), 3.0, dtype=torch.float32, device="cuda")
+    assert B.rlhf_gen_op_gemm(B.GEMM_TILED, a, _tiled(B, w), part, M, N, K, B.EPI_STORE_F32, ns, pairs) == 0
+    torch.cuda.synchronize()
+    assert (part.cpu().double().sum(0) - ref).abs().max() < 1e-5 * math.sqrt(K) + 1e-6
+    if ns > 1:
+        # every plane holds a share of the sum (none is left at its fill value, none is the whole product)
+        assert float((part[0].cpu().double() - ref).abs().max()) > 1e-3
+    if nkw % 7 and nkw > 7 and -(-nkw // (-(-nkw // 7))) != 7:
+        assert B.rlhf_gen_op_gemm(B.GEMM_TILED, a, _tiled(B, w), part, M, N, K, B.EPI_STORE_F32, 7, pairs) == B.E_UNSUPPORTED
+
+
 def test_gemm_rejects_bad_shapes(B):
     t = torch.zeros(256, 256, dtype=torch.float16, device="cuda")
     o = torch.zeros(256, 256, dtype=torch.float32, device="cuda")

@@ -133,9 +133,9 @@ def test_small_bf16_teacher_forced(B, shape, flags):
 
 @pytest.mark.parametrize("batch", [17, 100, 200, 300])
 def test_small_bf16_larger_batches(B, batch):
-    """Batches that take the other instantiations of the decode GEMM (up to 32 / 128 / 256 rows, the pair-input
-    projections in slabs of 128 rows) and, above 256 rows, the tiled GEMM; page size 16 with contexts that cross page
-    boundaries during decode."""
+    """Batches that take the other instantiations of the decode GEMM (up to 32 / 128 rows), the split-K tile GEMMs
+    with the separate SwiGLU kernel (129..256 rows) and, above 256 rows, the tiled GEMM of the prefill; page size 16
+    with contexts that cross page boundaries during decode."""
     shape = BF16_SMALL
     w = synth.make_weights(shape, 21, "bf16")
     synth.randomize_norm_gains(w, 22)
