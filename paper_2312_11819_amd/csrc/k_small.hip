@@ -109,13 +109,12 @@ __global__ __launch_bounds__(NT) void rmsnorm_kernel(float* __restrict__ x, cons
       if (nsplit > 0) {
         const float* pp = part + (size_t)m * d + i;
         int sidx = 0;
-        if (nsplit == 8) {  // the usual split count: eight independent loads in flight, added in order
+        for (; sidx + 8 <= nsplit; sidx += 8) {  // the usual split counts (8, 16): eight independent loads in flight, added in order
           float4 pv[8];
 #pragma unroll
-          for (int s8 = 0; s8 < 8; ++s8) pv[s8] = *(const float4*)(pp + (size_t)s8 * part_stride);
+          for (int s8 = 0; s8 < 8; ++s8) pv[s8] = *(const float4*)(pp + (size_t)(sidx + s8) * part_stride);
 #pragma unroll
           for (int s8 = 0; s8 < 8; ++s8) { a.x += pv[s8].x; a.y += pv[s8].y; a.z += pv[s8].z; a.w += pv[s8].w; }
-          sidx = 8;
         }
         for (; sidx + 4 <= nsplit; sidx += 4) {  // four independent loads in flight, added in order
           float4 p0 = *(const float4*)(pp + (size_t)(sidx + 0) * part_stride);
@@ -325,11 +324,41 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ g
     ((float*)h_out)[(size_t)m * F + f] = v;
 }
 
+// Four features per thread, 16-bit output (F % 4 == 0): the decode path at 129..256 rows, where gate and up arrive
+// as split-K planes.  Planes are added in order 0, 1, ..., like the scalar kernel.
+__global__ __launch_bounds__(256) void swiglu4_kernel(const float* __restrict__ gu, int nsplit, size_t part_stride,
+                                                      h16_t* __restrict__ h_out, int F) {
+  const int m = blockIdx.y;
+  const int f = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (f >= F) return;
+  const float* row = gu + (size_t)m * 2 * F;
+  float4 g = *(const float4*)(row + f), u = *(const float4*)(row + F + f);
+  int sidx = 1;
+  for (; sidx + 2 <= nsplit; sidx += 2) {
+    const float4 g0 = *(const float4*)(row + (size_t)sidx * part_stride + f), u0 = *(const float4*)(row + (size_t)sidx * part_stride + F + f);
+    const float4 g1 = *(const float4*)(row + (size_t)(sidx + 1) * part_stride + f), u1 = *(const float4*)(row + (size_t)(sidx + 1) * part_stride + F + f);
+    g.x += g0.x; g.y += g0.y; g.z += g0.z; g.w += g0.w; u.x += u0.x; u.y += u0.y; u.z += u0.z; u.w += u0.w;
+    g.x += g1.x; g.y += g1.y; g.z += g1.z; g.w += g1.w; u.x += u1.x; u.y += u1.y; u.z += u1.z; u.w += u1.w;
+  }
+  for (; sidx < nsplit; ++sidx) {
+    const float4 g0 = *(const float4*)(row + (size_t)sidx * part_stride + f), u0 = *(const float4*)(row + (size_t)sidx * part_stride + F + f);
+    g.x += g0.x; g.y += g0.y; g.z += g0.z; g.w += g0.w; u.x += u0.x; u.y += u0.y; u.z += u0.z; u.w += u0.w;
+  }
+  uint2 o;
+  o.x = pack_h16x2(g.x / (1.f + __expf(-g.x)) * u.x, g.y / (1.f + __expf(-g.y)) * u.y);
+  o.y = pack_h16x2(g.z / (1.f + __expf(-g.z)) * u.z, g.w / (1.f + __expf(-g.w)) * u.w);
+  *(uint2*)(h_out + (size_t)m * F + f) = o;
+}
+
 hipError_t launch_swiglu(hipStream_t s, const float* gu, int nsplit, size_t part_stride, void* h_out, int act_bf16,
                          int M, int F) {
   if (M <= 0) return hipSuccess;
-  dim3 grid((F + 255) / 256, M);
   if (nsplit < 1) nsplit = 1;
+  if (act_bf16 && F % 4 == 0 && part_stride % 4 == 0) {
+    swiglu4_kernel<<<dim3((F / 4 + 255) / 256, M), 256, 0, s>>>(gu, nsplit, part_stride, (h16_t*)h_out, F);
+    return hipGetLastError();
+  }
+  dim3 grid((F + 255) / 256, M);
   if (act_bf16)
     swiglu_kernel<true><<<grid, 256, 0, s>>>(gu, nsplit, part_stride, h_out, F);
   else

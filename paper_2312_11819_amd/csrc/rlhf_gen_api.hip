@@ -354,7 +354,11 @@ int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
   LAUNCH(c, launch_rmsnorm(s, c->x, pending ? c->part : nullptr, pending, (size_t)B * d, c->final_norm, 1, c->yl, 1, B,
                            d, g.rms_eps, nullptr, 0), "final rmsnorm");
   prof_mark(c, RLHF_GEN_PROF_NORM);
-  LAUNCH(c, launch_gemm_skinny_h16(s, c->yl, c->lm_head, c->logits, B, g.vocab, d, 1, 0), "gemm_skinny lm_head");
+  if (tiles && g.vocab % 256 == 0 && (size_t)g.vocab * d * 2 < ((size_t)1 << 32)) {
+    LAUNCH(c, launch_gemm_h16(s, c->yl, c->lm_head, c->logits, B, g.vocab, d, EPI_STORE_F32, 0), "gemm lm_head");
+  } else {
+    LAUNCH(c, launch_gemm_skinny_h16(s, c->yl, c->lm_head, c->logits, B, g.vocab, d, 1, 0), "gemm_skinny lm_head");
+  }
   prof_mark(c, RLHF_GEN_PROF_LM_HEAD);
   return RLHF_GEN_OK;
 }
