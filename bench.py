@@ -210,7 +210,8 @@ def main() -> int:
                         "bytes_per_launch": attn_bytes / n_attn}
         else:
             n_g = sum(prof["launches"][k] for k in ("gemm_qkv", "gemm_wo", "gemm_gate_up", "gemm_down", "lm_head"))
-            roofline = {"kernel": "gemm_skinny_kernel", "bound": "hbm", "achieved": gemm_bytes / (gemm_ms * 1e-3) / 1e9,
+            # (batches of more than 128 rows run the projections as the split-K form of the large-tile GEMM)
+            roofline = {"kernel": "gemm_skinny_kernel" if B <= 128 else "gemm_h16_dma_kernel<0, true>", "bound": "hbm", "achieved": gemm_bytes / (gemm_ms * 1e-3) / 1e9,
                         "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": gemm_bytes / (gemm_ms * 1e-3) / HBM_PEAK,
                         "traffic": None, "avg_launch_us": gemm_ms / n_g * 1e3, "launches_timed": n_g,
                         "bytes_per_launch": gemm_bytes / n_g}
@@ -218,7 +219,7 @@ def main() -> int:
         # weight-conversion copy kernel): measured on a 2-layer, 48-token run of this workload, because counter runs of
         # the full-size command do not finish; the fetched / algorithmic ratio of those launches is applied to this
         # run's launches (profiles/bench_7b_b64_pmc_traffic.md)
-        pmc = {"attn_decode_kernel": (1.058, 1.05e6), "gemm_skinny_kernel": (1.111, 10.7e6)}[roofline["kernel"]]
+        pmc = {"attn_decode_kernel": (1.058, 1.05e6), "gemm_skinny_kernel": (1.111, 10.7e6)}.get(roofline["kernel"])
         if wl.name == "7b_b64":
             roofline["traffic"] = pmc[0] * roofline["bytes_per_launch"] + pmc[1]
             roofline["traffic_source"] = "rocprofv3 --pmc ratio of a reduced-depth run, see profiles/bench_7b_b64_pmc_traffic.md"
