@@ -184,6 +184,10 @@ def main() -> int:
     pre_flop = 2 * layer_mm * shape.n_layers * lsum + 2 * B * shape.vocab * shape.d_model
     pre_flop_attn = sum(2 * int(l) * int(l) * shape.n_heads * shape.head_dim * shape.n_layers for l in lens)
     pre_frac = (pre_flop + pre_flop_attn) / (pre_ms * 1e-3) / MFMA_BF16_PEAK if pre_ms > 0 else None
+    # a decode step's projections as a fraction of the MFMA peak (matters at B = 256, where 2 B flop per 2-byte
+    # weight is near the ridge point)
+    dec_flop_step = 2 * B * (layer_mm * shape.n_layers + shape.vocab * shape.d_model)
+    dec_mfma_frac = dec_flop_step * max(R - 1, 1) / (dec_ms * 1e-3) / MFMA_BF16_PEAK if dec_ms > 0 else None
 
     roofline = None
     kernels = {}
@@ -291,7 +295,8 @@ def main() -> int:
                    "valid": not args.layers and not args.resp_len,
                    "rollouts_bit_identical": repeatable},
         "decode": {"ms_per_decode_step": dec_ms / max(R - 1, 1), "tokens_per_s_decode_only": B * (R - 1) / (dec_ms * 1e-3) if dec_ms else None,
-                   "hbm_roofline_frac_per_decode_step": dec_frac, "algorithmic_GB_per_step_mean": dec_bytes / max(R - 1, 1) / 1e9,
+                   "hbm_roofline_frac_per_decode_step": dec_frac, "mfma_bf16_frac_per_decode_step": dec_mfma_frac,
+                   "gemm_TFLOP_per_step": dec_flop_step / 1e12, "algorithmic_GB_per_step_mean": dec_bytes / max(R - 1, 1) / 1e9,
                    "hbm_roofline_frac_step_min": min(step_fracs) if step_fracs else None,
                    "hbm_roofline_frac_step_max": max(step_fracs) if step_fracs else None,
                    "hbm_roofline_frac_step_mean": sum(step_fracs) / len(step_fracs) if step_fracs else None},
