@@ -281,13 +281,16 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __res
   constexpr int XR = DUAL ? 2 * MB : MB;   // 16-row blocks of the staged slice
   constexpr int XBYTES = 16 * XR * SK_ROW;
   constexpr int NT = 64 * NW;
-  constexpr int XL = 256 * XR / NT;        // 16-byte chunks of the slice each thread moves per k-step
-  static_assert(XL * NT == 256 * XR, "slice chunks must divide evenly over the threads");
+  constexpr int XL = (256 * XR + NT - 1) / NT;   // 16-byte chunks of the slice each thread moves per k-step
+  constexpr bool XEXACT = XL * NT == 256 * XR;   // otherwise the last round of chunks is taken by some threads only
   const int ldx = DUAL ? 2 * K : K;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, t = lane & 15, g = lane >> 4;
-  // GLU: W = [gate rows | up rows] of F = Nw / 2 features each; the workgroup owns 32 features, each wavefront
-  // 8 of them with the gate rows in MFMA rows 0..7 and the matching up rows in 8..15.
+  // GLU: W = [gate rows | up rows] of F = Nw / 2 features each; the workgroup owns 8 NW features, each wavefront
+  // 8 of them with the gate rows in MFMA rows 0..7 and the matching up rows in 8..15.  8 NW need not divide F: the
+  // wavefronts of the last workgroup that fall beyond F go through the motions on rows 0.. and store nothing.
   const int n0 = GLU ? blockIdx.x * (8 * NW) : blockIdx.x * (16 * NW);
+  const bool live = !GLU || n0 + 8 * w < (Nw >> 1);
+  const int nb = live ? n0 + 8 * w : 0;
   const int nsteps_total = K / SK;
   const int s0 = blockIdx.y * steps_per_split;
   const int s1 = min(nsteps_total, s0 + steps_per_split);
@@ -296,7 +299,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __res
 #pragma unroll
   for (int i = 0; i < MB; ++i) acc[i] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
-  const int wrow = GLU ? ((t < 8) ? n0 + 8 * w + t : (Nw >> 1) + n0 + 8 * w + (t - 8)) : n0 + 16 * w + t;
+  const int wrow = GLU ? ((t < 8) ? nb + t : (Nw >> 1) + nb + (t - 8)) : n0 + 16 * w + t;
   const h16_t* wp = W + wtile_offset(wrow, 8 * g, K);   // W is in the tiled working layout: 2048 halves per k-step
   // Activation slice: 16 MB rows x 16 chunks of 16 B per k-step, MB chunks per thread.  Rows beyond M are read
   // from row M - 1 instead: they only feed output columns that are never stored.
@@ -304,7 +307,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __res
   int xo[XL];
 #pragma unroll
   for (int it = 0; it < XL; ++it) {
-    int c = it * NT + tid, r = c >> 4, kc = c & 15;   // r in [0, 16 XR): rows >= 16 MB are the lo parts
+    int c = it * NT + tid;
+    if (!XEXACT) c = min(c, 256 * XR - 1);            // (a thread without a chunk in the last round repeats the last chunk)
+    const int r = c >> 4, kc = c & 15;                // r in [0, 16 XR): rows >= 16 MB are the lo parts
     int rr = DUAL ? r % (16 * MB) : r;
     xp[it] = X + (size_t)min(rr, M - 1) * ldx + ((DUAL && r >= 16 * MB) ? K : 0) + kc * 8;
     xo[it] = r * SK_ROW + kc * 16;
@@ -342,7 +347,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __res
 #define SKINNY_STEP(S, PAR)                                                                              \
   {                                                                                                      \
     char* buf = smem + (PAR) * XBYTES;                                                                   \
-    _Pragma("unroll") for (int it = 0; it < XL; ++it) *(uint4*)(buf + xo[it]) = S.x[it];                 \
+    _Pragma("unroll") for (int it = 0; it < XL; ++it)                                                    \
+        if (XEXACT || it * NT + tid < 256 * XR) *(uint4*)(buf + xo[it]) = S.x[it];                       \
     __syncthreads();                                                                                     \
     uint4 xf[2][XR];                                                                                     \
     _Pragma("unroll") for (int mb = 0; mb < XR; ++mb)                                                    \
@@ -394,6 +400,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __res
 #undef SKINNY_STEP
 #undef SKINNY_LOAD
   if (GLU) {
+    if (!live) return;
     // lane (t, g < 2) holds gate features 4g..4g+3 of column t, lane (t, g + 2) the matching up values
     h16_t* hout = (h16_t*)part;
     const int F = Nw >> 1;
@@ -592,13 +599,54 @@ hipError_t launch_skinny_nw(hipStream_t s, const void* A, const void* W, float* 
   return hipGetLastError();
 }
 
+// Fused gate/up form (no split, so the grid cannot be tuned by the split count): NW wavefronts of 8 features each per
+// workgroup, the last workgroup possibly ragged.
+template <int MB, int NW>
+hipError_t launch_skinny_glu(hipStream_t s, const void* A, const void* W, void* out, int M, int Nw, int K, bool configure_only) {
+  constexpr int SMEM = 2 * 16 * MB * SK_ROW;
+  constexpr int D = MB <= 4 ? 4 : 2;
+  auto kern = gemm_skinny_kernel<MB, D, true, false, NW>;
+  if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+  const int F = Nw / 2;
+  kern<<<dim3((F + 8 * NW - 1) / (8 * NW), 1), 64 * NW, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, (float*)out, M, Nw, K, K / SK, M);
+  return hipGetLastError();
+}
+
+// Workgroup width for the gate/up form: the one of 8, 7, 6 wavefronts that gives the most workgroups without
+// exceeding the number of compute units (a function of F only, never of the batch).  Measured at 64 rows:
+// 7B (F = 11008) 172 / 197 / 230 workgroups = 41.8 / 38.1 / 37.2 us and 276 workgroups (5 wavefronts) 56.6 us;
+// 13B (F = 13824) 216 / 247 workgroups = 51.7 / 49.5 us, 288 workgroups 79.9 us; 70B (448 / 512 workgroups) no difference.
+inline int skinny_glu_width(int F) {
+  int best = 8, best_wgs = 0;
+  for (int nw = 8; nw >= 6; --nw) {
+    const int wgs = (F + 8 * nw - 1) / (8 * nw);
+    if (wgs <= g_num_cu && wgs > best_wgs) { best = nw; best_wgs = wgs; }
+  }
+  return best;
+}
+
 template <int MB>
 hipError_t launch_skinny(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K, int nsplit,
                          int a_dual, int plane_rows, bool configure_only = false) {
   if (configure_only) {
     hipError_t e = launch_skinny_nw<MB, 4>(s, A, W, part, M, Nw, K, nsplit, a_dual, plane_rows, true);
     if (e != hipSuccess) return e;
+    if constexpr (MB <= 8) {
+      if ((e = launch_skinny_glu<MB, 6>(s, A, W, part, M, Nw, K, true)) != hipSuccess) return e;
+      if ((e = launch_skinny_glu<MB, 7>(s, A, W, part, M, Nw, K, true)) != hipSuccess) return e;
+      if ((e = launch_skinny_glu<MB, 8>(s, A, W, part, M, Nw, K, true)) != hipSuccess) return e;
+    }
     return launch_skinny_nw<MB, 8>(s, A, W, part, M, Nw, K, nsplit, a_dual, plane_rows, true);
+  }
+  if constexpr (MB <= 8) {
+    if (nsplit == 0) {
+      if (a_dual || Nw % 16) return hipErrorInvalidValue;
+      switch (skinny_glu_width(Nw / 2)) {
+        case 6: return launch_skinny_glu<MB, 6>(s, A, W, part, M, Nw, K, false);
+        case 7: return launch_skinny_glu<MB, 7>(s, A, W, part, M, Nw, K, false);
+        default: return launch_skinny_glu<MB, 8>(s, A, W, part, M, Nw, K, false);
+      }
+    }
   }
   // eight wavefronts (128 rows of W per workgroup) when the shape allows: half the activation-slice traffic
   const bool wide = Nw % 128 == 0 && (a_dual ? true : 4 * MB >= 8) && MB <= 8;

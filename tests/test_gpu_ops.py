@@ -88,7 +88,10 @@ def test_gemm_streaming(B, M, N, K, ns):
     assert (got - ref).abs().max() < 1e-5 * math.sqrt(K) + 1e-6
 
 
-@pytest.mark.parametrize("M,F,K", [(64, 352, 256), (5, 32, 128), (200, 96, 512)])
+@pytest.mark.parametrize("M,F,K", [(64, 352, 256), (5, 32, 128), (200, 96, 512),
+                                   # widths that 8, 7 or 6 wavefronts of 8 features do not divide (ragged last workgroup),
+                                   # at every batch-width instantiation; the last is the 7B width (230 workgroups of 6)
+                                   (16, 1376, 256), (32, 13824, 128), (128, 480, 256), (64, 11008, 512)])
 def test_gemm_streaming_swiglu(B, M, F, K):
     a, w = _rand((M, K), 13), _rand((2 * F, K), 14, 0.1)
     gu = a.double() @ w.double().T
