@@ -695,10 +695,10 @@ hipError_t launch_gemm_h16(hipStream_t s, const void* A, const void* W, void* ou
   return hipErrorInvalidValue;
 }
 
-int gemm_tiled_pick_split(int M, int N, int K) {
+int gemm_tiled_pick_split(int M, int N, int K, int max_splits) {
   // as many splits as it takes to give every compute unit one workgroup, none of them empty
   const int tiles = ((M + 255) / 256) * (N / 256), nkw = K / 32;
-  int want = std::max(1, std::min(g_num_cu / std::max(tiles, 1), 16));
+  int want = std::max(1, std::min(g_num_cu / std::max(tiles, 1), max_splits));
   want = std::min(want, nkw);
   const int per = (nkw + want - 1) / want;
   return (nkw + per - 1) / per;

@@ -20,7 +20,7 @@ hipError_t launch_gemm_h16(hipStream_t s, const void* A, const void* W, void* ou
 // (no split may be empty: take nsplit from gemm_tiled_pick_split), N % 256 == 0, K % 128 == 0; the consumer adds the planes.
 hipError_t launch_gemm_h16_splitk(hipStream_t s, const void* A, const void* W, float* part, int M, int N, int K, int a_dual,
                                   int nsplit, int plane_rows = 0);
-int gemm_tiled_pick_split(int M, int N, int K);
+int gemm_tiled_pick_split(int M, int N, int K, int max_splits = 16);
 // Weight-streaming GEMM for M <= 256 rows: writes fp32 partial sums part[ks][M][Nw] (Nw = rows of W)
 // for ks < nsplit; the consumer kernel adds them.  nsplit = 0 selects the fused SwiGLU form: W = [2F, K]
 // (gate rows, then up rows; Nw = 2F), no split, and `part` receives fp16 [M, F] = silu(gate) * up.

@@ -834,7 +834,7 @@ static int allocate_all(rlhf_gen_ctx* c) {
                  g.d_ffn % 128 == 0 && (size_t)2 * g.d_ffn * g.d_model * 2 < ((size_t)1 << 32) &&
                  (size_t)g.d_model * g.d_ffn * 2 < ((size_t)1 << 32) && (size_t)qkv_w * g.d_model * 2 < ((size_t)1 << 32);
     if (c->tile_ok) {
-      c->kt_qkv = gemm_tiled_pick_split(Bm, qkv_w, g.d_model);
+      c->kt_qkv = gemm_tiled_pick_split(Bm, qkv_w, g.d_model, 8);   // (the fused RoPE + attention kernel takes up to 8 planes)
       c->kt_wo = gemm_tiled_pick_split(Bm, g.d_model, attn_w);
       c->kt_gu = gemm_tiled_pick_split(Bm, 2 * g.d_ffn, g.d_model);
       c->kt_down = gemm_tiled_pick_split(Bm, g.d_model, g.d_ffn);

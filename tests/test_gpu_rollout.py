@@ -131,12 +131,12 @@ def test_small_bf16_teacher_forced(B, shape, flags):
     assert abs(sum(steps) - dec_ms) <= 0.05 * dec_ms + 0.05
 
 
-@pytest.mark.parametrize("batch", [17, 100, 200, 300])
-def test_small_bf16_larger_batches(B, batch):
+@pytest.mark.parametrize("batch,shape,flags", [(17, BF16_SMALL, 0), (100, BF16_SMALL, 0), (200, BF16_SMALL, 0),
+                                               (300, BF16_SMALL, 0), (200, BF16_SMALL_GQA, 16), (129, BF16_SMALL_GQA, 0)])
+def test_small_bf16_larger_batches(B, batch, shape, flags):
     """Batches that take the other instantiations of the decode GEMM (up to 32 / 128 rows), the split-K tile GEMMs
     with the separate SwiGLU kernel (129..256 rows) and, above 256 rows, the tiled GEMM of the prefill; page size 16
     with contexts that cross page boundaries during decode."""
-    shape = BF16_SMALL
     w = synth.make_weights(shape, 21, "bf16")
     synth.randomize_norm_gains(w, 22)
     toks, lens = synth.make_queries(shape.vocab, batch, 3, 40, 23, pad_token=1)
@@ -144,7 +144,7 @@ def test_small_bf16_larger_batches(B, batch):
     osp = OSampling(**cfgs)
     rows = sorted({0, batch // 3, batch - 1})
     ref = oracle_generate(w, shape, _queries(toks, lens), 20, osp, rows=rows)
-    ctx = B.Context(synth.weights_to(w, "cuda"), shape, "bf16", batch, 64)
+    ctx = B.Context(synth.weights_to(w, "cuda"), shape, "bf16", batch, 64, flags=flags)
     sp = B.make_sampling(**cfgs)
     tok, lp = ctx.rlhf_gen_prefill(toks.cuda(), lens.tolist(), sp)
     worst = 0.0
