@@ -332,15 +332,16 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __res
     return (size_t)(s0 + r) * SK;
   };
   // Ring of D named slots (separate variables, so that they live in registers).  The weights are read once: the
-  // nontemporal hint is worth 10 % on the gate/up and down projections; with the doubled activation slice of the
-  // pair-input variant it measured 3 % slower than plain loads, so that variant keeps plain loads.
+  // nontemporal hint is worth 10 % on the gate/up and down projections.  In the pair-input variant it is worth 3-8 %
+  // up to 32 rows (measured on the 13B and 70B shapes) but costs 3-5 % at 64 rows with their doubled activation slice
+  // (7B output projection), so that variant uses it for the one- and two-block instantiations only.
   struct Slot { uint4 w[4]; uint4 x[XL]; };
   Slot r0, r1, r2, r3;
 #define SKINNY_LOAD(S, I)                                                                                \
   {                                                                                                      \
     const size_t ko = step_off(I);                                                                       \
     _Pragma("unroll") for (int kk = 0; kk < 4; ++kk)                                                    \
-        S.w[kk] = DUAL ? *(const uint4*)(wp + ko * 16 + kk * 512) : load_stream16(wp + ko * 16 + kk * 512);  \
+        S.w[kk] = (DUAL && MB > 2) ? *(const uint4*)(wp + ko * 16 + kk * 512) : load_stream16(wp + ko * 16 + kk * 512);  \
     _Pragma("unroll") for (int it = 0; it < XL; ++it) S.x[it] = *(const uint4*)(xp[it] + ko);            \
   }
   // one k-step on slot S (LDS buffer PAR)
