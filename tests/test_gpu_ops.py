@@ -88,6 +88,57 @@ def test_gemm_streaming(B, M, N, K, ns):
     assert (got - ref).abs().max() < 1e-5 * math.sqrt(K) + 1e-6
 
 
+def test_gemm_seeded_shape_sweep(B):
+    """Thirty seeded shapes across the three forms of the decode GEMM and the split-K tile form: every batch-width
+    instantiation, ragged row counts, split counts with a short last split, gate/up widths with a ragged last
+    workgroup."""
+    rng = torch.Generator().manual_seed(2024)
+    ri = lambda lo, hi: int(torch.randint(lo, hi + 1, (1,), generator=rng))
+    for case in range(30):
+        form = ("plain", "pairs", "swiglu", "tile_split")[case % 4]
+        K = 128 * ri(1, 12)
+        steps = K // 128
+        if form == "swiglu":
+            M, F = ri(1, 128), 32 * ri(1, 40)
+            a, w = _rand((M, K), 100 + case), _rand((2 * F, K), 200 + case, 0.1)
+            gu = a.double() @ w.double().T
+            ref = OT.silu(gu[:, :F]) * gu[:, F:]
+            out = torch.zeros((M, F), dtype=torch.float16, device="cuda")
+            assert B.rlhf_gen_op_gemm(B.GEMM_STREAMING, a.cuda(), _tiled(B, w), out, M, F, K, B.EPI_SWIGLU, 1) == 0, (case, M, F, K)
+            torch.cuda.synchronize()
+            assert ((out.cpu().double() - ref).abs() <= ref.abs() * 2 ** -11 + 1e-4).all(), (case, M, F, K)
+            continue
+        pairs = form == "pairs"
+        if form == "tile_split":
+            M, N = ri(129, 300), 256 * ri(1, 4)
+            nkw = K // 32
+            per = -(-nkw // ri(2, 8))
+            ns = -(-nkw // per)
+            pairs = bool(case % 8 >= 4)
+        else:
+            M, N = ri(1, 128), 64 * ri(1, 12)
+            per = -(-steps // ri(1, min(8, steps)))
+            ns = -(-steps // per)
+        x = torch.randn(M, K, generator=rng, dtype=torch.float64)
+        hi = x.to(torch.float16)
+        w = _rand((N, K), 300 + case, 0.05)
+        if pairs:
+            lo = (x - hi.double()).to(torch.float16)
+            a = torch.cat([hi, lo], dim=1).contiguous().cuda()
+            ref = (hi.double() + lo.double()) @ w.double().T
+        else:
+            a, ref = hi.cuda(), hi.double() @ w.double().T
+        part = torch.full((ns, M, N), float("nan"), dtype=torch.float32, device="cuda")
+        kind = B.GEMM_TILED if form == "tile_split" else B.GEMM_STREAMING
+        rc = B.rlhf_gen_op_gemm(kind, a, _tiled(B, w), part, M, N, K, 0, ns, int(pairs))
+        if form == "tile_split" and ns == 1:
+            part = part[0]
+        assert rc == 0, (case, form, M, N, K, ns)
+        torch.cuda.synchronize()
+        got = part.cpu().double().sum(0) if part.dim() == 3 else part.cpu().double()
+        assert (got - ref).abs().max() < 1e-5 * math.sqrt(K) + 1e-6, (case, form, M, N, K, ns)
+
+
 @pytest.mark.parametrize("M,F,K", [(64, 352, 256), (5, 32, 128), (200, 96, 512),
                                    # widths that 8, 7 or 6 wavefronts of 8 features do not divide (ragged last workgroup),
                                    # at every batch-width instantiation; the last is the 7B width (230 workgroups of 6)
