@@ -32,8 +32,9 @@ int rlhf_gen_op_probe_mfma_loop(void* stream, const void* operands, int32_t work
 
 /* Re-order an fp16 weight matrix W [N, K] (row-major) into the library's working layout, which the 16-bit GEMMs below
  * expect (rlhf_gen_init does the same to the Actor's matrices while converting them from bf16): tiles of 16 rows x
- * 128 columns, 4 KB each, stored row-block major, and inside a tile the halves in the order
- * [k/32 % 4][row % 16][k % 32].  N % 16 == 0, K % 128 == 0; the two buffers must not overlap. */
+ * 128 columns, 4 KB each, inside a tile the halves in the order [k/32 % 4][row % 16][k % 32]; the tiles are stored
+ * in slabs of 256 rows (the last slab may be shorter), slab after slab, and inside a slab in the order
+ * [k/128][row/16 within the slab].  N % 16 == 0, K % 128 == 0; the two buffers must not overlap. */
 int rlhf_gen_op_tile_weights(void* stream, const void* w_rowmajor, void* w_tiled, int32_t N, int32_t K);
 
 /* out = A[M,K] * W[N,K]^T (the projections of a decoder layer, y = x W^T).

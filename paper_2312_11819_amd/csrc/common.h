@@ -76,12 +76,24 @@ __device__ __forceinline__ float wave_max(float v) {
 //   values: 16 B chunk (j, lane) at 4096 + j*1024 + lane*16 holds, for tokens 4*(lane>>4) .. +4,
 //           V[token][dim 32j + (lane&15)] in its first 8 B and V[token][dim 32j + 16 + (lane&15)] in the rest
 // Working layout of a 16-bit weight matrix W [N, K] (N % 16 == 0, K % 128 == 0): tiles of 16 rows x 128 columns,
-// 4 KB each, row-block major ([N/16][K/128] tiles); inside a tile the halves are ordered [k/32 % 4][row % 16][k/8 % 4][k % 8].
-// A wavefront of the weight-streaming GEMM then takes one k-step of its 16 rows with four loads of 1 KB of
-// consecutive bytes (whole cache lines, so the nontemporal hint pays), and the large-tile GEMM finds the 64 bytes
-// of one (row, 32-column k-tile) together.  Offset in halves of element (n, k):
-__host__ __device__ __forceinline__ size_t wtile_offset(int n, int k, int K) {
-  return ((size_t)(n >> 4) * (size_t)(K >> 7) + (size_t)(k >> 7)) * 2048 + (size_t)(((k >> 5) & 3) * 512 + (n & 15) * 32 + (k & 31));
+// 4 KB each; inside a tile the halves are ordered [k/32 % 4][row % 16][k/8 % 4][k % 8].  Tiles are grouped in slabs
+// of 16 row-blocks (256 rows; the last slab of a matrix may hold fewer), slab after slab, and inside a slab they are
+// ordered k-step major: [k/128][row-block in slab].  A wavefront of the weight-streaming GEMM takes one k-step of its
+// 16 rows with four loads of 1 KB of consecutive bytes (whole cache lines, so the nontemporal hint pays), the eight
+// wavefronts of a workgroup together read 32 KB of consecutive bytes per k-step (measured: a weight stream in which
+// each wavefront walks a run of its own, 128 KB apart, reaches 4.1-5.5 TB/s on the decode shapes, this order 5.0-5.9),
+// and the large-tile GEMM finds the 64 bytes of one (row, 32-column k-tile) together.  A slab is 256 whole rows, so
+// a block of rows that starts at a multiple of 256 occupies the same bytes as in the row-major matrix, which is what
+// the in-place conversion relies on.  Row-blocks in the slab of row-block rb, and offset in halves of element (n, k):
+constexpr int WSLAB_RB = 16;
+__host__ __device__ __forceinline__ int wslab_blocks(int rb, int N) {
+  const int left = (N >> 4) - (rb & ~(WSLAB_RB - 1));
+  return left < WSLAB_RB ? left : WSLAB_RB;
+}
+__host__ __device__ __forceinline__ size_t wtile_offset(int n, int k, int K, int N) {
+  const int rb = n >> 4, s0 = rb & ~(WSLAB_RB - 1);
+  const size_t tile = (size_t)s0 * (size_t)(K >> 7) + (size_t)(k >> 7) * (size_t)wslab_blocks(rb, N) + (size_t)(rb - s0);
+  return tile * 2048 + (size_t)(((k >> 5) & 3) * 512 + (n & 15) * 32 + (k & 31));
 }
 
 constexpr int KV_PAGE_TOKENS = 16;

@@ -98,7 +98,7 @@ __global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restri
     // A is row-major; W is in the tiled working layout (16-row x 128-column tiles of 4 KB, a row's 64 bytes of one
     // k-tile together)
     go[it] = loads_a ? (uint32_t)grow * (uint32_t)(a_dual ? 2 * K : K) * 2u + chunk * 16u
-                     : (uint32_t)(wtile_offset(grow, 0, K) * 2) + chunk * 16u;
+                     : (uint32_t)(wtile_offset(grow, 0, K, EPI == EPI_SWIGLU ? 2 * N : N) * 2) + chunk * 16u;
   }
   const int nkw = K / 32;                 // k-tiles of W
   int kw0 = 0, kw1 = nkw;                 // this workgroup's k-tiles of W
@@ -117,11 +117,11 @@ __global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restri
     if (SPLIT) {
       const int kw = kw0 + (a_dual ? kt >> 1 : kt);
       if (loads_a) return gbase + ((a_dual && (kt & 1)) ? (size_t)K * 2 : (size_t)0) + (size_t)kw * 64;
-      return gbase + (size_t)(kw >> 2) * 4096 + (size_t)(kw & 3) * 1024;
+      return gbase + (size_t)(kw >> 2) * (WSLAB_RB * 4096) + (size_t)(kw & 3) * 1024;   // (every slab is full: rows % 256 == 0)
     }
     if (loads_a) return gbase + (size_t)kt * 64;
     const int kw = kt >= nkw ? kt - nkw : kt;
-    return gbase + (size_t)(kw >> 2) * 4096 + (size_t)(kw & 3) * 1024;
+    return gbase + (size_t)(kw >> 2) * (WSLAB_RB * 4096) + (size_t)(kw & 3) * 1024;   // (every slab is full: rows % 256 == 0)
   };
 #define DMA1(SRC, SOFF, IT) \
   __builtin_amdgcn_global_load_lds((g_void*)((SRC) + go[IT]), (lds_void*)(dma_dst + (SOFF) + (IT) * 1024), 16, 0, 0);
@@ -300,7 +300,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __res
   for (int i = 0; i < MB; ++i) acc[i] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
   const int wrow = GLU ? ((t < 8) ? nb + t : (Nw >> 1) + nb + (t - 8)) : n0 + 16 * w + t;
-  const h16_t* wp = W + wtile_offset(wrow, 8 * g, K);   // W is in the tiled working layout: 2048 halves per k-step
+  // W is in the tiled working layout: consecutive k-steps of a row-block lie (row-blocks in its slab) tiles apart
+  const h16_t* wp = W + wtile_offset(wrow, 8 * g, K, Nw);
+  const size_t wstep = (size_t)wslab_blocks(wrow >> 4, Nw) * 2048;
   // Activation slice: 16 MB rows x 16 chunks of 16 B per k-step, MB chunks per thread.  Rows beyond M are read
   // from row M - 1 instead: they only feed output columns that are never stored.
   const h16_t* xp[XL];
@@ -326,10 +328,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __res
   // Loads are issued without any branch around them (a step index past the end re-reads the last step, which
   // hits in cache): with straight-line code the compiler can keep D - 1 steps of loads in flight and wait only
   // for the oldest.
-  auto step_off = [&](int i) -> size_t {
+  auto step_off = [&](int i) -> size_t {   // the k-step behind ring index i
     int r = min(i, nst - 1) + rot;
     if (r >= nst) r -= nst;
-    return (size_t)(s0 + r) * SK;
+    return (size_t)(s0 + r);
   };
   // Ring of D named slots (separate variables, so that they live in registers).  The weights are read once: the
   // nontemporal hint is worth 10 % on the gate/up and down projections.  In the pair-input variant it is worth 3-8 %
@@ -339,10 +341,11 @@ __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __res
   Slot r0, r1, r2, r3;
 #define SKINNY_LOAD(S, I)                                                                                \
   {                                                                                                      \
-    const size_t ko = step_off(I);                                                                       \
+    const size_t st_ = step_off(I);                                                                      \
+    const h16_t* wq_ = wp + st_ * wstep;                                                                 \
     _Pragma("unroll") for (int kk = 0; kk < 4; ++kk)                                                    \
-        S.w[kk] = (DUAL && MB > 2) ? *(const uint4*)(wp + ko * 16 + kk * 512) : load_stream16(wp + ko * 16 + kk * 512);  \
-    _Pragma("unroll") for (int it = 0; it < XL; ++it) S.x[it] = *(const uint4*)(xp[it] + ko);            \
+        S.w[kk] = (DUAL && MB > 2) ? *(const uint4*)(wq_ + kk * 512) : load_stream16(wq_ + kk * 512);    \
+    _Pragma("unroll") for (int it = 0; it < XL; ++it) S.x[it] = *(const uint4*)(xp[it] + st_ * SK);      \
   }
   // one k-step on slot S (LDS buffer PAR)
 #define SKINNY_STEP(S, PAR)                                                                              \
@@ -463,7 +466,7 @@ __global__ __launch_bounds__(512) void gemm_skinny_xres_kernel(const h16_t* __re
   const h16_t* wlane = W + (size_t)(t * 32 + g * 8);
   auto w_off = [&](int f) -> size_t {
     f = min(f, F - 1);
-    return ((size_t)((j + (f >> 2) * G) * 8 + w) * nsteps + (size_t)(4 * s + (f & 3))) * 2048;
+    return wtile_offset(((j + (f >> 2) * G) * 8 + w) * 16, (4 * s + (f & 3)) * 128, K, Nw);
   };
   struct Slot { uint4 w[4]; };
   Slot r0, r1, r2, r3;

@@ -415,7 +415,7 @@ __global__ void to_h16_tiled_kernel(const uint16_t* __restrict__ src, h16_t* __r
                          fmaf(scale, d[2 * j + 1], __uint_as_float(vw[j] & 0xffff0000u)));
     o = make_uint4(ow[0], ow[1], ow[2], ow[3]);
   }
-  *(uint4*)(dst + wtile_offset(n, k, cols)) = o;
+  *(uint4*)(dst + wtile_offset(n, k, cols, rows)) = o;
 }
 
 hipError_t launch_to_h16_tiled(hipStream_t s, const void* src, int src_is_h16, void* dst, int rows, int cols, const void* A,

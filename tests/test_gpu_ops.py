@@ -27,13 +27,19 @@ def _tiled(B, w: torch.Tensor) -> torch.Tensor:
     return dst
 
 
-def test_tile_weights_layout(B):
-    """Tiles of 16 rows x 128 columns, row-block major; inside a tile [k/32 % 4][row % 16][k % 32]."""
-    N, K = 48, 384
+@pytest.mark.parametrize("N,K", [(48, 384), (256, 256), (592, 128), (1040, 384)])
+def test_tile_weights_layout(B, N, K):
+    """Tiles of 16 rows x 128 columns, inside a tile [k/32 % 4][row % 16][k % 32]; slabs of 16 row-blocks (the last one
+    may be shorter), inside a slab [k/128][row-block]."""
     w = torch.arange(N * K, dtype=torch.int32).remainder(30000).to(torch.int16).view(N, K)
     got = _tiled(B, w.view(torch.float16)).cpu().view(torch.int16).flatten()
-    want = w.view(N // 16, 16, K // 128, 4, 32).permute(0, 2, 3, 1, 4).contiguous().flatten()
-    assert torch.equal(got, want)
+    slabs = []
+    for r0 in range(0, N, 256):
+        sl = w[r0:r0 + 256]                                                   # [rows, K], rows a multiple of 16
+        nb = sl.shape[0] // 16
+        # [rb, 16, ks, 4, 32] -> [ks, rb, 4 (k/32), 16 (row), 32]
+        slabs.append(sl.reshape(nb, 16, K // 128, 4, 32).permute(2, 0, 3, 1, 4).contiguous().flatten())
+    assert torch.equal(got, torch.cat(slabs))
     t = torch.zeros(16, 128, dtype=torch.float16, device="cuda")
     assert B.rlhf_gen_op_tile_weights(t, t) == B.E_INVALID                   # in place is not possible
     assert B.rlhf_gen_op_tile_weights(torch.zeros(8, 128, dtype=torch.float16, device="cuda"),
