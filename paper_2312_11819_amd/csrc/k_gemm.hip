@@ -1,9 +1,11 @@
 // GEMMs of the rollout, out = A[M,K] * W[N,K]^T with both operands K-contiguous.
 //   gemm_h16_dma_kernel : large-tile fp16 MFMA GEMM for prefill (M = thousands of tokens): 256x256x32 block tile,
 //                         4 wavefronts of 128x128, LDS ring filled by LDS-DMA loads, 32x32x16 MFMA.
-//   gemm_skinny_kernel  : weight-streaming GEMM for decode (M = batch <= 256): W is the MFMA row operand read
-//                         straight from HBM into registers exactly once, the activation slice is staged in LDS,
-//                         split-K partial sums go to a workspace that the consumer kernel adds up in a fixed order.
+//   gemm_skinny_kernel  : weight-streaming GEMM for decode (M = batch <= 128; up to 256 where the split-K form of the
+//                         large-tile GEMM does not apply): W is the MFMA row operand read straight from HBM into
+//                         registers exactly once, the activation slice is staged in LDS, split-K partial sums go
+//                         to a workspace that the consumer kernel adds up in a fixed order.
+//   gemm_skinny_xres_kernel : the same with the activation slice of a split resident in LDS (QKV at <= 64 rows).
 //   gemm_f32_kernel     : plain-ALU fp32 GEMM for the small fp32 configuration.
 #include <stdlib.h>
 
@@ -264,12 +266,15 @@ hipError_t launch_large_dma_split(hipStream_t s, const void* A, const void* W, f
 constexpr int SK = 128;                 // k extent of one staged activation slice
 constexpr int SK_ROW = SK * 2 + 16;     // bytes per LDS row (padded)
 
-// grid (Nw / (16 NW), nsplit), 64 NW threads; wavefront w owns W rows n0 + 16 w .. +16 and all M (<= 16 MB) columns.
-// Measured on MI355X the kernel's time follows (weight bytes + activation-slice bytes requested from L2) / ~6.5 TB/s,
-// so the slice re-reads matter as much as the weights: eight wavefronts per workgroup (128 rows of W) halve them.
+// grid (Nw / (16 NW), nsplit), 64 NW threads; wavefront w owns W rows n0 + 16 w .. +16 and all M (<= 16 MB) columns
+// (the fused gate/up form: 8 gate and 8 up rows per wavefront, grid ceil(F / 8 NW), last workgroup ragged).
 // Loads run D - 1 k-steps ahead of the MFMAs through a register ring (weights and the activation slice alike:
 // the memory counter retires in order, so both must share one prefetch distance); the activation slice then
-// passes through a double-buffered LDS tile that the four wavefronts share.
+// passes through a double-buffered LDS tile that the workgroup's wavefronts share.  What the time is made of,
+// measured on MI355X on the 7B gate/up shape at 64 rows (37 us): the weight loads alone 29 us, the MFMAs +3, the
+// LDS staging and its per-step barrier +1, the slice loads from L2 +2, the output stores +2.  Workgroups, not
+// bytes, are the first-order term: the kernel is fastest with one workgroup per compute unit, all in flight from
+// the first cycle (see the launchers for how the split count and the workgroup width are chosen for that).
 template <int MB, int D, bool GLU, bool DUAL, int NW>
 __global__ __launch_bounds__(64 * NW) void gemm_skinny_kernel(const h16_t* __restrict__ X, const h16_t* __restrict__ W,
                                                           float* __restrict__ part, int M, int Nw, int K,
