@@ -38,14 +38,19 @@ __device__ __forceinline__ void load_page(const char* page, int lane, uint4 kf[4
 
 // tok0: index of the page's first token; limit: number of tokens visible to this lane's query row.
 // qf[0..3]: high parts of the query fragments, qf[4..7]: low parts (queries are fp16 pairs).
-template <bool MASK>
-__device__ __forceinline__ void attn_page(const uint4 kf[4], const uint4 vf[4], const uint4 qf[8], AttnState& st,
-                                          float scale_log2, int tok0, int limit, int g) {
+// The two halves of a page's work: scores from the key half, then the softmax update and the value half.
+__device__ __forceinline__ f32x4_t attn_scores(const uint4 kf[4], const uint4 qf[8]) {
   f32x4_t s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) s = mfma_16x16x32(kf[kk], qf[4 + kk], s);
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) s = mfma_16x16x32(kf[kk], qf[kk], s);
+  return s;
+}
+
+template <bool MASK>
+__device__ __forceinline__ void attn_update(f32x4_t s, const uint4 vf[4], AttnState& st, float scale_log2, int tok0,
+                                            int limit, int g) {
   float sv[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -84,6 +89,12 @@ __device__ __forceinline__ void attn_page(const uint4 kf[4], const uint4 vf[4], 
   }
 }
 
+template <bool MASK>
+__device__ __forceinline__ void attn_page(const uint4 kf[4], const uint4 vf[4], const uint4 qf[8], AttnState& st,
+                                          float scale_log2, int tok0, int limit, int g) {
+  attn_update<MASK>(attn_scores(kf, qf), vf, st, scale_log2, tok0, limit, g);
+}
+
 __device__ __forceinline__ void init_state(AttnState& st) {
 #pragma unroll
   for (int db = 0; db < 8; ++db) st.o[db] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
@@ -107,14 +118,20 @@ struct FusedArgs {
   const float* sin_t;
 };
 
-template <bool FUSED>
-__global__ __launch_bounds__(256) void attn_decode_kernel(const h16_t* __restrict__ q, char* __restrict__ pool,
+// NWV wavefronts per workgroup share a sequence's pages (page p goes to wavefront p % NWV); ROWS >= Hq / Hkv query rows.
+// Measured on MI355X with the bare read pattern of this kernel (no arithmetic, same residency of 8 wavefronts per
+// compute unit): four wavefronts with the next page prefetched while the current one is consumed reach 6.4-6.7 TB/s,
+// eight wavefronts that each fetch a page, consume it and only then fetch the next reach 7.0-7.1 TB/s - the eight
+// page loads of a workgroup then cover 64 KB of consecutive bytes and nothing else of that sequence is in flight.
+// PREFETCH selects the former (kept for the fused form and for groups of more than 8 query heads).
+template <bool FUSED, int NWV, int ROWS, bool PREFETCH>
+__global__ __launch_bounds__(64 * NWV) void attn_decode_kernel(const h16_t* __restrict__ q, char* __restrict__ pool,
                                                           const int* __restrict__ block_table, int max_blocks, int n_blocks,
                                                           const int* __restrict__ seq_len, h16_t* __restrict__ out,
                                                           int Hq, int Hkv, float scale_log2, FusedArgs fa) {
-  __shared__ float m_s[4][16];
-  __shared__ float l_s[4][16];
-  __shared__ float o_s[4][16][132];
+  __shared__ float m_s[NWV][16];
+  __shared__ float l_s[NWV][16];
+  __shared__ float o_s[NWV][ROWS][132];
   __shared__ __attribute__((aligned(16))) h16_t q_s[FUSED ? 16 : 1][256];  // [row][hi 128 | lo 128]
   __shared__ h16_t kn_s[FUSED ? 128 : 1], vn_s[FUSED ? 128 : 1];
   __shared__ float snew_s[16];
@@ -128,7 +145,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const h16_t* __restric
   uint4 qf[8];
   // block-table entries of this wavefront's first 64 pages and its first page: issued before anything else
   const int last = npages - 1;
-  const int my_blk0 = npages > 0 ? bt[min(w + 4 * lane, last)] : 0;
+  const int my_blk0 = npages > 0 ? bt[min(w + NWV * lane, last)] : 0;
   uint4 ka[4], va[4], kb[4], vb[4];
   load_page<true>(pool + ((size_t)kvh * n_blocks + __shfl(my_blk0, 0)) * KV_PAGE_BYTES, lane, ka, va);
   if (FUSED) {
@@ -138,7 +155,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const h16_t* __restric
     char* page = pool + ((size_t)kvh * n_blocks + bt[pos >> 4]) * KV_PAGE_BYTES;
     const int slot = pos & 15;
     // tasks: (group + 2) vectors of 128 (the group's query heads, the key, the value), 64 dimension pairs each
-    for (int task = threadIdx.x; task < (group + 2) * 64; task += 256) {
+    for (int task = threadIdx.x; task < (group + 2) * 64; task += 64 * NWV) {
       const int vec = task >> 6, i = task & 63;
       int col;  // column of dimension i of this vector in the fused qkv row
       if (vec < group) col = (kvh * group + vec) * 128 + i;
@@ -186,7 +203,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const h16_t* __restric
       if (t < group) qf[kk] = *(const uint4*)(&q_s[t][(kk >> 2) * 128 + 8 * (4 * (kk & 3) + g)]);
     }
     // score of the new token against each query row (same fp16 values a later step will read from the cache)
-    for (int r = w; r < group; r += 4) {
+    for (int r = w; r < group; r += NWV) {
       float acc = 0.f;
 #pragma unroll
       for (int e = 0; e < 2; ++e) {
@@ -206,25 +223,44 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const h16_t* __restric
   }
   AttnState st;
   init_state(st);
-  // This wavefront takes pages w, w + 4, w + 8, ...  Their block-table entries are fetched up front, 64 at a time
-  // (lane i holds the entry of page w + 4 i), and broadcast from registers inside the loop.  Page loads are issued
+  // This wavefront takes pages w, w + NWV, w + 2 NWV, ...  Their block-table entries are fetched up front, 64 at a time
+  // (lane i holds the entry of page w + NWV i), and broadcast from registers inside the loop.  Page loads are issued
   // with no branch around them (an index past the end re-reads the last page), so that the loads of the next page
   // stay in flight while the current one is consumed.
-  for (int base = w; base < npages; base += 256) {
+  for (int base = w; base < npages; base += 64 * NWV) {
     int my_blk = my_blk0;
-    if (base != w) {  // beyond 4096 tokens: next batch of 64 pages
-      my_blk = bt[min(base + 4 * lane, last)];
+    if (base != w) {  // beyond 64 NWV pages: next batch of 64 pages per wavefront
+      my_blk = bt[min(base + NWV * lane, last)];
       load_page<true>(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, 0)) * KV_PAGE_BYTES, lane, ka, va);
     }
-    const int cnt = min(64, (npages - base + 3) >> 2);  // pages of this wavefront in this batch
-    int i = 0;
-    for (; i + 2 <= cnt; i += 2) {
-      load_page<true>(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, i + 1)) * KV_PAGE_BYTES, lane, kb, vb);
-      attn_page<true>(ka, va, qf, st, scale_log2, (base + 4 * i) * 16, L, g);
-      load_page<true>(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, min(i + 2, cnt - 1))) * KV_PAGE_BYTES, lane, ka, va);
-      attn_page<true>(kb, vb, qf, st, scale_log2, (base + 4 * (i + 1)) * 16, L, g);
+    const int cnt = min(64, (npages - base + NWV - 1) / NWV);  // pages of this wavefront in this batch
+    if (PREFETCH) {
+      int i = 0;
+      for (; i + 2 <= cnt; i += 2) {
+        load_page<true>(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, i + 1)) * KV_PAGE_BYTES, lane, kb, vb);
+        attn_page<true>(ka, va, qf, st, scale_log2, (base + NWV * i) * 16, L, g);
+        load_page<true>(pool + ((size_t)kvh * n_blocks + __shfl(my_blk, min(i + 2, cnt - 1))) * KV_PAGE_BYTES, lane, ka, va);
+        attn_page<true>(kb, vb, qf, st, scale_log2, (base + NWV * (i + 1)) * 16, L, g);
+      }
+      if (i < cnt) attn_page<true>(ka, va, qf, st, scale_log2, (base + NWV * i) * 16, L, g);
+    } else {
+      // one page in flight per wavefront: the key half of the next page is requested as soon as the scores of
+      // this one have been issued, its value half after the value MFMAs
+      for (int i = 0; i < cnt; ++i) {
+        const f32x4_t sc = attn_scores(ka, qf);
+        const bool more = i + 1 < cnt;
+        const char* next = pool + ((size_t)kvh * n_blocks + __shfl(my_blk, min(i + 1, cnt - 1))) * KV_PAGE_BYTES;
+        if (more) {
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) ka[kk] = load_stream16(next + kk * 1024 + lane * 16);
+        }
+        attn_update<true>(sc, va, st, scale_log2, (base + NWV * i) * 16, L, g);
+        if (more) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) va[j] = load_stream16(next + 4096 + j * 1024 + lane * 16);
+        }
+      }
     }
-    if (i < cnt) attn_page<true>(ka, va, qf, st, scale_log2, (base + 4 * i) * 16, L, g);
   }
   float lt = st.l;
   lt += __shfl_xor(lt, 16);
@@ -237,13 +273,15 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const h16_t* __restric
       for (int i = 0; i < 4; ++i) o_s[w][t][db * 16 + 4 * g + i] = st.o[db][i];
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < group * 128; idx += 256) {
+  for (int idx = threadIdx.x; idx < group * 128; idx += 64 * NWV) {
     int r = idx >> 7, dim = idx & 127;
-    float M = fmaxf(fmaxf(m_s[0][r], m_s[1][r]), fmaxf(m_s[2][r], m_s[3][r]));
+    float M = m_s[0][r];
+#pragma unroll
+    for (int ww = 1; ww < NWV; ++ww) M = fmaxf(M, m_s[ww][r]);
     if (FUSED) M = fmaxf(M, snew_s[r]);
     float num = 0.f, den = 0.f;
 #pragma unroll
-    for (int ww = 0; ww < 4; ++ww) {
+    for (int ww = 0; ww < NWV; ++ww) {
       float mw = m_s[ww][r];
       float a = (mw == -INFINITY) ? 0.f : exp2f(mw - M);
       num += a * o_s[ww][r][dim];
@@ -386,8 +424,15 @@ hipError_t launch_attn_decode_h16(hipStream_t s, const void* q, const void* kv_p
   if (Hq % Hkv || Hq / Hkv > 16) return hipErrorInvalidValue;
   float scale_log2 = LOG2E / sqrtf((float)KV_HEAD_DIM);
   FusedArgs fa{};
-  attn_decode_kernel<false><<<dim3(Hkv, B), 256, 0, s>>>((const h16_t*)q, (char*)const_cast<void*>(kv_pool_layer), block_table,
-                                                         max_blocks, n_blocks, seq_len, (h16_t*)out, Hq, Hkv, scale_log2, fa);
+  // (the form depends on the head counts only, never on the batch, so a sequence's result is the same bits in any batch)
+  if (Hq / Hkv <= 8)
+    attn_decode_kernel<false, 8, 8, false><<<dim3(Hkv, B), 512, 0, s>>>((const h16_t*)q, (char*)const_cast<void*>(kv_pool_layer),
+                                                                        block_table, max_blocks, n_blocks, seq_len, (h16_t*)out,
+                                                                        Hq, Hkv, scale_log2, fa);
+  else
+    attn_decode_kernel<false, 4, 16, true><<<dim3(Hkv, B), 256, 0, s>>>((const h16_t*)q, (char*)const_cast<void*>(kv_pool_layer),
+                                                                        block_table, max_blocks, n_blocks, seq_len, (h16_t*)out,
+                                                                        Hq, Hkv, scale_log2, fa);
   return hipGetLastError();
 }
 
@@ -399,7 +444,7 @@ hipError_t launch_attn_decode_fused_h16(hipStream_t s, const float* qkv_part, in
   if (Hq % Hkv || Hq / Hkv > 16 || nsplit < 1 || nsplit > 8) return hipErrorInvalidValue;
   float scale_log2 = LOG2E / sqrtf((float)KV_HEAD_DIM);
   FusedArgs fa{qkv_part, nsplit, part_stride, (Hq + 2 * Hkv) * KV_HEAD_DIM, cos_t, sin_t};
-  attn_decode_kernel<true><<<dim3(Hkv, B), 256, 0, s>>>(nullptr, (char*)kv_pool_layer, block_table, max_blocks, n_blocks,
+  attn_decode_kernel<true, 4, 16, true><<<dim3(Hkv, B), 256, 0, s>>>(nullptr, (char*)kv_pool_layer, block_table, max_blocks, n_blocks,
                                                         seq_len, (h16_t*)out, Hq, Hkv, scale_log2, fa);
   return hipGetLastError();
 }
