@@ -138,16 +138,22 @@ __global__ __launch_bounds__(64 * NWV) void attn_decode_kernel(const h16_t* __re
   const int kvh = blockIdx.x, b = blockIdx.y;
   const int group = Hq / Hkv;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, t = lane & 15, g = lane >> 4;
+  // A workgroup's start is a chain of dependent loads: sequence length, then block-table entry, then page.  The
+  // entry of this wavefront's first page (page w) does not need the length, so it is fetched alongside it and the
+  // first page load follows one round trip earlier.  If the sequence has no page w the entry may be anything: it is
+  // clamped to a valid page, and what comes back is never used (the wavefront has no pages then).
+  const int* bt = block_table + (size_t)b * max_blocks;
+  int first_blk = bt[min(w, max_blocks - 1)];
   const int pos = seq_len[b];                  // position of the step's token = tokens already cached
+  first_blk = min(max(first_blk, 0), n_blocks - 1);
+  uint4 qf[8];
+  uint4 ka[4], va[4], kb[4], vb[4];
+  load_page<true>(pool + ((size_t)kvh * n_blocks + first_blk) * KV_PAGE_BYTES, lane, ka, va);
   const int L = FUSED ? pos : pos + 1;         // tokens read from the cache
   const int npages = (L + 15) >> 4;
-  const int* bt = block_table + (size_t)b * max_blocks;
-  uint4 qf[8];
-  // block-table entries of this wavefront's first 64 pages and its first page: issued before anything else
+  // block-table entries of this wavefront's first 64 pages (lane i: page w + NWV i)
   const int last = npages - 1;
   const int my_blk0 = npages > 0 ? bt[min(w + NWV * lane, last)] : 0;
-  uint4 ka[4], va[4], kb[4], vb[4];
-  load_page<true>(pool + ((size_t)kvh * n_blocks + __shfl(my_blk0, 0)) * KV_PAGE_BYTES, lane, ka, va);
   if (FUSED) {
     const float* row = fa.qkv_part + (size_t)b * fa.qkv_w;
     const float* cs = fa.cos_t + (size_t)pos * 64;
