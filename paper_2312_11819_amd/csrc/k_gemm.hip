@@ -270,7 +270,10 @@ constexpr int SK_ROW = SK * 2 + 16;     // bytes per LDS row (padded)
 // (the fused gate/up form: 8 gate and 8 up rows per wavefront, grid ceil(F / 8 NW), last workgroup ragged).
 // Loads run D - 1 k-steps ahead of the MFMAs through a register ring (weights and the activation slice alike:
 // the memory counter retires in order, so both must share one prefetch distance); the activation slice then
-// passes through a double-buffered LDS tile that the workgroup's wavefronts share.  What the time is made of,
+// passes through a double-buffered LDS tile that the workgroup's wavefronts share.  D = 2 everywhere: on this
+// memory system a deeper ring is slower, not faster - the bare weight stream of these grids measures 5.0-5.9 TB/s
+// with three k-steps in flight per wavefront and 6.1-6.5 with one (QKV shape: 20.2 -> 16.4 us), and the whole
+// kernels gain 1-2 us each.  What counts is that a workgroup's outstanding loads form one run of consecutive bytes.  What the time is made of,
 // measured on MI355X on the 7B gate/up shape at 64 rows (37 us): the weight loads alone 29 us, the MFMAs +3, the
 // LDS staging and its per-step barrier +1, the slice loads from L2 +2, the output stores +2.  Workgroups, not
 // bytes, are the first-order term: the kernel is fastest with one workgroup per compute unit, all in flight from
@@ -473,18 +476,16 @@ __global__ __launch_bounds__(512) void gemm_skinny_xres_kernel(const h16_t* __re
     f = min(f, F - 1);
     return wtile_offset(((j + (f >> 2) * G) * 8 + w) * 16, (4 * s + (f & 3)) * 128, K, Nw);
   };
+  // two slots, loads one k-step ahead (three ahead measured slower: 27.8 against 26.0 us on the 7B QKV shape; none at
+  // all 27.2 us)
   struct Slot { uint4 w[4]; };
-  Slot r0, r1, r2, r3;
+  Slot r0, r1;
 #define XRES_LOAD(S, FI)                                                                              \
   {                                                                                                   \
     const h16_t* p_ = wlane + w_off(FI);                                                              \
     _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) S.w[kk] = *(const uint4*)(p_ + kk * 512);        \
   }
-  if (F > 0) {
-    XRES_LOAD(r0, 0)
-    XRES_LOAD(r1, 1)
-    XRES_LOAD(r2, 2)
-  }
+  if (F > 0) XRES_LOAD(r0, 0)
   // stage the slice: XROWS rows of 64 chunks (16 bytes each); rows beyond M repeat row M - 1 (never stored)
   {
     constexpr int NCH = XROWS * 64, PER = NCH / 512;
@@ -523,14 +524,14 @@ __global__ __launch_bounds__(512) void gemm_skinny_xres_kernel(const h16_t* __re
   }
   for (int ti = 0; ti < ntiles; ++ti) {
     const int f = 4 * ti;
-    XRES_LOAD(r3, f + 3)
+    XRES_LOAD(r1, f + 1)
     XRES_STEP(r0, 0)
-    XRES_LOAD(r0, f + 4)
+    XRES_LOAD(r0, f + 2)
     XRES_STEP(r1, 1)
-    XRES_LOAD(r1, f + 5)
-    XRES_STEP(r2, 2)
-    XRES_LOAD(r2, f + 6)
-    XRES_STEP(r3, 3)
+    XRES_LOAD(r1, f + 3)
+    XRES_STEP(r0, 2)
+    XRES_LOAD(r0, f + 4)
+    XRES_STEP(r1, 3)
     float* dst = part + (size_t)s * plane_rows * Nw + (size_t)(j + ti * G) * 128 + 16 * w + 4 * g;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
@@ -570,7 +571,7 @@ template <int MB, int NW>
 hipError_t launch_skinny_nw(hipStream_t s, const void* A, const void* W, float* part, int M, int Nw, int K, int nsplit,
                             int a_dual, int plane_rows, bool configure_only) {
   constexpr int SMEM = 2 * 16 * MB * SK_ROW;
-  constexpr int D = MB <= 4 ? 4 : 2;
+  constexpr int D = 2;   // loads one k-step ahead: measured faster than three ahead (see gemm_skinny_kernel)
   constexpr bool HAS_DUAL = MB <= 8;          // the doubled slice of the largest variant would not fit in LDS
   constexpr bool HAS_SINGLE = 4 * MB >= NW;   // at least one slice chunk per thread
   if (configure_only) {
@@ -613,7 +614,7 @@ hipError_t launch_skinny_nw(hipStream_t s, const void* A, const void* W, float* 
 template <int MB, int NW>
 hipError_t launch_skinny_glu(hipStream_t s, const void* A, const void* W, void* out, int M, int Nw, int K, bool configure_only) {
   constexpr int SMEM = 2 * 16 * MB * SK_ROW;
-  constexpr int D = MB <= 4 ? 4 : 2;
+  constexpr int D = 2;   // loads one k-step ahead: measured faster than three ahead (see gemm_skinny_kernel)
   auto kern = gemm_skinny_kernel<MB, D, true, false, NW>;
   if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
   const int F = Nw / 2;
