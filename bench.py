@@ -223,7 +223,7 @@ def main() -> int:
         # weight-conversion copy kernel): measured on a 2-layer, 48-token run of this workload, because counter runs of
         # the full-size command do not finish; the fetched / algorithmic ratio of those launches is applied to this
         # run's launches (profiles/bench_7b_b64_pmc_traffic.md)
-        pmc = {"attn_decode_kernel": (1.058, 1.05e6), "gemm_skinny_kernel": (1.089, 10.6e6)}.get(roofline["kernel"])
+        pmc = {"attn_decode_kernel": (1.014, 1.05e6), "gemm_skinny_kernel": (1.073, 10.6e6)}.get(roofline["kernel"])
         if wl.name == "7b_b64":
             roofline["traffic"] = pmc[0] * roofline["bytes_per_launch"] + pmc[1]
             roofline["traffic_source"] = "rocprofv3 --pmc ratio of a reduced-depth run, see profiles/bench_7b_b64_pmc_traffic.md"
