@@ -41,11 +41,11 @@ def _time_gpu(fn, reps=5, warm=2):
 
 
 def hardware_probes(binding, dev):
-    """What the card sustains with nothing in the way: a read-only stream over 1 GiB (plain and nontemporal loads) and
+    """What the card sustains with nothing in the way: a read-only stream over 4 GiB (plain and nontemporal loads, one workgroup per compute unit) and
     the fp16 MFMA pipe on register-resident operands (random values in [-1, 1], and zeros: the clock follows the data)."""
     import torch
     scratch = torch.zeros(1024, dtype=torch.uint8, device=dev)
-    buf = torch.empty(1 << 28, dtype=torch.int32, device=dev).random_()
+    buf = torch.empty(1 << 30, dtype=torch.int32, device=dev).random_()   # 4 GiB: long enough that the launch ramp does not count
     out = {}
     for name, nt in (("hbm_read_plain_GBps", False), ("hbm_read_nontemporal_GBps", True)):
         t = _time_gpu(lambda: binding.rlhf_gen_op_probe_stream_read(buf, nt, scratch))

@@ -19,7 +19,7 @@ __device__ __forceinline__ h16_t f32_to_h16(float f) {
 }
 // 16-byte load of data that is read exactly once and in whole cache lines per instruction (cached K/V pages in
 // decode, the tiled weights of the decode GEMM): the nontemporal hint keeps it from displacing reusable lines in L2
-// and measures 10-12 % faster than a plain load on MI355X for read-only streams (6.7 vs 6.0 TB/s).  It loses when
+// and measures 10-12 % faster than a plain load on MI355X for read-only streams (7.2 vs 6.4 TB/s at best).  It loses when
 // one instruction takes only part of a line and another instruction the rest (the line is fetched twice).
 typedef unsigned u32x4_native_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 load_stream16(const void* p) {
