@@ -7,8 +7,8 @@
 // exactly the operand layout, so keys and values go from HBM to the MFMA through eight coalesced 16 B
 // loads per lane with no shuffles and no LDS.
 //   decode : the 16 rows are the query heads of one KV group at the newest position (rows beyond the group
-//            size are zero padding); four wavefronts split the pages of one (sequence, KV head) and merge
-//            their partial (max, sum, O) through LDS.
+//            size are zero padding); eight (or four) wavefronts split the pages of one (sequence, KV head) and
+//            merge their partial (max, sum, O) through LDS.
 //   prefill: the 16 rows are 16 consecutive positions of one query head; a wavefront walks the pages up to
 //            its diagonal page and masks inside it.
 // HBM-bound in decode: every cached byte is read once per step per KV head; the MFMA work is negligible.
@@ -102,7 +102,7 @@ __device__ __forceinline__ void init_state(AttnState& st) {
   st.l = 0.f;
 }
 
-// grid (Hkv, B), 256 threads.  out [B, 2, Hq*128] fp16 (hi | lo).  seq_len[b] = tokens cached BEFORE this step.
+// grid (Hkv, B), 64 NWV threads.  out [B, 2, Hq*128] fp16 (hi | lo).  seq_len[b] = tokens cached BEFORE this step.
 //   FUSED = false: q [B, Hq, 2, 128] fp16 (hi | lo per head) is given and the step's own key/value has already been
 //     appended, so seq_len[b] + 1 tokens are read from the cache.
 //   FUSED = true: the kernel starts from the QKV projection's split-K partial sums (qkv_part[s][b][qkv_w], s < nsplit):
