@@ -134,9 +134,14 @@ int rlhf_gen_prefill(rlhf_gen_ctx* ctx, const int32_t* query_tokens, const int32
 /* One KV-cached decode step for the current batch: feed each sequence one token (the one drawn by
  * the previous call, or forced_tokens[b] if forced_tokens is not NULL - teacher forcing), append
  * its key/value to the cache, and draw the next response token and its log-prob.
- *   forced_tokens device int32 [B] or NULL (ids outside [0, vocab) are clamped)
+ *   forced_tokens device int32 [B] or NULL
  *   tok_out       device int32 [B]; logprob_out device float [B]
- * Errors: E_STATE (no prefill yet, or a sequence would exceed max_seq), E_NOMEM (pool exhausted). */
+ * The call does not wait for the device, so it cannot refuse a forced id outside [0, vocab) itself: the step runs with
+ * the nearest valid id, the kernel raises a flag, and the mistake is reported as E_INVALID by the next
+ * rlhf_gen_decode_step that finds the step completed (always, if the stream was synchronised in between) or by the next
+ * rlhf_gen_get_logits, whichever comes first; the flag is then cleared.
+ * Errors: E_STATE (no prefill yet, or a sequence would exceed max_seq), E_NOMEM (pool exhausted), E_INVALID (deferred,
+ * see above). */
 int rlhf_gen_decode_step(rlhf_gen_ctx* ctx, const int32_t* forced_tokens, int32_t* tok_out, float* logprob_out);
 
 /* Whole rollout = prefill + (max_resp_len - 1) decode steps; every sequence gets exactly
@@ -180,7 +185,8 @@ int rlhf_gen_generate_stream(rlhf_gen_ctx* ctx, const int32_t* query_tokens, con
  * library and never written out.  Replaces the batch held by the context (a following decode_step fails with E_STATE).
  *   query_tokens device int32 [B, Lmax]; lengths HOST int32 [B]; resp_tokens device int32 [B, R];
  *   lengths[b] + R - 1 <= max_seq; logprobs_out device float [B, R], valid after the stream is synchronised.
- * Errors as for rlhf_gen_prefill. */
+ * Errors as for rlhf_gen_prefill; every query and response id, the last response token included, is validated before
+ * the forward pass (E_INVALID). */
 int rlhf_gen_score(rlhf_gen_ctx* ctx, const int32_t* query_tokens, const int32_t* lengths, int32_t B, int32_t Lmax,
                    const int32_t* resp_tokens, int32_t R, float* logprobs_out);
 
@@ -209,9 +215,9 @@ typedef struct {
  * where lora names an adapter the update W + scale * B A is formed in fp32 on the way (one rounding to fp16).
  * lora may be NULL.  fp32 mode: the pointers are adopted; adapters are E_UNSUPPORTED there.
  * The work is enqueued on cfg.stream; the sources may be reused once it has completed.  The batch held by the context
- * is dropped (its KV cache belongs to the old weights): the next call must be prefill, generate or score.  A
- * captured decode graph stays valid unless an address the kernels read directly changed (token embedding, norm gains,
- * any matrix in fp32 or in-place mode); then it is recorded again by the next rlhf_gen_generate.
+ * is dropped (its KV cache belongs to the old weights): the next call must be prefill, generate or score.
+ * Captured decode graphs stay valid unless an address the kernels read directly changed (token embedding, norm gains,
+ * any matrix in fp32 or in-place mode); then they are recorded again by the next rlhf_gen_generate.
  * Errors: E_INVALID (NULL pointers, rank out of range), E_UNSUPPORTED, E_DEVICE. */
 int rlhf_gen_update_weights(rlhf_gen_ctx* ctx, const rlhf_gen_weights* weights, const rlhf_gen_lora* lora);
 
@@ -236,8 +242,16 @@ int rlhf_gen_plan_capacity(const rlhf_gen_cfg* cfg, int64_t capacity_bytes, doub
 /* Device bytes the context requested from HIP in rlhf_gen_init (what rlhf_gen_plan_capacity predicts). */
 int64_t rlhf_gen_context_bytes(const rlhf_gen_ctx* ctx);
 
+/* Number of decode-step graphs this context has recorded so far.  rlhf_gen_generate replays one captured graph per
+ * decode step; the graph depends only on the number of batch rows - the sampling rule, the seed and the output
+ * buffers are read from device memory at run time - so a PPO loop that calls generate with a new seed and fresh
+ * output buffers every round (Alg. 1: one Actor.generate per batch of queries) records once and replays thereafter.
+ * Up to 16 graphs (batch widths) are kept. */
+int64_t rlhf_gen_graph_captures(const rlhf_gen_ctx* ctx);
+
 /* Copy the fp32 logits [B, vocab] that the last prefill/decode step sampled from into a device
- * buffer (parity checks).  E_STATE if no step has run. */
+ * buffer (parity checks), and wait for the steps enqueued so far.  E_STATE if no step has run; E_INVALID if an
+ * earlier rlhf_gen_decode_step was given a forced token id outside [0, vocab) (see there). */
 int rlhf_gen_get_logits(rlhf_gen_ctx* ctx, float* out);
 
 /* Timing of the last rlhf_gen_generate on this context, measured with HIP events on cfg.stream:

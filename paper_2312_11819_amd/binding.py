@@ -28,7 +28,7 @@ PROF_CLASSES = ["embed", "norm", "gemm_qkv", "rope_append", "attn_decode", "gemm
 
 EXPORTS = [
     "rlhf_gen_init", "rlhf_gen_prefill", "rlhf_gen_decode_step", "rlhf_gen_generate", "rlhf_gen_generate_stream", "rlhf_gen_score", "rlhf_gen_update_weights",
-    "rlhf_gen_plan_capacity", "rlhf_gen_context_bytes",
+    "rlhf_gen_plan_capacity", "rlhf_gen_context_bytes", "rlhf_gen_graph_captures",
     "rlhf_gen_get_logits",
     "rlhf_gen_last_timing", "rlhf_gen_last_step_ms", "rlhf_gen_set_profile", "rlhf_gen_get_profile", "rlhf_gen_last_error", "rlhf_gen_destroy",
     "rlhf_gen_op_probe_stream_read", "rlhf_gen_op_probe_mfma_loop", "rlhf_gen_op_tile_weights", "rlhf_gen_op_gemm", "rlhf_gen_op_rope_append", "rlhf_gen_op_attn_decode", "rlhf_gen_op_attn_prefill",
@@ -99,6 +99,8 @@ def lib() -> C.CDLL:
                                              C.POINTER(C.c_int64)]
         L.rlhf_gen_context_bytes.argtypes = [C.c_void_p]
         L.rlhf_gen_context_bytes.restype = C.c_int64
+        L.rlhf_gen_graph_captures.argtypes = [C.c_void_p]
+        L.rlhf_gen_graph_captures.restype = C.c_int64
         L.rlhf_gen_get_logits.argtypes = [C.c_void_p, C.c_void_p]
         L.rlhf_gen_last_timing.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_int32)]
         L.rlhf_gen_last_step_ms.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)]
@@ -120,7 +122,7 @@ def lib() -> C.CDLL:
         L.rlhf_gen_op_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.POINTER(Sampling), C.c_void_p,
                                          C.c_void_p, C.c_void_p, C.c_void_p]
         for name in EXPORTS:
-            if name not in ("rlhf_gen_last_error", "rlhf_gen_destroy"):
+            if name not in ("rlhf_gen_last_error", "rlhf_gen_destroy", "rlhf_gen_context_bytes", "rlhf_gen_graph_captures"):
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -174,6 +176,16 @@ class Context:
         self._h = h
         self.B = 0
 
+    def _enqueued(self, *tensors) -> None:
+        """After a call that enqueued work on the context's stream: the tensors it reads or writes were allocated on
+        the caller's stream, so tell the allocator they are in use on ours (their memory is not handed out again
+        before that work has run), and make the caller's stream wait for ours, so that the caller may read the
+        outputs, or drop them, in stream order without an explicit synchronisation."""
+        for t in tensors:
+            if t is not None:
+                t.record_stream(self.stream)
+        torch.cuda.current_stream(self.device).wait_stream(self.stream)
+
     def _marshal_weights(self, weights: dict) -> Weights:
         self._weights = weights  # borrowed by the library: keep alive
         n = self.shape.n_layers
@@ -208,6 +220,8 @@ class Context:
                                                         ("wqkv", "wo", "w_gate_up", "w_down")], head)
         self.stream.wait_stream(torch.cuda.current_stream(self.device))
         _check(self._h, lib().rlhf_gen_update_weights(self._h, C.byref(w), C.byref(lp) if lp is not None else None))
+        # the conversion reads the sources and the adapters on our stream: later writes to them must come after it
+        torch.cuda.current_stream(self.device).wait_stream(self.stream)
         self.B = 0
 
     def rlhf_gen_prefill(self, query_tokens: torch.Tensor, lengths: Sequence[int], sampling: Sampling):
@@ -216,7 +230,10 @@ class Context:
         tok = torch.empty(B, dtype=torch.int32, device=self.device)
         lp = torch.empty(B, dtype=torch.float32, device=self.device)
         self.stream.wait_stream(torch.cuda.current_stream(self.device))
-        _check(self._h, lib().rlhf_gen_prefill(self._h, _ptr(query_tokens), lens, B, Lmax, C.byref(sampling), _ptr(tok), _ptr(lp)))
+        try:
+            _check(self._h, lib().rlhf_gen_prefill(self._h, _ptr(query_tokens), lens, B, Lmax, C.byref(sampling), _ptr(tok), _ptr(lp)))
+        finally:
+            self._enqueued(query_tokens, tok, lp)
         self.B = B
         return tok, lp
 
@@ -224,7 +241,10 @@ class Context:
         tok = torch.empty(max(self.B, 1), dtype=torch.int32, device=self.device)
         lp = torch.empty(max(self.B, 1), dtype=torch.float32, device=self.device)
         self.stream.wait_stream(torch.cuda.current_stream(self.device))
-        _check(self._h, lib().rlhf_gen_decode_step(self._h, _ptr(forced_tokens), _ptr(tok), _ptr(lp)))
+        try:
+            _check(self._h, lib().rlhf_gen_decode_step(self._h, _ptr(forced_tokens), _ptr(tok), _ptr(lp)))
+        finally:
+            self._enqueued(forced_tokens, tok, lp)
         return tok, lp
 
     def rlhf_gen_generate(self, query_tokens: torch.Tensor, lengths: Sequence[int], max_resp_len: int,
@@ -235,8 +255,11 @@ class Context:
         toks = out_tokens if out_tokens is not None else torch.empty(B, max_resp_len, dtype=torch.int32, device=self.device)
         lps = out_logprobs if out_logprobs is not None else torch.empty(B, max_resp_len, dtype=torch.float32, device=self.device)
         self.stream.wait_stream(torch.cuda.current_stream(self.device))
-        _check(self._h, lib().rlhf_gen_generate(self._h, _ptr(query_tokens), lens, B, Lmax, max_resp_len,
-                                                C.byref(sampling), _ptr(toks), _ptr(lps)))
+        try:
+            _check(self._h, lib().rlhf_gen_generate(self._h, _ptr(query_tokens), lens, B, Lmax, max_resp_len,
+                                                    C.byref(sampling), _ptr(toks), _ptr(lps)))
+        finally:
+            self._enqueued(query_tokens, toks, lps)
         self.B = B
         return toks, lps
 
@@ -267,9 +290,12 @@ class Context:
 
         cb = MICROBATCH_FN(trampoline)
         self.stream.wait_stream(torch.cuda.current_stream(self.device))
-        _check(self._h, lib().rlhf_gen_generate_stream(self._h, _ptr(query_tokens), lens, B, Lmax, max_resp_len,
-                                                       C.byref(sampling), _ptr(toks), _ptr(lps), micro_batch, handles, cb,
-                                                       None))
+        try:
+            _check(self._h, lib().rlhf_gen_generate_stream(self._h, _ptr(query_tokens), lens, B, Lmax, max_resp_len,
+                                                           C.byref(sampling), _ptr(toks), _ptr(lps), micro_batch, handles, cb,
+                                                           None))
+        finally:
+            self._enqueued(query_tokens, toks, lps)
         if failure:
             raise failure[0]
         self.B = min(micro_batch, B)
@@ -281,7 +307,10 @@ class Context:
         lens = (C.c_int32 * B)(*[int(x) for x in lengths])
         out = torch.empty(B, R, dtype=torch.float32, device=self.device)
         self.stream.wait_stream(torch.cuda.current_stream(self.device))
-        _check(self._h, lib().rlhf_gen_score(self._h, _ptr(query_tokens), lens, B, Lmax, _ptr(resp_tokens), R, _ptr(out)))
+        try:
+            _check(self._h, lib().rlhf_gen_score(self._h, _ptr(query_tokens), lens, B, Lmax, _ptr(resp_tokens), R, _ptr(out)))
+        finally:
+            self._enqueued(query_tokens, resp_tokens, out)
         self.synchronize()
         self.B = 0
         return out
@@ -289,9 +318,16 @@ class Context:
     def rlhf_gen_context_bytes(self) -> int:
         return int(lib().rlhf_gen_context_bytes(self._h))
 
+    def rlhf_gen_graph_captures(self) -> int:
+        return int(lib().rlhf_gen_graph_captures(self._h))
+
     def rlhf_gen_get_logits(self) -> torch.Tensor:
         out = torch.empty(self.B, self.shape.vocab, dtype=torch.float32, device=self.device)
-        _check(self._h, lib().rlhf_gen_get_logits(self._h, _ptr(out)))
+        self.stream.wait_stream(torch.cuda.current_stream(self.device))
+        try:
+            _check(self._h, lib().rlhf_gen_get_logits(self._h, _ptr(out)))
+        finally:
+            self._enqueued(out)
         self.synchronize()
         return out
 

@@ -123,17 +123,19 @@ __device__ unsigned block_excl_scan_u(unsigned v, Shared& sh) {
 }
 
 template <bool CACHE>
-__global__ __launch_bounds__(ST) void sampler_kernel(const float* __restrict__ logits, int V, SamplerParams p,
-                                                     const int* __restrict__ step_ptr, int out_stride,
-                                                     int use_step_col, int* __restrict__ tok_out,
-                                                     float* __restrict__ lp_out, int* __restrict__ cur_tok) {
+__global__ __launch_bounds__(ST) void sampler_kernel(const float* __restrict__ logits, int V, SamplerArgs p,
+                                                     const SamplerArgs* __restrict__ args_dev,
+                                                     const int* __restrict__ step_ptr, int* __restrict__ cur_tok) {
   __shared__ Shared sh;
   extern __shared__ float row_s[];   // CACHE: the row, element i at i + i / 32
+  if (args_dev) p = *args_dev;       // (uniform: every lane reads the same block)
   const int b = blockIdx.x;
   const int tid = threadIdx.x;
   const float* grow = logits + (size_t)b * V;
-  const int t = *step_ptr;
-  const size_t out_idx = (size_t)b * out_stride + (use_step_col ? t : 0);
+  const int t = step_ptr[b * p.step_stride];
+  const size_t out_idx = (size_t)b * p.out_stride + (p.use_step_col ? t : 0);
+  int* __restrict__ tok_out = p.tok_out;
+  float* __restrict__ lp_out = p.lp_out;
   struct Row {
     const float* g;
     const float* s;
@@ -193,6 +195,9 @@ __global__ __launch_bounds__(ST) void sampler_kernel(const float* __restrict__ l
   // tempered weight of token i: read back from the cache, or recomputed (same expression, same bits)
   auto wgt = [&](int i) -> float { return CACHE ? row_s[i + (i >> 5)] : expf((grow[i] - vmax) * invT); };
   const double Zraw = block_sum_d(sraw, sh);
+  // A row of NaNs has no maximum (every comparison is false): the index stays at its start value and is brought
+  // into range here, so that whatever follows reads and feeds back a valid token id.
+  imax = min(max(imax, 0), V - 1);
   if (p.greedy) {
     if (tid == 0) {
       tok_out[out_idx] = imax;
@@ -289,6 +294,7 @@ __global__ __launch_bounds__(ST) void sampler_kernel(const float* __restrict__ l
   __syncthreads();
   if (tid == 0) {
     int tok = sh.found != 0x7fffffff ? sh.found : sh.last;
+    if (tok < 0) tok = imax;   // no nucleus member at all (NaN logits): fall back to the arg-max index, which is in range
     float v = grow[tok];
     float lp;
     if (p.logprob_mode == 0)
@@ -350,13 +356,12 @@ hipError_t sampler_configure() {
                              (SAMPLER_MAX_CACHED_V + SAMPLER_MAX_CACHED_V / 32) * 4);
 }
 
-hipError_t launch_sampler(hipStream_t s, const float* logits, int B, int V, SamplerParams p, const int* step_ptr,
-                          int out_stride, int use_step_col, int* tok_out, float* lp_out, int* cur_tok) {
+hipError_t launch_sampler(hipStream_t s, const float* logits, int B, int V, const SamplerArgs& args, const SamplerArgs* args_dev,
+                          const int* step_ptr, int* cur_tok) {
   if (B <= 0) return hipSuccess;
   if (V <= SAMPLER_MAX_CACHED_V)
-    sampler_kernel<true><<<B, ST, (size_t)(V + V / 32 + 1) * 4, s>>>(logits, V, p, step_ptr, out_stride, use_step_col, tok_out,
-                                                                     lp_out, cur_tok);
+    sampler_kernel<true><<<B, ST, (size_t)(V + V / 32 + 1) * 4, s>>>(logits, V, args, args_dev, step_ptr, cur_tok);
   else
-    sampler_kernel<false><<<B, ST, 0, s>>>(logits, V, p, step_ptr, out_stride, use_step_col, tok_out, lp_out, cur_tok);
+    sampler_kernel<false><<<B, ST, 0, s>>>(logits, V, args, args_dev, step_ptr, cur_tok);
   return hipGetLastError();
 }

@@ -32,6 +32,12 @@ __global__ void pack_tokens2_kernel(const int* __restrict__ query_tokens, int Lm
     id = id < 0 ? 0 : vocab - 1;
   }
   ids_out[i] = id;
+  // The last response token is scored but never fed: the thread of the row's last fed position validates it too, so
+  // that every token id of the call has been checked before the forward pass starts.
+  if (p == ql + R - 2) {
+    const int last = resp_tokens[(size_t)b * R + (R - 1)];
+    if (last < 0 || last >= vocab) *err_flag = 1;
+  }
 }
 
 hipError_t launch_pack_tokens2(hipStream_t s, const int* query_tokens, int Lmax, const int* resp_tokens, int R,
@@ -368,8 +374,21 @@ hipError_t launch_swiglu(hipStream_t s, const float* gu, int nsplit, size_t part
 
 __global__ void advance_kernel(int* seq_len, int* step, int B) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < B) seq_len[i] += 1;
-  if (i == 0) *step += 1;
+  if (i < B) {
+    seq_len[i] += 1;
+    step[i] += 1;
+  }
+}
+
+__global__ void fill_int_kernel(int* p, int n, int value) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = value;
+}
+
+hipError_t launch_fill_int(hipStream_t s, int* p, int n, int value) {
+  if (n <= 0) return hipSuccess;
+  fill_int_kernel<<<(n + 255) / 256, 256, 0, s>>>(p, n, value);
+  return hipGetLastError();
 }
 
 hipError_t launch_advance(hipStream_t s, int* seq_len, int* step, int B) {

@@ -55,6 +55,7 @@ hipError_t launch_rope_append(hipStream_t s, const float* qkv, const float* part
 // h[m][f] = silu(sum gate) * (sum up) from fp32 [M, 2F] (+ partial sums).
 hipError_t launch_swiglu(hipStream_t s, const float* gu, int nsplit, size_t part_stride, void* h_out, int act_bf16,
                          int M, int F);
+// seq_len[b] += 1 and step[b] += 1 for b < B (every row carries its own response index)
 hipError_t launch_advance(hipStream_t s, int* seq_len, int* step, int B);
 // bf16 -> fp16 copy of n elements (working copies of the weight matrices).
 // dst (tiled working layout, see common.h) = fp16(src + scale * B[row0.., :] A): src row-major [rows, cols], bf16 or
@@ -88,17 +89,25 @@ hipError_t launch_gemm_f32(hipStream_t s, const float* A, const float* W, float*
 // ---- sampler / log-prob gather ----
 hipError_t launch_logprob_gather(hipStream_t s, const float* logits, int rows, int V, const int* slot,
                                  const int* resp_tokens, float* out, int* err_flag);
-struct SamplerParams {
+// Everything the sampler needs besides the logits.  Passed by value for ordinary launches, or read from device memory
+// (args_dev != NULL) so that a captured decode graph serves every rollout: seed, temperature, top-p and the output
+// buffers then change without re-recording anything.
+struct SamplerArgs {
   float temperature, top_p;
   uint64_t seed;
   int greedy, logprob_mode;
-  int row0;   // batch row of logits row 0 (a micro-batch keeps the random stream of its rows in the full batch)
-  int pad_;
+  int row0;          // batch row of logits row 0 (a micro-batch keeps the random stream of its rows in the full batch)
+  int out_stride;    // elements between consecutive rows of tok_out / lp_out
+  int use_step_col;  // results go to column t (the row's response index) of the row instead of column 0
+  int step_stride;   // 1: step_ptr[b] is the response index of row b; 0: step_ptr[0] for every row
+  int* tok_out;
+  float* lp_out;
 };
-// One workgroup per row of logits [B, V].  Response index t = *step_ptr + step_add; results go to
-// tok_out[b*out_stride + col], col = use_step_col ? t : 0; cur_tok[b] receives the token too.
-hipError_t launch_sampler(hipStream_t s, const float* logits, int B, int V, SamplerParams p, const int* step_ptr,
-                          int out_stride, int use_step_col, int* tok_out, float* lp_out, int* cur_tok);
+// One workgroup per row of logits [B, V].  Response index of row b: t = step_ptr[b * step_stride]; results go to
+// tok_out[b * out_stride + (use_step_col ? t : 0)]; cur_tok[b] receives the token too.
+hipError_t launch_sampler(hipStream_t s, const float* logits, int B, int V, const SamplerArgs& args, const SamplerArgs* args_dev,
+                          const int* step_ptr, int* cur_tok);
+hipError_t launch_fill_int(hipStream_t s, int* p, int n, int value);
 
 // Hardware probes (k_probe.hip).  stream_read: reads bytes / 8192 chunks of 8 KB from buf (plain or nontemporal 16-byte
 // loads), scratch >= 1 KB.  mfma_loop: `workgroups` x 4 wavefronts each issue 8 * iters v_mfma_f32_32x32x16_f16

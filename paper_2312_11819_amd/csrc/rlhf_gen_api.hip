@@ -8,7 +8,9 @@
 #include <string.h>
 
 #include <algorithm>
+#include <map>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "../../include/rlhf_gen.h"
@@ -19,16 +21,11 @@ namespace {
 
 std::string g_init_error;
 
-struct GraphKey {
-  int B = 0, stride = 0, use_col = 0;
-  const void* tok = nullptr;
-  const void* lp = nullptr;
-  SamplerParams sp{};
-  bool operator==(const GraphKey& o) const {
-    return B == o.B && stride == o.stride && use_col == o.use_col && tok == o.tok && lp == o.lp &&
-           memcmp(&sp, &o.sp, sizeof(sp)) == 0;
-  }
-};
+// A captured decode step depends on the batch rows it covers and on nothing else: the sampling rule, the seed and the
+// output buffers are read from a block in device memory (SamplerArgs) that is rewritten before the first replay of a
+// rollout, positions and response indices from per-row device arrays.  Key: (first row, number of rows).
+typedef std::pair<int, int> GraphKey;
+constexpr size_t MAX_CACHED_GRAPHS = 16;
 
 }  // namespace
 
@@ -51,7 +48,10 @@ struct rlhf_gen_ctx {
   char* kv_pool = nullptr;
   size_t layer_pool_bytes = 0;
   int n_blocks = 0, max_blocks = 0;
+  // per batch row: pages, cached tokens, response index of the next token to draw, token to feed next
   int *d_table = nullptr, *d_seq_len = nullptr, *d_step = nullptr, *d_err = nullptr, *d_cur_tok = nullptr;
+  SamplerArgs* d_sargs = nullptr;   // sampling rule and output buffers of the rollout in flight (read by captured graphs)
+  SamplerArgs* h_sargs = nullptr;   // pinned staging copy of it
   float *d_cos = nullptr, *d_sin = nullptr;
   int *d_tok_seq = nullptr, *d_tok_pos = nullptr, *d_ids = nullptr, *d_cu = nullptr, *d_seq_ids = nullptr,
       *d_last_rows = nullptr;
@@ -80,8 +80,13 @@ struct rlhf_gen_ctx {
   int h_step = 0;
   int reserve_extra = 0;  // tokens beyond the query that prefill must reserve pages for
   int row_offset = 0;     // batch row of row 0 of the current (micro-)batch, for the sampler's random stream
-  SamplerParams sp{};
+  SamplerArgs sp{};       // sampling rule in force (output fields filled per launch)
   std::string err;
+  // decode_step cannot wait for the device: the flag the embedding kernel raises for an out-of-range forced token is
+  // copied to pinned memory behind each step and looked at by the next call that finds the copy complete
+  int* h_step_err = nullptr;
+  hipEvent_t ev_step_err = nullptr;
+  bool step_err_pending = false;
 
   // optional per-kernel timing of sampled decode steps (rlhf_gen_set_profile)
   int prof_every = 0;
@@ -94,8 +99,8 @@ struct rlhf_gen_ctx {
   double prof_ms[RLHF_GEN_PROF_CLASSES] = {0};
   long long prof_n[RLHF_GEN_PROF_CLASSES] = {0};
 
-  hipGraphExec_t graph_exec = nullptr;
-  GraphKey graph_key;
+  std::map<GraphKey, hipGraphExec_t> graphs;
+  long long graph_captures = 0;
   hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
   std::vector<hipEvent_t> step_ev;   // one event after every decode step of the last rollout
   std::vector<float> step_ms;
@@ -370,7 +375,9 @@ bool use_streaming(const rlhf_gen_ctx* c, int B) {
 }
 
 // Kernels of one decode step, in order, ending with the sampler and the counter update.
-int enqueue_decode_body(rlhf_gen_ctx* c, int* tok_out, float* lp_out, int stride, int use_col) {
+// `from_dev`: the sampler reads its arguments from c->d_sargs (graph capture and everything else inside a rollout);
+// otherwise they are passed by value with the given outputs (single decode steps, whose buffers change per call).
+int enqueue_decode_body(rlhf_gen_ctx* c, int* tok_out, float* lp_out, int stride, int use_col, bool from_dev) {
   const rlhf_gen_cfg& g = c->cfg;
   const int B = c->B;
   int rc;
@@ -389,8 +396,10 @@ int enqueue_decode_body(rlhf_gen_ctx* c, int* tok_out, float* lp_out, int stride
     rc = gemm_any(c, c->yl, c->lm_head, c->logits, B, g.vocab, g.d_model, EPI_STORE_F32);
     if (rc) return rc;
   }
-  LAUNCH(c, launch_sampler(c->stream, c->logits, B, g.vocab, c->sp, c->d_step, stride, use_col, tok_out, lp_out,
-                           c->d_cur_tok), "sampler");
+  SamplerArgs a = c->sp;
+  a.out_stride = stride; a.use_step_col = use_col; a.step_stride = 1; a.tok_out = tok_out; a.lp_out = lp_out;
+  LAUNCH(c, launch_sampler(c->stream, c->logits, B, g.vocab, a, from_dev ? c->d_sargs : nullptr, c->d_step, c->d_cur_tok),
+         "sampler");
   LAUNCH(c, launch_advance(c->stream, c->d_seq_len, c->d_step, B), "advance");
   prof_mark(c, RLHF_GEN_PROF_SAMPLER);
   return RLHF_GEN_OK;
@@ -439,7 +448,6 @@ int prefill_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* le
   c->sp.greedy = sampling->greedy;
   c->sp.logprob_mode = sampling->logprob_mode;
   c->sp.row0 = c->row_offset;
-  c->sp.pad_ = 0;
   reset_free_list(c);
   int T = 0;
   for (int b = 0; b < B; ++b) {
@@ -463,7 +471,9 @@ int prefill_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* le
   c->h_misc[0] = 0;
   c->h_misc[1] = 1;
   HIP_TRY(c, hipMemcpyAsync(c->d_err, &c->h_misc[0], sizeof(int), hipMemcpyHostToDevice, s));
-  HIP_TRY(c, hipMemcpyAsync(c->d_step, &c->h_misc[0], sizeof(int), hipMemcpyHostToDevice, s));
+  c->step_err_pending = false;   // (the stream was synchronised above: no copy of the flag is in flight)
+  *c->h_step_err = 0;
+  LAUNCH(c, launch_fill_int(s, c->d_step, B, 0), "fill");
   LAUNCH(c, launch_pack_tokens(s, query_tokens, Lmax, c->d_tok_seq, c->d_tok_pos, T, g.vocab, c->d_ids, c->d_err),
          "pack_tokens");
   HIP_TRY(c, hipMemcpyAsync(&c->h_misc[2], c->d_err, sizeof(int), hipMemcpyDeviceToHost, s));
@@ -527,9 +537,12 @@ int prefill_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* le
   }
   rc = gemm_any(c, c->yl, c->lm_head, c->logits, B, g.vocab, g.d_model, EPI_STORE_F32);
   if (rc) return rc;
-  LAUNCH(c, launch_sampler(s, c->logits, B, g.vocab, c->sp, c->d_step, out_stride, 1, tok_out, lp_out, c->d_cur_tok),
-         "sampler");
-  HIP_TRY(c, hipMemcpyAsync(c->d_step, &c->h_misc[1], sizeof(int), hipMemcpyHostToDevice, s));
+  {
+    SamplerArgs a = c->sp;
+    a.out_stride = out_stride; a.use_step_col = 1; a.step_stride = 1; a.tok_out = tok_out; a.lp_out = lp_out;
+    LAUNCH(c, launch_sampler(s, c->logits, B, g.vocab, a, nullptr, c->d_step, c->d_cur_tok), "sampler");
+  }
+  LAUNCH(c, launch_fill_int(s, c->d_step, B, 1), "fill");
   c->h_step = 1;
   c->have_batch = true;
   c->have_logits = true;
@@ -683,10 +696,60 @@ void after_step(rlhf_gen_ctx* c) {
 }
 
 void drop_graph(rlhf_gen_ctx* c) {
-  if (c->graph_exec) {
-    (void)hipGraphExecDestroy(c->graph_exec);
-    c->graph_exec = nullptr;
+  for (auto& kv : c->graphs) (void)hipGraphExecDestroy(kv.second);
+  c->graphs.clear();
+}
+
+// The decode step for batch rows [0, B) as an executable graph: recorded once, then reused by every rollout of that
+// width (nothing a rollout changes - seed, temperature, top-p, output buffers - is baked into it).
+int decode_graph(rlhf_gen_ctx* c, int B, hipGraphExec_t* out) {
+  const GraphKey key(0, B);
+  auto it = c->graphs.find(key);
+  if (it != c->graphs.end()) {
+    *out = it->second;
+    return RLHF_GEN_OK;
   }
+  if (c->graphs.size() >= MAX_CACHED_GRAPHS) drop_graph(c);
+  hipGraph_t graph = nullptr;
+  HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+  int rc = enqueue_decode_body(c, nullptr, nullptr, 0, 0, true);
+  hipError_t e = hipStreamEndCapture(c->stream, &graph);
+  if (rc) {
+    if (graph) (void)hipGraphDestroy(graph);
+    return rc;
+  }
+  if (e != hipSuccess) return fail(c, RLHF_GEN_E_DEVICE, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+  hipGraphExec_t exec = nullptr;
+  e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+  (void)hipGraphDestroy(graph);
+  if (e != hipSuccess) return fail(c, RLHF_GEN_E_DEVICE, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
+  c->graphs[key] = exec;
+  c->graph_captures++;
+  *out = exec;
+  return RLHF_GEN_OK;
+}
+
+// Result of the asynchronous check that decode_step leaves behind (see rlhf_gen_ctx::h_step_err).  `wait`: block
+// until the copy has landed (callers that synchronise anyway); otherwise only look if it already has.
+int take_step_error(rlhf_gen_ctx* c, bool wait) {
+  if (!c->step_err_pending) return RLHF_GEN_OK;
+  if (wait) {
+    HIP_TRY(c, hipEventSynchronize(c->ev_step_err));
+  } else {
+    hipError_t q = hipEventQuery(c->ev_step_err);
+    if (q == hipErrorNotReady) return RLHF_GEN_OK;
+    if (q != hipSuccess) return fail(c, RLHF_GEN_E_DEVICE, "hipEventQuery failed: %s", hipGetErrorString(q));
+  }
+  c->step_err_pending = false;
+  if (*c->h_step_err) {
+    *c->h_step_err = 0;
+    c->h_misc[0] = 0;
+    HIP_TRY(c, hipMemcpyAsync(c->d_err, &c->h_misc[0], sizeof(int), hipMemcpyHostToDevice, c->stream));
+    return fail(c, RLHF_GEN_E_INVALID,
+                "a forced token id of an earlier decode step lay outside [0, vocab = %d); that step used the nearest valid id",
+                c->cfg.vocab);
+  }
+  return RLHF_GEN_OK;
 }
 
 }  // namespace
@@ -797,7 +860,8 @@ static int allocate_all(rlhf_gen_ctx* c) {
   A_(dev_alloc(c, &c->kv_pool, c->layer_pool_bytes * g.n_layers, true));
   A_(dev_alloc(c, &c->d_table, sizeof(int) * (size_t)g.max_batch * c->max_blocks, true));
   A_(dev_alloc(c, &c->d_seq_len, sizeof(int) * g.max_batch, true));
-  A_(dev_alloc(c, &c->d_step, sizeof(int), true));
+  A_(dev_alloc(c, &c->d_step, sizeof(int) * g.max_batch, true));
+  A_(dev_alloc(c, &c->d_sargs, sizeof(SamplerArgs), true));
   A_(dev_alloc(c, &c->d_err, sizeof(int), true));
   A_(dev_alloc(c, &c->d_cur_tok, sizeof(int) * g.max_batch, true));
   A_(dev_alloc(c, &c->d_cos, sizeof(float) * (size_t)(g.max_seq + 1) * half, false));
@@ -851,6 +915,8 @@ static int allocate_all(rlhf_gen_ctx* c) {
   A_(host_alloc(c, &c->h_table, sizeof(int) * (size_t)g.max_batch * c->max_blocks));
   A_(host_alloc(c, &c->h_lenbuf, sizeof(int) * g.max_batch));
   A_(host_alloc(c, &c->h_misc, sizeof(int) * 8));
+  A_(host_alloc(c, &c->h_step_err, sizeof(int)));
+  A_(host_alloc(c, &c->h_sargs, sizeof(SamplerArgs)));
   A_(host_alloc(c, &c->h_srows, sizeof(int) * total_tok));
   A_(host_alloc(c, &c->h_sslot, sizeof(int) * total_tok));
 #undef A_
@@ -943,6 +1009,10 @@ int rlhf_gen_init(const rlhf_gen_weights* w, const rlhf_gen_cfg* cfg, rlhf_gen_c
       c->err = "hipEventCreate failed";
       return bail(RLHF_GEN_E_DEVICE);
     }
+  if (hipEventCreateWithFlags(&c->ev_step_err, hipEventDisableTiming) != hipSuccess) {
+    c->err = "hipEventCreate failed";
+    return bail(RLHF_GEN_E_DEVICE);
+  }
   reset_free_list(c);
   if (hipDeviceSynchronize() != hipSuccess) {
     c->err = "device synchronisation after init failed";
@@ -963,13 +1033,22 @@ int rlhf_gen_decode_step(rlhf_gen_ctx* c, const int32_t* forced_tokens, int32_t*
   if (!c) return RLHF_GEN_E_INVALID;
   if (!tok_out || !logprob_out) return fail(c, RLHF_GEN_E_INVALID, "NULL output pointer");
   HIP_TRY(c, hipSetDevice(c->cfg.device));
-  int rc = decode_checks(c);
+  int rc = take_step_error(c, false);
+  if (rc) return rc;
+  rc = decode_checks(c);
   if (rc) return rc;
   if (forced_tokens)
     HIP_TRY(c, hipMemcpyAsync(c->d_cur_tok, forced_tokens, sizeof(int) * c->B, hipMemcpyDeviceToDevice, c->stream));
-  rc = enqueue_decode_body(c, tok_out, logprob_out, 1, 0);
+  rc = enqueue_decode_body(c, tok_out, logprob_out, 1, 0, false);
   if (rc) return rc;
   after_step(c);
+  if (forced_tokens) {
+    // the embedding kernel has flagged ids outside the vocabulary; fetch the flag behind the step without waiting
+    if (c->step_err_pending) HIP_TRY(c, hipEventSynchronize(c->ev_step_err));   // one pinned word: the previous copy must have landed
+    HIP_TRY(c, hipMemcpyAsync(c->h_step_err, c->d_err, sizeof(int), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipEventRecord(c->ev_step_err, c->stream));
+    c->step_err_pending = true;
+  }
   return RLHF_GEN_OK;
 }
 
@@ -985,29 +1064,17 @@ static int generate_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int
   c->reserve_extra = 0;
   if (rc) return rc;
   HIP_TRY(c, hipEventRecord(c->ev[1], s));
+  // the decode steps read the sampling rule and the output buffers from device memory (prefill_impl has
+  // synchronised the stream since the staging copy was last read, so it may be rewritten)
+  *c->h_sargs = c->sp;
+  c->h_sargs->out_stride = R; c->h_sargs->use_step_col = 1; c->h_sargs->step_stride = 1;
+  c->h_sargs->tok_out = resp_tokens; c->h_sargs->lp_out = resp_logprobs;
+  HIP_TRY(c, hipMemcpyAsync(c->d_sargs, c->h_sargs, sizeof(SamplerArgs), hipMemcpyHostToDevice, s));
   const bool use_graph = !(c->cfg.flags & RLHF_GEN_FLAG_NO_GRAPH) && R > 2;
+  hipGraphExec_t graph_exec = nullptr;
   if (use_graph) {
-    GraphKey key;
-    key.B = B; key.stride = R; key.use_col = 1; key.tok = resp_tokens; key.lp = resp_logprobs; key.sp = c->sp;
-    if (!c->graph_exec || !(key == c->graph_key)) {
-      drop_graph(c);
-      hipGraph_t graph = nullptr;
-      HIP_TRY(c, hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
-      rc = enqueue_decode_body(c, resp_tokens, resp_logprobs, R, 1);
-      hipError_t e = hipStreamEndCapture(s, &graph);
-      if (rc) {
-        if (graph) (void)hipGraphDestroy(graph);
-        return rc;
-      }
-      if (e != hipSuccess) return fail(c, RLHF_GEN_E_DEVICE, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
-      e = hipGraphInstantiate(&c->graph_exec, graph, nullptr, nullptr, 0);
-      (void)hipGraphDestroy(graph);
-      if (e != hipSuccess) {
-        c->graph_exec = nullptr;
-        return fail(c, RLHF_GEN_E_DEVICE, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
-      }
-      c->graph_key = key;
-    }
+    rc = decode_graph(c, B, &graph_exec);
+    if (rc) return rc;
   }
   for (int t = 1; t < R; ++t) {
     rc = decode_checks(c);  // pages were reserved by prefill: never allocates here
@@ -1015,10 +1082,10 @@ static int generate_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int
     const bool sampled = c->prof_every > 0 && t % c->prof_every == 0 && use_streaming(c, B) &&
                          c->prof_used + 16 * c->cfg.n_layers + 16 <= (int)c->prof_ev.size();
     if (use_graph && !sampled) {
-      HIP_TRY(c, hipGraphLaunch(c->graph_exec, s));
+      HIP_TRY(c, hipGraphLaunch(graph_exec, s));
     } else {
       c->prof_on = sampled;
-      rc = enqueue_decode_body(c, resp_tokens, resp_logprobs, R, 1);
+      rc = enqueue_decode_body(c, nullptr, nullptr, 0, 0, true);
       c->prof_on = false;
       if (rc) return rc;
       if (sampled) {
@@ -1103,7 +1170,7 @@ int rlhf_gen_get_logits(rlhf_gen_ctx* c, float* out) {
   if (!out) return fail(c, RLHF_GEN_E_INVALID, "NULL output pointer");
   if (!c->have_logits) return fail(c, RLHF_GEN_E_STATE, "no step has produced logits yet");
   HIP_TRY(c, hipMemcpyAsync(out, c->logits, sizeof(float) * (size_t)c->B * c->cfg.vocab, hipMemcpyDeviceToDevice, c->stream));
-  return RLHF_GEN_OK;
+  return take_step_error(c, true);
 }
 
 int rlhf_gen_last_timing(const rlhf_gen_ctx* c, float* prefill_ms, float* decode_ms, int32_t* decode_steps) {
@@ -1159,6 +1226,8 @@ int rlhf_gen_get_profile(const rlhf_gen_ctx* c, double* ms, int64_t* launches, i
 const char* rlhf_gen_last_error(const rlhf_gen_ctx* c) { return c ? c->err.c_str() : g_init_error.c_str(); }
 
 int64_t rlhf_gen_context_bytes(const rlhf_gen_ctx* c) { return c ? (int64_t)c->dev_bytes : 0; }
+
+int64_t rlhf_gen_graph_captures(const rlhf_gen_ctx* c) { return c ? (int64_t)c->graph_captures : 0; }
 
 int rlhf_gen_plan_capacity(const rlhf_gen_cfg* cfg, int64_t capacity_bytes, double fraction, int64_t reserved_bytes,
                            int32_t* max_batch_out, int64_t* context_bytes_out) {
@@ -1302,6 +1371,9 @@ void rlhf_gen_destroy(rlhf_gen_ctx* c) {
     if (p) (void)hipHostFree(p);
   for (int i = 0; i < 3; ++i)
     if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
+  if (c->ev_step_err) (void)hipEventDestroy(c->ev_step_err);
+  if (c->h_step_err) (void)hipHostFree(c->h_step_err);
+  if (c->h_sargs) (void)hipHostFree(c->h_sargs);
   for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
   for (hipEvent_t e : c->step_ev) (void)hipEventDestroy(e);
   if (c->own_stream && c->stream) (void)hipStreamDestroy(c->stream);
@@ -1387,9 +1459,10 @@ int rlhf_gen_op_sample(void* stream, const float* logits, int32_t B, int32_t V, 
     if (sampler_configure() != hipSuccess) return RLHF_GEN_E_DEVICE;
     configured = true;
   }
-  SamplerParams p{};
+  SamplerArgs p{};
   p.temperature = sp->temperature; p.top_p = sp->top_p; p.seed = sp->seed; p.greedy = sp->greedy; p.logprob_mode = sp->logprob_mode;
-  hipError_t e = launch_sampler((hipStream_t)stream, logits, B, V, p, step, 1, 0, tok_out, logprob_out, scratch_tok);
+  p.out_stride = 1; p.tok_out = tok_out; p.lp_out = logprob_out;   // one response index for all rows, results in column 0
+  hipError_t e = launch_sampler((hipStream_t)stream, logits, B, V, p, nullptr, step, scratch_tok);
   return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;
 }
 
