@@ -1,6 +1,12 @@
 """Parity at the benchmark's real per-token shapes (7B width, B = 64, 512-token queries, bf16), in the launch
 configuration bench.py times.  The oracle (float64) runs on a few batch rows only - rows are independent - and
-every comparison is teacher-forced with the oracle's tokens on those rows."""
+every comparison is teacher-forced with the oracle's tokens on those rows.  Full-depth runs (32, 40 and 80 layers) are
+in test_gpu_depth.py.
+
+Token parity at V = 32000 with T = 1, top-p = 1 is "unpinned by design": the distribution over random-init logits is
+nearly flat, so a draw almost always lies within the logit tolerance of a CDF edge and `_run` can only require that
+every differing token is such a case (it reports the fraction).  What pins the tokens at this shape is
+test_7b_width_sampler_agrees_with_oracle_on_every_row, which runs the oracle's sampler on the GPU's own logits."""
 import time
 
 import pytest
@@ -28,6 +34,9 @@ def _run(B, shape, batch, len_lo, len_hi, rows, steps, cfgs, weight_seed, token_
     w = synth.make_weights(shape, weight_seed, "bf16", "cuda")
     toks, lens = synth.make_queries(shape.vocab, batch, len_lo, len_hi, token_seed)
     w_cpu = synth.weights_to(w, "cpu")
+    # widened once here (the values do not change), so that the oracle's per-call conversion of the weights is a no-op
+    w_cpu = {**{k: v.to(dtype) for k, v in w_cpu.items() if k != "layers"},
+             "layers": [{k: v.to(dtype) for k, v in lw.items()} for lw in w_cpu["layers"]]}
     qs = [toks[b, : lens[b]].tolist() for b in range(batch)]
     osp = OSampling(**cfgs)
     ref = oracle_generate(w_cpu, shape, qs, steps, osp, rows=rows, dtype=dtype)
@@ -83,10 +92,14 @@ def test_7b_width_2_layers_ragged_long_context(B):
     assert dl <= 3e-2 and dlp <= 2e-2 and frac <= 0.34
 
 
-def test_7b_full_depth_one_row(B):
-    dl, dlp, frac = _run(B, synth.LLAMA_7B, 64, 512, 512, [5], 3, dict(temperature=1.0, top_p=1.0, seed=2), 2, 2,
-                         dtype=torch.float32)
-    assert dl <= 3e-2 and dlp <= 2e-2
+def test_7b_width_b256_2_layers(B):
+    """The large-batch configuration (256 queries of 256 tokens, greedy, 16-token pages) at the real 7B width: decode
+    batches of 129..256 rows take the split-K form of the large-tile GEMM, the separate SwiGLU kernel and the tiled LM
+    head, which no other configuration exercises.  Rows 0, 128 and 255; 21 decode steps, so every context crosses a
+    page boundary (256 -> 277 tokens)."""
+    shape = synth.with_layers(synth.LLAMA_7B, 2)
+    dl, dlp, frac = _run(B, shape, 256, 256, 256, [0, 128, 255], 22, dict(greedy=True), 2, 4)
+    assert dl <= 3e-2 and dlp <= 2e-2 and frac <= 0.34
 
 
 def test_70b_width_gqa_2_layers(B):

@@ -1,0 +1,159 @@
+"""Parity at full depth: the rounding error of the 16-bit path grows with the number of layers, so the tolerance of the
+rollout (max |dlogit| <= 3e-2, max |dlogprob| <= 2e-2) is checked on the whole 7B stack (32 layers, the benchmark's
+batch and lengths, several rows and steps, and one step at a context beyond 1000 tokens), on the 13B stack (40 layers)
+and on the 70B grouped-query stack (80 layers).  The oracle runs in its float32 mode on a few batch rows (rows are
+independent), teacher-forced with its own tokens; sequences are kept short where the oracle's cost per token is high.
+Progress lines go to the terminal while a test runs (each takes a minute or two, most of it on the host)."""
+import time
+
+import pytest
+import torch
+
+from oracle import sampling as OS
+from oracle.generate import generate as oracle_generate
+from oracle.sampling import Sampling as OSampling
+from paper_2312_11819_amd import synth
+from tests.gpu_util import need_gpu
+
+pytestmark = pytest.mark.gpu
+
+LOGIT_TOL, LOGPROB_TOL = 3e-2, 2e-2
+
+
+@pytest.fixture(scope="module")
+def B():
+    need_gpu()
+    from paper_2312_11819_amd import binding
+    binding.lib()
+    return binding
+
+
+def _say(capsys, msg):
+    with capsys.disabled():
+        print(msg, flush=True)
+
+
+def _host_copy(w, dtype=None):
+    """The same weights on the host; with dtype float32 the oracle's per-call conversion becomes a no-op."""
+    def conv(t):
+        t = t.to("cpu")
+        return t.to(dtype) if dtype is not None else t
+    out = {k: conv(v) for k, v in w.items() if k != "layers"}
+    out["layers"] = [{k: conv(v) for k, v in lw.items()} for lw in w["layers"]]
+    return out
+
+
+def _teacher_forced_parity(B, capsys, name, w, w_host, shape, toks, lens, rows, steps, cfgs, flags=0):
+    """prefill + (steps - 1) decode steps; the checked rows are fed the oracle's tokens.  Returns max |dlogit|, rms,
+    max |dlogprob| over rows x steps x vocab."""
+    t0 = time.time()
+    batch = toks.shape[0]
+    qs = [toks[b, : lens[b]].tolist() for b in range(batch)]
+    osp = OSampling(**cfgs)
+    ref = {"tokens": [], "logprobs": [], "logits": []}
+    for b in rows:   # row by row, so that progress shows
+        r = oracle_generate(w_host, shape, qs, steps, osp, rows=[b], dtype=torch.float32)
+        for k in ref:
+            ref[k].append(r[k][0])
+        _say(capsys, f"  [{name}] oracle row {b} ({int(lens[b])} + {steps} tokens) done at {time.time() - t0:.0f} s")
+    ref = {k: torch.stack(v) for k, v in ref.items()}
+    ctx = B.Context(w, shape, "bf16", batch, int(lens.max()) + steps + 1, flags=flags)
+    sp = B.make_sampling(**cfgs)
+    got_t, got_lp, got_lg = [], [], []
+    tok, lp = ctx.rlhf_gen_prefill(toks.cuda(), lens.tolist(), sp)
+    for s in range(steps):
+        lg = ctx.rlhf_gen_get_logits()
+        got_t.append(tok[rows].cpu().long()); got_lp.append(lp[rows].cpu().double()); got_lg.append(lg[rows].cpu().double())
+        if s + 1 < steps:
+            forced = tok.clone()
+            forced[rows] = ref["tokens"][:, s].to(torch.int32).cuda()
+            tok, lp = ctx.rlhf_gen_decode_step(forced)
+    ctx.synchronize()
+    ctx.rlhf_gen_destroy()
+    got_t, got_lp, got_lg = torch.stack(got_t, 1), torch.stack(got_lp, 1), torch.stack(got_lg, 1)
+    diff = got_lg - ref["logits"]
+    dl, rms = diff.abs().max().item(), diff.pow(2).mean().sqrt().item()
+    dlp, skipped = 0.0, 0
+    for ri, b in enumerate(rows):
+        for t in range(steps):
+            want = int(ref["tokens"][ri, t])
+            if int(got_t[ri, t]) != want:
+                # a different token is legitimate only next to a tie / a CDF edge of the oracle's own distribution
+                if osp.greedy:
+                    top2 = ref["logits"][ri, t].topk(2).values
+                    assert float(top2[0] - top2[1]) < 2 * LOGIT_TOL, (b, t)
+                else:
+                    _, _, info = OS.sample(ref["logits"][ri, t], osp, b, t)
+                    assert OS.cdf_margin(info, want) < LOGIT_TOL, (b, t)
+                skipped += 1
+                continue
+            dlp = max(dlp, abs(float(got_lp[ri, t]) - float(ref["logprobs"][ri, t])))
+    _say(capsys, f"  [{name}] {shape.n_layers} layers, rows {rows} x {steps} steps: max|dlogit| = {dl:.4f}, rms = {rms:.5f}, "
+                 f"max|dlogprob| = {dlp:.4f}, tokens not compared {skipped}/{len(rows) * steps}, {time.time() - t0:.0f} s")
+    return dl, rms, dlp
+
+
+@pytest.fixture(scope="module")
+def w7b(B):
+    w = synth.make_weights(synth.LLAMA_7B, 2, "bf16", "cuda")
+    yield w, _host_copy(w, torch.float32)
+    del w
+    torch.cuda.empty_cache()
+
+
+def test_7b_full_depth_three_rows_six_decode_steps(B, capsys, w7b):
+    """The benchmark's configuration (64 queries of 512 tokens, T = 1, top-p = 1, seed 2): rows 0, 32 and 63, the prefill
+    step and six decode steps each, all 32000 logits of every step.  At this vocabulary and a near-flat distribution
+    almost every draw lies next to a CDF edge, so token equality decides little here ("parity unpinned" by design for the
+    sampled token at this configuration; the sampler has its own test on the GPU's logits) - logits and log-probs carry
+    the check."""
+    w, w_host = w7b
+    toks, lens = synth.make_queries(synth.LLAMA_7B.vocab, 64, 512, 512, 2)
+    dl, rms, dlp = _teacher_forced_parity(B, capsys, "7B", w, w_host, synth.LLAMA_7B, toks, lens, [0, 32, 63], 7,
+                                          dict(temperature=1.0, top_p=1.0, seed=2))
+    assert dl <= LOGIT_TOL and dlp <= LOGPROB_TOL
+
+
+def test_7b_full_depth_context_beyond_1000(B, capsys, w7b):
+    """One row with a 1010-token query (the benchmark's last decode steps read 1023 cached tokens), three steps."""
+    w, w_host = w7b
+    toks, lens = synth.make_queries(synth.LLAMA_7B.vocab, 4, 1010, 1010, 12)
+    dl, rms, dlp = _teacher_forced_parity(B, capsys, "7B ctx 1010", w, w_host, synth.LLAMA_7B, toks, lens, [2], 3,
+                                          dict(temperature=1.0, top_p=1.0, seed=2))
+    assert dl <= LOGIT_TOL and dlp <= LOGPROB_TOL
+
+
+def test_13b_full_depth(B, capsys):
+    """40 layers at d_model 5120 (ragged batch, T = 0.8, top-p = 0.9): the longest row, prefill + three decode steps."""
+    torch.cuda.empty_cache()
+    shape = synth.LLAMA_13B
+    w = synth.make_weights(shape, 3, "bf16", "cuda")
+    w_host = _host_copy(w, torch.float32)
+    toks, lens = synth.make_queries(shape.vocab, 8, 64, 300, 3)
+    rows = [int(lens.argmax())]
+    dl, rms, dlp = _teacher_forced_parity(B, capsys, "13B", w, w_host, shape, toks, lens, rows, 4,
+                                          dict(temperature=0.8, top_p=0.9, seed=3))
+    del w, w_host
+    torch.cuda.empty_cache()
+    assert dl <= LOGIT_TOL and dlp <= LOGPROB_TOL
+
+
+def test_70b_full_depth_gqa(B, capsys):
+    """80 layers at d_model 8192 with 64 query / 8 KV heads (137 GB of bf16 weights, converted in place so that they fit
+    the card once): a short query, prefill + three decode steps on one row.  The host keeps the weights in bf16 (a
+    float32 copy would be 276 GB) and the oracle widens them layer by layer."""
+    torch.cuda.empty_cache()
+    free, total = torch.cuda.mem_get_info()
+    if free < 150 * 2 ** 30:
+        pytest.skip(f"needs 150 GiB of free device memory for the 70B-shaped weights (free: {free >> 30} GiB)")
+    t0 = time.time()
+    shape = synth.LLAMA_70B_GQA
+    w = synth.make_weights(shape, 5, "bf16", "cuda")
+    w_host = _host_copy(w)                                   # before the context rewrites the device buffers in place
+    _say(capsys, f"  [70B] weights drawn and copied to the host in {time.time() - t0:.0f} s")
+    toks, lens = synth.make_queries(shape.vocab, 4, 24, 40, 5)
+    dl, rms, dlp = _teacher_forced_parity(B, capsys, "70B", w, w_host, shape, toks, lens, [1], 4,
+                                          dict(temperature=1.0, top_p=0.9, seed=5), flags=B.FLAG_CONVERT_IN_PLACE)
+    del w, w_host
+    torch.cuda.empty_cache()
+    assert dl <= LOGIT_TOL and dlp <= LOGPROB_TOL

@@ -1,0 +1,95 @@
+"""Why the 16-bit path computes in fp16 (with four tensors carried as fp16 pairs) and not in bf16: a float64 forward of
+the decoder at the 7B width in which chosen activation tensors are rounded the way a 16-bit kernel would store them.
+The rollout's tolerance is max |dlogit| <= 3e-2 against the unrounded forward.  Measured here, 4 layers deep:
+
+  * every activation rounded to bf16 (8 significant bits): the tolerance is exceeded several times over;
+  * every activation rounded to fp16 (11 bits): within the tolerance at 4 layers, but with no margin left for the
+    8x deeper real stack (the error grows roughly with the square root of the depth);
+  * fp16 everywhere, with the QKV-projection input, the rotated queries, the attention probabilities and the
+    output-projection input carried as two-term fp16 pairs hi + lo: 0.64 of the fp16 error (those four tensors carry
+    60 % of its variance), which is the margin the 32-layer stack needs.
+
+This file has its own forward and rounding helpers: it pins a design decision of the HIP path, not the oracle, and
+imports neither."""
+import math
+
+import pytest
+import torch
+
+from paper_2312_11819_amd import synth
+
+TENSORS = ["y1", "q", "k", "v", "p", "a", "y2", "h", "yf"]   # every tensor a 16-bit kernel writes or feeds to an MFMA
+PAIRS = ("y1", "q", "p", "a")                                # the four that travel as fp16 pairs in the HIP path
+
+
+def _round(x, mode):
+    if mode == "exact":
+        return x
+    if mode == "bf16":
+        return x.to(torch.bfloat16).to(x.dtype)
+    hi = x.to(torch.float16).to(x.dtype)
+    if mode == "fp16":
+        return hi
+    assert mode == "pair"
+    return hi + (x - hi).to(torch.float16).to(x.dtype)
+
+
+def _forward(w, shape, toks, modes):
+    """Logits of the last 8 positions; modes[name] in {"exact", "bf16", "fp16", "pair"} per rounded tensor."""
+    d = torch.float64
+    Hq, h, F = shape.n_heads, shape.head_dim, shape.d_ffn
+    n = len(toks)
+    x = w["tok_emb"].to(d)[torch.tensor(toks)]
+    inv = shape.rope_theta ** (-2.0 * torch.arange(h // 2, dtype=d) / h)
+    ang = torch.arange(n, dtype=d)[:, None] * inv[None, :]
+    c, s_ = torch.cos(ang)[:, None, :], torch.sin(ang)[:, None, :]
+
+    def rope(t):
+        lo, hi = t[..., : h // 2], t[..., h // 2:]
+        return torch.cat([lo * c - hi * s_, hi * c + lo * s_], -1)
+
+    def norm(t):
+        return t / torch.sqrt((t * t).mean(-1, keepdim=True) + shape.rms_eps)
+
+    mask = torch.tril(torch.ones(n, n, dtype=torch.bool))
+    for lw in w["layers"]:
+        y = _round(norm(x), modes["y1"])
+        qkv = y @ lw["wqkv"].to(d).T
+        q = _round(rope(qkv[:, : Hq * h].reshape(n, Hq, h)), modes["q"])
+        k = _round(rope(qkv[:, Hq * h: 2 * Hq * h].reshape(n, Hq, h)), modes["k"])
+        v = _round(qkv[:, 2 * Hq * h:].reshape(n, Hq, h), modes["v"])
+        sc = (torch.einsum("ihd,jhd->hij", q, k) / math.sqrt(h)).masked_fill(~mask, float("-inf"))
+        p = _round(torch.softmax(sc, -1), modes["p"])
+        a = _round(torch.einsum("hij,jhd->ihd", p, v).reshape(n, Hq * h), modes["a"])
+        x = x + a @ lw["wo"].to(d).T
+        y = _round(norm(x), modes["y2"])
+        gu = y @ lw["w_gate_up"].to(d).T
+        g, u = gu[:, :F], gu[:, F:]
+        x = x + _round(g / (1.0 + torch.exp(-g)) * u, modes["h"]) @ lw["w_down"].to(d).T
+    y = _round(norm(x[-8:]), modes["yf"])
+    return y @ w["lm_head"].to(d).T
+
+
+def test_bf16_activations_miss_the_tolerance_fp16_pairs_meet_it():
+    # the 7B layer shape (d_model 4096, 32 heads of 128, FFN 11008), 4 layers; a 4096-entry vocabulary keeps the test short
+    shape = synth.ModelShape(4, 4096, 32, 32, 128, 11008, 4096)
+    w = synth.make_weights(shape, 2, "bf16")
+    toks = torch.randint(0, shape.vocab, (64,), generator=torch.Generator().manual_seed(1)).tolist()
+    base = _forward(w, shape, toks, {k: "exact" for k in TENSORS})
+    err = {}
+    for name, modes in (("bf16", {k: "bf16" for k in TENSORS}),
+                        ("fp16", {k: "fp16" for k in TENSORS}),
+                        ("design", {k: ("pair" if k in PAIRS else "fp16") for k in TENSORS})):
+        e = _forward(w, shape, toks, modes) - base
+        err[name] = (float(e.abs().max()), float(e.pow(2).mean().sqrt()))
+    print("\nmax / rms logit error after 4 layers:", {k: (round(a, 5), round(b, 5)) for k, (a, b) in err.items()})
+    assert err["bf16"][0] > 3e-2                        # bf16 activations: beyond the tolerance after 4 of 32 layers
+    assert err["fp16"][0] < 3e-2
+    assert err["bf16"][1] > 6 * err["fp16"][1]          # 3 fewer significant bits: ~8x the rms error
+    assert err["design"][1] < 0.7 * err["fp16"][1]      # the four pair tensors remove more than half of the error variance
+    # extrapolated to 32 layers (rms grows ~ sqrt(depth); the maximum over a step's 32000 logits sits ~4.5 sigma out):
+    # plain fp16 lands at the tolerance with nothing to spare, the pair design stays inside it - which the full-depth
+    # GPU tests confirm on the real stack
+    scale = math.sqrt(32 / 4) * 4.5
+    assert err["fp16"][1] * scale > 0.9 * 3e-2
+    assert err["design"][1] * scale < 0.7 * 3e-2
