@@ -83,22 +83,100 @@ def prefill_gemm_shapes(binding, shape, rows, dev):
     return out
 
 
-def cpu_baseline(wl, w_dev, toks, lens, decode_steps=2):
-    """The oracle as it stands, fp32 mode, on one sequence of the batch: full prefill + a few decode steps."""
+def traffic_ratios(workload: str):
+    """Fetched / algorithmic byte ratios and written bytes per launch of the decode kernels, read from the committed
+    counter summary profiles/bench_<workload>_pmc_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs).  Returns
+    {kernel name prefix: (ratio, written bytes)} or raises if a kernel this bench reports on is no longer in the table
+    (the summary is stale: the counters have to be collected again)."""
+    path = os.path.join(ROOT, "profiles", f"bench_{workload}_pmc_traffic.md")
+    if not os.path.exists(path):
+        return None
+    rows = {}
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) == 6 and cells[0] and cells[1].isdigit():
+            try:
+                rows[cells[0]] = {"launches": int(cells[1]), "fetched": float(cells[2]) * 1e6, "written": float(cells[3]) * 1e6,
+                                  "algorithmic": float(cells[4]) * 1e6 if cells[4] not in ("-", "") else None}
+            except ValueError:
+                continue
+    out = {}
+    for key in ("attn_decode_kernel", "gemm_skinny"):
+        sel = [r for k, r in rows.items() if k.startswith(key) and r["algorithmic"]]
+        if not sel:
+            raise RuntimeError(f"{path} has no row for {key}*: collect the traffic counters again for the current kernels")
+        n = sum(r["launches"] for r in sel)
+        out[key] = (sum(r["fetched"] * r["launches"] for r in sel) / sum(r["algorithmic"] * r["launches"] for r in sel),
+                    sum(r["written"] * r["launches"] for r in sel) / n)
+    return out
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline_and_parity(binding, ctx, wl, w_dev, toks, lens, rows, decode_steps=4):
+    """The oracle as it stands (float32 mode, KV-cached) on a bounded sample of the workload - whole query prefill +
+    `decode_steps` decode steps for the batch rows `rows` - timed on the host cores; and, with the logits it produced,
+    the parity of the GPU path on the same rows in the same run: the context replays the prefill and the decode steps,
+    the sampled rows teacher-forced with the oracle's tokens, and every logit and log-prob is compared."""
     import torch
     from oracle.generate import generate as oracle_generate
     from oracle.sampling import Sampling as OSampling
     from paper_2312_11819_amd import synth
     w_cpu = synth.weights_to(w_dev, "cpu")
+    # the caller's bf16 values widened once, outside the timed region (the GPU path's one-time weight conversion is
+    # outside its timed region too)
+    w_cpu = {**{k: v.float() for k, v in w_cpu.items() if k != "layers"},
+             "layers": [{k: v.float() for k, v in lw.items()} for lw in w_cpu["layers"]]}
     qs = [toks[b, : lens[b]].tolist() for b in range(toks.shape[0])]
     osp = OSampling(temperature=wl.temperature, top_p=wl.top_p, seed=wl.sample_seed, greedy=wl.greedy)
     n_tok = decode_steps + 1
     t0 = time.perf_counter()
-    oracle_generate(w_cpu, wl.shape, qs, n_tok, osp, rows=[0], dtype=torch.float32, keep_logits=False)
+    ref = oracle_generate(w_cpu, wl.shape, qs, n_tok, osp, rows=rows, dtype=torch.float32)
     dt = time.perf_counter() - t0
-    return {"value": n_tok / dt, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
-            "sample": f"row 0 of the batch: {int(lens[0])}-token prefill + {decode_steps} decode steps "
-                      f"({n_tok} tokens) in {dt:.1f} s, oracle in float32 mode, torch CPU threads as listed"}
+    del w_cpu
+    rate = len(rows) * n_tok / dt
+    B, R = toks.shape[0], wl.resp_len
+    fed = sum(int(lens[b]) for b in rows) + len(rows) * decode_steps          # tokens the sample pushed through the model
+    fed_full = int(lens.sum()) + B * (R - 1)
+    cpu = {"value": rate, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+           "nproc": os.cpu_count(), "cpu_model": cpu_model(),
+           "sample": f"rows {rows} of the batch: {int(lens[rows[0]])}-token prefill + {decode_steps} decode steps each "
+                     f"({len(rows) * n_tok} generated tokens, {fed} tokens through the model) in {dt:.1f} s; oracle in "
+                     f"float32 mode on weights widened to fp32 beforehand, torch CPU threads as listed",
+           "extrapolated": {"full_workload_s": dt * fed_full / fed, "tokens_per_s": B * R / (dt * fed_full / fed),
+                            "how": "linear in tokens pushed through the model (prefill and decode tokens alike), so an "
+                                   "underestimate of the time: attention over longer contexts is not scaled"}}
+    # parity of the GPU path on the sampled rows
+    sp = binding.make_sampling(wl.temperature, wl.top_p, wl.sample_seed, wl.greedy, 0)
+    tok, lp = ctx.rlhf_gen_prefill(toks.to("cuda:0"), lens.tolist(), sp)
+    dl = dlp = 0.0
+    agree = total = 0
+    for s in range(n_tok):
+        lg = ctx.rlhf_gen_get_logits()[rows].cpu().double()
+        dl = max(dl, float((lg - ref["logits"][:, s]).abs().max()))
+        for ri, b in enumerate(rows):
+            total += 1
+            if int(tok[b]) == int(ref["tokens"][ri, s]):
+                agree += 1
+                dlp = max(dlp, abs(float(lp[b]) - float(ref["logprobs"][ri, s])))
+        if s + 1 < n_tok:
+            forced = tok.clone()
+            forced[rows] = ref["tokens"][:, s].to(torch.int32).to(forced.device)
+            tok, lp = ctx.rlhf_gen_decode_step(forced)
+    ctx.synchronize()
+    parity = {"rows": rows, "steps": n_tok, "max_dlogit": dl, "max_dlogprob": dlp, "tokens_equal": f"{agree}/{total}",
+              "tolerance": {"dlogit": 3e-2 if wl.dtype == "bf16" else 1e-4, "dlogprob": 2e-2 if wl.dtype == "bf16" else 1e-4},
+              "logits_compared": len(rows) * n_tok * wl.shape.vocab}
+    parity["ok"] = bool(dl <= parity["tolerance"]["dlogit"] and dlp <= parity["tolerance"]["dlogprob"])
+    return cpu, parity
 
 
 def main() -> int:
@@ -223,10 +301,12 @@ def main() -> int:
         # weight-conversion copy kernel): measured on a 2-layer, 48-token run of this workload, because counter runs of
         # the full-size command do not finish; the fetched / algorithmic ratio of those launches is applied to this
         # run's launches (profiles/bench_7b_b64_pmc_traffic.md)
-        pmc = {"attn_decode_kernel": (1.014, 1.05e6), "gemm_skinny_kernel": (1.073, 10.6e6)}.get(roofline["kernel"])
-        if wl.name == "7b_b64":
+        ratios = traffic_ratios(wl.name)
+        if ratios is not None:
+            pmc = ratios["attn_decode_kernel" if roofline["kernel"].startswith("attn") else "gemm_skinny"]
             roofline["traffic"] = pmc[0] * roofline["bytes_per_launch"] + pmc[1]
-            roofline["traffic_source"] = "rocprofv3 --pmc ratio of a reduced-depth run, see profiles/bench_7b_b64_pmc_traffic.md"
+            roofline["traffic_source"] = (f"fetched / algorithmic = {pmc[0]:.3f} and {pmc[1] / 1e6:.1f} MB written per launch, from the "
+                                          f"rocprofv3 --pmc summary profiles/bench_{wl.name}_pmc_traffic.md (reduced-depth run of this workload)")
         roofline["attn_decode_GBps"] = attn_bytes / attn_s / 1e9 if attn_s > 0 else None
         roofline["gemm_skinny_GBps"] = gemm_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else None
 
@@ -279,9 +359,11 @@ def main() -> int:
             roofline["measured_peak"] = probes["hbm_read_nontemporal_GBps"]
             roofline["frac_of_measured_peak"] = roofline["achieved"] / probes["hbm_read_nontemporal_GBps"]
 
-    cpu = None
-    if not args.no_cpu_baseline:
-        cpu = cpu_baseline(wl if not args.layers else synth.dataclasses.replace(wl, shape=shape), w, toks, lens)
+    cpu = parity = None
+    if not args.no_cpu_baseline and not (args.flags & 8):   # (converted in place, the caller's buffers no longer hold bf16)
+        rows = sorted({0, B // 2})
+        cpu, parity = cpu_baseline_and_parity(binding, ctx, wl if not args.layers else synth.dataclasses.replace(wl, shape=shape),
+                                              w, toks, lens, rows)
 
     line = {
         "metric": "generated tokens/sec + % HBM roofline per decode step, 7B-shape bf16 B=64",
@@ -292,7 +374,9 @@ def main() -> int:
                    "query_len": [wl.len_lo, wl.len_hi], "resp_len": R, "temperature": wl.temperature, "top_p": wl.top_p,
                    "kv_block": 16,
                    "weights": "bf16 at the boundary; fp16 MFMA operands (exact conversion), fp32 accumulation" if wl.dtype == "bf16" else "fp32",
-                   "valid": not args.layers and not args.resp_len,
+                   # the configuration is the named one, and this run's own output was checked against the oracle
+                   "valid": bool(not args.layers and not args.resp_len and (parity is None or parity["ok"])),
+                   "checked_against_oracle": parity is not None,
                    "rollouts_bit_identical": repeatable},
         "decode": {"ms_per_decode_step": dec_ms / max(R - 1, 1), "tokens_per_s_decode_only": B * (R - 1) / (dec_ms * 1e-3) if dec_ms else None,
                    "hbm_roofline_frac_per_decode_step": dec_frac, "mfma_bf16_frac_per_decode_step": dec_mfma_frac,
@@ -309,6 +393,7 @@ def main() -> int:
         "measured_peaks": probes,
         "weight_refresh": refresh,
         "cpu_baseline": cpu,
+        "parity_vs_oracle": parity,
     }
     print(json.dumps(line))
     ctx.rlhf_gen_destroy()
