@@ -37,7 +37,7 @@ def _round(x, mode):
 def _forward(w, shape, toks, modes):
     """Logits of the last 8 positions; modes[name] in {"exact", "bf16", "fp16", "pair"} per rounded tensor."""
     d = torch.float64
-    Hq, h, F = shape.n_heads, shape.head_dim, shape.d_ffn
+    Hq, Hkv, h, F = shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn
     n = len(toks)
     x = w["tok_emb"].to(d)[torch.tensor(toks)]
     inv = shape.rope_theta ** (-2.0 * torch.arange(h // 2, dtype=d) / h)
@@ -56,8 +56,9 @@ def _forward(w, shape, toks, modes):
         y = _round(norm(x), modes["y1"])
         qkv = y @ lw["wqkv"].to(d).T
         q = _round(rope(qkv[:, : Hq * h].reshape(n, Hq, h)), modes["q"])
-        k = _round(rope(qkv[:, Hq * h: 2 * Hq * h].reshape(n, Hq, h)), modes["k"])
-        v = _round(qkv[:, 2 * Hq * h:].reshape(n, Hq, h), modes["v"])
+        k = _round(rope(qkv[:, Hq * h: (Hq + Hkv) * h].reshape(n, Hkv, h)), modes["k"])
+        v = _round(qkv[:, (Hq + Hkv) * h:].reshape(n, Hkv, h), modes["v"])
+        k, v = k.repeat_interleave(Hq // Hkv, dim=1), v.repeat_interleave(Hq // Hkv, dim=1)   # grouped KV heads
         sc = (torch.einsum("ihd,jhd->hij", q, k) / math.sqrt(h)).masked_fill(~mask, float("-inf"))
         p = _round(torch.softmax(sc, -1), modes["p"])
         a = _round(torch.einsum("hij,jhd->ihd", p, v).reshape(n, Hq * h), modes["a"])
@@ -93,3 +94,26 @@ def test_bf16_activations_miss_the_tolerance_fp16_pairs_meet_it():
     scale = math.sqrt(32 / 4) * 4.5
     assert err["fp16"][1] * scale > 0.9 * 3e-2
     assert err["design"][1] * scale < 0.7 * 3e-2
+
+
+def test_rounding_noise_grows_with_width_and_depth_beyond_the_tolerance_at_70b_shape():
+    """The same experiment at the 70B layer shape (d_model 8192, 64 query / 8 KV heads, FFN 28672), 2 layers: with
+    N(0, 0.02^2) matrices a wider layer writes a larger update into the residual stream and amplifies perturbations
+    more, so the same fp16-pair design leaves ~1.7x the logit error of the 7B shape at equal depth - and the stack is
+    2.5x deeper.  Extrapolated with the square root of the depth (the full-depth GPU runs grow slightly faster), the
+    80-layer stack ends near rms 0.011: its maximum over a step's 32000 logits, ~4.4 sigma, is beyond 3e-2 whatever
+    the kernels do, short of carrying every activation and the KV cache as pairs.  This is the reason the full-depth
+    GPU tests of the 13B and 70B shapes assert the log-prob tolerance and an rms bound, and report the logit maximum
+    as an expected failure."""
+    def design_rms(shape, seed):
+        w = synth.make_weights(shape, seed, "bf16")
+        toks = torch.randint(0, shape.vocab, (32,), generator=torch.Generator().manual_seed(1)).tolist()
+        base = _forward(w, shape, toks, {k: "exact" for k in TENSORS})
+        e = _forward(w, shape, toks, {k: ("pair" if k in PAIRS else "fp16") for k in TENSORS}) - base
+        return float(e.pow(2).mean().sqrt()), float(base.std())
+    r7, s7 = design_rms(synth.ModelShape(2, 4096, 32, 32, 128, 11008, 2048), 2)
+    r70, s70 = design_rms(synth.ModelShape(2, 8192, 64, 8, 128, 28672, 2048), 5)
+    print(f"\n2 layers: 7B shape rms {r7:.5f} (logit std {s7:.2f}), 70B shape rms {r70:.5f} (logit std {s70:.2f})")
+    assert r70 > 1.4 * r7
+    assert r70 * math.sqrt(80 / 2) * 4.4 > 3e-2          # 80 layers, maximum over 32000 logits
+    assert r7 * math.sqrt(32 / 2) * 4.5 < 3e-2           # the benchmark's 32-layer stack stays inside
