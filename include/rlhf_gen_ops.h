@@ -54,6 +54,22 @@ int rlhf_gen_op_tile_weights(void* stream, const void* w_rowmajor, void* w_tiled
 int rlhf_gen_op_gemm(void* stream, int kind, const void* A, const void* W, void* out, int32_t M, int32_t N, int32_t K,
                      int32_t epilogue, int32_t nsplit, int32_t a_pairs);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, serving loops and harnesses that forbid
+ * hipMalloc): the STREAMING product out = A W^T of rlhf_gen_op_gemm with its split-K partial sums summed inside the
+ * library.  rlhf_gen_op_gemm(STREAMING) needs a caller-provided fp32 [nsplit, M, N] buffer for the partial sums; here they
+ * go to a workspace of 32 MiB that is part of the library's device image (each GPU the library runs on holds it until
+ * the process ends), and the call allocates nothing - no hipMalloc, no hipFree, no allocating library routine.
+ *   A fp16 [M, K] (a_pairs != 0: [M, 2K] hi | lo pairs), W fp16 [N, K] in the working layout, out fp32 [M, N] (written
+ *   completely); M <= 256 (128 with a_pairs), N % 64 == 0, K % 128 == 0, else UNSUPPORTED.  The split count is the one
+ *   the rollout uses for this weight shape; *nsplit_out (host, may be NULL) receives it.  The planes are added in
+ *   ascending order, as the rollout's consumer kernels add them.
+ * Errors: E_INVALID if nsplit * M * N * 4 bytes exceed the 32 MiB workspace (message via rlhf_gen_last_error(NULL)).
+ * Every call on a GPU uses that GPU's one workspace: calls that overlap in time on the same GPU (different streams or
+ * threads) race and must be serialised by the caller.  The workspace keeps the previous call's contents; nothing in it
+ * has to start at zero, since every element the summation reads is written by the same call first. */
+int rlhf_gen_op_gemm_static(void* stream, const void* A, const void* W, float* out, int32_t M, int32_t N, int32_t K,
+                            int32_t a_pairs, int32_t* nsplit_out);
+
 /* Rotate q and k of fp32 qkv rows [M, (Hq + 2 Hkv) head_dim] by their positions and append k, v to the paged
  * cache.  row_pos [M] position of each row; row_seq [M] batch row (NULL = identity); cos_t / sin_t
  * [positions, head_dim/2] fp32 tables; block_table int32 [batch, max_blocks]; kv_pool = one layer's pool

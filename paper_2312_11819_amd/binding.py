@@ -32,7 +32,7 @@ EXPORTS = [
     "rlhf_gen_get_logits",
     "rlhf_gen_last_timing", "rlhf_gen_last_step_ms", "rlhf_gen_set_profile", "rlhf_gen_get_profile", "rlhf_gen_last_error", "rlhf_gen_destroy",
     "rlhf_gen_op_probe_stream_read", "rlhf_gen_op_probe_mfma_loop", "rlhf_gen_op_tile_weights", "rlhf_gen_op_gemm", "rlhf_gen_op_rope_append", "rlhf_gen_op_attn_decode", "rlhf_gen_op_attn_prefill",
-    "rlhf_gen_op_sample",
+    "rlhf_gen_op_sample", "rlhf_gen_op_gemm_static",
 ]
 
 
@@ -121,6 +121,8 @@ def lib() -> C.CDLL:
         L.rlhf_gen_op_attn_prefill.argtypes = [C.c_void_p] * 4 + [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p] + [C.c_int32] * 4
         L.rlhf_gen_op_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.POINTER(Sampling), C.c_void_p,
                                          C.c_void_p, C.c_void_p, C.c_void_p]
+        L.rlhf_gen_op_gemm_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                              C.c_int32, C.POINTER(C.c_int32)]
         for name in EXPORTS:
             if name not in ("rlhf_gen_last_error", "rlhf_gen_destroy", "rlhf_gen_context_bytes", "rlhf_gen_graph_captures"):
                 getattr(L, name).restype = C.c_int
@@ -385,6 +387,13 @@ def rlhf_gen_op_tile_weights(w_rowmajor: torch.Tensor, w_tiled: torch.Tensor) ->
 
 def rlhf_gen_op_gemm(kind, A, W, out, M, N, K, epilogue=0, nsplit=1, a_pairs=0) -> int:
     return lib().rlhf_gen_op_gemm(None, kind, _ptr(A), _ptr(W), _ptr(out), M, N, K, epilogue, nsplit, a_pairs)
+
+
+def rlhf_gen_op_gemm_static(A, W, out, M, N, K, a_pairs=0):
+    """Returns (status, split count used)."""
+    ns = C.c_int32(0)
+    rc = lib().rlhf_gen_op_gemm_static(None, _ptr(A), _ptr(W), _ptr(out), M, N, K, a_pairs, C.byref(ns))
+    return rc, ns.value
 
 
 def rlhf_gen_op_rope_append(qkv, row_pos, row_seq, cos_t, sin_t, q_out, kv_pool, block_table, max_blocks, n_blocks, M,

@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librlhf_gen.so")
-SOURCES = ["k_small.hip", "k_sampler.hip", "k_attention.hip", "k_gemm.hip", "k_probe.hip", "rlhf_gen_api.hip"]
+SOURCES = ["k_small.hip", "k_sampler.hip", "k_attention.hip", "k_gemm.hip", "k_probe.hip", "rlhf_gen_api.hip", "rlhf_gen_static.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

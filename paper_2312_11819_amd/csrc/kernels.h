@@ -109,6 +109,11 @@ hipError_t launch_sampler(hipStream_t s, const float* logits, int B, int V, cons
                           const int* step_ptr, int* cur_tok);
 hipError_t launch_fill_int(hipStream_t s, int* p, int n, int value);
 
+// Message that rlhf_gen_last_error(NULL) returns (entry points that have no context to attach it to).
+void set_global_error(const char* msg);
+// Device address of the library's static workspace for the current device, resolved once per device (rlhf_gen_static.hip).
+hipError_t static_scratch_prepare();
+
 // Hardware probes (k_probe.hip).  stream_read: reads bytes / 8192 chunks of 8 KB from buf (plain or nontemporal 16-byte
 // loads), scratch >= 1 KB.  mfma_loop: `workgroups` x 4 wavefronts each issue 8 * iters v_mfma_f32_32x32x16_f16
 // (32768 flop each) on operands taken from a 16 KB buffer; scratch >= 1 KB.

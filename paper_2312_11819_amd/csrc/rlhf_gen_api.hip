@@ -29,6 +29,8 @@ constexpr size_t MAX_CACHED_GRAPHS = 16;
 
 }  // namespace
 
+void set_global_error(const char* msg) { g_init_error = msg ? msg : ""; }
+
 struct rlhf_gen_ctx {
   rlhf_gen_cfg cfg{};
   bool bf16 = false;
@@ -979,7 +981,7 @@ int rlhf_gen_init(const rlhf_gen_weights* w, const rlhf_gen_cfg* cfg, rlhf_gen_c
     }
     c->own_stream = true;
   }
-  if (gemm_configure() != hipSuccess || sampler_configure() != hipSuccess) {
+  if (gemm_configure() != hipSuccess || sampler_configure() != hipSuccess || static_scratch_prepare() != hipSuccess) {
     (void)hipGetLastError();
     c->err = "kernel attribute setup failed";
     return bail(RLHF_GEN_E_DEVICE);
