@@ -339,6 +339,25 @@ def main() -> int:
                  "first_micro_batch_ready_ms": ready[0] * 1e3, "ready_ms": [r * 1e3 for r in ready],
                  "equals_whole_batch_rollout": bool(torch.equal(mt, out_t) and torch.equal(mlp, out_lp))}
 
+    # the same micro-batches inside one decode loop (continuous batching): they are admitted `stagger` decode steps apart and
+    # complete that far apart, sharing every step's weight stream
+    cont = None
+    if args.micro_batch > 0 and not args.no_score and args.micro_batch < B:
+        cont = []
+        for stagger in (0, 32):
+            torch.cuda.synchronize()
+            ev0 = torch.cuda.Event(enable_timing=True)
+            with torch.cuda.stream(ctx.stream):
+                ev0.record()
+            t1 = time.perf_counter()
+            mt, mlp, evs = ctx.rlhf_gen_generate_continuous(toks_d, lens.tolist(), R, sp, args.micro_batch, stagger)
+            ctx.synchronize()
+            dt = time.perf_counter() - t1
+            cont.append({"micro_batch": args.micro_batch, "stagger_steps": stagger, "ms": dt * 1e3, "tokens_per_s": B * R / dt,
+                         "decode_steps": ctx.rlhf_gen_last_timing()[2], "peak_rows": ctx.rlhf_gen_last_peak_rows(),
+                         "ready_ms": [ev0.elapsed_time(e) for e in evs],
+                         "equals_whole_batch_rollout": bool(torch.equal(mt, out_t) and torch.equal(mlp, out_lp))})
+
     # weight refresh of the shadow Actor (the parameter synchronisation of Alg. 2), outside the timed region:
     # every projection matrix and the LM head is read as bf16 and rewritten as fp16
     refresh = None
@@ -389,6 +408,7 @@ def main() -> int:
         "kernels_sampled": kernels,
         "score_pass": score,
         "micro_batched": micro,
+        "micro_batched_continuous": cont,
         "prefill_gemm_shapes": gemm_shapes,
         "measured_peaks": probes,
         "weight_refresh": refresh,

@@ -177,6 +177,45 @@ int rlhf_gen_generate_stream(rlhf_gen_ctx* ctx, const int32_t* query_tokens, con
                              float* resp_logprobs, int32_t micro_batch, void* const* done_events,
                              rlhf_gen_microbatch_fn on_ready, void* user);
 
+/* Micro-batched rollout inside ONE decode loop (continuous batching).  rlhf_gen_generate_stream generates its
+ * micro-batches one after the other, so every micro-batch streams all the weights again at every step: at 16 rows per
+ * micro-batch the whole batch takes twice as long as in one piece.  Here the micro-batches share the decode steps: rows
+ * join the running batch a micro-batch at a time and leave it when they have their R tokens (exactly R per row, Sec. V-A),
+ * so a decode step carries rows at different response indices and the weights are streamed once per step for all of
+ * them.  Micro-batch i (rows i * micro_batch ...) is prefilled and admitted once stagger_steps decode steps have passed
+ * since the previous admission (0: all at the start, which is rlhf_gen_generate with per-micro-batch completion events)
+ * AND the KV pool has free pages for all of its rows to the end of their responses; until then the running rows keep
+ * decoding and admission resumes when finished rows hand their pages back.  That second condition is the paper's rule
+ * for sizing a run - the batch is what memory allows (Sec. V-A "Hyperparameters"; Sec. IV-C, raise the batch while below
+ * 95 % of memory): with cfg.kv_pool_blocks set from rlhf_gen_plan_capacity the call keeps as many rows in flight as
+ * the pool holds, whatever B is.  Micro-batch i completes stagger_steps decode steps after micro-batch i - 1 (later if
+ * it had to wait for pages), which is the spacing the consumer of done_events / on_ready sees (Sec. IV-A: the next stage
+ * works on one micro-batch while the following ones are generated).
+ * Requirements beyond rlhf_gen_generate's: B <= cfg.max_batch (every row keeps its own state row; the pool may be smaller
+ * than B rows' worth) and every single micro-batch must fit the pool (else E_NOMEM before any work).  Results: row b draws
+ * the random numbers it draws in rlhf_gen_generate, and its arithmetic does not depend on its batch mates up to 128
+ * rows in flight, so the output equals rlhf_gen_generate's bit for bit under that limit.  done_events / on_ready as in
+ * rlhf_gen_generate_stream.  rlhf_gen_last_timing reports the prefill time (sum), the rest as decode time, and the
+ * number of decode steps run; rlhf_gen_last_peak_rows the most rows that decoded together. */
+int rlhf_gen_generate_continuous(rlhf_gen_ctx* ctx, const int32_t* query_tokens, const int32_t* lengths, int32_t B,
+                                 int32_t Lmax, int32_t max_resp_len, const rlhf_gen_sampling* sampling,
+                                 int32_t* resp_tokens, float* resp_logprobs, int32_t micro_batch, int32_t stagger_steps,
+                                 void* const* done_events, rlhf_gen_microbatch_fn on_ready, void* user);
+int32_t rlhf_gen_last_peak_rows(const rlhf_gen_ctx* ctx);
+
+/* The admission schedule rlhf_gen_generate_continuous would follow, without a context or a GPU: for each of the
+ * ceil(B / micro_batch) micro-batches the decode-step count at which it is admitted and at which it completes
+ * (admit + max_resp_len - 1), and the most rows decoding together.  A pure function of its arguments: micro-batch i is
+ * admitted at the first step boundary where stagger_steps steps have passed since the previous admission and
+ * kv_pool_blocks pages minus those held by running rows cover ceil((lengths[b] + max_resp_len - 1) / 16) pages for each of
+ * its rows (pages of micro-batches completing at that boundary count as free).  With rlhf_gen_plan_capacity this answers
+ * "how many rows will be in flight, and when does each micro-batch reach the next stage" for a memory budget (Sec. IV-C).
+ *   lengths HOST int32 [B]; admit_step / done_step HOST int32 [ceil(B / micro_batch)] or NULL; peak_rows HOST or NULL.
+ * Errors: E_INVALID, E_NOMEM (a micro-batch needs more pages than the pool has). */
+int rlhf_gen_plan_admission(const int32_t* lengths, int32_t B, int32_t max_resp_len, int32_t micro_batch,
+                            int32_t stagger_steps, int32_t kv_pool_blocks, int32_t* admit_step, int32_t* done_step,
+                            int32_t* peak_rows);
+
 /* Teacher-forced scoring pass: the raw-model log-probability of every token of given responses, by one forward over
  * query ++ response per sequence - `ActorOutput <- Actor.forward(Query, Response)` of Alg. 1 (the same call scores the
  * Ref model).  logprobs_out[b, t] = log softmax(logits at position lengths[b] - 1 + t)[resp_tokens[b, t]]; for a
@@ -246,7 +285,7 @@ int64_t rlhf_gen_context_bytes(const rlhf_gen_ctx* ctx);
  * decode step; the graph depends only on the number of batch rows - the sampling rule, the seed and the output
  * buffers are read from device memory at run time - so a PPO loop that calls generate with a new seed and fresh
  * output buffers every round (Alg. 1: one Actor.generate per batch of queries) records once and replays thereafter.
- * Up to 16 graphs (batch widths) are kept. */
+ * Up to 64 graphs (batch widths; row windows of rlhf_gen_generate_continuous) are kept. */
 int64_t rlhf_gen_graph_captures(const rlhf_gen_ctx* ctx);
 
 /* Copy the fp32 logits [B, vocab] that the last prefill/decode step sampled from into a device

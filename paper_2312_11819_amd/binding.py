@@ -27,7 +27,7 @@ PROF_CLASSES = ["embed", "norm", "gemm_qkv", "rope_append", "attn_decode", "gemm
                 "gemm_down", "lm_head", "sampler"]
 
 EXPORTS = [
-    "rlhf_gen_init", "rlhf_gen_prefill", "rlhf_gen_decode_step", "rlhf_gen_generate", "rlhf_gen_generate_stream", "rlhf_gen_score", "rlhf_gen_update_weights",
+    "rlhf_gen_init", "rlhf_gen_prefill", "rlhf_gen_decode_step", "rlhf_gen_generate", "rlhf_gen_generate_stream", "rlhf_gen_generate_continuous", "rlhf_gen_last_peak_rows", "rlhf_gen_plan_admission", "rlhf_gen_score", "rlhf_gen_update_weights",
     "rlhf_gen_plan_capacity", "rlhf_gen_context_bytes", "rlhf_gen_graph_captures",
     "rlhf_gen_get_logits",
     "rlhf_gen_last_timing", "rlhf_gen_last_step_ms", "rlhf_gen_set_profile", "rlhf_gen_get_profile", "rlhf_gen_last_error", "rlhf_gen_destroy",
@@ -92,6 +92,12 @@ def lib() -> C.CDLL:
         L.rlhf_gen_generate_stream.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_int32,
                                                C.POINTER(Sampling), C.c_void_p, C.c_void_p, C.c_int32,
                                                C.POINTER(C.c_void_p), MICROBATCH_FN, C.c_void_p]
+        L.rlhf_gen_generate_continuous.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_int32,
+                                                   C.POINTER(Sampling), C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                                   C.POINTER(C.c_void_p), MICROBATCH_FN, C.c_void_p]
+        L.rlhf_gen_last_peak_rows.argtypes = [C.c_void_p]
+        L.rlhf_gen_plan_admission.argtypes = [C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                              C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.rlhf_gen_score.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_void_p,
                                      C.c_int32, C.c_void_p]
         L.rlhf_gen_update_weights.argtypes = [C.c_void_p, C.POINTER(Weights), C.POINTER(Lora)]
@@ -147,6 +153,18 @@ def rlhf_gen_plan_capacity(shape, dtype: str, max_seq: int, capacity_bytes: int,
     _check(None, lib().rlhf_gen_plan_capacity(C.byref(cfg), int(capacity_bytes), float(fraction), int(reserved_bytes),
                                               C.byref(b), C.byref(n)))
     return b.value, n.value
+
+
+def rlhf_gen_plan_admission(lengths: Sequence[int], max_resp_len: int, micro_batch: int, stagger_steps: int,
+                            kv_pool_blocks: int):
+    """(admit_step per micro-batch, done_step per micro-batch, peak rows in flight) - host only, no GPU."""
+    B = len(lengths)
+    n_mb = -(-B // max(min(micro_batch, B), 1))
+    lens = (C.c_int32 * B)(*[int(x) for x in lengths])
+    admit, done, peak = (C.c_int32 * n_mb)(), (C.c_int32 * n_mb)(), C.c_int32()
+    _check(None, lib().rlhf_gen_plan_admission(lens, B, max_resp_len, micro_batch, stagger_steps, kv_pool_blocks, admit, done,
+                                               C.byref(peak)))
+    return list(admit), list(done), peak.value
 
 
 def make_sampling(temperature=1.0, top_p=1.0, seed=0, greedy=False, logprob_mode=0) -> Sampling:
@@ -302,6 +320,45 @@ class Context:
             raise failure[0]
         self.B = min(micro_batch, B)
         return toks, lps, events
+
+    def rlhf_gen_generate_continuous(self, query_tokens: torch.Tensor, lengths: Sequence[int], max_resp_len: int,
+                                     sampling: Sampling, micro_batch: int, stagger_steps: int = 0, on_ready=None,
+                                     out_tokens: Optional[torch.Tensor] = None, out_logprobs: Optional[torch.Tensor] = None):
+        """Arguments and return value as rlhf_gen_generate_stream, plus the admission spacing in decode steps."""
+        B, Lmax = query_tokens.shape
+        lens = (C.c_int32 * B)(*[int(x) for x in lengths])
+        toks = out_tokens if out_tokens is not None else torch.empty(B, max_resp_len, dtype=torch.int32, device=self.device)
+        lps = out_logprobs if out_logprobs is not None else torch.empty(B, max_resp_len, dtype=torch.float32, device=self.device)
+        n_mb = -(-B // max(min(micro_batch, B), 1))
+        events = [torch.cuda.Event(enable_timing=True) for _ in range(n_mb)]
+        with torch.cuda.stream(self.stream):
+            for e in events:
+                e.record()          # torch creates the HIP event at its first record
+        handles = (C.c_void_p * n_mb)(*[e.cuda_event for e in events])
+        failure = []
+
+        def trampoline(_user, index, row0, rows, _ev):
+            try:
+                if on_ready is not None:
+                    on_ready(index, row0, rows, events[index])
+            except BaseException as exc:   # never unwind through the C frames
+                failure.append(exc)
+
+        cb = MICROBATCH_FN(trampoline)
+        self.stream.wait_stream(torch.cuda.current_stream(self.device))
+        try:
+            _check(self._h, lib().rlhf_gen_generate_continuous(self._h, _ptr(query_tokens), lens, B, Lmax, max_resp_len,
+                                                               C.byref(sampling), _ptr(toks), _ptr(lps), micro_batch,
+                                                               stagger_steps, handles, cb, None))
+        finally:
+            self._enqueued(query_tokens, toks, lps)
+        if failure:
+            raise failure[0]
+        self.B = 0
+        return toks, lps, events
+
+    def rlhf_gen_last_peak_rows(self) -> int:
+        return int(lib().rlhf_gen_last_peak_rows(self._h))
 
     def rlhf_gen_score(self, query_tokens: torch.Tensor, lengths: Sequence[int], resp_tokens: torch.Tensor) -> torch.Tensor:
         B, Lmax = query_tokens.shape

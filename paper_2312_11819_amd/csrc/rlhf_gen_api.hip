@@ -25,7 +25,8 @@ std::string g_init_error;
 // output buffers are read from a block in device memory (SamplerArgs) that is rewritten before the first replay of a
 // rollout, positions and response indices from per-row device arrays.  Key: (first row, number of rows).
 typedef std::pair<int, int> GraphKey;
-constexpr size_t MAX_CACHED_GRAPHS = 16;
+constexpr size_t MAX_CACHED_GRAPHS = 64;
+constexpr int SARGS_RING = 32;
 
 }  // namespace
 
@@ -53,7 +54,8 @@ struct rlhf_gen_ctx {
   // per batch row: pages, cached tokens, response index of the next token to draw, token to feed next
   int *d_table = nullptr, *d_seq_len = nullptr, *d_step = nullptr, *d_err = nullptr, *d_cur_tok = nullptr;
   SamplerArgs* d_sargs = nullptr;   // sampling rule and output buffers of the rollout in flight (read by captured graphs)
-  SamplerArgs* h_sargs = nullptr;   // pinned staging copy of it
+  SamplerArgs* h_sargs = nullptr;   // pinned staging copies of it (a ring: a copy may still be in flight when the next is written)
+  int sargs_next = 0;
   float *d_cos = nullptr, *d_sin = nullptr;
   int *d_tok_seq = nullptr, *d_tok_pos = nullptr, *d_ids = nullptr, *d_cu = nullptr, *d_seq_ids = nullptr,
       *d_last_rows = nullptr;
@@ -78,6 +80,11 @@ struct rlhf_gen_ctx {
   // host state
   std::vector<int> h_len, n_alloc, free_list;
   int B = 0;
+  // The per-row device state (block-table rows, lengths, response indices, next tokens) of the rows the kernels are
+  // working on starts at row win_lo of those arrays: 0 everywhere except in rlhf_gen_generate_continuous, where rows
+  // [win_lo, win_lo + B) of the whole batch are the ones currently decoding.  Activations and logits are always
+  // indexed from 0; host-side row state (h_len, n_alloc, h_table) is indexed by batch row like the device arrays.
+  int win_lo = 0;
   bool have_batch = false, have_logits = false;
   int h_step = 0;
   int reserve_extra = 0;  // tokens beyond the query that prefill must reserve pages for
@@ -108,6 +115,7 @@ struct rlhf_gen_ctx {
   std::vector<float> step_ms;
   float prefill_ms = 0.f, decode_ms = 0.f;
   int decode_steps = 0;
+  int peak_rows = 0;   // most rows decoding together in the last rlhf_gen_generate_continuous
 };
 
 namespace {
@@ -162,6 +170,12 @@ int host_alloc(rlhf_gen_ctx* c, T** p, size_t bytes) {
 }
 
 size_t act_size(const rlhf_gen_ctx* c) { return c->bf16 ? 2 : 4; }
+
+// per-row device state of the current window (see rlhf_gen_ctx::win_lo)
+int* w_seq_len(const rlhf_gen_ctx* c) { return c->d_seq_len + c->win_lo; }
+int* w_step(const rlhf_gen_ctx* c) { return c->d_step + c->win_lo; }
+int* w_cur_tok(const rlhf_gen_ctx* c) { return c->d_cur_tok + c->win_lo; }
+int* w_table(const rlhf_gen_ctx* c) { return c->d_table + (size_t)c->win_lo * c->max_blocks; }
 
 void reset_free_list(rlhf_gen_ctx* c) {
   c->free_list.resize(c->n_blocks);
@@ -248,15 +262,15 @@ int forward_layers_generic(rlhf_gen_ctx* c, const RowSet& r) {
     int rc = gemm_any(c, c->y, c->wqkv[l], c->qkv, r.M, qkv_w, d, EPI_STORE_F32, c->bf16);
     if (rc) return rc;
     LAUNCH(c, launch_rope_append(s, c->qkv, nullptr, 0, 0, r.row_pos, r.row_seq, c->d_cos, c->d_sin, c->qb, pool,
-                                 c->d_table, c->max_blocks, c->n_blocks, r.M, Hq, Hkv, h, c->bf16), "rope_append");
+                                 w_table(c), c->max_blocks, c->n_blocks, r.M, Hq, Hkv, h, c->bf16), "rope_append");
     if (!c->bf16) {
-      LAUNCH(c, launch_attn_f32(s, (const float*)c->qb, (const float*)pool, c->d_table, c->max_blocks, c->n_blocks, r.row_pos,
+      LAUNCH(c, launch_attn_f32(s, (const float*)c->qb, (const float*)pool, w_table(c), c->max_blocks, c->n_blocks, r.row_pos,
                                 r.row_seq, (float*)c->ab, r.M, Hq, Hkv, h), "attn_f32");
     } else if (r.prefill) {
-      LAUNCH(c, launch_attn_prefill_h16(s, c->qb, pool, c->d_table, c->max_blocks, c->n_blocks, r.cu, r.seq_ids, c->ab, r.nseq,
+      LAUNCH(c, launch_attn_prefill_h16(s, c->qb, pool, w_table(c), c->max_blocks, c->n_blocks, r.cu, r.seq_ids, c->ab, r.nseq,
                                          r.max_len, Hq, Hkv), "attn_prefill");
     } else {
-      LAUNCH(c, launch_attn_decode_h16(s, c->qb, pool, c->d_table, c->max_blocks, c->n_blocks, c->d_seq_len, c->ab, r.M, Hq, Hkv),
+      LAUNCH(c, launch_attn_decode_h16(s, c->qb, pool, w_table(c), c->max_blocks, c->n_blocks, w_seq_len(c), c->ab, r.M, Hq, Hkv),
              "attn_decode");
     }
     rc = gemm_any(c, c->ab, c->wo[l], c->x, r.M, d, Hq * h, EPI_RESID_F32, c->bf16);
@@ -306,7 +320,7 @@ int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
   const int ks_qkv = tiles ? c->kt_qkv : c->ks_qkv, ks_wo = tiles ? c->kt_wo : c->ks_wo;
   const int ks_down = tiles ? c->kt_down : c->ks_down;
   prof_mark(c, -1);
-  LAUNCH(c, launch_embed(s, c->d_cur_tok, c->tok_emb, 1, c->x, B, d, g.vocab, c->d_err), "embed");
+  LAUNCH(c, launch_embed(s, w_cur_tok(c), c->tok_emb, 1, c->x, B, d, g.vocab, c->d_err), "embed");
   prof_mark(c, RLHF_GEN_PROF_EMBED);
   int pending = 0;  // split count of the down-projection partial sums not yet added to x
   for (int l = 0; l < g.n_layers; ++l) {
@@ -322,15 +336,15 @@ int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
     prof_mark(c, RLHF_GEN_PROF_GEMM_QKV);
     size_t st = (size_t)B * qkv_w;
     if (!(c->cfg.flags & RLHF_GEN_FLAG_FUSED_ROPE)) {
-      LAUNCH(c, launch_rope_append(s, c->part, ks_qkv > 1 ? c->part + st : nullptr, ks_qkv - 1, st, c->d_seq_len,
-                                   nullptr, c->d_cos, c->d_sin, c->qb, pool, c->d_table, c->max_blocks, c->n_blocks, B, Hq,
+      LAUNCH(c, launch_rope_append(s, c->part, ks_qkv > 1 ? c->part + st : nullptr, ks_qkv - 1, st, w_seq_len(c),
+                                   nullptr, c->d_cos, c->d_sin, c->qb, pool, w_table(c), c->max_blocks, c->n_blocks, B, Hq,
                                    Hkv, h, 1), "rope_append");
       prof_mark(c, RLHF_GEN_PROF_ROPE);
-      LAUNCH(c, launch_attn_decode_h16(s, c->qb, pool, c->d_table, c->max_blocks, c->n_blocks, c->d_seq_len, c->ab, B, Hq,
+      LAUNCH(c, launch_attn_decode_h16(s, c->qb, pool, w_table(c), c->max_blocks, c->n_blocks, w_seq_len(c), c->ab, B, Hq,
                                        Hkv), "attn_decode");
     } else {
-      LAUNCH(c, launch_attn_decode_fused_h16(s, c->part, ks_qkv, st, c->d_cos, c->d_sin, pool, c->d_table, c->max_blocks,
-                                             c->n_blocks, c->d_seq_len, c->ab, B, Hq, Hkv), "attn_decode_fused");
+      LAUNCH(c, launch_attn_decode_fused_h16(s, c->part, ks_qkv, st, c->d_cos, c->d_sin, pool, w_table(c), c->max_blocks,
+                                             c->n_blocks, w_seq_len(c), c->ab, B, Hq, Hkv), "attn_decode_fused");
     }
     prof_mark(c, RLHF_GEN_PROF_ATTN);
     if (tiles) {
@@ -389,8 +403,8 @@ int enqueue_decode_body(rlhf_gen_ctx* c, int* tok_out, float* lp_out, int stride
   } else {
     RowSet r;
     r.M = B;
-    r.ids = c->d_cur_tok;
-    r.row_pos = c->d_seq_len;
+    r.ids = w_cur_tok(c);
+    r.row_pos = w_seq_len(c);
     rc = forward_layers_generic(c, r);
     if (rc) return rc;
     LAUNCH(c, launch_rmsnorm(c->stream, c->x, nullptr, 0, 0, c->final_norm, c->bf16, c->yl, c->bf16, B, g.d_model,
@@ -400,9 +414,9 @@ int enqueue_decode_body(rlhf_gen_ctx* c, int* tok_out, float* lp_out, int stride
   }
   SamplerArgs a = c->sp;
   a.out_stride = stride; a.use_step_col = use_col; a.step_stride = 1; a.tok_out = tok_out; a.lp_out = lp_out;
-  LAUNCH(c, launch_sampler(c->stream, c->logits, B, g.vocab, a, from_dev ? c->d_sargs : nullptr, c->d_step, c->d_cur_tok),
+  LAUNCH(c, launch_sampler(c->stream, c->logits, B, g.vocab, a, from_dev ? c->d_sargs : nullptr, w_step(c), w_cur_tok(c)),
          "sampler");
-  LAUNCH(c, launch_advance(c->stream, c->d_seq_len, c->d_step, B), "advance");
+  LAUNCH(c, launch_advance(c->stream, w_seq_len(c), w_step(c), B), "advance");
   prof_mark(c, RLHF_GEN_PROF_SAMPLER);
   return RLHF_GEN_OK;
 }
@@ -419,13 +433,18 @@ int check_sampling(rlhf_gen_ctx* c, const rlhf_gen_sampling* sp) {
   return RLHF_GEN_OK;
 }
 
+// Prefill of B queries into batch rows [c->win_lo, c->win_lo + B): query_tokens / lengths / the outputs point at the first
+// of these rows.  fresh: the context holds nothing else (every page is free again); otherwise rows outside the range
+// keep their cache pages and state, and the new rows take pages from what is left.
 int prefill_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* lengths, int32_t B, int32_t Lmax,
-                 const rlhf_gen_sampling* sampling, int32_t* tok_out, float* lp_out, int out_stride) {
+                 const rlhf_gen_sampling* sampling, int32_t* tok_out, float* lp_out, int out_stride, bool fresh = true) {
   const rlhf_gen_cfg& g = c->cfg;
+  const int lo = c->win_lo;
   if (!query_tokens || !lengths || !tok_out || !lp_out) return fail(c, RLHF_GEN_E_INVALID, "NULL pointer argument");
   int rc = check_sampling(c, sampling);
   if (rc) return rc;
-  if (B < 1 || B > g.max_batch) return fail(c, RLHF_GEN_E_INVALID, "B = %d outside [1, max_batch = %d]", B, g.max_batch);
+  if (B < 1 || lo + B > g.max_batch)
+    return fail(c, RLHF_GEN_E_INVALID, "B = %d outside [1, max_batch = %d]", lo + B, g.max_batch);
   if (Lmax < 1) return fail(c, RLHF_GEN_E_INVALID, "Lmax = %d must be positive", Lmax);
   long need_blocks = 0;
   for (int b = 0; b < B; ++b) {
@@ -436,8 +455,9 @@ int prefill_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* le
                   c->reserve_extra, g.max_seq);
     need_blocks += blocks_for(lengths[b] + c->reserve_extra);
   }
-  if (need_blocks > c->n_blocks)
-    return fail(c, RLHF_GEN_E_NOMEM, "KV pool has %d pages, the batch needs %ld", c->n_blocks, need_blocks);
+  if (need_blocks > (fresh ? (long)c->n_blocks : (long)c->free_list.size()))
+    return fail(c, RLHF_GEN_E_NOMEM, "KV pool has %ld free pages, the batch needs %ld",
+                fresh ? (long)c->n_blocks : (long)c->free_list.size(), need_blocks);
 
   HIP_TRY(c, hipSetDevice(g.device));
   HIP_TRY(c, hipStreamSynchronize(c->stream));  // staging buffers are free again
@@ -449,12 +469,12 @@ int prefill_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* le
   c->sp.seed = sampling->seed;
   c->sp.greedy = sampling->greedy;
   c->sp.logprob_mode = sampling->logprob_mode;
-  c->sp.row0 = c->row_offset;
-  reset_free_list(c);
+  c->sp.row0 = c->row_offset + lo;
+  if (fresh) reset_free_list(c);
   int T = 0;
   for (int b = 0; b < B; ++b) {
-    c->h_len[b] = lengths[b];
-    grow_seq(c, b, lengths[b] + c->reserve_extra);
+    c->h_len[lo + b] = lengths[b];
+    grow_seq(c, lo + b, lengths[b] + c->reserve_extra);
     for (int p = 0; p < lengths[b]; ++p) {
       c->h_tok_seq[T] = b;
       c->h_tok_pos[T] = p;
@@ -464,18 +484,18 @@ int prefill_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* le
     c->h_seq_ids[b] = b;
   }
   hipStream_t s = c->stream;
-  HIP_TRY(c, hipMemcpyAsync(c->d_table, c->h_table, sizeof(int) * (size_t)g.max_batch * c->max_blocks,
+  HIP_TRY(c, hipMemcpyAsync(w_table(c), c->h_table + (size_t)lo * c->max_blocks, sizeof(int) * (size_t)B * c->max_blocks,
                             hipMemcpyHostToDevice, s));
   HIP_TRY(c, hipMemcpyAsync(c->d_tok_seq, c->h_tok_seq, sizeof(int) * T, hipMemcpyHostToDevice, s));
   HIP_TRY(c, hipMemcpyAsync(c->d_tok_pos, c->h_tok_pos, sizeof(int) * T, hipMemcpyHostToDevice, s));
-  HIP_TRY(c, hipMemcpyAsync(c->d_seq_len, c->h_lenbuf, sizeof(int) * B, hipMemcpyHostToDevice, s));
+  HIP_TRY(c, hipMemcpyAsync(w_seq_len(c), c->h_lenbuf, sizeof(int) * B, hipMemcpyHostToDevice, s));
   HIP_TRY(c, hipMemcpyAsync(c->d_seq_ids, c->h_seq_ids, sizeof(int) * B, hipMemcpyHostToDevice, s));
   c->h_misc[0] = 0;
   c->h_misc[1] = 1;
-  HIP_TRY(c, hipMemcpyAsync(c->d_err, &c->h_misc[0], sizeof(int), hipMemcpyHostToDevice, s));
+  if (fresh) HIP_TRY(c, hipMemcpyAsync(c->d_err, &c->h_misc[0], sizeof(int), hipMemcpyHostToDevice, s));
   c->step_err_pending = false;   // (the stream was synchronised above: no copy of the flag is in flight)
   *c->h_step_err = 0;
-  LAUNCH(c, launch_fill_int(s, c->d_step, B, 0), "fill");
+  LAUNCH(c, launch_fill_int(s, w_step(c), B, 0), "fill");
   LAUNCH(c, launch_pack_tokens(s, query_tokens, Lmax, c->d_tok_seq, c->d_tok_pos, T, g.vocab, c->d_ids, c->d_err),
          "pack_tokens");
   HIP_TRY(c, hipMemcpyAsync(&c->h_misc[2], c->d_err, sizeof(int), hipMemcpyDeviceToHost, s));
@@ -542,9 +562,9 @@ int prefill_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* le
   {
     SamplerArgs a = c->sp;
     a.out_stride = out_stride; a.use_step_col = 1; a.step_stride = 1; a.tok_out = tok_out; a.lp_out = lp_out;
-    LAUNCH(c, launch_sampler(s, c->logits, B, g.vocab, a, nullptr, c->d_step, c->d_cur_tok), "sampler");
+    LAUNCH(c, launch_sampler(s, c->logits, B, g.vocab, a, nullptr, w_step(c), w_cur_tok(c)), "sampler");
   }
-  LAUNCH(c, launch_fill_int(s, c->d_step, B, 1), "fill");
+  LAUNCH(c, launch_fill_int(s, w_step(c), B, 1), "fill");
   c->h_step = 1;
   c->have_batch = true;
   c->have_logits = true;
@@ -575,6 +595,7 @@ int score_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* leng
   c->have_batch = false;
   c->have_logits = false;
   c->B = B;
+  c->win_lo = 0;
   reset_free_list(c);
   int T = 0;
   for (int b = 0; b < B; ++b) {
@@ -676,7 +697,7 @@ int score_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* leng
 int decode_checks(rlhf_gen_ctx* c) {
   if (!c->have_batch) return fail(c, RLHF_GEN_E_STATE, "decode_step before a successful prefill");
   long need = 0;
-  for (int b = 0; b < c->B; ++b) {
+  for (int b = c->win_lo; b < c->win_lo + c->B; ++b) {
     if (c->h_len[b] + 1 > c->cfg.max_seq)
       return fail(c, RLHF_GEN_E_STATE, "sequence %d already holds %d tokens (max_seq = %d)", b, c->h_len[b], c->cfg.max_seq);
     if (c->n_alloc[b] * 16 < c->h_len[b] + 1) need++;
@@ -685,7 +706,7 @@ int decode_checks(rlhf_gen_ctx* c) {
     return fail(c, RLHF_GEN_E_NOMEM, "KV pool exhausted: %ld more pages needed, %zu free", need, c->free_list.size());
   if (need) {
     HIP_TRY(c, hipStreamSynchronize(c->stream));  // the pinned table may still be in flight
-    for (int b = 0; b < c->B; ++b) grow_seq(c, b, c->h_len[b] + 1);
+    for (int b = c->win_lo; b < c->win_lo + c->B; ++b) grow_seq(c, b, c->h_len[b] + 1);
     HIP_TRY(c, hipMemcpyAsync(c->d_table, c->h_table, sizeof(int) * (size_t)c->cfg.max_batch * c->max_blocks,
                               hipMemcpyHostToDevice, c->stream));
   }
@@ -693,7 +714,7 @@ int decode_checks(rlhf_gen_ctx* c) {
 }
 
 void after_step(rlhf_gen_ctx* c) {
-  for (int b = 0; b < c->B; ++b) c->h_len[b]++;
+  for (int b = c->win_lo; b < c->win_lo + c->B; ++b) c->h_len[b]++;
   c->h_step++;
 }
 
@@ -702,10 +723,10 @@ void drop_graph(rlhf_gen_ctx* c) {
   c->graphs.clear();
 }
 
-// The decode step for batch rows [0, B) as an executable graph: recorded once, then reused by every rollout of that
+// The decode step for batch rows [c->win_lo, c->win_lo + B) as an executable graph: recorded once, then reused by every rollout of that
 // width (nothing a rollout changes - seed, temperature, top-p, output buffers - is baked into it).
 int decode_graph(rlhf_gen_ctx* c, int B, hipGraphExec_t* out) {
-  const GraphKey key(0, B);
+  const GraphKey key(c->win_lo, B);
   auto it = c->graphs.find(key);
   if (it != c->graphs.end()) {
     *out = it->second;
@@ -728,6 +749,23 @@ int decode_graph(rlhf_gen_ctx* c, int B, hipGraphExec_t* out) {
   c->graphs[key] = exec;
   c->graph_captures++;
   *out = exec;
+  return RLHF_GEN_OK;
+}
+
+// Sampling rule, random-stream row and output rows of the decode window [c->win_lo, c->win_lo + c->B) into the device
+// block that the (captured) sampler reads.  tok_base / lp_base: row 0 of the whole batch's [rows, R] outputs.
+int push_sampler_args(rlhf_gen_ctx* c, int R, int32_t* tok_base, float* lp_base) {
+  if (c->sargs_next == SARGS_RING) {   // every staging slot has been handed to a copy: let them all finish
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->sargs_next = 0;
+  }
+  SamplerArgs* h = c->h_sargs + c->sargs_next++;
+  *h = c->sp;
+  h->row0 = c->row_offset + c->win_lo;
+  h->out_stride = R; h->use_step_col = 1; h->step_stride = 1;
+  h->tok_out = tok_base + (size_t)c->win_lo * R;
+  h->lp_out = lp_base + (size_t)c->win_lo * R;
+  HIP_TRY(c, hipMemcpyAsync(c->d_sargs, h, sizeof(SamplerArgs), hipMemcpyHostToDevice, c->stream));
   return RLHF_GEN_OK;
 }
 
@@ -918,7 +956,7 @@ static int allocate_all(rlhf_gen_ctx* c) {
   A_(host_alloc(c, &c->h_lenbuf, sizeof(int) * g.max_batch));
   A_(host_alloc(c, &c->h_misc, sizeof(int) * 8));
   A_(host_alloc(c, &c->h_step_err, sizeof(int)));
-  A_(host_alloc(c, &c->h_sargs, sizeof(SamplerArgs)));
+  A_(host_alloc(c, &c->h_sargs, sizeof(SamplerArgs) * SARGS_RING));
   A_(host_alloc(c, &c->h_srows, sizeof(int) * total_tok));
   A_(host_alloc(c, &c->h_sslot, sizeof(int) * total_tok));
 #undef A_
@@ -1028,6 +1066,7 @@ int rlhf_gen_prefill(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t
                      const rlhf_gen_sampling* sampling, int32_t* tok_out, float* logprob_out) {
   if (!c) return RLHF_GEN_E_INVALID;
   c->reserve_extra = 0;
+  c->win_lo = 0;
   return prefill_impl(c, query_tokens, lengths, B, Lmax, sampling, tok_out, logprob_out, 1);
 }
 
@@ -1058,20 +1097,19 @@ static int generate_impl(rlhf_gen_ctx* c, const int32_t* query_tokens, const int
                          int32_t R, const rlhf_gen_sampling* sampling, int32_t* resp_tokens, float* resp_logprobs) {
   if (R < 1) return fail(c, RLHF_GEN_E_INVALID, "max_resp_len = %d must be positive", R);
   HIP_TRY(c, hipSetDevice(c->cfg.device));
+  c->win_lo = 0;
   c->reserve_extra = R - 1;
   hipStream_t s = c->stream;
   HIP_TRY(c, hipStreamSynchronize(s));
+  c->sargs_next = 0;
   HIP_TRY(c, hipEventRecord(c->ev[0], s));
   int rc = prefill_impl(c, query_tokens, lengths, B, Lmax, sampling, resp_tokens, resp_logprobs, R);
   c->reserve_extra = 0;
   if (rc) return rc;
   HIP_TRY(c, hipEventRecord(c->ev[1], s));
-  // the decode steps read the sampling rule and the output buffers from device memory (prefill_impl has
-  // synchronised the stream since the staging copy was last read, so it may be rewritten)
-  *c->h_sargs = c->sp;
-  c->h_sargs->out_stride = R; c->h_sargs->use_step_col = 1; c->h_sargs->step_stride = 1;
-  c->h_sargs->tok_out = resp_tokens; c->h_sargs->lp_out = resp_logprobs;
-  HIP_TRY(c, hipMemcpyAsync(c->d_sargs, c->h_sargs, sizeof(SamplerArgs), hipMemcpyHostToDevice, s));
+  // the decode steps read the sampling rule and the output buffers from device memory
+  rc = push_sampler_args(c, R, resp_tokens, resp_logprobs);
+  if (rc) return rc;
   const bool use_graph = !(c->cfg.flags & RLHF_GEN_FLAG_NO_GRAPH) && R > 2;
   hipGraphExec_t graph_exec = nullptr;
   if (use_graph) {
@@ -1161,6 +1199,182 @@ int rlhf_gen_generate_stream(rlhf_gen_ctx* c, const int32_t* query_tokens, const
   return RLHF_GEN_OK;
 }
 
+// When each micro-batch joins and leaves the running batch: a pure function of the lengths, the response length, the
+// micro-batch size, the stagger and the number of KV pages, in units of decode steps.  Micro-batch i is admitted at the
+// first step boundary at which (a) stagger steps have passed since the previous admission and (b) the pool has free
+// pages for all of its rows to the end of their responses (pages of micro-batches that complete at that boundary count
+// as free); it completes R - 1 decode steps later.  Shared by rlhf_gen_plan_admission and the rollout that executes it.
+static int plan_admission(rlhf_gen_ctx* c, const int32_t* lengths, int B, int R, int micro_batch, int stagger, long pool_blocks,
+                          std::vector<long>& admit, std::vector<long>& done, std::vector<long>& pages, int* peak_rows) {
+  const int n_mb = (B + micro_batch - 1) / micro_batch;
+  admit.assign(n_mb, 0); done.assign(n_mb, 0); pages.assign(n_mb, 0);
+  for (int b = 0; b < B; ++b) {
+    if (lengths[b] < 1) return fail(c, RLHF_GEN_E_INVALID, "lengths[%d] = %d must be positive", b, lengths[b]);
+    pages[b / micro_batch] += blocks_for(lengths[b] + R - 1);
+  }
+  for (int i = 0; i < n_mb; ++i)
+    if (pages[i] > pool_blocks)   // it could never be admitted
+      return fail(c, RLHF_GEN_E_NOMEM, "KV pool has %ld pages, micro-batch %d alone needs %ld", pool_blocks, i, pages[i]);
+  long free_pages = pool_blocks, step = 0, last_admit = 0;
+  int front = 0, next = 0, peak = 0;
+  while (front < n_mb) {
+    for (bool moved = true; moved;) {
+      moved = false;
+      while (front < next && done[front] <= step) { free_pages += pages[front++]; moved = true; }
+      while (next < n_mb && (next == 0 || step - last_admit >= stagger) && pages[next] <= free_pages) {
+        admit[next] = step; done[next] = step + (R - 1); free_pages -= pages[next]; last_admit = step; ++next; moved = true;
+      }
+    }
+    if (front == n_mb) break;
+    const int rows = std::min(B, next * micro_batch) - front * micro_batch;
+    peak = std::max(peak, rows);
+    // the next boundary at which something changes: the front micro-batch completes, or the stagger lets the next one
+    // in (with nothing running the pool is empty, so only the stagger holds the next one back)
+    long next_event = front < next ? done[front] : last_admit + stagger;
+    if (front < next && next < n_mb && pages[next] <= free_pages) next_event = std::min(next_event, last_admit + stagger);
+    step = std::max(step + 1, next_event);
+  }
+  if (peak_rows) *peak_rows = peak;
+  return RLHF_GEN_OK;
+}
+
+int rlhf_gen_plan_admission(const int32_t* lengths, int32_t B, int32_t max_resp_len, int32_t micro_batch, int32_t stagger_steps,
+                            int32_t kv_pool_blocks, int32_t* admit_step, int32_t* done_step, int32_t* peak_rows) {
+  if (!lengths || B < 1 || max_resp_len < 1 || micro_batch < 1 || stagger_steps < 0 || kv_pool_blocks < 1)
+    return fail(nullptr, RLHF_GEN_E_INVALID, "rlhf_gen_plan_admission: NULL lengths or a size out of range");
+  micro_batch = std::min(micro_batch, B);
+  std::vector<long> admit, done, pages;
+  int peak = 0;
+  int rc = plan_admission(nullptr, lengths, B, max_resp_len, micro_batch, stagger_steps, kv_pool_blocks, admit, done, pages, &peak);
+  if (rc) return rc;
+  for (size_t i = 0; i < admit.size(); ++i) {
+    if (admit_step) admit_step[i] = (int32_t)admit[i];
+    if (done_step) done_step[i] = (int32_t)done[i];
+  }
+  if (peak_rows) *peak_rows = peak;
+  return RLHF_GEN_OK;
+}
+
+int rlhf_gen_generate_continuous(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* lengths, int32_t B, int32_t Lmax,
+                                 int32_t R, const rlhf_gen_sampling* sampling, int32_t* resp_tokens, float* resp_logprobs,
+                                 int32_t micro_batch, int32_t stagger_steps, void* const* done_events,
+                                 rlhf_gen_microbatch_fn on_ready, void* user) {
+  if (!c) return RLHF_GEN_E_INVALID;
+  const rlhf_gen_cfg& g = c->cfg;
+  if (!query_tokens || !lengths || !resp_tokens || !resp_logprobs) return fail(c, RLHF_GEN_E_INVALID, "NULL argument");
+  if (B < 1 || Lmax < 1 || R < 1) return fail(c, RLHF_GEN_E_INVALID, "B = %d, Lmax = %d and max_resp_len = %d must be positive", B, Lmax, R);
+  if (B > g.max_batch)
+    return fail(c, RLHF_GEN_E_INVALID, "B = %d exceeds max_batch = %d (every row of the batch keeps its own state row)", B, g.max_batch);
+  if (micro_batch < 1 || stagger_steps < 0)
+    return fail(c, RLHF_GEN_E_INVALID, "micro_batch = %d must be positive and stagger_steps = %d non-negative", micro_batch, stagger_steps);
+  micro_batch = std::min(micro_batch, B);
+  int rc = check_sampling(c, sampling);
+  if (rc) return rc;
+  for (int b = 0; b < B; ++b) {
+    if (lengths[b] < 1 || lengths[b] > Lmax)
+      return fail(c, RLHF_GEN_E_INVALID, "lengths[%d] = %d outside [1, Lmax = %d]", b, lengths[b], Lmax);
+    if (lengths[b] + R - 1 > g.max_seq)
+      return fail(c, RLHF_GEN_E_INVALID, "sequence %d: %d query + %d further tokens exceed max_seq = %d", b, lengths[b], R - 1, g.max_seq);
+  }
+  const int n_mb = (B + micro_batch - 1) / micro_batch;
+  std::vector<long> admit, done, pages;
+  int peak_rows = 0;
+  rc = plan_admission(c, lengths, B, R, micro_batch, stagger_steps, c->n_blocks, admit, done, pages, &peak_rows);
+  if (rc) return rc;
+  HIP_TRY(c, hipSetDevice(g.device));
+  hipStream_t s = c->stream;
+  HIP_TRY(c, hipStreamSynchronize(s));
+  c->sargs_next = 0;
+  c->row_offset = 0;
+  c->have_batch = c->have_logits = false;
+  reset_free_list(c);
+  c->h_misc[0] = 0;
+  HIP_TRY(c, hipMemcpyAsync(c->d_err, &c->h_misc[0], sizeof(int), hipMemcpyHostToDevice, s));
+  HIP_TRY(c, hipEventRecord(c->ev[0], s));
+  const bool use_graph = !(g.flags & RLHF_GEN_FLAG_NO_GRAPH);
+  float prefill_ms = 0.f;
+  int front = 0, next = 0;   // micro-batches [front, next) are decoding
+  long step = 0;             // decode steps enqueued so far
+  auto row_of = [&](int mb) { return std::min(B, mb * micro_batch); };
+  auto bail = [&](int code) { c->win_lo = 0; c->B = 0; c->have_batch = false; return code; };
+  while (front < n_mb) {
+    for (bool moved = true; moved;) {
+      moved = false;
+      while (front < next && done[front] <= step) {   // micro-batches at the front of the window that have all R tokens
+        for (int b = row_of(front); b < row_of(front + 1); ++b) {   // their pages go back to the pool
+          for (int k = 0; k < c->n_alloc[b]; ++k) c->free_list.push_back(c->h_table[(size_t)b * c->max_blocks + k]);
+          c->n_alloc[b] = 0;
+        }
+        void* ev = done_events ? done_events[front] : nullptr;
+        if (ev && hipEventRecord((hipEvent_t)ev, s) != hipSuccess) return bail(fail(c, RLHF_GEN_E_DEVICE, "hipEventRecord failed"));
+        if (on_ready) on_ready(user, front, row_of(front), row_of(front + 1) - row_of(front), ev);
+        ++front;
+        moved = true;
+      }
+      while (next < n_mb && admit[next] <= step) {    // admissions due at this step boundary
+        if (pages[next] > (long)c->free_list.size()) return bail(fail(c, RLHF_GEN_E_STATE, "admission plan and page pool disagree"));
+        const int r0 = row_of(next), rows = row_of(next + 1) - r0;
+        c->win_lo = r0;
+        c->reserve_extra = R - 1;
+        if (hipEventRecord(c->ev[1], s) != hipSuccess) return bail(fail(c, RLHF_GEN_E_DEVICE, "hipEventRecord failed"));
+        rc = prefill_impl(c, query_tokens + (size_t)r0 * Lmax, lengths + r0, rows, Lmax, sampling, resp_tokens + (size_t)r0 * R,
+                          resp_logprobs + (size_t)r0 * R, R, /*fresh=*/false);
+        c->reserve_extra = 0;
+        if (rc) return bail(rc);
+        // (the next prefill synchronises the stream anyway; waiting here makes this one's time readable)
+        float ms = 0.f;
+        if (hipEventRecord(c->ev[2], s) != hipSuccess || hipEventSynchronize(c->ev[2]) != hipSuccess ||
+            hipEventElapsedTime(&ms, c->ev[1], c->ev[2]) != hipSuccess)
+          return bail(fail(c, RLHF_GEN_E_DEVICE, "timing the prefill of micro-batch %d failed", next));
+        prefill_ms += ms;
+        c->sargs_next = 0;
+        ++next;
+        moved = true;
+      }
+    }
+    if (front == n_mb) break;
+    // decode rows [front, next) up to the next boundary at which the plan changes the window
+    if (front == next) {   // nothing is decoding and the stagger holds the next micro-batch back: skip to its admission
+      step = admit[next];
+      continue;
+    }
+    const long until = next < n_mb ? std::min(done[front], admit[next]) : done[front];
+    const long run = until - step;
+    if (run < 1) return bail(fail(c, RLHF_GEN_E_STATE, "admission plan stalled at step %ld", step));
+    c->win_lo = row_of(front);
+    c->B = row_of(next) - row_of(front);
+    rc = push_sampler_args(c, R, resp_tokens, resp_logprobs);
+    if (rc) return bail(rc);
+    hipGraphExec_t graph_exec = nullptr;
+    if (use_graph && run > 1 && (rc = decode_graph(c, c->B, &graph_exec))) return bail(rc);
+    for (long k = 0; k < run; ++k) {
+      if (graph_exec) {
+        const hipError_t e = hipGraphLaunch(graph_exec, s);
+        if (e != hipSuccess) return bail(fail(c, RLHF_GEN_E_DEVICE, "hipGraphLaunch failed: %s", hipGetErrorString(e)));
+      } else if ((rc = enqueue_decode_body(c, nullptr, nullptr, 0, 0, true))) {
+        return bail(rc);
+      }
+      after_step(c);
+    }
+    step = until;
+  }
+  c->win_lo = 0;
+  c->B = 0;
+  c->have_batch = c->have_logits = false;   // every row has its R tokens: there is nothing left to step
+  HIP_TRY(c, hipEventRecord(c->ev[2], s));
+  HIP_TRY(c, hipMemcpyAsync(&c->h_misc[2], c->d_err, sizeof(int), hipMemcpyDeviceToHost, s));
+  HIP_TRY(c, hipStreamSynchronize(s));
+  float total = 0.f;
+  HIP_TRY(c, hipEventElapsedTime(&total, c->ev[0], c->ev[2]));
+  c->prefill_ms = prefill_ms;
+  c->decode_ms = total - prefill_ms;
+  c->decode_steps = (int)step;
+  c->step_ms.clear();
+  c->peak_rows = peak_rows;
+  if (c->h_misc[2]) return fail(c, RLHF_GEN_E_INVALID, "a token id outside [0, vocab) reached the embedding");
+  return RLHF_GEN_OK;
+}
+
 int rlhf_gen_score(rlhf_gen_ctx* c, const int32_t* query_tokens, const int32_t* lengths, int32_t B, int32_t Lmax,
                    const int32_t* resp_tokens, int32_t R, float* logprobs_out) {
   if (!c) return RLHF_GEN_E_INVALID;
@@ -1230,6 +1444,8 @@ const char* rlhf_gen_last_error(const rlhf_gen_ctx* c) { return c ? c->err.c_str
 int64_t rlhf_gen_context_bytes(const rlhf_gen_ctx* c) { return c ? (int64_t)c->dev_bytes : 0; }
 
 int64_t rlhf_gen_graph_captures(const rlhf_gen_ctx* c) { return c ? (int64_t)c->graph_captures : 0; }
+
+int32_t rlhf_gen_last_peak_rows(const rlhf_gen_ctx* c) { return c ? c->peak_rows : 0; }
 
 int rlhf_gen_plan_capacity(const rlhf_gen_cfg* cfg, int64_t capacity_bytes, double fraction, int64_t reserved_bytes,
                            int32_t* max_batch_out, int64_t* context_bytes_out) {

@@ -67,3 +67,77 @@ def test_nothing_fits_and_errors():
         _plan(bad, "bf16", 64, GiB)
     assert e.value.status == B.E_UNSUPPORTED
     assert _plan(synth.TINY, "fp32", 32, GiB)[0] > 1000
+
+
+# ---- admission schedule of the continuous-batching rollout (host only) ---------------------------------------------
+def _brute_force_schedule(lengths, R, mb, stagger, pool):
+    """One decode step at a time: retire what is complete, then admit while the stagger and the free pages allow it."""
+    B = len(lengths)
+    n = -(-B // mb)
+    pages = [sum(-(-(lengths[b] + R - 1) // 16) for b in range(i * mb, min(B, (i + 1) * mb))) for i in range(n)]
+    admit, done = [None] * n, [None] * n
+    free, step, last, front, nxt, peak = pool, 0, 0, 0, 0, 0
+    while front < n:
+        moved = True
+        while moved:
+            moved = False
+            while front < nxt and done[front] <= step:
+                free += pages[front]; front += 1; moved = True
+            while nxt < n and (nxt == 0 or step - last >= stagger) and pages[nxt] <= free:
+                admit[nxt], done[nxt] = step, step + R - 1
+                free -= pages[nxt]; last = step; nxt += 1; moved = True
+        assert 0 <= free <= pool
+        if front < n:
+            peak = max(peak, min(B, nxt * mb) - front * mb)
+        step += 1
+        assert step < 10 ** 6
+    return admit, done, peak
+
+
+def test_admission_plan_closed_forms():
+    from paper_2312_11819_amd import binding as B
+    lens = [100] * 64                                   # 100 + 50 - 1 = 149 tokens -> 10 pages per row, 160 per micro-batch of 16
+    R = 50
+    ample = 64 * 10
+    assert B.rlhf_gen_plan_admission(lens, R, 16, 0, ample) == ([0, 0, 0, 0], [49] * 4, 64)          # everything at once
+    assert B.rlhf_gen_plan_admission(lens, R, 16, 7, ample) == ([0, 7, 14, 21], [49, 56, 63, 70], 64)
+    assert B.rlhf_gen_plan_admission(lens, R, 16, 49, ample) == ([0, 49, 98, 147], [49, 98, 147, 196], 16)   # one after the other
+    assert B.rlhf_gen_plan_admission(lens, R, 16, 200, ample) == ([0, 200, 400, 600], [49, 249, 449, 649], 16)
+    # a pool for two micro-batches: the third waits for the first to finish, the fourth for the second
+    assert B.rlhf_gen_plan_admission(lens, R, 16, 7, 320) == ([0, 7, 49, 56], [49, 56, 98, 105], 32)
+    assert B.rlhf_gen_plan_admission(lens, R, 16, 0, 320) == ([0, 0, 49, 49], [49, 49, 98, 98], 32)
+    assert B.rlhf_gen_plan_admission(lens, R, 16, 0, 479) == ([0, 0, 49, 49], [49, 49, 98, 98], 32)  # one page short of three
+    assert B.rlhf_gen_plan_admission(lens, 1, 16, 5, 160)[:2] == ([0, 5, 10, 15], [0, 5, 10, 15])    # R = 1: no decode steps
+    assert B.rlhf_gen_plan_admission(lens[:40], R, 16, 3, ample) == ([0, 3, 6], [49, 52, 55], 40)     # ragged last micro-batch
+    assert B.rlhf_gen_plan_admission(lens, R, 100, 3, ample) == ([0], [49], 64)                       # micro_batch > B
+    with pytest.raises(B.RlhfGenError) as e:
+        B.rlhf_gen_plan_admission(lens, R, 16, 0, 159)                                                # not even one micro-batch fits
+    assert e.value.status == B.E_NOMEM
+    for bad in (dict(max_resp_len=0), dict(micro_batch=0), dict(stagger_steps=-1), dict(kv_pool_blocks=0)):
+        args = dict(lengths=lens, max_resp_len=R, micro_batch=16, stagger_steps=0, kv_pool_blocks=ample); args.update(bad)
+        with pytest.raises(B.RlhfGenError) as e:
+            B.rlhf_gen_plan_admission(**args)
+        assert e.value.status == B.E_INVALID
+
+
+def test_admission_plan_equals_step_by_step_simulation():
+    """Seeded ragged batches, pools from 'barely one micro-batch' to 'everything': the plan is the earliest-admission
+    schedule of a step-by-step simulation, pages in use never exceed the pool, micro-batches enter and leave in order."""
+    import random
+    from paper_2312_11819_amd import binding as B
+    rng = random.Random(7)
+    for _ in range(200):
+        n_rows = rng.randint(1, 70)
+        lens = [rng.randint(1, 300) for _ in range(n_rows)]
+        R = rng.randint(1, 80)
+        mb = rng.randint(1, 24)
+        stagger = rng.choice([0, 1, 2, 5, 17, 100])
+        per_mb = [sum(-(-(lens[b] + R - 1) // 16) for b in range(i, min(n_rows, i + mb))) for i in range(0, n_rows, mb)]
+        pool = rng.randint(max(per_mb), sum(per_mb) + 5)
+        want = _brute_force_schedule(lens, R, mb, stagger, pool)
+        got = B.rlhf_gen_plan_admission(lens, R, mb, stagger, pool)
+        assert got == want, (lens, R, mb, stagger, pool)
+        admit, done, peak = got
+        assert admit == sorted(admit) and all(d == a + R - 1 for a, d in zip(admit, done))
+        assert all(b - a >= stagger for a, b in zip(admit, admit[1:]))
+        assert (1 if R > 1 else 0) <= peak <= n_rows            # (R = 1: no row ever decodes)
