@@ -59,7 +59,8 @@ __device__ __forceinline__ f32x16_t mfma_32x32x16_v(u32x4_t a, u32x4_t b, f32x16
 template <int EPI, bool SPLIT>
 __global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restrict__ A, const h16_t* __restrict__ W,
                                                             void* __restrict__ out, int M, int N, int K, int tilesM,
-                                                            int tilesN, int a_dual, int nsplit, size_t plane_stride) {
+                                                            int tilesN, int a_dual, int nsplit, size_t plane_stride,
+                                                            RopeEpi re) {
   // a_dual: A rows are [hi (K) | lo (K)]; the k loop then runs over 2K columns of A against W's K columns twice.
   constexpr int NS = DMA_NS, DIST = NS - 1, LPT = 8;  // LPT: DMA loads per thread and k-tile
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -207,6 +208,87 @@ __global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restri
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // the trailing prefetches (never consumed) are done
 
   const int c2 = 2 * (lane & 31);
+  if (EPI == EPI_QKV_ROPE) {
+    // this wavefront's 128 columns are head hd of the fused q|k|v row; the lane holds dimensions c2, c2 + 1 (blocks 0, 1)
+    // and 64 + c2, 64 + c2 + 1 (blocks 2, 3) of it: the pairs the rotation mixes
+    const int hd = tn * 2 + wn;
+    const bool is_q = hd < re.Hq, is_k = !is_q && hd < re.Hq + re.Hkv;
+    const int kvh = is_k ? hd - re.Hq : hd - re.Hq - re.Hkv;
+    if (!is_q && !is_k) {
+      // Values: a lane holds four consecutive rows (e & 3) of each of its four dimensions, and the value layout keeps
+      // the four tokens of an aligned group of slots next to each other: where the four rows are four consecutive
+      // positions of one sequence starting at a multiple of four, they go out as one 8-byte store per dimension
+      // instead of four 2-byte ones (a query of 512 tokens: always).
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int eg = 0; eg < 4; ++eg) {
+          const int m = m0 + wm * 128 + i * 32 + 8 * eg + 4 * (lane >> 5);
+          asm volatile("" ::: "memory");
+          if (m >= M) continue;
+          const int pos = re.row_pos[m];
+          const int bseq = re.row_seq ? re.row_seq[m] : m;
+          const int m3 = min(m + 3, M - 1);
+          const bool together = m + 3 < M && (pos & 3) == 0 && re.row_pos[m3] == pos + 3 && re.row_seq != nullptr && re.row_seq[m3] == bseq;   // (no row_seq: every row is a sequence of its own)
+          if (together) {
+            const int blk = re.block_table[(size_t)bseq * re.max_blocks + (pos >> 4)];
+            char* page = (char*)re.kv_pool_layer + ((size_t)kvh * re.n_blocks + blk) * KV_PAGE_BYTES;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const int dim = c2 + (j & 1) + 64 * (j >> 1);   // blocks 0, 1: c2, c2 + 1; blocks 2, 3: 64 + c2, 65 + c2
+              *(uint2*)(page + vpage_offset(pos & 15, dim)) =
+                  make_uint2(pack_h16x2(acc[i][j][4 * eg], acc[i][j][4 * eg + 1]), pack_h16x2(acc[i][j][4 * eg + 2], acc[i][j][4 * eg + 3]));
+            }
+          } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              if (m + r >= M) continue;
+              const int pr = re.row_pos[m + r], br = re.row_seq ? re.row_seq[m + r] : m + r;
+              char* page = (char*)re.kv_pool_layer + ((size_t)kvh * re.n_blocks + re.block_table[(size_t)br * re.max_blocks + (pr >> 4)]) * KV_PAGE_BYTES;
+#pragma unroll
+              for (int j = 0; j < 4; ++j)
+                *(h16_t*)(page + vpage_offset(pr & 15, c2 + (j & 1) + 64 * (j >> 1))) = f32_to_h16(acc[i][j][4 * eg + r]);
+            }
+          }
+        }
+      }
+      return;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int m = m0 + wm * 128 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        asm volatile("" ::: "memory");   // one row at a time: hoisting the 64 rows' loads to the top would spill the accumulators
+        if (m >= M) continue;
+        const int pos = re.row_pos[m];
+        float a0 = acc[i][0][e], a1 = acc[i][1][e], b0 = acc[i][2][e], b1 = acc[i][3][e];
+        if (is_q || is_k) {
+          const float2 cs = *(const float2*)(re.cos_t + (size_t)pos * 64 + c2), sn = *(const float2*)(re.sin_t + (size_t)pos * 64 + c2);
+          const float r00 = a0 * cs.x - b0 * sn.x, r10 = b0 * cs.x + a0 * sn.x;
+          const float r01 = a1 * cs.y - b1 * sn.y, r11 = b1 * cs.y + a1 * sn.y;
+          a0 = r00; b0 = r10; a1 = r01; b1 = r11;
+        }
+        if (is_q) {
+          h16_t* qo = (h16_t*)re.q_out + ((size_t)m * re.Hq + hd) * 256 + c2;   // [hi (128) | lo (128)]
+          h16_t h[4], l[4];
+          split_h16(a0, h[0], l[0]); split_h16(a1, h[1], l[1]); split_h16(b0, h[2], l[2]); split_h16(b1, h[3], l[3]);
+          *(uint32_t*)(qo) = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+          *(uint32_t*)(qo + 64) = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+          *(uint32_t*)(qo + 128) = (uint32_t)l[0] | ((uint32_t)l[1] << 16);
+          *(uint32_t*)(qo + 192) = (uint32_t)l[2] | ((uint32_t)l[3] << 16);
+        } else {
+          const int bseq = re.row_seq ? re.row_seq[m] : m;
+          const int blk = re.block_table[(size_t)bseq * re.max_blocks + (pos >> 4)], slot = pos & 15;
+          char* page = (char*)re.kv_pool_layer + ((size_t)kvh * re.n_blocks + blk) * KV_PAGE_BYTES;
+          // two adjacent dimensions share a 16-byte chunk of the key layout
+          *(uint32_t*)(page + kpage_offset(slot, c2)) = pack_h16x2(a0, a1);
+          *(uint32_t*)(page + kpage_offset(slot, c2 + 64)) = pack_h16x2(b0, b1);
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -246,7 +328,17 @@ hipError_t launch_large_dma(hipStream_t s, const void* A, const void* W, void* o
   if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
   int tilesM = (M + 255) / 256;
   int tilesN = (EPI == EPI_SWIGLU) ? N / 128 : N / 256;
-  kern<<<tilesM * tilesN, 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, out, M, N, K, tilesM, tilesN, a_dual, 1, 0);
+  kern<<<tilesM * tilesN, 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, out, M, N, K, tilesM, tilesN, a_dual, 1, 0, RopeEpi{});
+  return hipGetLastError();
+}
+
+hipError_t launch_large_dma_qkv_rope(hipStream_t s, const void* A, const void* W, int M, int N, int K, const RopeEpi* re,
+                                     bool configure_only = false) {
+  constexpr int SMEM = DMA_NS * DMA_STAGE;
+  auto kern = gemm_h16_dma_kernel<EPI_QKV_ROPE, false>;
+  if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+  const int tilesM = (M + 255) / 256, tilesN = N / 256;
+  kern<<<tilesM * tilesN, 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, nullptr, M, N, K, tilesM, tilesN, 1, 1, 0, *re);
   return hipGetLastError();
 }
 
@@ -258,7 +350,7 @@ hipError_t launch_large_dma_split(hipStream_t s, const void* A, const void* W, f
   if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
   const int tilesM = (M + 255) / 256, tilesN = N / 256;
   kern<<<tilesM * tilesN * nsplit, 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, N, K, tilesM, tilesN, a_dual,
-                                                   nsplit, (size_t)plane_rows * N);
+                                                   nsplit, (size_t)plane_rows * N, RopeEpi{});
   return hipGetLastError();
 }
 
@@ -706,6 +798,14 @@ hipError_t launch_gemm_h16(hipStream_t s, const void* A, const void* W, void* ou
   return hipErrorInvalidValue;
 }
 
+hipError_t launch_gemm_h16_qkv_rope(hipStream_t s, const void* A, const void* W, int M, int K, const RopeEpi& re) {
+  if (M <= 0) return hipSuccess;
+  const int N = (re.Hq + 2 * re.Hkv) * KV_HEAD_DIM;
+  if (K % 128 || N % 256 || re.Hq < 1 || re.Hkv < 1) return hipErrorInvalidValue;   // (a 256-column tile = two whole heads)
+  if ((size_t)M * 2 * K * 2 >= ((size_t)1 << 32) || (size_t)N * K * 2 >= ((size_t)1 << 32)) return hipErrorInvalidValue;
+  return launch_large_dma_qkv_rope(s, A, W, M, N, K, &re);
+}
+
 int gemm_tiled_pick_split(int M, int N, int K, int max_splits) {
   // as many splits as it takes to give every compute unit one workgroup, none of them empty
   const int tiles = ((M + 255) / 256) * (N / 256), nkw = K / 32;
@@ -734,6 +834,7 @@ hipError_t gemm_configure() {
   if ((e = launch_large_dma<EPI_SWIGLU>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, true)) != hipSuccess) return e;
   if ((e = launch_large_dma<EPI_STORE_ACT>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, true)) != hipSuccess) return e;
   if ((e = launch_large_dma_split(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, 1, 0, true)) != hipSuccess) return e;
+  if ((e = launch_large_dma_qkv_rope(nullptr, nullptr, nullptr, 0, 0, 0, nullptr, true)) != hipSuccess) return e;
   {
     int dev = 0;
     hipDeviceProp_t prop;

@@ -7,7 +7,9 @@ enum GemmEpilogue {
   EPI_STORE_F32 = 0,   // out fp32 [M, N] = acc
   EPI_RESID_F32 = 1,   // out fp32 [M, N] += acc
   EPI_SWIGLU = 2,      // W is [2F, K] (gate rows then up rows), N = F: out [M, F] = silu(gate) * up
-  EPI_STORE_ACT = 3    // out [M, N] in the activation type (fp16 on the MFMA path)
+  EPI_STORE_ACT = 3,   // out [M, N] in the activation type (fp16 on the MFMA path)
+  EPI_QKV_ROPE = 4     // W is the fused q|k|v projection: rotate q and k by the row's position, write the query pairs and
+                       // append k / v to the paged cache (launch_gemm_h16_qkv_rope); nothing else is stored
 };
 
 // ---- 16-bit MFMA path (fp16 operands, fp32 accumulation) ----
@@ -16,6 +18,23 @@ enum GemmEpilogue {
 // out = (hi + lo) W^T.
 hipError_t launch_gemm_h16(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K, int epi,
                            int a_dual);
+// The QKV projection of prefill with the rotary embedding and the cache append as its epilogue: the fp32 q|k|v rows are
+// never written (at 16384 rows of the 7B shape that is 0.8 GB out and back in per layer, plus a kernel of 1.5 M
+// workgroups).  A wavefront's 128 output columns are one head, and a lane holds dimensions 2c, 2c + 1 and their partners
+// 64 + 2c, 64 + 2c + 1 of it, so the rotation happens in registers.  A fp16 [M, 2K] hi|lo pairs, W the [(Hq + 2 Hkv) 128, K]
+// matrix in the working layout; row_pos [M] position of each row, row_seq [M] its block-table row (NULL = identity);
+// q_out fp16 [M, Hq, 2, 128].
+struct RopeEpi {
+  const int* row_pos;
+  const int* row_seq;
+  const float* cos_t;      // [positions, 64]
+  const float* sin_t;
+  void* q_out;
+  void* kv_pool_layer;
+  const int* block_table;
+  int max_blocks, n_blocks, Hq, Hkv;
+};
+hipError_t launch_gemm_h16_qkv_rope(hipStream_t s, const void* A, const void* W, int M, int K, const RopeEpi& re);
 // Split-K form of the large-tile GEMM for a few hundred rows: fp32 partial sums part[ks][plane_rows][N], ks < nsplit
 // (no split may be empty: take nsplit from gemm_tiled_pick_split), N % 256 == 0, K % 128 == 0; the consumer adds the planes.
 hipError_t launch_gemm_h16_splitk(hipStream_t s, const void* A, const void* W, float* part, int M, int N, int K, int a_dual,

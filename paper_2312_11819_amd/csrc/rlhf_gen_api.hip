@@ -259,10 +259,17 @@ int forward_layers_generic(rlhf_gen_ctx* c, const RowSet& r) {
     // 16-bit mode: the inputs of the QKV and output projections travel as fp16 hi|lo pairs
     LAUNCH(c, launch_rmsnorm(s, c->x, nullptr, 0, 0, c->attn_norm[l], c->bf16, c->y, c->bf16, r.M, d, g.rms_eps, nullptr,
                              c->bf16), "rmsnorm");
-    int rc = gemm_any(c, c->y, c->wqkv[l], c->qkv, r.M, qkv_w, d, EPI_STORE_F32, c->bf16);
-    if (rc) return rc;
-    LAUNCH(c, launch_rope_append(s, c->qkv, nullptr, 0, 0, r.row_pos, r.row_seq, c->d_cos, c->d_sin, c->qb, pool,
-                                 w_table(c), c->max_blocks, c->n_blocks, r.M, Hq, Hkv, h, c->bf16), "rope_append");
+    int rc = RLHF_GEN_OK;
+    if (c->bf16) {
+      // 16-bit mode: rotation and cache append are the projection's epilogue (head_dim is 128 there)
+      const RopeEpi re{r.row_pos, r.row_seq, c->d_cos, c->d_sin, c->qb, pool, w_table(c), c->max_blocks, c->n_blocks, Hq, Hkv};
+      LAUNCH(c, launch_gemm_h16_qkv_rope(s, c->y, c->wqkv[l], r.M, d, re), "gemm_qkv_rope");
+    } else {
+      rc = gemm_any(c, c->y, c->wqkv[l], c->qkv, r.M, qkv_w, d, EPI_STORE_F32, 0);
+      if (rc) return rc;
+      LAUNCH(c, launch_rope_append(s, c->qkv, nullptr, 0, 0, r.row_pos, r.row_seq, c->d_cos, c->d_sin, c->qb, pool,
+                                   w_table(c), c->max_blocks, c->n_blocks, r.M, Hq, Hkv, h, 0), "rope_append");
+    }
     if (!c->bf16) {
       LAUNCH(c, launch_attn_f32(s, (const float*)c->qb, (const float*)pool, w_table(c), c->max_blocks, c->n_blocks, r.row_pos,
                                 r.row_seq, (float*)c->ab, r.M, Hq, Hkv, h), "attn_f32");
@@ -913,7 +920,8 @@ static int allocate_all(rlhf_gen_ctx* c) {
   A_(dev_alloc(c, &c->d_seq_ids, sizeof(int) * g.max_batch, true));
   A_(dev_alloc(c, &c->d_last_rows, sizeof(int) * g.max_batch, true));
   A_(dev_alloc(c, &c->x, 4 * rows * g.d_model, true));
-  A_(dev_alloc(c, &c->qkv, 4 * rows * std::max(qkv_w, c->bf16 ? 0 : 2 * g.d_ffn), true));
+  // fp32 q|k|v (and gate|up) rows of the fp32 path; the 16-bit path never materialises them
+  A_(dev_alloc(c, &c->qkv, c->bf16 ? 16 : 4 * rows * std::max(qkv_w, 2 * g.d_ffn), true));
   A_(dev_alloc(c, &c->y, 2 * as * rows * g.d_model, true));              // room for hi|lo pairs
   A_(dev_alloc(c, &c->yl, as * ((size_t)g.max_batch + 256) * g.d_model, true));
   A_(dev_alloc(c, &c->qb, 2 * as * rows * g.n_heads * g.head_dim, true));
