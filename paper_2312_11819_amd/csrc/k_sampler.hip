@@ -125,7 +125,8 @@ __device__ unsigned block_excl_scan_u(unsigned v, Shared& sh) {
 template <bool CACHE>
 __global__ __launch_bounds__(ST) void sampler_kernel(const float* __restrict__ logits, int V, SamplerArgs p,
                                                      const SamplerArgs* __restrict__ args_dev,
-                                                     const int* __restrict__ step_ptr, int* __restrict__ cur_tok) {
+                                                     const int* step_ptr, int* __restrict__ cur_tok,
+                                                     int* adv_seq_len, int* adv_step) {   // (adv_step is step_ptr when set)
   __shared__ Shared sh;
   extern __shared__ float row_s[];   // CACHE: the row, element i at i + i / 32
   if (args_dev) p = *args_dev;       // (uniform: every lane reads the same block)
@@ -203,6 +204,10 @@ __global__ __launch_bounds__(ST) void sampler_kernel(const float* __restrict__ l
       tok_out[out_idx] = imax;
       lp_out[out_idx] = (float)(-log(Zraw));
       cur_tok[b] = imax;
+      if (adv_seq_len) {   // the step's bookkeeping: one more cached token, next response index (every thread read t long ago)
+        adv_seq_len[b] += 1;
+        adv_step[b] = t + 1;
+      }
     }
     return;
   }
@@ -304,6 +309,10 @@ __global__ __launch_bounds__(ST) void sampler_kernel(const float* __restrict__ l
     tok_out[out_idx] = tok;
     lp_out[out_idx] = lp;
     cur_tok[b] = tok;
+    if (adv_seq_len) {
+      adv_seq_len[b] += 1;
+      adv_step[b] = t + 1;
+    }
   }
   (void)Zn;
 }
@@ -357,11 +366,13 @@ hipError_t sampler_configure() {
 }
 
 hipError_t launch_sampler(hipStream_t s, const float* logits, int B, int V, const SamplerArgs& args, const SamplerArgs* args_dev,
-                          const int* step_ptr, int* cur_tok) {
+                          const int* step_ptr, int* cur_tok, int* advance_seq_len, int* advance_step) {
   if (B <= 0) return hipSuccess;
+  if ((advance_seq_len != nullptr) != (advance_step != nullptr)) return hipErrorInvalidValue;
   if (V <= SAMPLER_MAX_CACHED_V)
-    sampler_kernel<true><<<B, ST, (size_t)(V + V / 32 + 1) * 4, s>>>(logits, V, args, args_dev, step_ptr, cur_tok);
+    sampler_kernel<true><<<B, ST, (size_t)(V + V / 32 + 1) * 4, s>>>(logits, V, args, args_dev, step_ptr, cur_tok, advance_seq_len,
+                                                                     advance_step);
   else
-    sampler_kernel<false><<<B, ST, 0, s>>>(logits, V, args, args_dev, step_ptr, cur_tok);
+    sampler_kernel<false><<<B, ST, 0, s>>>(logits, V, args, args_dev, step_ptr, cur_tok, advance_seq_len, advance_step);
   return hipGetLastError();
 }

@@ -74,7 +74,7 @@ hipError_t launch_rope_append(hipStream_t s, const float* qkv, const float* part
 // h[m][f] = silu(sum gate) * (sum up) from fp32 [M, 2F] (+ partial sums).
 hipError_t launch_swiglu(hipStream_t s, const float* gu, int nsplit, size_t part_stride, void* h_out, int act_bf16,
                          int M, int F);
-// seq_len[b] += 1 and step[b] += 1 for b < B (every row carries its own response index)
+// seq_len[b] += 1 and step[b] += 1 for b < B (every row carries its own response index); the decode step lets the sampler do it
 hipError_t launch_advance(hipStream_t s, int* seq_len, int* step, int B);
 // bf16 -> fp16 copy of n elements (working copies of the weight matrices).
 // dst (tiled working layout, see common.h) = fp16(src + scale * B[row0.., :] A): src row-major [rows, cols], bf16 or
@@ -123,9 +123,11 @@ struct SamplerArgs {
   float* lp_out;
 };
 // One workgroup per row of logits [B, V].  Response index of row b: t = step_ptr[b * step_stride]; results go to
-// tok_out[b * out_stride + (use_step_col ? t : 0)]; cur_tok[b] receives the token too.
+// tok_out[b * out_stride + (use_step_col ? t : 0)]; cur_tok[b] receives the token too.  advance_seq_len / advance_step
+// (both or neither; advance_step must then be step_ptr with step_stride 1): the step's bookkeeping is done here as well,
+// seq_len[b] += 1 and step[b] = t + 1, which saves the decode step a launch.
 hipError_t launch_sampler(hipStream_t s, const float* logits, int B, int V, const SamplerArgs& args, const SamplerArgs* args_dev,
-                          const int* step_ptr, int* cur_tok);
+                          const int* step_ptr, int* cur_tok, int* advance_seq_len = nullptr, int* advance_step = nullptr);
 hipError_t launch_fill_int(hipStream_t s, int* p, int n, int value);
 
 // Message that rlhf_gen_last_error(NULL) returns (entry points that have no context to attach it to).

@@ -421,9 +421,8 @@ int enqueue_decode_body(rlhf_gen_ctx* c, int* tok_out, float* lp_out, int stride
   }
   SamplerArgs a = c->sp;
   a.out_stride = stride; a.use_step_col = use_col; a.step_stride = 1; a.tok_out = tok_out; a.lp_out = lp_out;
-  LAUNCH(c, launch_sampler(c->stream, c->logits, B, g.vocab, a, from_dev ? c->d_sargs : nullptr, w_step(c), w_cur_tok(c)),
-         "sampler");
-  LAUNCH(c, launch_advance(c->stream, w_seq_len(c), w_step(c), B), "advance");
+  LAUNCH(c, launch_sampler(c->stream, c->logits, B, g.vocab, a, from_dev ? c->d_sargs : nullptr, w_step(c), w_cur_tok(c),
+                           w_seq_len(c), w_step(c)), "sampler");   // (and the step's bookkeeping)
   prof_mark(c, RLHF_GEN_PROF_SAMPLER);
   return RLHF_GEN_OK;
 }
