@@ -298,8 +298,8 @@ def main() -> int:
                         "traffic": None, "avg_launch_us": gemm_ms / n_g * 1e3, "launches_timed": n_g,
                         "bytes_per_launch": gemm_bytes / n_g}
         # HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by what the counters read for the
-        # weight-conversion copy kernel): measured on a 2-layer, 48-token run of this workload, because counter runs of
-        # the full-size command do not finish; the fetched / algorithmic ratio of those launches is applied to this
+        # weight-conversion copy kernel): measured on a 2-layer, 48-token run of this workload (per-launch traffic does
+        # not depend on the depth); the fetched / algorithmic ratio of those launches is applied to this
         # run's launches (profiles/bench_7b_b64_pmc_traffic.md)
         ratios = traffic_ratios(wl.name)
         if ratios is not None:
