@@ -60,25 +60,44 @@ def hardware_probes(binding, dev):
     return out
 
 
-def prefill_gemm_shapes(binding, shape, rows, dev):
+def prefill_gemm_shapes(binding, shape, rows, dev, lo4=True):
     """The four projection GEMMs of one layer at the prefill chunk size, one by one through the kernel entry point:
-    time, flop rate of the product (2 M N K; x 2 for the fused gate/up pair) and of what the kernel executes (the
-    QKV and output projections take hi|lo activation pairs, i.e. twice the flops)."""
+    time, flop rate of the product (2 M N K; x 2 for the fused gate/up pair) and of what the kernel executes.  The QKV
+    and output projections take their input as a pair hi + lo: with the low half in the 4-bit side format (the
+    rollout's form where the widths allow it) the second pass costs a quarter of an fp16 pass, so the kernel executes
+    1.25 x the product's flops in fp16-equivalent MFMA time; with fp16 low halves it executes 2 x."""
     import torch
     d, F, hq = shape.d_model, shape.d_ffn, shape.n_heads * shape.head_dim
     out = {}
     for name, N, K, epi, dual in (("qkv", shape.qkv_rows, d, 0, 1), ("attn_out", d, hq, 1, 1), ("gate_up_swiglu", F, d, 2, 0),
                                   ("down", d, F, 1, 0)):
-        a = torch.randn(rows, K * (2 if dual else 1), device=dev).half()
         w0 = (torch.randn(N * (2 if epi == 2 else 1), K, device=dev) * 0.02).half()
         w = torch.empty_like(w0)
         binding.rlhf_gen_op_tile_weights(w0, w)
         o = torch.zeros(rows, N, device=dev, dtype=torch.float16 if epi == 2 else torch.float32)
-        t = _time_gpu(lambda: binding.rlhf_gen_op_gemm(binding.GEMM_TILED, a, w, o, rows, N, K, epi, 1, dual))
+        four_bit = bool(dual and lo4 and K % 512 == 0 and N % 256 == 0)
+        if four_bit:
+            groups = 2 * ((rows + 255) // 256)
+            a = torch.zeros(rows, 4 * K, device=dev, dtype=torch.uint8)
+            sc = torch.zeros(K // 128 * groups * 128, device=dev, dtype=torch.uint8)
+            rc = binding.rlhf_gen_op_rmsnorm_lo4(torch.randn(rows, K, device=dev), torch.ones(K, device=dev, dtype=torch.bfloat16), a, sc,
+                                                 groups, rows, K, 1e-5)
+            w4 = torch.zeros(N * K // 2, device=dev, dtype=torch.uint8)
+            ws = torch.zeros(N, device=dev, dtype=torch.uint8)
+            rc = rc or binding.rlhf_gen_op_tile_weights4(w, w4, ws, N, K)
+            if rc:
+                raise RuntimeError(f"4-bit operands for the {name} shape: status {rc}")
+            t = _time_gpu(lambda: binding.rlhf_gen_op_gemm_lo4(a, w, w4, ws, sc, groups, o, rows, N, K, epi))
+            executed = 1.25
+        else:
+            a = torch.randn(rows, K * (2 if dual else 1), device=dev).half()
+            t = _time_gpu(lambda: binding.rlhf_gen_op_gemm(binding.GEMM_TILED, a, w, o, rows, N, K, epi, 1, dual))
+            executed = 2.0 if dual else 1.0
         flop = 2.0 * rows * N * K * (2 if epi == 2 else 1)
         out[name] = {"M": rows, "N": N * (2 if epi == 2 else 1), "K": K, "ms": t * 1e3, "TFLOPs": flop / t / 1e12,
-                     "executed_TFLOPs": flop * (2 if dual else 1) / t / 1e12,
-                     "executed_frac_of_mfma_peak": flop * (2 if dual else 1) / t / MFMA_BF16_PEAK}
+                     "input": ("fp16 + 4-bit low half" if four_bit else "fp16 pair") if dual else "fp16",
+                     "executed_TFLOPs": flop * executed / t / 1e12,
+                     "executed_frac_of_mfma_peak": flop * executed / t / MFMA_BF16_PEAK}
         del a, w0, w, o
     return out
 
@@ -373,7 +392,7 @@ def main() -> int:
     probes = gemm_shapes = None
     if wl.dtype == "bf16" and not args.no_score:
         probes = hardware_probes(binding, dev)
-        gemm_shapes = prefill_gemm_shapes(binding, shape, min(16384, lsum), dev)
+        gemm_shapes = prefill_gemm_shapes(binding, shape, min(16384, lsum), dev, lo4=not (args.flags & 32))
         if roofline is not None:   # the same achieved rate against what a bare read-only stream sustains on this card
             roofline["measured_peak"] = probes["hbm_read_nontemporal_GBps"]
             roofline["frac_of_measured_peak"] = roofline["achieved"] / probes["hbm_read_nontemporal_GBps"]
@@ -392,7 +411,8 @@ def main() -> int:
         "config": {"workload": wl.name, "layers": shape.n_layers, "d_model": shape.d_model, "batch": B,
                    "query_len": [wl.len_lo, wl.len_hi], "resp_len": R, "temperature": wl.temperature, "top_p": wl.top_p,
                    "kv_block": 16,
-                   "weights": "bf16 at the boundary; fp16 MFMA operands (exact conversion), fp32 accumulation" if wl.dtype == "bf16" else "fp32",
+                   "weights": ("bf16 at the boundary; fp16 MFMA operands (exact conversion), fp32 accumulation; four activation tensors as fp16 pairs hi + lo"
+                               + ("" if args.flags & 32 else ", the low halves of two of them contracted in 4-bit (e2m1, block-scaled MFMA) in prefill")) if wl.dtype == "bf16" else "fp32",
                    # the configuration is the named one, and this run's own output was checked against the oracle
                    "valid": bool(not args.layers and not args.resp_len and (parity is None or parity["ok"])),
                    "checked_against_oracle": parity is not None,

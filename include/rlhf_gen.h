@@ -52,10 +52,14 @@ enum {
   RLHF_GEN_FLAG_GENERIC_GEMM = 4u,   /* decode uses the large-tile GEMM instead of the weight-streaming one (cross-check) */
   RLHF_GEN_FLAG_FUSED_ROPE = 16u,    /* decode folds RoPE + KV append into the attention kernel (one launch fewer per layer;
                                         measured 2 % slower per step on MI355X at the 7B shape, so it is off by default) */
-  RLHF_GEN_FLAG_CONVERT_IN_PLACE = 8u /* bf16 mode: rewrite the caller's projection matrices and LM head in place into
+  RLHF_GEN_FLAG_CONVERT_IN_PLACE = 8u, /* bf16 mode: rewrite the caller's projection matrices and LM head in place into
                                          the fp16 working format (tiled layout) instead of allocating working copies
                                          (for models that fill the card; the buffers then no longer hold row-major
                                          bf16 and must not be reused as such); costs a 1024-row staging buffer */
+  RLHF_GEN_FLAG_PREFILL_FP16_PAIRS = 32u /* bf16 mode: prefill and scoring contract the low halves of the QKV and output
+                                         projections' inputs in fp16, as decode does, instead of the 4-bit side format
+                                         (a second pass at full cost instead of a quarter; no 4-bit copies of those two
+                                         matrices, which take 1/4 of their fp16 size; cross-check) */
 };
 
 /* Model and capacity description.  Architecture: pre-norm decoder, RMSNorm (eps inside the

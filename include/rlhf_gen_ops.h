@@ -54,6 +54,29 @@ int rlhf_gen_op_tile_weights(void* stream, const void* w_rowmajor, void* w_tiled
 int rlhf_gen_op_gemm(void* stream, int kind, const void* A, const void* W, void* out, int32_t M, int32_t N, int32_t K,
                      int32_t epilogue, int32_t nsplit, int32_t a_pairs);
 
+/* The prefill form of the two projections whose input travels as a pair hi + lo (the QKV and the output projection:
+ * x W^T of a decoder layer with x carried beyond fp16 precision).  The low half is 2^-11 of the value it corrects, so
+ * its product with W is taken in a 4-bit side format by the block-scaled MFMA, at a quarter of the cost of a second
+ * fp16 pass: elements are e2m1 (sign; magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6), two per byte with the even k in the low
+ * nibble; a group shares a power-of-two scale 2^(byte - 127), the smallest that brings the group's largest magnitude
+ * to at most 6.
+ *   tile_weights4: w_tiled [N, K] fp16 in the working layout -> w4 (N K / 2 bytes: the working layout of a matrix with
+ *                  K / 4 16-bit columns, each holding four consecutive k) and w_scale [N] bytes, one group per row.
+ *                  N % 16 == 0, K % 512 == 0.
+ *   rmsnorm_lo4:   y = rmsnorm(x) * gain for x fp32 [M, d], gain bf16 [d], in the form the GEMM reads: row m of y
+ *                  (pitch 4 d bytes) = [hi: d fp16 | lo4: d / 2 bytes | unused]; one scale byte per (row, 128 columns)
+ *                  at row_scale[((t G + m / 128) 32 + m % 32) 4 + (m / 32) % 4] for column group t, with G =
+ *                  scale_groups >= ceil(M / 128) (row_scale holds (d / 128) G 128 bytes).  d % 128 == 0, d <= 8192.
+ *   gemm_lo4:      out fp32 [M, N] (=, or += with RESID_F32) hi W^T + lo4 W4^T for A in that row form.  N % 256 == 0,
+ *                  K % 512 == 0, scale_groups >= 2 ceil(M / 256); bytes of row_scale that belong to rows >= M must
+ *                  not be 255 (the format's NaN).
+ * All pointers device memory.  Errors: INVALID, UNSUPPORTED (shape), DEVICE. */
+int rlhf_gen_op_tile_weights4(void* stream, const void* w_tiled, void* w4, void* w_scale, int32_t N, int32_t K);
+int rlhf_gen_op_rmsnorm_lo4(void* stream, const float* x, const void* gain_bf16, void* y, void* row_scale, int32_t scale_groups,
+                            int32_t M, int32_t d, float eps);
+int rlhf_gen_op_gemm_lo4(void* stream, const void* A, const void* W, const void* W4, const void* w_scale, const void* a_scale,
+                         int32_t scale_groups, float* out, int32_t M, int32_t N, int32_t K, int32_t epilogue);
+
 /* For callers that cannot allocate device memory (code under HIP graph capture, serving loops and harnesses that forbid
  * hipMalloc): the STREAMING product out = A W^T of rlhf_gen_op_gemm with its split-K partial sums summed inside the
  * library.  rlhf_gen_op_gemm(STREAMING) needs a caller-provided fp32 [nsplit, M, N] buffer for the partial sums; here they

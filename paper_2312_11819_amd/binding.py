@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "librlhf_gen.so")
 
 OK, E_INVALID, E_NOMEM, E_STATE, E_DEVICE, E_UNSUPPORTED = 0, -1, -2, -3, -4, -5
 DTYPE_FP32, DTYPE_BF16 = 0, 1
-FLAG_SHUFFLE_BLOCKS, FLAG_NO_GRAPH, FLAG_GENERIC_GEMM, FLAG_CONVERT_IN_PLACE, FLAG_FUSED_ROPE = 1, 2, 4, 8, 16
+FLAG_SHUFFLE_BLOCKS, FLAG_NO_GRAPH, FLAG_GENERIC_GEMM, FLAG_CONVERT_IN_PLACE, FLAG_FUSED_ROPE, FLAG_PREFILL_FP16_PAIRS = 1, 2, 4, 8, 16, 32
 GEMM_TILED, GEMM_STREAMING, GEMM_FP32 = 0, 1, 2
 EPI_STORE_F32, EPI_RESID_F32, EPI_SWIGLU, EPI_STORE_H16 = 0, 1, 2, 3
 
@@ -32,7 +32,7 @@ EXPORTS = [
     "rlhf_gen_get_logits",
     "rlhf_gen_last_timing", "rlhf_gen_last_step_ms", "rlhf_gen_set_profile", "rlhf_gen_get_profile", "rlhf_gen_last_error", "rlhf_gen_destroy",
     "rlhf_gen_op_probe_stream_read", "rlhf_gen_op_probe_mfma_loop", "rlhf_gen_op_tile_weights", "rlhf_gen_op_gemm", "rlhf_gen_op_rope_append", "rlhf_gen_op_attn_decode", "rlhf_gen_op_attn_prefill",
-    "rlhf_gen_op_sample", "rlhf_gen_op_gemm_static",
+    "rlhf_gen_op_sample", "rlhf_gen_op_gemm_static", "rlhf_gen_op_tile_weights4", "rlhf_gen_op_rmsnorm_lo4", "rlhf_gen_op_gemm_lo4",
 ]
 
 
@@ -129,6 +129,11 @@ def lib() -> C.CDLL:
                                          C.c_void_p, C.c_void_p, C.c_void_p]
         L.rlhf_gen_op_gemm_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                               C.c_int32, C.POINTER(C.c_int32)]
+        L.rlhf_gen_op_tile_weights4.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32]
+        L.rlhf_gen_op_rmsnorm_lo4.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                              C.c_int32, C.c_float]
+        L.rlhf_gen_op_gemm_lo4.argtypes = [C.c_void_p] + [C.c_void_p] * 5 + [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                                                            C.c_int32]
         for name in EXPORTS:
             if name not in ("rlhf_gen_last_error", "rlhf_gen_destroy", "rlhf_gen_context_bytes", "rlhf_gen_graph_captures"):
                 getattr(L, name).restype = C.c_int
@@ -444,6 +449,19 @@ def rlhf_gen_op_tile_weights(w_rowmajor: torch.Tensor, w_tiled: torch.Tensor) ->
 
 def rlhf_gen_op_gemm(kind, A, W, out, M, N, K, epilogue=0, nsplit=1, a_pairs=0) -> int:
     return lib().rlhf_gen_op_gemm(None, kind, _ptr(A), _ptr(W), _ptr(out), M, N, K, epilogue, nsplit, a_pairs)
+
+
+def rlhf_gen_op_tile_weights4(w_tiled, w4, w_scale, N, K) -> int:
+    return lib().rlhf_gen_op_tile_weights4(None, _ptr(w_tiled), _ptr(w4), _ptr(w_scale), N, K)
+
+
+def rlhf_gen_op_rmsnorm_lo4(x, gain_bf16, y, row_scale, scale_groups, M, d, eps) -> int:
+    return lib().rlhf_gen_op_rmsnorm_lo4(None, _ptr(x), _ptr(gain_bf16), _ptr(y), _ptr(row_scale), scale_groups, M, d, eps)
+
+
+def rlhf_gen_op_gemm_lo4(A, W, W4, w_scale, a_scale, scale_groups, out, M, N, K, epilogue=0) -> int:
+    return lib().rlhf_gen_op_gemm_lo4(None, _ptr(A), _ptr(W), _ptr(W4), _ptr(w_scale), _ptr(a_scale), scale_groups, _ptr(out),
+                                      M, N, K, epilogue)
 
 
 def rlhf_gen_op_gemm_static(A, W, out, M, N, K, a_pairs=0):

@@ -57,6 +57,35 @@ __device__ __forceinline__ f32x16_t mfma_32x32x16(uint4 a, uint4 b, f32x16_t c) 
   return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
 }
 
+// ---- 4-bit side format of the pair tensors' low halves (prefill GEMMs) ----------------------------------------
+// The low half of an fp16 pair is 2^-11 of the value it corrects, so its product with the weights needs only a few
+// good bits.  In the large-tile GEMM it is therefore contracted by the block-scaled 4-bit MFMA (32x32x64, four times
+// the k extent of the fp16 MFMA per instruction at the same issue cost) against a 4-bit copy of the weights:
+// elements are e2m1 (sign, then magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6), two per byte with the even k in the low
+// nibble, and a group of elements (128 consecutive k of an activation row; a whole row of a weight matrix) shares a
+// power-of-two scale stored as an E8M0 byte (scale = 2^(byte - 127)), chosen as the smallest that brings the group's
+// largest magnitude to 6 or below.  A CPU simulation of the rounding (tests/test_precision_design_cpu.py) shows the
+// logit error of the rollout unchanged within a few per cent of its rms against fp16 low halves.
+__device__ __forceinline__ uint32_t fp4_scale_byte(float amax) {
+  const uint32_t bits = __float_as_uint(amax);
+  const int e = (int)(bits >> 23) - 2 + ((bits & 0x7fffffu) > 0x400000u ? 1 : 0);   // amax = m 2^x: 6 * 2^(x-2) covers m <= 1.5
+  return (uint32_t)min(max(e, 1), 254);
+}
+__device__ __forceinline__ float fp4_inv_scale(uint32_t byte) { return __uint_as_float((254u - byte) << 23); }   // 2^(127 - byte)
+// nearest e2m1 code of v (already divided by the scale, |v| <= 6)
+__device__ __forceinline__ uint32_t fp4_code(float v) {
+  const float a = fabsf(v);
+  const uint32_t c = (uint32_t)(a > 0.25f) + (uint32_t)(a > 0.75f) + (uint32_t)(a > 1.25f) + (uint32_t)(a > 1.75f) +
+                     (uint32_t)(a > 2.5f) + (uint32_t)(a > 3.5f) + (uint32_t)(a > 5.f);
+  return c | (v < 0.f ? 8u : 0u);
+}
+// Scale bytes of the activation rows, as the large-tile GEMM fetches them: for k-group t (128 columns) the four bytes
+// of rows r, r + 32, r + 64, r + 96 of a 128-row group lie in one 32-bit word, the 32 words of a group side by side.
+// groups = number of 128-row groups the array was laid out for (twice the number of 256-row tiles).
+__host__ __device__ __forceinline__ size_t fp4_row_scale_offset(int m, int t, int groups) {
+  return (((size_t)t * groups + (m >> 7)) * 32 + (m & 31)) * 4 + ((m >> 5) & 3);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);

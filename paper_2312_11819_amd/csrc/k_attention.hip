@@ -310,7 +310,8 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const h16_t* __restri
                                                            const int* __restrict__ block_table, int max_blocks, int n_blocks,
                                                            const int* __restrict__ cu_seqlens,
                                                            const int* __restrict__ seq_ids, h16_t* __restrict__ out,
-                                                           int Hq, int Hkv, float scale_log2) {
+                                                           int Hq, int Hkv, float scale_log2,
+                                                           unsigned char* __restrict__ row_scale, int scale_groups) {
   const int z = blockIdx.z, head = blockIdx.y;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, t = lane & 15, g = lane >> 4;
   const int row0 = cu_seqlens[z], len = cu_seqlens[z + 1] - row0;
@@ -361,7 +362,37 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const h16_t* __restri
   float lt = st.l;
   lt += __shfl_xor(lt, 16);
   lt += __shfl_xor(lt, 32);
-  if (valid) {
+  if (valid && row_scale) {
+    // low halves in the 4-bit side format: row = [hi (Hq*128) | lo4 (Hq*64 bytes) | unused], one scale per (row, head);
+    // the head's 128 dimensions of this row are spread over the four lanes t, t + 16, t + 32, t + 48
+    const float inv = 1.f / lt;
+    const int m = row0 + p0 + t;
+    char* orow = (char*)out + (size_t)m * 4 * Hq * 128;
+    float am = 0.f;
+#pragma unroll
+    for (int db = 0; db < 8; ++db) {
+      h16_t hi[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float v = st.o[db][i] * inv;
+        hi[i] = f32_to_h16(v);
+        st.o[db][i] = v - h16_to_f32(hi[i]);
+        am = fmaxf(am, fabsf(st.o[db][i]));
+      }
+      *(uint2*)(orow + 2 * (head * 128 + db * 16 + 4 * g)) =
+          make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+    }
+    am = fmaxf(am, __shfl_xor(am, 16));
+    am = fmaxf(am, __shfl_xor(am, 32));
+    const uint32_t sb = fp4_scale_byte(am);
+    const float is = fp4_inv_scale(sb);
+#pragma unroll
+    for (int db = 0; db < 8; ++db)
+      *(uint16_t*)(orow + 2 * Hq * 128 + ((head * 128 + db * 16 + 4 * g) >> 1)) =
+          (uint16_t)(fp4_code(st.o[db][0] * is) | (fp4_code(st.o[db][1] * is) << 4) | (fp4_code(st.o[db][2] * is) << 8) |
+                     (fp4_code(st.o[db][3] * is) << 12));
+    if (g == 0) row_scale[fp4_row_scale_offset(m, head, scale_groups)] = (unsigned char)sb;
+  } else if (valid) {
     float inv = 1.f / lt;
     h16_t* orow = out + (size_t)(row0 + p0 + t) * 2 * Hq * 128 + head * 128 + 4 * g;  // row = [hi (Hq*128) | lo]
 #pragma unroll
@@ -457,13 +488,15 @@ hipError_t launch_attn_decode_fused_h16(hipStream_t s, const float* qkv_part, in
 
 hipError_t launch_attn_prefill_h16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
                                     int max_blocks, int n_blocks, const int* cu_seqlens, const int* seq_ids, void* out, int nseq,
-                                    int max_len, int Hq, int Hkv) {
+                                    int max_len, int Hq, int Hkv, void* row_scale, int scale_groups) {
   if (nseq <= 0 || max_len <= 0) return hipSuccess;
   if (Hq % Hkv) return hipErrorInvalidValue;
+  // (row_scale: the caller guarantees that 128 * scale_groups covers cu_seqlens[nseq], the number of rows)
+  if (row_scale && scale_groups <= 0) return hipErrorInvalidValue;
   float scale_log2 = LOG2E / sqrtf((float)KV_HEAD_DIM);
   attn_prefill_kernel<<<dim3((max_len + 63) / 64, Hq, nseq), 256, 0, s>>>(
       (const h16_t*)q, (const char*)kv_pool_layer, block_table, max_blocks, n_blocks, cu_seqlens, seq_ids, (h16_t*)out, Hq, Hkv,
-      scale_log2);
+      scale_log2, (unsigned char*)row_scale, scale_groups);
   return hipGetLastError();
 }
 

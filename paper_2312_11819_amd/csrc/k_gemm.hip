@@ -49,20 +49,56 @@ __device__ __forceinline__ u32x4_t lds_read128(uint32_t addr) {
 __device__ __forceinline__ f32x16_t mfma_32x32x16_v(u32x4_t a, u32x4_t b, f32x16_t c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
 }
+__device__ __forceinline__ uint32_t lds_read32(uint32_t addr) {
+  uint32_t v;
+  asm volatile("ds_read_b32 %0, %1" : "=v"(v) : "v"(addr));
+  return v;
+}
+// D(32x32) += A(32x64) * B(64x32) with 4-bit (e2m1) operands and one power-of-two scale per lane and operand: lane l
+// supplies row/column (l & 31) and the 32 consecutive k of group l >> 5 as 16 bytes (even k in the low nibble); byte
+// SELA of sa / SELB of sb is the E8M0 scale of the lane's 32 elements.  Same issue cost as the 32x32x16 fp16 MFMA
+// (measured), four times its k extent; the accumulator layout is that of the fp16 MFMA.
+typedef int __attribute__((ext_vector_type(4))) i32x4_t;
+template <int SELA, int SELB>
+__device__ __forceinline__ f32x16_t mfma_32x32x64_f4(u32x4_t a, u32x4_t b, f32x16_t c, uint32_t sa, uint32_t sb) {
+  const i32x4_t ai = __builtin_bit_cast(i32x4_t, a), bi = __builtin_bit_cast(i32x4_t, b);
+  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(__builtin_shufflevector(ai, ai, 0, 1, 2, 3, -1, -1, -1, -1),
+                                                         __builtin_shufflevector(bi, bi, 0, 1, 2, 3, -1, -1, -1, -1), c, 4, 4,
+                                                         SELA, (int)sa, SELB, (int)sb);
+}
 #define LDS_WAIT8(N, f0, f1, f2, f3, f4, f5, f6, f7) \
   asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(f0), "+v"(f1), "+v"(f2), "+v"(f3), "+v"(f4), "+v"(f5), "+v"(f6), "+v"(f7))
+#define LDS_WAIT9(N, f0, f1, f2, f3, f4, f5, f6, f7, f8) \
+  asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(f0), "+v"(f1), "+v"(f2), "+v"(f3), "+v"(f4), "+v"(f5), "+v"(f6), "+v"(f7), "+v"(f8))
+
+// LO4 form: what the low-half phase of the k loop needs besides A and W
+struct Lo4Args {
+  const void* w4;                  // 4-bit copy of W (launch_to_w4_tiled)
+  const unsigned char* w_scale;    // its scale byte per row of W
+  const unsigned char* a_scale;    // scale bytes of A's low halves, fp4_row_scale_offset order
+  int groups;                      // 128-row groups that order was laid out for
+};
 
 // SPLIT: split-K form for a few hundred rows (large decode batches), where the output tiles alone cannot fill the
 // chip: workgroup (tile, split) contracts k-tiles [kw0, kw1) of W only and stores its fp32 tile into plane `split` of
 // `out` (plane_stride floats apart); the consumer kernel adds the planes in a fixed order.  With hi|lo inputs the
 // split walks (k-tile, hi), (k-tile, lo), ... so that the W tile fetched for the hi half is still in L2 for the lo half.
-template <int EPI, bool SPLIT>
+// LO4: A rows are [hi (K) | 4-bit low halves (K / 2 bytes) | unused] at the pitch of the pair form.  The k loop runs
+// the K / 32 fp16 k-tiles and then K / 128 stages of the low halves against the 4-bit copy of W: such a stage has the
+// byte layout of an fp16 stage (64 bytes per row: here 128 columns), the same DMA loads, operand reads and schedule,
+// and one 4-bit MFMA where the fp16 phase has one fp16 MFMA - a quarter of the pair form's second pass.  The scale
+// bytes of the A rows travel with their stage: every wavefront brings the 128 words of its own rows into a small LDS
+// ring by one more DMA load per stage (issued in the fp16 phase too, so that every stage counts the same number of
+// memory operations) and reads its word back when the stage is consumed.
+template <int EPI, bool SPLIT, bool LO4 = false>
 __global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restrict__ A, const h16_t* __restrict__ W,
                                                             void* __restrict__ out, int M, int N, int K, int tilesM,
                                                             int tilesN, int a_dual, int nsplit, size_t plane_stride,
-                                                            RopeEpi re) {
+                                                            RopeEpi re, Lo4Args l4) {
   // a_dual: A rows are [hi (K) | lo (K)]; the k loop then runs over 2K columns of A against W's K columns twice.
   constexpr int NS = DMA_NS, DIST = NS - 1, LPT = 8;  // LPT: DMA loads per thread and k-tile
+  constexpr int VMS = LPT + (LO4 ? 1 : 0);            // memory operations per wavefront and stage
+  static_assert(!(LO4 && (SPLIT || EPI == EPI_SWIGLU)), "the 4-bit low-half phase exists for the plain and the QKV forms");
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   int pid = blockIdx.x;
   int split = 0;
@@ -110,7 +146,10 @@ __global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restri
     kw0 = split * per;
     kw1 = min(nkw, kw0 + per);
   }
-  const int nk = SPLIT ? (kw1 - kw0) * (a_dual ? 2 : 1) : (a_dual ? 2 * nkw : nkw);  // k-tiles of the product
+  const int nlo = LO4 ? K / 128 : 0;      // stages of the 4-bit low-half phase
+  const int nk = SPLIT ? (kw1 - kw0) * (a_dual ? 2 : 1) : LO4 ? nkw + nlo : (a_dual ? 2 * nkw : nkw);  // k-tiles of the product
+  // 4-bit W: the tiled order of a matrix with K / 4 columns, so its slabs are a quarter as long (tile tn = slab tn)
+  const size_t w4_adj = LO4 ? (size_t)tn * WSLAB_RB * (size_t)((K >> 7) - (K >> 9)) * 4096 : 0;
   typedef __attribute__((address_space(3))) void lds_void;
   typedef const __attribute__((address_space(1))) void g_void;
   char* dma_dst = smem + wave * 8192;
@@ -122,12 +161,27 @@ __global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restri
       if (loads_a) return gbase + ((a_dual && (kt & 1)) ? (size_t)K * 2 : (size_t)0) + (size_t)kw * 64;
       return gbase + (size_t)(kw >> 2) * (WSLAB_RB * 4096) + (size_t)(kw & 3) * 1024;   // (every slab is full: rows % 256 == 0)
     }
+    if (LO4 && kt >= nkw) {
+      const int kl = kt - nkw;
+      if (loads_a) return gbase + (size_t)K * 2 + (size_t)kl * 64;
+      return (const char*)l4.w4 + ((size_t)(kl >> 2) * (WSLAB_RB * 4096) + (size_t)(kl & 3) * 1024) - w4_adj;
+    }
     if (loads_a) return gbase + (size_t)kt * 64;
     const int kw = kt >= nkw ? kt - nkw : kt;
     return gbase + (size_t)(kw >> 2) * (WSLAB_RB * 4096) + (size_t)(kw & 3) * 1024;   // (every slab is full: rows % 256 == 0)
   };
 #define DMA1(SRC, SOFF, IT) \
   __builtin_amdgcn_global_load_lds((g_void*)((SRC) + go[IT]), (lds_void*)(dma_dst + (SOFF) + (IT) * 1024), 16, 0, 0);
+  // scale words of this wavefront's 128 A rows for stage KT (clamped into the low-half phase), one per lane (the upper
+  // half of the wavefront repeats the lower), into this wavefront's 256 bytes of the ring slot of the stage at SOFF
+  const char* sa_src = LO4 ? (const char*)l4.a_scale + ((size_t)((m0 >> 7) + wm) * 32 + (lane & 31)) * 4 : nullptr;
+  const size_t sa_stride = (size_t)l4.groups * 128;
+  char* sc_dst = smem + NS * DMA_STAGE + wave * 256;
+#define DMAS(KT, SOFF)                                                                                             \
+  if (LO4) {                                                                                                       \
+    const int kl_ = min(max((KT) - nkw, 0), nlo - 1);                                                              \
+    __builtin_amdgcn_global_load_lds((g_void*)(sa_src + (size_t)kl_ * sa_stride), (lds_void*)(sc_dst + ((SOFF) >> 5)), 4, 0, 0); \
+  }
 
   f32x16_t acc[4][4];
 #pragma unroll
@@ -152,8 +206,17 @@ __global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restri
     const char* src = tile_src(d);
 #pragma unroll
     for (int it = 0; it < LPT; ++it) DMA1(src, d * DMA_STAGE, it)
+    DMAS(d, d * DMA_STAGE)
   }
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 1) * LPT) : "memory");
+  // scale bytes of this lane's four W rows (32-column blocks j = 0..3), the same for every stage
+  uint32_t scb = 0, sca = 0, scn = 0;   // scale words: W rows; A rows of the current and of the next stage
+  const uint32_t sc_rd = (uint32_t)(size_t)smem + NS * DMA_STAGE + wave * 256 + lane * 4;
+  if (LO4) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) scb |= (uint32_t)l4.w_scale[wrow(wn * 128 + j * 32 + (lane & 31))] << (8 * j);
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(scb)::"memory");   // (ordinary loads: keep them out of the DMA accounting below)
+  }
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 1) * VMS) : "memory");
   __builtin_amdgcn_s_barrier();
   u32x4_t p0, p1, p2, p3, p4, p5, p6, p7, q0, q1, q2, q3, q4, q5, q6, q7;
   uint32_t so_cur = 0;                     // stage of k-tile kt
@@ -164,47 +227,63 @@ __global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restri
     p0 = lds_read128<0>(ra); p1 = lds_read128<2048>(ra); p2 = lds_read128<4096>(ra); p3 = lds_read128<6144>(ra);
   }
 #define SB0 __builtin_amdgcn_sched_barrier(0);
-#define MF(I, J, SA, SB) acc[I][J] = mfma_32x32x16_v(SA, SB, acc[I][J]);
-  for (int kt = 0; kt < nk; ++kt) {
-    {
-      // first half of k-tile kt from p, while the second half is read into q
-      const uint32_t ra = a_rd[1] + so_cur, rb = b_rd[1] + so_cur;
-      LDS_WAIT8(0, p0, p1, p2, p3, p4, p5, p6, p7);
-      SB0 MF(0, 0, p0, p4) MF(0, 1, p0, p5) SB0 q4 = lds_read128<0>(rb);
-      SB0 MF(0, 2, p0, p6) MF(0, 3, p0, p7) SB0 q5 = lds_read128<2048>(rb);
-      SB0 MF(1, 0, p1, p4) MF(1, 1, p1, p5) SB0 q6 = lds_read128<4096>(rb);
-      SB0 MF(1, 2, p1, p6) MF(1, 3, p1, p7) SB0 q7 = lds_read128<6144>(rb);
-      SB0 MF(2, 0, p2, p4) MF(2, 1, p2, p5) SB0 q0 = lds_read128<0>(ra);
-      SB0 MF(2, 2, p2, p6) MF(2, 3, p2, p7) SB0 q1 = lds_read128<2048>(ra);
-      SB0 MF(3, 0, p3, p4) MF(3, 1, p3, p5) SB0 q2 = lds_read128<4096>(ra);
-      SB0 MF(3, 2, p3, p6) MF(3, 3, p3, p7) SB0 q3 = lds_read128<6144>(ra);
-      SB0
-    }
-    // k-tile kt + 1 has landed (this wavefront's share: the barrier covers the others'), and nobody reads the
-    // stage of k-tile kt - 1 any more, which is where k-tile kt + DIST goes
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 2) * LPT) : "memory");
-    __builtin_amdgcn_s_barrier();
-    {
-      const char* src = tile_src(kt + DIST);
-      const uint32_t so_i = so_issue;
-      so_cur = so_cur + DMA_STAGE == NS * DMA_STAGE ? 0 : so_cur + DMA_STAGE;
-      so_issue = so_issue + DMA_STAGE == NS * DMA_STAGE ? 0 : so_issue + DMA_STAGE;
-      const uint32_t ra = a_rd[0] + so_cur, rb = b_rd[0] + so_cur;
-      LDS_WAIT8(0, q0, q1, q2, q3, q4, q5, q6, q7);
-      SB0 MF(0, 0, q0, q4) MF(0, 1, q0, q5) SB0 p4 = lds_read128<0>(rb);    DMA1(src, so_i, 0)
-      SB0 MF(0, 2, q0, q6) MF(0, 3, q0, q7) SB0 p5 = lds_read128<2048>(rb); DMA1(src, so_i, 1)
-      SB0 MF(1, 0, q1, q4) MF(1, 1, q1, q5) SB0 p6 = lds_read128<4096>(rb); DMA1(src, so_i, 2)
-      SB0 MF(1, 2, q1, q6) MF(1, 3, q1, q7) SB0 p7 = lds_read128<6144>(rb); DMA1(src, so_i, 3)
-      SB0 MF(2, 0, q2, q4) MF(2, 1, q2, q5) SB0 p0 = lds_read128<0>(ra);    DMA1(src, so_i, 4)
-      SB0 MF(2, 2, q2, q6) MF(2, 3, q2, q7) SB0 p1 = lds_read128<2048>(ra); DMA1(src, so_i, 5)
-      SB0 MF(3, 0, q3, q4) MF(3, 1, q3, q5) SB0 p2 = lds_read128<4096>(ra); DMA1(src, so_i, 6)
-      SB0 MF(3, 2, q3, q6) MF(3, 3, q3, q7) SB0 p3 = lds_read128<6144>(ra); DMA1(src, so_i, 7)
-      SB0
-    }
+#define MFH(I, J, SA, SB) acc[I][J] = mfma_32x32x16_v(SA, SB, acc[I][J]);
+#define MF4(I, J, SA, SB) acc[I][J] = mfma_32x32x64_f4<I, J>(SA, SB, acc[I][J], sca, scb);
+  // One stage: its first half (chunks 0, 1 of every row: 16 columns of an fp16 k-tile, 64 of a low-half stage) from p
+  // while the second half is read into q; then the barrier; then the second half from q while the first half of the
+  // next stage (and its scale word) is read into p and the stage DIST ahead is requested.
+#define KSTAGE(MF)                                                                                                  \
+  {                                                                                                                 \
+    {                                                                                                               \
+      const uint32_t ra = a_rd[1] + so_cur, rb = b_rd[1] + so_cur;                                                  \
+      LDS_WAIT9(0, p0, p1, p2, p3, p4, p5, p6, p7, scn);                                                            \
+      sca = scn;                                                                                                    \
+      SB0 MF(0, 0, p0, p4) MF(0, 1, p0, p5) SB0 q4 = lds_read128<0>(rb);                                            \
+      SB0 MF(0, 2, p0, p6) MF(0, 3, p0, p7) SB0 q5 = lds_read128<2048>(rb);                                         \
+      SB0 MF(1, 0, p1, p4) MF(1, 1, p1, p5) SB0 q6 = lds_read128<4096>(rb);                                         \
+      SB0 MF(1, 2, p1, p6) MF(1, 3, p1, p7) SB0 q7 = lds_read128<6144>(rb);                                         \
+      SB0 MF(2, 0, p2, p4) MF(2, 1, p2, p5) SB0 q0 = lds_read128<0>(ra);                                            \
+      SB0 MF(2, 2, p2, p6) MF(2, 3, p2, p7) SB0 q1 = lds_read128<2048>(ra);                                         \
+      SB0 MF(3, 0, p3, p4) MF(3, 1, p3, p5) SB0 q2 = lds_read128<4096>(ra);                                         \
+      SB0 MF(3, 2, p3, p6) MF(3, 3, p3, p7) SB0 q3 = lds_read128<6144>(ra);                                         \
+      SB0                                                                                                           \
+    }                                                                                                               \
+    /* stage kt + 1 has landed (this wavefront's share: the barrier covers the others'), and nobody reads the */    \
+    /* stage of k-tile kt - 1 any more, which is where stage kt + DIST goes */                                      \
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DIST - 2) * VMS) : "memory");                                         \
+    __builtin_amdgcn_s_barrier();                                                                                   \
+    {                                                                                                               \
+      const char* src = tile_src(kt + DIST);                                                                        \
+      const uint32_t so_i = so_issue;                                                                               \
+      so_cur = so_cur + DMA_STAGE == NS * DMA_STAGE ? 0 : so_cur + DMA_STAGE;                                       \
+      so_issue = so_issue + DMA_STAGE == NS * DMA_STAGE ? 0 : so_issue + DMA_STAGE;                                 \
+      const uint32_t ra = a_rd[0] + so_cur, rb = b_rd[0] + so_cur;                                                  \
+      LDS_WAIT8(0, q0, q1, q2, q3, q4, q5, q6, q7);                                                                 \
+      SB0 MF(0, 0, q0, q4) MF(0, 1, q0, q5) SB0 p4 = lds_read128<0>(rb);    DMA1(src, so_i, 0)                      \
+      SB0 MF(0, 2, q0, q6) MF(0, 3, q0, q7) SB0 p5 = lds_read128<2048>(rb); DMA1(src, so_i, 1)                      \
+      SB0 MF(1, 0, q1, q4) MF(1, 1, q1, q5) SB0 p6 = lds_read128<4096>(rb); DMA1(src, so_i, 2)                      \
+      SB0 MF(1, 2, q1, q6) MF(1, 3, q1, q7) SB0 p7 = lds_read128<6144>(rb); DMA1(src, so_i, 3)                      \
+      SB0 MF(2, 0, q2, q4) MF(2, 1, q2, q5) SB0 p0 = lds_read128<0>(ra);    DMA1(src, so_i, 4)                      \
+      SB0 MF(2, 2, q2, q6) MF(2, 3, q2, q7) SB0 p1 = lds_read128<2048>(ra); DMA1(src, so_i, 5)                      \
+      SB0 MF(3, 0, q3, q4) MF(3, 1, q3, q5) SB0 p2 = lds_read128<4096>(ra); DMA1(src, so_i, 6)                      \
+      SB0 MF(3, 2, q3, q6) MF(3, 3, q3, q7) SB0 p3 = lds_read128<6144>(ra); DMA1(src, so_i, 7)                      \
+      SB0 DMAS(kt + DIST, so_i)                                                                                     \
+      if (LO4) scn = lds_read32(sc_rd + (so_cur >> 5));                                                             \
+    }                                                                                                               \
   }
-#undef MF
+  {
+    int kt = 0;
+    const int nk_hi = LO4 ? nkw : nk;
+    for (; kt < nk_hi; ++kt) KSTAGE(MFH)
+    if (LO4)
+      for (; kt < nk; ++kt) KSTAGE(MF4)
+  }
+#undef KSTAGE
+#undef MFH
+#undef MF4
 #undef SB0
 #undef DMA1
+#undef DMAS
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // the trailing prefetches (never consumed) are done
 
   const int c2 = 2 * (lane & 31);
@@ -328,7 +407,7 @@ hipError_t launch_large_dma(hipStream_t s, const void* A, const void* W, void* o
   if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
   int tilesM = (M + 255) / 256;
   int tilesN = (EPI == EPI_SWIGLU) ? N / 128 : N / 256;
-  kern<<<tilesM * tilesN, 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, out, M, N, K, tilesM, tilesN, a_dual, 1, 0, RopeEpi{});
+  kern<<<tilesM * tilesN, 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, out, M, N, K, tilesM, tilesN, a_dual, 1, 0, RopeEpi{}, Lo4Args{});
   return hipGetLastError();
 }
 
@@ -338,7 +417,20 @@ hipError_t launch_large_dma_qkv_rope(hipStream_t s, const void* A, const void* W
   auto kern = gemm_h16_dma_kernel<EPI_QKV_ROPE, false>;
   if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
   const int tilesM = (M + 255) / 256, tilesN = N / 256;
-  kern<<<tilesM * tilesN, 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, nullptr, M, N, K, tilesM, tilesN, 1, 1, 0, *re);
+  kern<<<tilesM * tilesN, 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, nullptr, M, N, K, tilesM, tilesN, 1, 1, 0, *re, Lo4Args{});
+  return hipGetLastError();
+}
+
+// The form with 4-bit low halves (EPI_STORE_F32, EPI_RESID_F32 or EPI_QKV_ROPE)
+template <int EPI>
+hipError_t launch_large_dma_lo4(hipStream_t s, const void* A, const void* W, void* out, int M, int N, int K, const RopeEpi* re,
+                                const Lo4Args* l4, bool configure_only = false) {
+  constexpr int SMEM = DMA_NS * DMA_STAGE + DMA_NS * 1024;   // + the ring of scale words
+  auto kern = gemm_h16_dma_kernel<EPI, false, true>;
+  if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+  const int tilesM = (M + 255) / 256, tilesN = N / 256;
+  kern<<<tilesM * tilesN, 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, out, M, N, K, tilesM, tilesN, 1, 1, 0,
+                                          re ? *re : RopeEpi{}, *l4);
   return hipGetLastError();
 }
 
@@ -350,7 +442,7 @@ hipError_t launch_large_dma_split(hipStream_t s, const void* A, const void* W, f
   if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
   const int tilesM = (M + 255) / 256, tilesN = N / 256;
   kern<<<tilesM * tilesN * nsplit, 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, N, K, tilesM, tilesN, a_dual,
-                                                   nsplit, (size_t)plane_rows * N, RopeEpi{});
+                                                   nsplit, (size_t)plane_rows * N, RopeEpi{}, Lo4Args{});
   return hipGetLastError();
 }
 
@@ -798,6 +890,27 @@ hipError_t launch_gemm_h16(hipStream_t s, const void* A, const void* W, void* ou
   return hipErrorInvalidValue;
 }
 
+hipError_t launch_gemm_h16_lo4(hipStream_t s, const void* A, const void* W, const void* W4, const void* w_scale,
+                               const void* a_scale, int scale_groups, void* out, int M, int N, int K, int epi, const RopeEpi* re) {
+  if (M <= 0) return hipSuccess;
+  if (epi == EPI_QKV_ROPE) {
+    if (!re || re->Hq < 1 || re->Hkv < 1 || N != (re->Hq + 2 * re->Hkv) * KV_HEAD_DIM) return hipErrorInvalidValue;
+  } else if (!out) {
+    return hipErrorInvalidValue;
+  }
+  if (!A || !W || !W4 || !w_scale || !a_scale) return hipErrorInvalidValue;
+  if (K % 512 || N % 256) return hipErrorInvalidValue;   // (the 4-bit copy of W is tiled as a matrix with K / 4 columns)
+  if (scale_groups < 2 * ((M + 255) / 256)) return hipErrorInvalidValue;   // a scale word for every row of every 256-row tile
+  if ((size_t)M * 2 * K * 2 >= ((size_t)1 << 32) || (size_t)N * K * 2 >= ((size_t)1 << 32)) return hipErrorInvalidValue;
+  const Lo4Args l4{W4, (const unsigned char*)w_scale, (const unsigned char*)a_scale, scale_groups};
+  switch (epi) {
+    case EPI_STORE_F32: return launch_large_dma_lo4<EPI_STORE_F32>(s, A, W, out, M, N, K, nullptr, &l4);
+    case EPI_RESID_F32: return launch_large_dma_lo4<EPI_RESID_F32>(s, A, W, out, M, N, K, nullptr, &l4);
+    case EPI_QKV_ROPE: return launch_large_dma_lo4<EPI_QKV_ROPE>(s, A, W, nullptr, M, N, K, re, &l4);
+  }
+  return hipErrorInvalidValue;
+}
+
 hipError_t launch_gemm_h16_qkv_rope(hipStream_t s, const void* A, const void* W, int M, int K, const RopeEpi& re) {
   if (M <= 0) return hipSuccess;
   const int N = (re.Hq + 2 * re.Hkv) * KV_HEAD_DIM;
@@ -835,6 +948,9 @@ hipError_t gemm_configure() {
   if ((e = launch_large_dma<EPI_STORE_ACT>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, true)) != hipSuccess) return e;
   if ((e = launch_large_dma_split(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, 1, 0, true)) != hipSuccess) return e;
   if ((e = launch_large_dma_qkv_rope(nullptr, nullptr, nullptr, 0, 0, 0, nullptr, true)) != hipSuccess) return e;
+  if ((e = launch_large_dma_lo4<EPI_STORE_F32>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, nullptr, nullptr, true)) != hipSuccess) return e;
+  if ((e = launch_large_dma_lo4<EPI_RESID_F32>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, nullptr, nullptr, true)) != hipSuccess) return e;
+  if ((e = launch_large_dma_lo4<EPI_QKV_ROPE>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, nullptr, nullptr, true)) != hipSuccess) return e;
   {
     int dev = 0;
     hipDeviceProp_t prop;

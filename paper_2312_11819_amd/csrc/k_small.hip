@@ -95,11 +95,15 @@ hipError_t launch_embed(hipStream_t s, const int* ids, const void* table, int w_
 
 // One workgroup of NT threads per row, d <= 8 * 4 * NT, d % 4 == 0.  The sum of squares is taken in a fixed
 // order, so the result does not change from run to run.  Partial sums are added in split order 0, 1, ...
-template <bool WBF16, bool A16, int NT, bool DUAL>
+// DUAL: 0 = one 16-bit (or fp32) value per element; 1 = fp16 pairs, row = [hi (d) | lo (d)]; 2 = fp16 high halves and
+// 4-bit low halves, row = [hi (d) | lo4 (d / 2 bytes) | unused] with the same row pitch as form 1, one scale byte per
+// 128 columns in row_scale (common.h, fp4_row_scale_offset; d % 128 == 0).
+template <bool WBF16, bool A16, int NT, int DUAL>
 __global__ __launch_bounds__(NT) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ part, int nsplit,
                                                      size_t part_stride, const void* __restrict__ gain,
                                                      void* __restrict__ y, int d, float eps,
-                                                     const int* __restrict__ rows) {
+                                                     const int* __restrict__ rows, unsigned char* __restrict__ row_scale,
+                                                     int scale_groups) {
   constexpr int IT = 8192 / (4 * NT);
   __shared__ float red[NT / 64];
   int m = blockIdx.x;
@@ -164,7 +168,20 @@ __global__ __launch_bounds__(NT) void rmsnorm_kernel(float* __restrict__ x, cons
       }
       float4 a = v[it];
       float o0 = a.x * r * g0, o1 = a.y * r * g1, o2 = a.z * r * g2, o3 = a.w * r * g3;
-      if (A16 && DUAL) {  // row = [hi (d) | lo (d)]
+      if (A16 && DUAL == 2) {
+        const h16_t h0 = f32_to_h16(o0), h1 = f32_to_h16(o1), h2 = f32_to_h16(o2), h3 = f32_to_h16(o3);
+        const float l0 = o0 - h16_to_f32(h0), l1 = o1 - h16_to_f32(h1), l2 = o2 - h16_to_f32(h2), l3 = o3 - h16_to_f32(h3);
+        float am = fmaxf(fmaxf(fabsf(l0), fabsf(l1)), fmaxf(fabsf(l2), fabsf(l3)));
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) am = fmaxf(am, __shfl_xor(am, o));   // 32 threads = the 128 columns of one scale group
+        const uint32_t sb = fp4_scale_byte(am);
+        const float inv = fp4_inv_scale(sb);
+        char* yr = (char*)y + (size_t)m * 4 * d;
+        *(uint2*)(yr + 2 * i) = make_uint2((uint32_t)h0 | ((uint32_t)h1 << 16), (uint32_t)h2 | ((uint32_t)h3 << 16));
+        *(uint16_t*)(yr + 2 * d + (i >> 1)) =
+            (uint16_t)(fp4_code(l0 * inv) | (fp4_code(l1 * inv) << 4) | (fp4_code(l2 * inv) << 8) | (fp4_code(l3 * inv) << 12));
+        if ((threadIdx.x & 31) == 0) row_scale[fp4_row_scale_offset(m, i >> 7, scale_groups)] = (unsigned char)sb;
+      } else if (A16 && DUAL == 1) {  // row = [hi (d) | lo (d)]
         h16_t hi[4], lo[4];
         split_h16(o0, hi[0], lo[0]); split_h16(o1, hi[1], lo[1]);
         split_h16(o2, hi[2], lo[2]); split_h16(o3, hi[3], lo[3]);
@@ -184,18 +201,23 @@ __global__ __launch_bounds__(NT) void rmsnorm_kernel(float* __restrict__ x, cons
 }
 
 hipError_t launch_rmsnorm(hipStream_t s, float* x, const float* part, int nsplit, size_t part_stride, const void* gain,
-                          int w_bf16, void* y, int act_bf16, int M, int d, float eps, const int* rows, int dual) {
+                          int w_bf16, void* y, int act_bf16, int M, int d, float eps, const int* rows, int dual,
+                          void* row_scale, int scale_groups) {
   if (M <= 0) return hipSuccess;
   if (d > 8192 || (d & 3)) return hipErrorInvalidValue;
+  if (dual == 2 && (!row_scale || d % 128 || scale_groups * 128 < M || !(w_bf16 && act_bf16))) return hipErrorInvalidValue;
   if (!part) nsplit = 0;
   const bool wide = M <= 1024 && d >= 2048;  // few rows: spread each row over 1024 threads
+  unsigned char* rs = (unsigned char*)row_scale;
   if (w_bf16 && act_bf16) {
-    if (wide && dual) rmsnorm_kernel<true, true, 1024, true><<<M, 1024, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
-    else if (wide) rmsnorm_kernel<true, true, 1024, false><<<M, 1024, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
-    else if (dual) rmsnorm_kernel<true, true, 256, true><<<M, 256, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
-    else rmsnorm_kernel<true, true, 256, false><<<M, 256, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
+    if (wide && dual == 2) rmsnorm_kernel<true, true, 1024, 2><<<M, 1024, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows, rs, scale_groups);
+    else if (wide && dual) rmsnorm_kernel<true, true, 1024, 1><<<M, 1024, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows, rs, 0);
+    else if (wide) rmsnorm_kernel<true, true, 1024, 0><<<M, 1024, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows, rs, 0);
+    else if (dual == 2) rmsnorm_kernel<true, true, 256, 2><<<M, 256, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows, rs, scale_groups);
+    else if (dual) rmsnorm_kernel<true, true, 256, 1><<<M, 256, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows, rs, 0);
+    else rmsnorm_kernel<true, true, 256, 0><<<M, 256, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows, rs, 0);
   } else if (!w_bf16 && !act_bf16) {
-    rmsnorm_kernel<false, false, 256, false><<<M, 256, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows);
+    rmsnorm_kernel<false, false, 256, 0><<<M, 256, 0, s>>>(x, part, nsplit, part_stride, gain, y, d, eps, rows, rs, 0);
   } else {
     return hipErrorInvalidValue;
   }
@@ -435,6 +457,41 @@ __global__ void to_h16_tiled_kernel(const uint16_t* __restrict__ src, h16_t* __r
     o = make_uint4(ow[0], ow[1], ow[2], ow[3]);
   }
   *(uint4*)(dst + wtile_offset(n, k, cols, rows)) = o;
+}
+
+// 4-bit copy of a tiled fp16 weight matrix for the low-half contraction of the large-tile GEMM: one workgroup per
+// row; the row's largest magnitude fixes its scale byte, every group of four consecutive k becomes one 16-bit word of
+// nibbles, and the words are laid out like a tiled matrix with cols / 4 columns (so cols % 512 == 0).
+__global__ __launch_bounds__(256) void to_w4_tiled_kernel(const h16_t* __restrict__ src, uint16_t* __restrict__ dst,
+                                                          unsigned char* __restrict__ row_scale, int rows, int cols) {
+  __shared__ float red[4];
+  const int n = blockIdx.x;
+  float am = 0.f;
+  for (int k = threadIdx.x * 4; k < cols; k += 1024) {
+    const uint2 v = *(const uint2*)(src + wtile_offset(n, k, cols, rows));
+    am = fmaxf(am, fmaxf(fmaxf(fabsf(h16_to_f32((h16_t)(v.x & 0xffff))), fabsf(h16_to_f32((h16_t)(v.x >> 16)))),
+                         fmaxf(fabsf(h16_to_f32((h16_t)(v.y & 0xffff))), fabsf(h16_to_f32((h16_t)(v.y >> 16))))));
+  }
+  am = wave_max(am);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = am;
+  __syncthreads();
+  am = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  const uint32_t sb = fp4_scale_byte(am);
+  const float inv = fp4_inv_scale(sb);
+  for (int k = threadIdx.x * 4; k < cols; k += 1024) {
+    const uint2 v = *(const uint2*)(src + wtile_offset(n, k, cols, rows));
+    dst[wtile_offset(n, k >> 2, cols >> 2, rows)] =
+        (uint16_t)(fp4_code(h16_to_f32((h16_t)(v.x & 0xffff)) * inv) | (fp4_code(h16_to_f32((h16_t)(v.x >> 16)) * inv) << 4) |
+                   (fp4_code(h16_to_f32((h16_t)(v.y & 0xffff)) * inv) << 8) | (fp4_code(h16_to_f32((h16_t)(v.y >> 16)) * inv) << 12));
+  }
+  if (threadIdx.x == 0) row_scale[n] = (unsigned char)sb;
+}
+
+hipError_t launch_to_w4_tiled(hipStream_t s, const void* src_tiled_h16, void* dst, void* row_scale, int rows, int cols) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  if (rows % 16 || cols % 512 || !src_tiled_h16 || !dst || !row_scale) return hipErrorInvalidValue;
+  to_w4_tiled_kernel<<<rows, 256, 0, s>>>((const h16_t*)src_tiled_h16, (uint16_t*)dst, (unsigned char*)row_scale, rows, cols);
+  return hipGetLastError();
 }
 
 hipError_t launch_to_h16_tiled(hipStream_t s, const void* src, int src_is_h16, void* dst, int rows, int cols, const void* A,

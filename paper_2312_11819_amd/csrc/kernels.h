@@ -35,6 +35,13 @@ struct RopeEpi {
   int max_blocks, n_blocks, Hq, Hkv;
 };
 hipError_t launch_gemm_h16_qkv_rope(hipStream_t s, const void* A, const void* W, int M, int K, const RopeEpi& re);
+// The large-tile GEMM with the low halves of A in the 4-bit side format (common.h): A rows are [hi (K) | lo4 (K / 2
+// bytes) | unused] at a pitch of 2 K halves, a_scale their scale bytes (fp4_row_scale_offset order over scale_groups
+// 128-row groups, scale_groups >= 2 ceil(M / 256)), W the tiled fp16 matrix, W4 / w_scale its 4-bit copy
+// (launch_to_w4_tiled).  out = hi W^T + lo4 W4^T with epi EPI_STORE_F32 / EPI_RESID_F32, or the QKV form (EPI_QKV_ROPE,
+// re as in launch_gemm_h16_qkv_rope, out unused).  K % 512 == 0, N % 256 == 0.
+hipError_t launch_gemm_h16_lo4(hipStream_t s, const void* A, const void* W, const void* W4, const void* w_scale,
+                               const void* a_scale, int scale_groups, void* out, int M, int N, int K, int epi, const RopeEpi* re);
 // Split-K form of the large-tile GEMM for a few hundred rows: fp32 partial sums part[ks][plane_rows][N], ks < nsplit
 // (no split may be empty: take nsplit from gemm_tiled_pick_split), N % 256 == 0, K % 128 == 0; the consumer adds the planes.
 hipError_t launch_gemm_h16_splitk(hipStream_t s, const void* A, const void* W, float* part, int M, int N, int K, int a_dual,
@@ -61,10 +68,12 @@ hipError_t launch_pack_tokens2(hipStream_t s, const int* query_tokens, int Lmax,
 hipError_t launch_embed(hipStream_t s, const int* ids, const void* table, int w_bf16, float* x, int M, int d, int vocab,
                         int* err_flag);
 // x[m] += sum_{s<nsplit} part[s][m][:] (if part), then y = rmsnorm(x) * gain.  rows[m] (optional) selects
-// source rows of x (gather); then x is not updated.  dual (16-bit activations only): y rows are [hi (d) | lo (d)].
+// source rows of x (gather); then x is not updated.  dual (16-bit activations only): 1 = y rows are [hi (d) | lo (d)]
+// fp16 pairs; 2 = [hi (d) | 4-bit low halves (d / 2 bytes) | unused] at the same row pitch, with one scale byte per
+// (row, 128 columns) written to row_scale in the order of fp4_row_scale_offset(row, group, scale_groups) (common.h).
 hipError_t launch_rmsnorm(hipStream_t s, float* x, const float* part, int nsplit, size_t part_stride,
                           const void* gain, int w_bf16, void* y, int act_bf16, int M, int d, float eps, const int* rows,
-                          int dual);
+                          int dual, void* row_scale = nullptr, int scale_groups = 0);
 // qkv fp32 [M, (Hq+2Hkv)h] (+ optional partial sums) -> rotated q and the paged KV cache.  16-bit mode: q_out is
 // [M, Hq, 2, h] fp16 (hi | lo pair per head); fp32 mode: [M, Hq, h] floats.
 hipError_t launch_rope_append(hipStream_t s, const float* qkv, const float* part, int nsplit, size_t part_stride,
@@ -82,6 +91,9 @@ hipError_t launch_advance(hipStream_t s, int* seq_len, int* step, int B);
 // cols % 128 == 0; src and dst must not overlap.
 hipError_t launch_to_h16_tiled(hipStream_t s, const void* src, int src_is_h16, void* dst, int rows, int cols, const void* A,
                                const void* B, int rank, float scale, int row0);
+// 4-bit (e2m1) copy of a tiled fp16 matrix, rows * cols / 2 bytes in the tiled order of a matrix with cols / 4 16-bit
+// columns, and one scale byte per row (common.h); cols % 512 == 0.
+hipError_t launch_to_w4_tiled(hipStream_t s, const void* src_tiled_h16, void* dst, void* row_scale, int rows, int cols);
 
 // One layer's pool is [Hkv][n_blocks] pages: the pages a sequence gets from consecutive block ids are contiguous per
 // KV head, so a workgroup streams one contiguous region and different workgroups spread over the memory channels.
@@ -94,9 +106,11 @@ hipError_t launch_attn_decode_fused_h16(hipStream_t s, const float* qkv_part, in
                                         const float* cos_t, const float* sin_t, void* kv_pool_layer,
                                         const int* block_table, int max_blocks, int n_blocks, const int* seq_len, void* out,
                                         int B, int Hq, int Hkv);
+// out rows are [hi (Hq*128) | lo (Hq*128)] fp16 pairs; with row_scale the low halves take the 4-bit side format
+// instead ([hi | lo4 (Hq*64 bytes) | unused], one scale byte per (row, head), see launch_rmsnorm).
 hipError_t launch_attn_prefill_h16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
                                     int max_blocks, int n_blocks, const int* cu_seqlens, const int* seq_ids, void* out, int nseq,
-                                    int max_len, int Hq, int Hkv);
+                                    int max_len, int Hq, int Hkv, void* row_scale = nullptr, int scale_groups = 0);
 // fp32 path: one wavefront per (row, query head); row_pos[m] = position of the row's token.
 hipError_t launch_attn_f32(hipStream_t s, const float* q, const float* kv_pool_layer, const int* block_table,
                            int max_blocks, int n_blocks, const int* row_pos, const int* row_seq, float* out, int M, int Hq, int Hkv,

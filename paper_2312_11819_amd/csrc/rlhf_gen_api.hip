@@ -41,6 +41,12 @@ struct rlhf_gen_ctx {
   std::vector<const void*> attn_norm, wqkv, wo, ffn_norm, w_gate_up, w_down;
   // caller's bf16 matrices; in bf16 mode the members above point at fp16 working copies instead
   std::vector<const void*> src_wqkv, src_wo, src_w_gate_up, src_w_down;
+  // Prefill contracts the low halves of the two pair-input projections in the 4-bit side format (common.h): 4-bit
+  // copies of wqkv and wo with a scale byte per row, and the scale bytes of the activation rows' low halves.
+  bool lo4 = false;
+  std::vector<char*> w4_qkv, w4_wo, ws_qkv, ws_wo;
+  char* a_scale = nullptr;
+  int scale_groups = 0;
   const void* src_lm_head = nullptr;
 
   // device memory owned by the context
@@ -257,13 +263,19 @@ int forward_layers_generic(rlhf_gen_ctx* c, const RowSet& r) {
   for (int l = 0; l < g.n_layers; ++l) {
     char* pool = c->kv_pool + (size_t)l * c->layer_pool_bytes;
     // 16-bit mode: the inputs of the QKV and output projections travel as fp16 hi|lo pairs
+    const bool lo4 = c->lo4 && r.prefill;   // (rows that attend through the decode kernel keep fp16 pairs)
     LAUNCH(c, launch_rmsnorm(s, c->x, nullptr, 0, 0, c->attn_norm[l], c->bf16, c->y, c->bf16, r.M, d, g.rms_eps, nullptr,
-                             c->bf16), "rmsnorm");
+                             lo4 ? 2 : c->bf16, c->a_scale, c->scale_groups), "rmsnorm");
     int rc = RLHF_GEN_OK;
     if (c->bf16) {
       // 16-bit mode: rotation and cache append are the projection's epilogue (head_dim is 128 there)
       const RopeEpi re{r.row_pos, r.row_seq, c->d_cos, c->d_sin, c->qb, pool, w_table(c), c->max_blocks, c->n_blocks, Hq, Hkv};
-      LAUNCH(c, launch_gemm_h16_qkv_rope(s, c->y, c->wqkv[l], r.M, d, re), "gemm_qkv_rope");
+      if (lo4) {
+        LAUNCH(c, launch_gemm_h16_lo4(s, c->y, c->wqkv[l], c->w4_qkv[l], c->ws_qkv[l], c->a_scale, c->scale_groups, nullptr, r.M,
+                                      qkv_w, d, EPI_QKV_ROPE, &re), "gemm_qkv_rope lo4");
+      } else {
+        LAUNCH(c, launch_gemm_h16_qkv_rope(s, c->y, c->wqkv[l], r.M, d, re), "gemm_qkv_rope");
+      }
     } else {
       rc = gemm_any(c, c->y, c->wqkv[l], c->qkv, r.M, qkv_w, d, EPI_STORE_F32, 0);
       if (rc) return rc;
@@ -275,13 +287,18 @@ int forward_layers_generic(rlhf_gen_ctx* c, const RowSet& r) {
                                 r.row_seq, (float*)c->ab, r.M, Hq, Hkv, h), "attn_f32");
     } else if (r.prefill) {
       LAUNCH(c, launch_attn_prefill_h16(s, c->qb, pool, w_table(c), c->max_blocks, c->n_blocks, r.cu, r.seq_ids, c->ab, r.nseq,
-                                         r.max_len, Hq, Hkv), "attn_prefill");
+                                         r.max_len, Hq, Hkv, lo4 ? c->a_scale : nullptr, c->scale_groups), "attn_prefill");
     } else {
       LAUNCH(c, launch_attn_decode_h16(s, c->qb, pool, w_table(c), c->max_blocks, c->n_blocks, w_seq_len(c), c->ab, r.M, Hq, Hkv),
              "attn_decode");
     }
-    rc = gemm_any(c, c->ab, c->wo[l], c->x, r.M, d, Hq * h, EPI_RESID_F32, c->bf16);
-    if (rc) return rc;
+    if (lo4) {
+      LAUNCH(c, launch_gemm_h16_lo4(s, c->ab, c->wo[l], c->w4_wo[l], c->ws_wo[l], c->a_scale, c->scale_groups, c->x, r.M, d,
+                                    Hq * h, EPI_RESID_F32, nullptr), "gemm_wo lo4");
+    } else {
+      rc = gemm_any(c, c->ab, c->wo[l], c->x, r.M, d, Hq * h, EPI_RESID_F32, c->bf16);
+      if (rc) return rc;
+    }
     LAUNCH(c, launch_rmsnorm(s, c->x, nullptr, 0, 0, c->ffn_norm[l], c->bf16, c->y, c->bf16, r.M, d, g.rms_eps, nullptr, 0),
            "rmsnorm");
     if (c->bf16) {
@@ -855,6 +872,15 @@ static int convert_matrix(rlhf_gen_ctx* c, const void* src, void* dst, int rows,
   return RLHF_GEN_OK;
 }
 
+// 4-bit copies of layer l's pair-input projections, from their fp16 working copies.
+static int convert_w4(rlhf_gen_ctx* c, int l) {
+  const rlhf_gen_cfg& g = c->cfg;
+  const int qkv_w = (g.n_heads + 2 * g.n_kv_heads) * g.head_dim, attn_w = g.n_heads * g.head_dim;
+  LAUNCH(c, launch_to_w4_tiled(c->stream, c->wqkv[l], c->w4_qkv[l], c->ws_qkv[l], qkv_w, g.d_model), "to_w4_tiled qkv");
+  LAUNCH(c, launch_to_w4_tiled(c->stream, c->wo[l], c->w4_wo[l], c->ws_wo[l], g.d_model, attn_w), "to_w4_tiled wo");
+  return RLHF_GEN_OK;
+}
+
 // Every device and pinned-host allocation of a context, in one place.  With c->dry_run set nothing is allocated or
 // launched and c->dev_bytes ends up as the context's device footprint.
 static int allocate_all(rlhf_gen_ctx* c) {
@@ -895,11 +921,23 @@ static int allocate_all(rlhf_gen_ctx* c) {
       *dst = d;
       return c->dry_run ? RLHF_GEN_OK : convert_matrix(c, src, d, rows, cols, nullptr, 0.f);
     };
+    // the 4-bit low-half phase of the prefill GEMMs needs k extents that are multiples of 512 and whole 256-column tiles
+    const int attn_w = g.n_heads * g.head_dim;
+    c->lo4 = !(g.flags & RLHF_GEN_FLAG_PREFILL_FP16_PAIRS) && g.d_model % 512 == 0 && attn_w % 512 == 0 && qkv_w % 256 == 0 &&
+             g.d_model % 256 == 0;
+    c->w4_qkv.assign(g.n_layers, nullptr); c->w4_wo = c->ws_qkv = c->ws_wo = c->w4_qkv;
     for (int l = 0; l < g.n_layers; ++l) {
       A_(convert(c->src_wqkv[l], &c->wqkv[l], qkv_w, g.d_model));
-      A_(convert(c->src_wo[l], &c->wo[l], g.d_model, g.n_heads * g.head_dim));
+      A_(convert(c->src_wo[l], &c->wo[l], g.d_model, attn_w));
       A_(convert(c->src_w_gate_up[l], &c->w_gate_up[l], 2 * g.d_ffn, g.d_model));
       A_(convert(c->src_w_down[l], &c->w_down[l], g.d_model, g.d_ffn));
+      if (c->lo4) {
+        A_(dev_alloc(c, &c->w4_qkv[l], (size_t)qkv_w * g.d_model / 2, false));
+        A_(dev_alloc(c, &c->ws_qkv[l], (size_t)qkv_w, false));
+        A_(dev_alloc(c, &c->w4_wo[l], (size_t)g.d_model * attn_w / 2, false));
+        A_(dev_alloc(c, &c->ws_wo[l], (size_t)g.d_model, false));
+        if (!c->dry_run) A_(convert_w4(c, l));
+      }
     }
     A_(convert(c->src_lm_head, &c->lm_head, g.vocab, g.d_model));
   }
@@ -925,6 +963,12 @@ static int allocate_all(rlhf_gen_ctx* c) {
   A_(dev_alloc(c, &c->yl, as * ((size_t)g.max_batch + 256) * g.d_model, true));
   A_(dev_alloc(c, &c->qb, 2 * as * rows * g.n_heads * g.head_dim, true));
   A_(dev_alloc(c, &c->ab, 2 * as * rows * g.n_heads * g.head_dim, true));
+  if (c->lo4) {
+    // scale bytes of the activation rows' 4-bit low halves: one per (row, 128 columns), zero-filled (rows past the end of
+    // a chunk are multiplied into output rows that are never stored)
+    c->scale_groups = (int)(rows / 128);
+    A_(dev_alloc(c, &c->a_scale, rows * (size_t)(std::max(g.d_model, g.n_heads * g.head_dim) / 128), true));
+  }
   A_(dev_alloc(c, &c->hb, as * rows * g.d_ffn, true));
   A_(dev_alloc(c, &c->logits, 4 * (size_t)g.max_batch * g.vocab, true));
   c->score_cap = 1024;
@@ -1561,6 +1605,7 @@ int rlhf_gen_update_weights(rlhf_gen_ctx* c, const rlhf_gen_weights* w, const rl
       if ((rc = refresh(w->w_gate_up[l], &c->w_gate_up[l], 2 * g.d_ffn, g.d_model, pair_of(lora ? lora->w_gate_up : nullptr, l)))) return rc;
       if ((rc = refresh(w->w_down[l], &c->w_down[l], g.d_model, g.d_ffn, pair_of(lora ? lora->w_down : nullptr, l)))) return rc;
       c->src_wqkv[l] = w->wqkv[l]; c->src_wo[l] = w->wo[l]; c->src_w_gate_up[l] = w->w_gate_up[l]; c->src_w_down[l] = w->w_down[l];
+      if (c->lo4 && (rc = convert_w4(c, l))) return rc;
     }
     if ((rc = refresh(w->lm_head, &c->lm_head, g.vocab, g.d_model, (lora && lora->lm_head.a) ? &lora->lm_head : nullptr))) return rc;
     c->src_lm_head = w->lm_head;
@@ -1642,6 +1687,37 @@ int rlhf_gen_op_gemm(void* stream, int kind, const void* A, const void* W, void*
                                epilogue == EPI_SWIGLU ? 0 : nsplit, a_pairs);
   else if (kind == RLHF_GEN_GEMM_FP32) e = launch_gemm_f32(s, (const float*)A, (const float*)W, (float*)out, M, N, K, epilogue == EPI_RESID_F32);
   else return RLHF_GEN_E_INVALID;
+  if (e == hipErrorInvalidValue) return RLHF_GEN_E_UNSUPPORTED;
+  return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;
+}
+
+int rlhf_gen_op_tile_weights4(void* stream, const void* w_tiled, void* w4, void* w_scale, int32_t N, int32_t K) {
+  if (!w_tiled || !w4 || !w_scale || N < 16 || K < 512 || N % 16 || K % 512) return RLHF_GEN_E_INVALID;
+  hipError_t e = launch_to_w4_tiled((hipStream_t)stream, w_tiled, w4, w_scale, N, K);
+  return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;
+}
+
+int rlhf_gen_op_rmsnorm_lo4(void* stream, const float* x, const void* gain_bf16, void* y, void* row_scale, int32_t scale_groups,
+                            int32_t M, int32_t d, float eps) {
+  if (!x || !gain_bf16 || !y || !row_scale || M < 1 || d < 128 || d > 8192 || d % 128 || scale_groups < (M + 127) / 128)
+    return RLHF_GEN_E_INVALID;
+  // (the kernel writes x back only when it adds partial sums, which this call never passes)
+  hipError_t e = launch_rmsnorm((hipStream_t)stream, const_cast<float*>(x), nullptr, 0, 0, gain_bf16, 1, y, 1, M, d, eps, nullptr, 2,
+                                row_scale, scale_groups);
+  if (e == hipErrorInvalidValue) return RLHF_GEN_E_UNSUPPORTED;
+  return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;
+}
+
+int rlhf_gen_op_gemm_lo4(void* stream, const void* A, const void* W, const void* W4, const void* w_scale, const void* a_scale,
+                         int32_t scale_groups, float* out, int32_t M, int32_t N, int32_t K, int32_t epilogue) {
+  if (!A || !W || !W4 || !w_scale || !a_scale || !out || M < 1 || N < 1 || K < 1) return RLHF_GEN_E_INVALID;
+  if (epilogue != EPI_STORE_F32 && epilogue != EPI_RESID_F32) return RLHF_GEN_E_INVALID;
+  static bool configured = false;
+  if (!configured) {
+    if (gemm_configure() != hipSuccess) return RLHF_GEN_E_DEVICE;
+    configured = true;
+  }
+  hipError_t e = launch_gemm_h16_lo4((hipStream_t)stream, A, W, W4, w_scale, a_scale, scale_groups, out, M, N, K, epilogue, nullptr);
   if (e == hipErrorInvalidValue) return RLHF_GEN_E_UNSUPPORTED;
   return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;
 }

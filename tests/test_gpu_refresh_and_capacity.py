@@ -1,5 +1,7 @@
 """rlhf_gen_update_weights: the refreshed replica must behave like a context created with the new weights, and a
 refresh with adapters like the oracle run on the merged matrices."""
+import gc
+
 import pytest
 import torch
 
@@ -145,10 +147,11 @@ def test_fp32_refresh_and_error_paths(B):
 
 
 @pytest.mark.parametrize("shape,dtype,flags,batch,max_seq", [(synth.TINY, "fp32", 0, 5, 40), (BF16_SMALL, "bf16", 0, 7, 100),
-                                                             (BF16_SMALL_GQA, "bf16", 8, 130, 64)])
+                                                             (BF16_SMALL_GQA, "bf16", 8, 130, 64), (BF16_SMALL, "bf16", 0, 256, 1024)])
 def test_planner_predicts_what_init_allocates(B, shape, dtype, flags, batch, max_seq):
     """The planner's footprint at batch b is the sum init requests, so a capacity equal to it admits exactly b."""
     w = synth.weights_to(synth.make_weights(shape, 61, dtype), "cuda")
+    gc.collect()   # contexts of earlier tests that only the collector can free (they sit in cycles with caught exceptions)
     torch.cuda.synchronize()
     free0, _ = torch.cuda.mem_get_info()
     ctx = B.Context(w, shape, dtype, batch, max_seq, flags=flags)
@@ -156,7 +159,9 @@ def test_planner_predicts_what_init_allocates(B, shape, dtype, flags, batch, max
     n = ctx.rlhf_gen_context_bytes()
     b, planned = B.rlhf_gen_plan_capacity(shape, dtype, max_seq, n, 1.0, 0, flags)
     assert (b, planned) == (batch, n)
-    # what the driver really took is the request plus allocation granularity
-    assert n <= free0 - free1 <= n + (256 << 20)
+    # what the driver really took is the request plus allocation granularity - or a little less, where the runtime served
+    # small requests from memory it already held (the last case is large enough for that not to matter)
+    assert n - (32 << 20) <= free0 - free1 <= n + (256 << 20)
     b_dev, _ = B.rlhf_gen_plan_capacity(shape, dtype, max_seq, 0, 0.95, -1, flags)   # asks the device for its size
     assert b_dev > batch
+    ctx.rlhf_gen_destroy()
