@@ -128,7 +128,8 @@ template <bool FUSED, int NWV, int ROWS, bool PREFETCH>
 __global__ __launch_bounds__(64 * NWV) void attn_decode_kernel(const h16_t* __restrict__ q, char* __restrict__ pool,
                                                           const int* __restrict__ block_table, int max_blocks, int n_blocks,
                                                           const int* __restrict__ seq_len, h16_t* __restrict__ out,
-                                                          int Hq, int Hkv, float scale_log2, FusedArgs fa) {
+                                                          int Hq, int Hkv, float scale_log2, FusedArgs fa,
+                                                          unsigned char* __restrict__ row_scale, int scale_groups) {
   __shared__ float m_s[NWV][16];
   __shared__ float l_s[NWV][16];
   __shared__ float o_s[NWV][ROWS][132];
@@ -279,6 +280,36 @@ __global__ __launch_bounds__(64 * NWV) void attn_decode_kernel(const h16_t* __re
       for (int i = 0; i < 4; ++i) o_s[w][t][db * 16 + 4 * g + i] = st.o[db][i];
   }
   __syncthreads();
+  if (!FUSED && row_scale) {
+    // low halves in the 4-bit side format (row = [hi (Hq*128) | lo4 (Hq*64 bytes) | unused], one scale per (row, head)):
+    // a wavefront merges whole heads, two adjacent dimensions per lane, so that the head's largest low half is a
+    // wavefront reduction and a lane's two codes make one byte
+    for (int r = w; r < group; r += NWV) {
+      float M = m_s[0][r];
+#pragma unroll
+      for (int ww = 1; ww < NWV; ++ww) M = fmaxf(M, m_s[ww][r]);
+      float n0 = 0.f, n1 = 0.f, den = 0.f;
+#pragma unroll
+      for (int ww = 0; ww < NWV; ++ww) {
+        const float mw = m_s[ww][r];
+        const float a = (mw == -INFINITY) ? 0.f : exp2f(mw - M);
+        n0 += a * o_s[ww][r][2 * lane];
+        n1 += a * o_s[ww][r][2 * lane + 1];
+        den += a * l_s[ww][r];
+      }
+      const float v0 = n0 / den, v1 = n1 / den;
+      const h16_t h0 = f32_to_h16(v0), h1 = f32_to_h16(v1);
+      const float l0 = v0 - h16_to_f32(h0), l1 = v1 - h16_to_f32(h1);
+      const uint32_t sb = fp4_scale_byte(wave_max(fmaxf(fabsf(l0), fabsf(l1))));
+      const float is = fp4_inv_scale(sb);
+      const int head = kvh * group + r;
+      char* orow = (char*)out + (size_t)b * 4 * Hq * 128;
+      *(uint32_t*)(orow + 2 * (head * 128 + 2 * lane)) = (uint32_t)h0 | ((uint32_t)h1 << 16);
+      *(unsigned char*)(orow + 2 * Hq * 128 + head * 64 + lane) = (unsigned char)(fp4_code(l0 * is) | (fp4_code(l1 * is) << 4));
+      if (lane == 0) row_scale[fp4_row_scale_offset(b, head, scale_groups)] = (unsigned char)sb;
+    }
+    return;
+  }
   for (int idx = threadIdx.x; idx < group * 128; idx += 64 * NWV) {
     int r = idx >> 7, dim = idx & 127;
     float M = m_s[0][r];
@@ -456,20 +487,23 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float* __restrict__ 
 static const float LOG2E = 1.4426950408889634f;
 
 hipError_t launch_attn_decode_h16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
-                                   int max_blocks, int n_blocks, const int* seq_len, void* out, int B, int Hq, int Hkv) {
+                                   int max_blocks, int n_blocks, const int* seq_len, void* out, int B, int Hq, int Hkv,
+                                   void* row_scale, int scale_groups) {
   if (B <= 0) return hipSuccess;
   if (Hq % Hkv || Hq / Hkv > 16) return hipErrorInvalidValue;
+  if (row_scale && scale_groups * 128 < B) return hipErrorInvalidValue;
+  unsigned char* rs = (unsigned char*)row_scale;
   float scale_log2 = LOG2E / sqrtf((float)KV_HEAD_DIM);
   FusedArgs fa{};
   // (the form depends on the head counts only, never on the batch, so a sequence's result is the same bits in any batch)
   if (Hq / Hkv <= 8)
     attn_decode_kernel<false, 8, 8, false><<<dim3(Hkv, B), 512, 0, s>>>((const h16_t*)q, (char*)const_cast<void*>(kv_pool_layer),
                                                                         block_table, max_blocks, n_blocks, seq_len, (h16_t*)out,
-                                                                        Hq, Hkv, scale_log2, fa);
+                                                                        Hq, Hkv, scale_log2, fa, rs, scale_groups);
   else
     attn_decode_kernel<false, 4, 16, true><<<dim3(Hkv, B), 256, 0, s>>>((const h16_t*)q, (char*)const_cast<void*>(kv_pool_layer),
                                                                         block_table, max_blocks, n_blocks, seq_len, (h16_t*)out,
-                                                                        Hq, Hkv, scale_log2, fa);
+                                                                        Hq, Hkv, scale_log2, fa, rs, scale_groups);
   return hipGetLastError();
 }
 
@@ -482,7 +516,7 @@ hipError_t launch_attn_decode_fused_h16(hipStream_t s, const float* qkv_part, in
   float scale_log2 = LOG2E / sqrtf((float)KV_HEAD_DIM);
   FusedArgs fa{qkv_part, nsplit, part_stride, (Hq + 2 * Hkv) * KV_HEAD_DIM, cos_t, sin_t};
   attn_decode_kernel<true, 4, 16, true><<<dim3(Hkv, B), 256, 0, s>>>(nullptr, (char*)kv_pool_layer, block_table, max_blocks, n_blocks,
-                                                        seq_len, (h16_t*)out, Hq, Hkv, scale_log2, fa);
+                                                        seq_len, (h16_t*)out, Hq, Hkv, scale_log2, fa, nullptr, 0);
   return hipGetLastError();
 }
 

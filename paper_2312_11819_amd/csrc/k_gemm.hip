@@ -98,7 +98,7 @@ __global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restri
   // a_dual: A rows are [hi (K) | lo (K)]; the k loop then runs over 2K columns of A against W's K columns twice.
   constexpr int NS = DMA_NS, DIST = NS - 1, LPT = 8;  // LPT: DMA loads per thread and k-tile
   constexpr int VMS = LPT + (LO4 ? 1 : 0);            // memory operations per wavefront and stage
-  static_assert(!(LO4 && (SPLIT || EPI == EPI_SWIGLU)), "the 4-bit low-half phase exists for the plain and the QKV forms");
+  static_assert(!(LO4 && EPI == EPI_SWIGLU), "the 4-bit low-half phase exists for the plain, the split-K and the QKV forms");
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   int pid = blockIdx.x;
   int split = 0;
@@ -142,12 +142,14 @@ __global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restri
   const int nkw = K / 32;                 // k-tiles of W
   int kw0 = 0, kw1 = nkw;                 // this workgroup's k-tiles of W
   if (SPLIT) {
-    const int per = (nkw + nsplit - 1) / nsplit;
+    int per = (nkw + nsplit - 1) / nsplit;
+    if (LO4) per = (per + 3) & ~3;        // a low-half stage covers four k-tiles: splits begin at multiples of four
     kw0 = split * per;
     kw1 = min(nkw, kw0 + per);
   }
-  const int nlo = LO4 ? K / 128 : 0;      // stages of the 4-bit low-half phase
-  const int nk = SPLIT ? (kw1 - kw0) * (a_dual ? 2 : 1) : LO4 ? nkw + nlo : (a_dual ? 2 * nkw : nkw);  // k-tiles of the product
+  const int nhi = LO4 ? kw1 - kw0 : 0;    // LO4: fp16 k-tiles [kw0, kw1), then the low-half stages [kw0 / 4, kw1 / 4)
+  const int nlo = LO4 ? nhi / 4 : 0, lo0 = kw0 >> 2;
+  const int nk = LO4 ? nhi + nlo : SPLIT ? (kw1 - kw0) * (a_dual ? 2 : 1) : (a_dual ? 2 * nkw : nkw);  // k-tiles of the product
   // 4-bit W: the tiled order of a matrix with K / 4 columns, so its slabs are a quarter as long (tile tn = slab tn)
   const size_t w4_adj = LO4 ? (size_t)tn * WSLAB_RB * (size_t)((K >> 7) - (K >> 9)) * 4096 : 0;
   typedef __attribute__((address_space(3))) void lds_void;
@@ -156,15 +158,20 @@ __global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restri
   // tile KT of this wavefront's operand (past the end: the last tile again, into a stage nobody reads any more)
   auto tile_src = [&](int kt) -> const char* {
     kt = min(kt, nk - 1);
+    if (LO4) {
+      if (kt >= nhi) {
+        const int kl = lo0 + kt - nhi;
+        if (loads_a) return gbase + (size_t)K * 2 + (size_t)kl * 64;
+        return (const char*)l4.w4 + ((size_t)(kl >> 2) * (WSLAB_RB * 4096) + (size_t)(kl & 3) * 1024) - w4_adj;
+      }
+      const int kw = kw0 + kt;
+      if (loads_a) return gbase + (size_t)kw * 64;
+      return gbase + (size_t)(kw >> 2) * (WSLAB_RB * 4096) + (size_t)(kw & 3) * 1024;
+    }
     if (SPLIT) {
       const int kw = kw0 + (a_dual ? kt >> 1 : kt);
       if (loads_a) return gbase + ((a_dual && (kt & 1)) ? (size_t)K * 2 : (size_t)0) + (size_t)kw * 64;
       return gbase + (size_t)(kw >> 2) * (WSLAB_RB * 4096) + (size_t)(kw & 3) * 1024;   // (every slab is full: rows % 256 == 0)
-    }
-    if (LO4 && kt >= nkw) {
-      const int kl = kt - nkw;
-      if (loads_a) return gbase + (size_t)K * 2 + (size_t)kl * 64;
-      return (const char*)l4.w4 + ((size_t)(kl >> 2) * (WSLAB_RB * 4096) + (size_t)(kl & 3) * 1024) - w4_adj;
     }
     if (loads_a) return gbase + (size_t)kt * 64;
     const int kw = kt >= nkw ? kt - nkw : kt;
@@ -179,7 +186,7 @@ __global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restri
   char* sc_dst = smem + NS * DMA_STAGE + wave * 256;
 #define DMAS(KT, SOFF)                                                                                             \
   if (LO4) {                                                                                                       \
-    const int kl_ = min(max((KT) - nkw, 0), nlo - 1);                                                              \
+    const int kl_ = lo0 + min(max((KT) - nhi, 0), nlo - 1);                                                        \
     __builtin_amdgcn_global_load_lds((g_void*)(sa_src + (size_t)kl_ * sa_stride), (lds_void*)(sc_dst + ((SOFF) >> 5)), 4, 0, 0); \
   }
 
@@ -273,7 +280,7 @@ __global__ __launch_bounds__(256) void gemm_h16_dma_kernel(const h16_t* __restri
   }
   {
     int kt = 0;
-    const int nk_hi = LO4 ? nkw : nk;
+    const int nk_hi = LO4 ? nhi : nk;
     for (; kt < nk_hi; ++kt) KSTAGE(MFH)
     if (LO4)
       for (; kt < nk; ++kt) KSTAGE(MF4)
@@ -431,6 +438,18 @@ hipError_t launch_large_dma_lo4(hipStream_t s, const void* A, const void* W, voi
   const int tilesM = (M + 255) / 256, tilesN = N / 256;
   kern<<<tilesM * tilesN, 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, out, M, N, K, tilesM, tilesN, 1, 1, 0,
                                           re ? *re : RopeEpi{}, *l4);
+  return hipGetLastError();
+}
+
+// split-K form with 4-bit low halves
+hipError_t launch_large_dma_split_lo4(hipStream_t s, const void* A, const void* W, float* part, int M, int N, int K, int nsplit,
+                                      int plane_rows, const Lo4Args* l4, bool configure_only = false) {
+  constexpr int SMEM = DMA_NS * DMA_STAGE + DMA_NS * 1024;
+  auto kern = gemm_h16_dma_kernel<EPI_STORE_F32, true, true>;
+  if (configure_only) return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+  const int tilesM = (M + 255) / 256, tilesN = N / 256;
+  kern<<<tilesM * tilesN * nsplit, 256, SMEM, s>>>((const h16_t*)A, (const h16_t*)W, part, M, N, K, tilesM, tilesN, 1, nsplit,
+                                                   (size_t)plane_rows * N, RopeEpi{}, *l4);
   return hipGetLastError();
 }
 
@@ -919,13 +938,29 @@ hipError_t launch_gemm_h16_qkv_rope(hipStream_t s, const void* A, const void* W,
   return launch_large_dma_qkv_rope(s, A, W, M, N, K, &re);
 }
 
-int gemm_tiled_pick_split(int M, int N, int K, int max_splits) {
+int gemm_tiled_pick_split(int M, int N, int K, int max_splits, int lo4) {
   // as many splits as it takes to give every compute unit one workgroup, none of them empty
   const int tiles = ((M + 255) / 256) * (N / 256), nkw = K / 32;
   int want = std::max(1, std::min(g_num_cu / std::max(tiles, 1), max_splits));
   want = std::min(want, nkw);
-  const int per = (nkw + want - 1) / want;
+  int per = (nkw + want - 1) / want;
+  if (lo4) per = (per + 3) & ~3;   // (the 4-bit low-half stages cover four k-tiles each)
   return (nkw + per - 1) / per;
+}
+
+hipError_t launch_gemm_h16_splitk_lo4(hipStream_t s, const void* A, const void* W, const void* W4, const void* w_scale,
+                                      const void* a_scale, int scale_groups, float* part, int M, int N, int K, int nsplit,
+                                      int plane_rows) {
+  if (M <= 0) return hipSuccess;
+  if (plane_rows <= 0) plane_rows = M;
+  if (!A || !W || !W4 || !w_scale || !a_scale || !part) return hipErrorInvalidValue;
+  if (K % 512 || N % 256 || nsplit < 1 || plane_rows < M) return hipErrorInvalidValue;
+  if (scale_groups < 2 * ((M + 255) / 256)) return hipErrorInvalidValue;
+  const int nkw = K / 32, per = ((nkw + nsplit - 1) / nsplit + 3) & ~3;
+  if ((nkw + per - 1) / per != nsplit) return hipErrorInvalidValue;   // a split would be empty
+  if ((size_t)M * 2 * K * 2 >= ((size_t)1 << 32) || (size_t)N * K * 2 >= ((size_t)1 << 32)) return hipErrorInvalidValue;
+  const Lo4Args l4{W4, (const unsigned char*)w_scale, (const unsigned char*)a_scale, scale_groups};
+  return launch_large_dma_split_lo4(s, A, W, part, M, N, K, nsplit, plane_rows, &l4);
 }
 
 hipError_t launch_gemm_h16_splitk(hipStream_t s, const void* A, const void* W, float* part, int M, int N, int K, int a_dual,
@@ -951,6 +986,7 @@ hipError_t gemm_configure() {
   if ((e = launch_large_dma_lo4<EPI_STORE_F32>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, nullptr, nullptr, true)) != hipSuccess) return e;
   if ((e = launch_large_dma_lo4<EPI_RESID_F32>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, nullptr, nullptr, true)) != hipSuccess) return e;
   if ((e = launch_large_dma_lo4<EPI_QKV_ROPE>(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, nullptr, nullptr, true)) != hipSuccess) return e;
+  if ((e = launch_large_dma_split_lo4(nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, nullptr, true)) != hipSuccess) return e;
   {
     int dev = 0;
     hipDeviceProp_t prop;

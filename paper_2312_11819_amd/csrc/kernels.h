@@ -46,7 +46,12 @@ hipError_t launch_gemm_h16_lo4(hipStream_t s, const void* A, const void* W, cons
 // (no split may be empty: take nsplit from gemm_tiled_pick_split), N % 256 == 0, K % 128 == 0; the consumer adds the planes.
 hipError_t launch_gemm_h16_splitk(hipStream_t s, const void* A, const void* W, float* part, int M, int N, int K, int a_dual,
                                   int nsplit, int plane_rows = 0);
-int gemm_tiled_pick_split(int M, int N, int K, int max_splits = 16);
+int gemm_tiled_pick_split(int M, int N, int K, int max_splits = 16, int lo4 = 0);
+// The same with the low halves of A in the 4-bit side format (launch_gemm_h16_lo4); nsplit from
+// gemm_tiled_pick_split(..., lo4 = 1): the splits begin at multiples of 128 columns.  K % 512 == 0.
+hipError_t launch_gemm_h16_splitk_lo4(hipStream_t s, const void* A, const void* W, const void* W4, const void* w_scale,
+                                      const void* a_scale, int scale_groups, float* part, int M, int N, int K, int nsplit,
+                                      int plane_rows = 0);
 // Weight-streaming GEMM for M <= 256 rows: writes fp32 partial sums part[ks][M][Nw] (Nw = rows of W)
 // for ks < nsplit; the consumer kernel adds them.  nsplit = 0 selects the fused SwiGLU form: W = [2F, K]
 // (gate rows, then up rows; Nw = 2F), no split, and `part` receives fp16 [M, F] = silu(gate) * up.
@@ -98,8 +103,10 @@ hipError_t launch_to_w4_tiled(hipStream_t s, const void* src_tiled_h16, void* ds
 // One layer's pool is [Hkv][n_blocks] pages: the pages a sequence gets from consecutive block ids are contiguous per
 // KV head, so a workgroup streams one contiguous region and different workgroups spread over the memory channels.
 // ---- attention over the paged cache (16-bit mode: q [rows, Hq, 2, 128] hi|lo pairs, out [rows, 2, Hq*128] hi|lo) ----
+// (row_scale != NULL: the low halves of out in the 4-bit side format, as launch_attn_prefill_h16 writes them)
 hipError_t launch_attn_decode_h16(hipStream_t s, const void* q, const void* kv_pool_layer, const int* block_table,
-                                   int max_blocks, int n_blocks, const int* seq_len, void* out, int B, int Hq, int Hkv);
+                                   int max_blocks, int n_blocks, const int* seq_len, void* out, int B, int Hq, int Hkv,
+                                   void* row_scale = nullptr, int scale_groups = 0);
 // Decode attention that starts from the QKV projection's partial sums: adds them, applies RoPE, appends the new
 // key/value to the cache and attends (no separate rope_append launch).
 hipError_t launch_attn_decode_fused_h16(hipStream_t s, const float* qkv_part, int nsplit, size_t part_stride,

@@ -341,6 +341,9 @@ int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
   const int qkv_w = (Hq + 2 * Hkv) * h;
   hipStream_t s = c->stream;
   const bool tiles = decode_uses_tiles(c, B);
+  // the split-K tile GEMMs of the two pair-input projections take the 4-bit low halves of the prefill (the fused
+  // RoPE + attention kernel writes fp16 pairs only)
+  const bool lo4 = tiles && c->lo4 && !(c->cfg.flags & RLHF_GEN_FLAG_FUSED_ROPE);
   const int ks_qkv = tiles ? c->kt_qkv : c->ks_qkv, ks_wo = tiles ? c->kt_wo : c->ks_wo;
   const int ks_down = tiles ? c->kt_down : c->ks_down;
   prof_mark(c, -1);
@@ -350,9 +353,12 @@ int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
   for (int l = 0; l < g.n_layers; ++l) {
     char* pool = c->kv_pool + (size_t)l * c->layer_pool_bytes;
     LAUNCH(c, launch_rmsnorm(s, c->x, pending ? c->part : nullptr, pending, (size_t)B * d, c->attn_norm[l], 1, c->y, 1,
-                             B, d, g.rms_eps, nullptr, 1), "rmsnorm");
+                             B, d, g.rms_eps, nullptr, lo4 ? 2 : 1, c->a_scale, c->scale_groups), "rmsnorm");
     prof_mark(c, RLHF_GEN_PROF_NORM);
-    if (tiles) {
+    if (lo4) {
+      LAUNCH(c, launch_gemm_h16_splitk_lo4(s, c->y, c->wqkv[l], c->w4_qkv[l], c->ws_qkv[l], c->a_scale, c->scale_groups, c->part, B,
+                                           qkv_w, d, ks_qkv, B), "gemm_splitk qkv lo4");
+    } else if (tiles) {
       LAUNCH(c, launch_gemm_h16_splitk(s, c->y, c->wqkv[l], c->part, B, qkv_w, d, 1, ks_qkv, B), "gemm_splitk qkv");
     } else if (int rc = skinny_pairs(c, c->y, c->wqkv[l], B, qkv_w, d, ks_qkv, "gemm_skinny qkv")) {
       return rc;
@@ -365,13 +371,16 @@ int forward_decode_streaming(rlhf_gen_ctx* c, int B) {
                                    Hkv, h, 1), "rope_append");
       prof_mark(c, RLHF_GEN_PROF_ROPE);
       LAUNCH(c, launch_attn_decode_h16(s, c->qb, pool, w_table(c), c->max_blocks, c->n_blocks, w_seq_len(c), c->ab, B, Hq,
-                                       Hkv), "attn_decode");
+                                       Hkv, lo4 ? c->a_scale : nullptr, c->scale_groups), "attn_decode");
     } else {
       LAUNCH(c, launch_attn_decode_fused_h16(s, c->part, ks_qkv, st, c->d_cos, c->d_sin, pool, w_table(c), c->max_blocks,
                                              c->n_blocks, w_seq_len(c), c->ab, B, Hq, Hkv), "attn_decode_fused");
     }
     prof_mark(c, RLHF_GEN_PROF_ATTN);
-    if (tiles) {
+    if (lo4) {
+      LAUNCH(c, launch_gemm_h16_splitk_lo4(s, c->ab, c->wo[l], c->w4_wo[l], c->ws_wo[l], c->a_scale, c->scale_groups, c->part, B, d,
+                                           Hq * h, ks_wo, B), "gemm_splitk wo lo4");
+    } else if (tiles) {
       LAUNCH(c, launch_gemm_h16_splitk(s, c->ab, c->wo[l], c->part, B, d, Hq * h, 1, ks_wo, B), "gemm_splitk wo");
     } else if (int rc = skinny_pairs(c, c->ab, c->wo[l], B, d, Hq * h, ks_wo, "gemm_skinny wo")) {
       return rc;
@@ -989,8 +998,10 @@ static int allocate_all(rlhf_gen_ctx* c) {
                  g.d_ffn % 128 == 0 && (size_t)2 * g.d_ffn * g.d_model * 2 < ((size_t)1 << 32) &&
                  (size_t)g.d_model * g.d_ffn * 2 < ((size_t)1 << 32) && (size_t)qkv_w * g.d_model * 2 < ((size_t)1 << 32);
     if (c->tile_ok) {
-      c->kt_qkv = gemm_tiled_pick_split(Bm, qkv_w, g.d_model, 8);   // (the fused RoPE + attention kernel takes up to 8 planes)
-      c->kt_wo = gemm_tiled_pick_split(Bm, g.d_model, attn_w);
+      const int l4 = c->lo4 && !(g.flags & RLHF_GEN_FLAG_FUSED_ROPE);
+      c->kt_qkv = gemm_tiled_pick_split(Bm, qkv_w, g.d_model, 8, l4);   // (the fused RoPE + attention kernel takes up to 8 planes)
+      c->kt_qkv = gemm_tiled_pick_split(Bm, qkv_w, g.d_model, 8, l4);   // (the fused RoPE + attention kernel takes up to 8 planes)
+      c->kt_wo = gemm_tiled_pick_split(Bm, g.d_model, attn_w, 16, l4);
       c->kt_gu = gemm_tiled_pick_split(Bm, 2 * g.d_ffn, g.d_model);
       c->kt_down = gemm_tiled_pick_split(Bm, g.d_model, g.d_ffn);
       pe = std::max(pe, std::max(std::max((size_t)c->kt_qkv * qkv_w, (size_t)c->kt_wo * g.d_model),
