@@ -117,6 +117,17 @@ int rlhf_gen_op_attn_prefill(void* stream, const void* q, const void* kv_pool, c
                              int32_t max_blocks, int32_t n_blocks, const int32_t* cu_seqlens, const int32_t* seq_ids, void* out,
                              int32_t nseq, int32_t max_len, int32_t Hq, int32_t Hkv);
 
+/* The two attention calls with the low halves of out in the 4-bit side format of rlhf_gen_op_gemm_lo4 (the input form
+ * of the output projection in prefill and in decode batches above 128 rows): row m of out (pitch 4 Hq 128 bytes) =
+ * [hi: Hq 128 fp16 | lo4: Hq 64 bytes | unused], one scale byte per (row, head) in row_scale at the position
+ * rlhf_gen_op_rmsnorm_lo4 documents (column group = head).  128 scale_groups must cover the rows. */
+int rlhf_gen_op_attn_decode_lo4(void* stream, const void* q, const void* kv_pool, const int32_t* block_table,
+                                int32_t max_blocks, int32_t n_blocks, const int32_t* seq_len, void* out, void* row_scale,
+                                int32_t scale_groups, int32_t B, int32_t Hq, int32_t Hkv);
+int rlhf_gen_op_attn_prefill_lo4(void* stream, const void* q, const void* kv_pool, const int32_t* block_table,
+                                 int32_t max_blocks, int32_t n_blocks, const int32_t* cu_seqlens, const int32_t* seq_ids, void* out,
+                                 void* row_scale, int32_t scale_groups, int32_t nseq, int32_t max_len, int32_t Hq, int32_t Hkv);
+
 /* Sampler on fp32 logits [B, V]: token and log-prob per row for response index *step (device int32).
  * sp is a host struct.  scratch_tok: device int32 [B] (receives a copy of the tokens). */
 int rlhf_gen_op_sample(void* stream, const float* logits, int32_t B, int32_t V, const rlhf_gen_sampling* sp,

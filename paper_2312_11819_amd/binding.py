@@ -33,6 +33,7 @@ EXPORTS = [
     "rlhf_gen_last_timing", "rlhf_gen_last_step_ms", "rlhf_gen_set_profile", "rlhf_gen_get_profile", "rlhf_gen_last_error", "rlhf_gen_destroy",
     "rlhf_gen_op_probe_stream_read", "rlhf_gen_op_probe_mfma_loop", "rlhf_gen_op_tile_weights", "rlhf_gen_op_gemm", "rlhf_gen_op_rope_append", "rlhf_gen_op_attn_decode", "rlhf_gen_op_attn_prefill",
     "rlhf_gen_op_sample", "rlhf_gen_op_gemm_static", "rlhf_gen_op_tile_weights4", "rlhf_gen_op_rmsnorm_lo4", "rlhf_gen_op_gemm_lo4",
+    "rlhf_gen_op_attn_decode_lo4", "rlhf_gen_op_attn_prefill_lo4",
 ]
 
 
@@ -129,6 +130,10 @@ def lib() -> C.CDLL:
                                          C.c_void_p, C.c_void_p, C.c_void_p]
         L.rlhf_gen_op_gemm_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                               C.c_int32, C.POINTER(C.c_int32)]
+        L.rlhf_gen_op_attn_decode_lo4.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                                  C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+        L.rlhf_gen_op_attn_prefill_lo4.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         L.rlhf_gen_op_tile_weights4.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32]
         L.rlhf_gen_op_rmsnorm_lo4.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                               C.c_int32, C.c_float]
@@ -487,6 +492,17 @@ def rlhf_gen_op_attn_prefill(q, kv_pool, block_table, max_blocks, n_blocks, cu_s
                              Hkv) -> int:
     return lib().rlhf_gen_op_attn_prefill(None, _ptr(q), _ptr(kv_pool), _ptr(block_table), max_blocks, n_blocks,
                                           _ptr(cu_seqlens), _ptr(seq_ids), _ptr(out), nseq, max_len, Hq, Hkv)
+
+
+def rlhf_gen_op_attn_decode_lo4(q, kv_pool, block_table, max_blocks, n_blocks, seq_len, out, row_scale, scale_groups, B, Hq, Hkv) -> int:
+    return lib().rlhf_gen_op_attn_decode_lo4(None, _ptr(q), _ptr(kv_pool), _ptr(block_table), max_blocks, n_blocks, _ptr(seq_len),
+                                             _ptr(out), _ptr(row_scale), scale_groups, B, Hq, Hkv)
+
+
+def rlhf_gen_op_attn_prefill_lo4(q, kv_pool, block_table, max_blocks, n_blocks, cu_seqlens, seq_ids, out, row_scale, scale_groups,
+                                 nseq, max_len, Hq, Hkv) -> int:
+    return lib().rlhf_gen_op_attn_prefill_lo4(None, _ptr(q), _ptr(kv_pool), _ptr(block_table), max_blocks, n_blocks, _ptr(cu_seqlens),
+                                              _ptr(seq_ids), _ptr(out), _ptr(row_scale), scale_groups, nseq, max_len, Hq, Hkv)
 
 
 def rlhf_gen_op_sample(logits, sampling: Sampling, step, tok_out, lp_out, scratch_tok) -> int:

@@ -1763,6 +1763,27 @@ int rlhf_gen_op_attn_prefill(void* stream, const void* q, const void* kv_pool, c
   return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;
 }
 
+int rlhf_gen_op_attn_decode_lo4(void* stream, const void* q, const void* kv_pool, const int32_t* block_table,
+                                int32_t max_blocks, int32_t n_blocks, const int32_t* seq_len, void* out, void* row_scale,
+                                int32_t scale_groups, int32_t B, int32_t Hq, int32_t Hkv) {
+  if (!q || !kv_pool || !block_table || !seq_len || !out || !row_scale || scale_groups < 1) return RLHF_GEN_E_INVALID;
+  hipError_t e = launch_attn_decode_h16((hipStream_t)stream, q, kv_pool, block_table, max_blocks, n_blocks, seq_len, out, B, Hq, Hkv,
+                                         row_scale, scale_groups);
+  if (e == hipErrorInvalidValue) return RLHF_GEN_E_UNSUPPORTED;
+  return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;
+}
+
+int rlhf_gen_op_attn_prefill_lo4(void* stream, const void* q, const void* kv_pool, const int32_t* block_table,
+                                 int32_t max_blocks, int32_t n_blocks, const int32_t* cu_seqlens, const int32_t* seq_ids, void* out,
+                                 void* row_scale, int32_t scale_groups, int32_t nseq, int32_t max_len, int32_t Hq, int32_t Hkv) {
+  if (!q || !kv_pool || !block_table || !cu_seqlens || !seq_ids || !out || !row_scale || scale_groups < 1) return RLHF_GEN_E_INVALID;
+  if ((int64_t)nseq * max_len > (int64_t)128 * scale_groups) return RLHF_GEN_E_INVALID;   // (an upper bound of the number of rows)
+  hipError_t e = launch_attn_prefill_h16((hipStream_t)stream, q, kv_pool, block_table, max_blocks, n_blocks, cu_seqlens, seq_ids, out,
+                                          nseq, max_len, Hq, Hkv, row_scale, scale_groups);
+  if (e == hipErrorInvalidValue) return RLHF_GEN_E_UNSUPPORTED;
+  return e == hipSuccess ? RLHF_GEN_OK : RLHF_GEN_E_DEVICE;
+}
+
 int rlhf_gen_op_sample(void* stream, const float* logits, int32_t B, int32_t V, const rlhf_gen_sampling* sp,
                        const int32_t* step, int32_t* tok_out, float* logprob_out, int32_t* scratch_tok) {
   if (!logits || !sp || !step || !tok_out || !logprob_out || !scratch_tok || B < 1 || V < 1) return RLHF_GEN_E_INVALID;

@@ -215,3 +215,63 @@ def test_prefill_with_4bit_low_halves_is_as_close_to_the_oracle_as_fp16_pairs(B)
     print(f"\n4-bit low halves: max {mx[0]:.5f} rms {rms[0]:.6f}; fp16 pairs: max {mx[1]:.5f} rms {rms[1]:.6f}")
     assert max(mx) < 3e-2
     assert rms[0] < 1.15 * rms[1]
+
+
+@pytest.mark.parametrize("Hq,Hkv,lens", [(2, 2, [1, 17, 64, 5]), (8, 1, [33, 100]), (4, 2, [16, 48, 31, 130])])
+def test_attention_outputs_in_the_4bit_pair_form(B, Hq, Hkv, lens):
+    """Prefill and decode attention write their output rows either as fp16 pairs or with 4-bit low halves.  On the same
+    cache and queries the high halves are the same bits, every scale byte is the smallest power of two that covers its
+    (row, head) group of fp16 low halves, and the decoded 4-bit low halves follow the fp16 ones to within the format's
+    step.  (The pair form itself is checked against the CPU definition in tests/test_gpu_ops.py.)"""
+    from tests.gpu_util import rope_tables
+    h, nseq = 128, len(lens)
+    width = (Hq + 2 * Hkv) * h
+    T = sum(lens)
+    maxpos = max(lens) + 1
+    max_blocks = (maxpos + 15) // 16
+    n_blocks = nseq * max_blocks + 3
+    g = torch.Generator().manual_seed(11)
+    table = torch.randperm(n_blocks, generator=g)[: nseq * max_blocks].reshape(nseq, max_blocks).to(torch.int32)
+    qkv = torch.randn(T + nseq, width, generator=g)
+    cos_t, sin_t = rope_tables(maxpos, h)
+    row_seq = torch.tensor([b for b, L in enumerate(lens) for _ in range(L)], dtype=torch.int32)
+    row_pos = torch.tensor([p for L in lens for p in range(L)], dtype=torch.int32)
+    cu = torch.tensor([0] + list(torch.tensor(lens).cumsum(0)), dtype=torch.int32)
+    pool = torch.zeros(Hkv, n_blocks, 8192, dtype=torch.uint8, device="cuda")
+    dev = lambda t: t.cuda().contiguous()
+    qkv_d, cos_d, sin_d, table_d = dev(qkv), dev(cos_t), dev(sin_t), dev(table)
+    q_out = torch.zeros(T, Hq, 2, h, dtype=torch.float16, device="cuda")
+    assert B.rlhf_gen_op_rope_append(qkv_d[:T].contiguous(), dev(row_pos), dev(row_seq), cos_d, sin_d, q_out, pool,
+                                     table_d, max_blocks, n_blocks, T, Hq, Hkv, h, True) == 0
+    seq_ids = torch.arange(nseq, dtype=torch.int32, device="cuda")
+    groups = 2 * ((nseq * max(lens) + 255) // 256)
+
+    def both_forms(rows, pair_call, lo4_call):
+        pair = torch.zeros(rows, 2, Hq * h, dtype=torch.float16, device="cuda")
+        assert pair_call(pair) == 0
+        four = torch.zeros(rows, 4 * Hq * h, dtype=torch.uint8, device="cuda")
+        sc = torch.zeros(Hq * groups * 128, dtype=torch.uint8, device="cuda")
+        assert lo4_call(four, sc) == 0
+        torch.cuda.synchronize()
+        hi, lo, sb = _decode_rows(four, sc, rows, Hq * h, groups)
+        p = pair.cpu().double()
+        assert torch.equal(hi, p[:, 0])
+        s = torch.exp2((sb - 127).double())
+        amax = p[:, 1].reshape(rows, Hq, h).abs().amax(-1)
+        assert (6 * s >= amax * (1 - 1e-2)).all() and (3 * s <= amax * (1 + 1e-2) + 1e-12).all()
+        err = (lo - p[:, 1]).reshape(rows, Hq, h)
+        # the fp16 low half is itself rounded (2^-11 of it), the 4-bit one to the nearest of 0, .5, 1, 1.5, 2, 3, 4, 6 scales
+        assert (err.abs().amax(-1) <= s * 1.02 + 1e-9).all()
+        assert err.pow(2).mean().sqrt() < 0.3 * p[:, 1].pow(2).mean().sqrt()
+
+    both_forms(T,
+               lambda o: B.rlhf_gen_op_attn_prefill(q_out, pool, table_d, max_blocks, n_blocks, dev(cu), seq_ids, o, nseq, max(lens), Hq, Hkv),
+               lambda o, sc: B.rlhf_gen_op_attn_prefill_lo4(q_out, pool, table_d, max_blocks, n_blocks, dev(cu), seq_ids, o, sc, groups, nseq,
+                                                           max(lens), Hq, Hkv))
+    qd = torch.zeros(nseq, Hq, 2, h, dtype=torch.float16, device="cuda")
+    seq_len = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    assert B.rlhf_gen_op_rope_append(qkv_d[T:].contiguous(), seq_len, None, cos_d, sin_d, qd, pool, table_d, max_blocks,
+                                     n_blocks, nseq, Hq, Hkv, h, True) == 0
+    both_forms(nseq,
+               lambda o: B.rlhf_gen_op_attn_decode(qd, pool, table_d, max_blocks, n_blocks, seq_len, o, nseq, Hq, Hkv),
+               lambda o, sc: B.rlhf_gen_op_attn_decode_lo4(qd, pool, table_d, max_blocks, n_blocks, seq_len, o, sc, groups, nseq, Hq, Hkv))
