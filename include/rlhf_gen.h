@@ -72,7 +72,12 @@ typedef struct {
   int32_t dtype;          /* RLHF_GEN_DTYPE_*: storage type of the caller's weights.  bf16: the projection matrices are
                              converted once to fp16 working copies in a tiled layout (exact unless |w| < 2^-17), every MFMA operand,
                              activation and the KV cache is fp16 (bf16's 8 significant bits cannot meet the parity
-                             tolerance over 32 layers), accumulation / residual / softmax / logits are fp32.  Like any
+                             tolerance over 32 layers), accumulation / residual / softmax / logits are fp32.  Four
+                             activation tensors (the inputs of the QKV and output projections, the rotated queries, the
+                             attention probabilities) travel as fp16 pairs hi + lo; where d_model and n_heads * head_dim
+                             are multiples of 512, prefill and scoring contract the low halves of the two projection
+                             inputs in a 4-bit format against 4-bit copies of wqkv and wo made at init (a quarter of
+                             their fp16 size; RLHF_GEN_FLAG_PREFILL_FP16_PAIRS turns that off).  Like any
                              fp16 inference it assumes activations within +-65504 (they saturate there).  fp32 is a
                              plain-ALU path meant for small models */
   int32_t max_batch;      /* largest B any call will pass */
@@ -271,7 +276,8 @@ int rlhf_gen_update_weights(rlhf_gen_ctx* ctx, const rlhf_gen_weights* weights, 
  * = query + response length of the longest sequence) fits into fraction * capacity_bytes - reserved_bytes.  The
  * footprint is computed by the same code that performs the allocations in rlhf_gen_init (KV pool of
  * max_batch * ceil(max_seq / 16) pages per layer, fp16 working copies of the matrices unless
- * RLHF_GEN_FLAG_CONVERT_IN_PLACE, activations, logits, split-K workspace), as the sum of the sizes requested.
+ * RLHF_GEN_FLAG_CONVERT_IN_PLACE, the 4-bit copies of wqkv and wo, activations, logits, split-K workspace), as the sum
+ * of the sizes requested.
  *   capacity_bytes   memory of the card; 0 = ask HIP for the total memory of cfg.device (the only case that touches a GPU)
  *   fraction         in (0, 1], e.g. 0.95
  *   reserved_bytes   memory others hold on the card; a negative value stands for "the caller's copy of this model in
