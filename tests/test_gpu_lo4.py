@@ -151,7 +151,8 @@ def test_rmsnorm_rows_in_the_4bit_pair_form(B, M, d):
     assert err.pow(2).mean().sqrt() < 0.3 * resid.pow(2).mean().sqrt()                         # ~ 5x closer than the fp16 value alone
 
 
-@pytest.mark.parametrize("M,N,K,resid", [(300, 512, 1024, False), (1024, 256, 512, True), (513, 768, 4096, False), (16384, 256, 512, False)])
+@pytest.mark.parametrize("M,N,K,resid", [(300, 512, 1024, False), (1024, 256, 512, True), (513, 768, 4096, False), (16384, 256, 512, False),
+                                         (777, 1280, 5120, True), (130, 10240, 8192, False), (1, 256, 512, False)])
 def test_gemm_with_4bit_low_halves(B, M, N, K, resid):
     g = torch.Generator().manual_seed(11)
     x = torch.randn(M, K, generator=g)
