@@ -1,6 +1,7 @@
 // GEMMs of the rollout, out = A[M,K] * W[N,K]^T with both operands K-contiguous.
 //   gemm_h16_dma_kernel : large-tile fp16 MFMA GEMM for prefill (M = thousands of tokens): 256x256x32 block tile,
-//                         4 wavefronts of 128x128, LDS ring filled by LDS-DMA loads, 32x32x16 MFMA.
+//                         4 wavefronts of 128x128, LDS ring filled by LDS-DMA loads, 32x32x16 MFMA; pair inputs may
+//                         carry their low halves in 4 bits, contracted by the block-scaled 32x32x64 MFMA.
 //   gemm_skinny_kernel  : weight-streaming GEMM for decode (M = batch <= 128; up to 256 where the split-K form of the
 //                         large-tile GEMM does not apply): W is the MFMA row operand read straight from HBM into
 //                         registers exactly once, the activation slice is staged in LDS, split-K partial sums go
@@ -84,7 +85,8 @@ struct Lo4Args {
 // `out` (plane_stride floats apart); the consumer kernel adds the planes in a fixed order.  With hi|lo inputs the
 // split walks (k-tile, hi), (k-tile, lo), ... so that the W tile fetched for the hi half is still in L2 for the lo half.
 // LO4: A rows are [hi (K) | 4-bit low halves (K / 2 bytes) | unused] at the pitch of the pair form.  The k loop runs
-// the K / 32 fp16 k-tiles and then K / 128 stages of the low halves against the 4-bit copy of W: such a stage has the
+// the K / 32 fp16 k-tiles (SPLIT: those of its split, which begins at a multiple of four) and then the K / 128 stages
+// of the low halves that cover the same columns, against the 4-bit copy of W: such a stage has the
 // byte layout of an fp16 stage (64 bytes per row: here 128 columns), the same DMA loads, operand reads and schedule,
 // and one 4-bit MFMA where the fp16 phase has one fp16 MFMA - a quarter of the pair form's second pass.  The scale
 // bytes of the A rows travel with their stage: every wavefront brings the 128 words of its own rows into a small LDS
